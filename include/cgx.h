@@ -1,0 +1,145 @@
+/*
+ * cgx.h -- C ABI of the MI355X (gfx950) implementation of the compute a rank
+ * performs in CGX's compressed all-reduce (arXiv 2111.08617): bucketed
+ * stochastic quantization of a fused gradient buffer, and the matching
+ * dequantize-and-reduce / requantize of a Scatter-Reduce-Allgather.
+ *
+ * Common conventions
+ *   Plan.  A fused buffer of n elements is described by L layers:
+ *   layer_offsets[0..L] (host, int64, layer_offsets[0] = 0, non-decreasing,
+ *   layer_offsets[L] = n; empty layers are allowed and skipped) and
+ *   bits_per_layer[0..L-1] (host, uint8: 0 = pass-through, 1..8 = quantize to
+ *   that many bits).  `bucket` is the bucket size in elements: a multiple of 32
+ *   in [32, 8192].  Buckets restart at every layer's first element; a layer's
+ *   last bucket may be short.  (Paper Sec. 4.1: fused buffers keep the layer
+ *   offsets, compression is per layer, small layers travel uncompressed;
+ *   Sec. 4.3: buckets with per-bucket scaling meta-data.)
+ *
+ *   Packed stream.  For each non-empty layer, in order, one segment padded with
+ *   zero bytes to a multiple of 16 bytes:
+ *     quantized layer of len elements at b bits: ceil(len*b/8) bytes holding
+ *       the codes as an LSB-first bitstream (code j in stream bits
+ *       [j*b, (j+1)*b); stream bit t is bit t&7 of byte t>>3);
+ *     pass-through layer: its len elements verbatim in the storage type.
+ *   Meta.  Two floats {unit, min} per bucket, buckets numbered in layer order
+ *   over the quantized layers.  A code q stands for fma(q, unit, min).
+ *
+ *   Memory.  Every pointer marked "device" is device memory owned by the
+ *   caller, 16-byte aligned, valid until the work queued on `stream` has run.
+ *   Pointers marked "host" are read during the call and may be reused on
+ *   return.  The library keeps a small device-resident table per distinct plan
+ *   (built on first use, which may synchronise; later calls with the same plan
+ *   only queue kernels) and frees them in cgx_shutdown().  No call synchronises
+ *   the stream.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *   stream).
+ *
+ *   Errors.  Every function returns CGX_OK or a negative cgx_status.  Argument
+ *   errors are found on the host before anything is queued; nothing is written
+ *   in that case.  Inputs must be finite with |x| < 2^126; other values do not
+ *   fault but give unspecified codes.
+ */
+#ifndef CGX_H
+#define CGX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CGX_OK = 0,
+    CGX_ERR_NULL = -1,     /* a required pointer is NULL */
+    CGX_ERR_SIZE = -2,     /* n or L negative, or n does not match layer_offsets[L] */
+    CGX_ERR_OFFSETS = -3,  /* layer_offsets[0] != 0 or offsets decrease */
+    CGX_ERR_BITS = -4,     /* a bits_per_layer entry above 8 */
+    CGX_ERR_BUCKET = -5,   /* bucket not a multiple of 32 in [32, 8192] */
+    CGX_ERR_PEERS = -6,    /* W outside [1, CGX_MAX_PEERS] */
+    CGX_ERR_DTYPE = -7,    /* unknown storage type */
+    CGX_ERR_HIP = -8,      /* the HIP runtime reported an error */
+    CGX_ERR_ALIGN = -9     /* a device pointer is not 16-byte aligned */
+} cgx_status;
+
+typedef enum {
+    CGX_F32 = 0,           /* gradient stored as IEEE binary32 */
+    CGX_F16 = 1            /* gradient stored as IEEE binary16, arithmetic in binary32 */
+} cgx_dtype;
+
+#define CGX_MAX_PEERS 64
+
+/*
+ * Sizes of the packed stream and of the meta array for a plan (pure host
+ * computation; follows the layout above).  Either output pointer may be NULL.
+ */
+int cgx_sizes(int64_t n, int32_t L, const int64_t *layer_offsets /* host [L+1] */,
+              const uint8_t *bits_per_layer /* host [L] */, int32_t bucket, cgx_dtype dt,
+              size_t *packed_bytes, size_t *meta_bytes);
+
+/*
+ * Bucketed stochastic quantization of a fused buffer (paper Sec. 2.2, the
+ * rounding rule q(v_i, s); Sec. 4.3, buckets; Sec. 4.1, per-layer parameters).
+ * Per bucket: mn = min, mx = max, Lv = 2^b - 1, unit = (mx - mn) / Lv,
+ * inv16 = (Lv * 65536) / (mx - mn); unit = inv16 = 0 for a constant or
+ * degenerate bucket; a zero minimum is stored as +0.  Per element with buffer
+ * index i: T = trunc((x - mn) * inv16), code = min((T + u) >> 16, Lv), where u
+ * is the 16-bit draw of a counter-based generator keyed on (seed, i).  All
+ * arithmetic is binary32 without fused operations.
+ *   grad    device, n elements of dt
+ *   packed  device, at least packed_bytes; every byte of it is written
+ *   meta    device, at least meta_bytes
+ */
+int cgx_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                 const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt,
+                 void *packed, void *meta, void *stream);
+
+/*
+ * Dequantize W compressed chunks of the same plan and sum them (paper Sec. 4:
+ * compression is not associative, so chunks are decompressed before the sum;
+ * Sec. 4.1, Scatter-Reduce-Allgather, first round on a rank's own share).
+ * sum[i] = deq_0[i] + deq_1[i] + ... in that order in binary32, where
+ * deq_w[i] = fma(code, unit, min) for quantized layers and the stored value,
+ * widened to binary32, for pass-through layers.
+ *   packed, meta  host arrays of W device pointers (chunk w's stream and meta)
+ *   sum           device, n floats
+ * A rank's share of a larger buffer is passed as a plan over the share alone.
+ */
+int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W,
+                       int64_t n, int32_t L, const int64_t *layer_offsets,
+                       const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
+                       float *sum, void *stream);
+
+/*
+ * Compress the aggregated chunk again before it is broadcast (paper Sec. 4.1,
+ * Scatter-Reduce-Allgather, second round): cgx_quantize on binary32 input.
+ * Pass-through layers are written as binary32.
+ */
+int cgx_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
+                   const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed,
+                   void *packed, void *meta, void *stream);
+
+/*
+ * Diagnostic: the table of wavefront work items ("tiles") the kernels walk for
+ * a plan, written to host memory as 32-byte records
+ *   { int64 first_element; int64 packed_byte_offset; uint32 first_bucket;
+ *     uint32 elements; uint32 info; uint32 pad_bytes }
+ * with info = bits | kind << 4 | log2(lanes per bucket) << 8 and kind 0 = generic
+ * quantize, 1 = vectorised quantize, 2 = element-wise copy, 3 = vectorised copy.
+ * Every element of every non-empty layer lies in exactly one tile and tiles never
+ * cross layers (paper Sec. 4.1).  At most `capacity` records are written;
+ * *n_tiles receives the full count.  Pure host computation.
+ */
+int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                   int32_t bucket, cgx_dtype dt, void *tiles_out /* host */, int64_t capacity,
+                   int64_t *n_tiles);
+
+/* Human-readable name of a status code (static storage). */
+const char *cgx_status_string(int status);
+
+/* Frees the cached plan tables.  Call with no work of this library in flight. */
+int cgx_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CGX_H */

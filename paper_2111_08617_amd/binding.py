@@ -1,0 +1,139 @@
+"""ctypes binding of ``libcgx.so``: the functions of ``include/cgx.h`` under the
+same names.  Argument marshalling only -- every step runs in the HIP kernels.
+
+Device buffers are torch tensors (PyTorch supplies device memory and the
+stream, nothing else); plan arrays are numpy arrays on the host.  There is no
+CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Sequence, Tuple
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcgx.so")
+
+F32, F16 = 0, 1
+MAX_PEERS = 64
+
+EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_requantize", "cgx_plan_tiles",
+           "cgx_status_string", "cgx_shutdown")
+
+TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
+                       ("info", "<u4"), ("pad", "<u4")])
+
+_lib = None
+
+
+class CgxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2111_08617_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        plan = [c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int32]
+        L.cgx_sizes.argtypes = plan + [c.c_int, c.POINTER(c.c_size_t), c.POINTER(c.c_size_t)]
+        L.cgx_quantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_requantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + [c.c_int, c.c_void_p, c.c_void_p]
+        L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
+        L.cgx_status_string.restype = c.c_char_p
+        L.cgx_status_string.argtypes = [c.c_int]
+        L.cgx_shutdown.argtypes = []
+        for name in EXPORTS:
+            if name != "cgx_status_string":
+                getattr(L, name).restype = c.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().cgx_status_string(int(status)).decode()
+
+
+class Plan:
+    """Host arrays of a plan, kept alive and contiguous for the C calls."""
+
+    def __init__(self, layer_offsets, bits_per_layer, bucket: int, dt: int = F32):
+        self.offsets = np.ascontiguousarray(layer_offsets, dtype=np.int64)
+        self.bits = np.ascontiguousarray(bits_per_layer, dtype=np.uint8)
+        if self.offsets.ndim != 1 or self.bits.ndim != 1 or self.offsets.size != self.bits.size + 1:
+            raise ValueError("layer_offsets must have one more entry than bits_per_layer")
+        self.bucket = int(bucket)
+        self.dt = int(dt)
+        self.n = int(self.offsets[-1])
+        self.L = int(self.bits.size)
+
+    @property
+    def args(self):
+        return (self.n, self.L, self.offsets.ctypes.data, self.bits.ctypes.data, self.bucket)
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise CgxError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def cgx_sizes(plan: Plan) -> Tuple[int, int]:
+    """(packed_bytes, meta_bytes) of a plan."""
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().cgx_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def cgx_plan_tiles(plan: Plan) -> np.ndarray:
+    """The tile table of a plan as a structured numpy array (host only)."""
+    count = ctypes.c_int64()
+    _check(lib().cgx_plan_tiles(*plan.args, plan.dt, None, 0, ctypes.byref(count)), "cgx_plan_tiles")
+    tiles = np.zeros(count.value, dtype=TILE_DTYPE)
+    _check(lib().cgx_plan_tiles(*plan.args, plan.dt, tiles.ctypes.data, count.value, ctypes.byref(count)),
+           "cgx_plan_tiles")
+    return tiles
+
+
+def cgx_quantize(grad, plan: Plan, seed: int, packed, meta, stream=None) -> None:
+    """grad: device tensor of n elements (float32 or float16 per plan.dt);
+    packed: device uint8 tensor of >= packed_bytes; meta: device float32 tensor of >= meta_bytes/4."""
+    _check(lib().cgx_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
+                              meta.data_ptr(), _stream(stream)), "cgx_quantize")
+
+
+def cgx_requantize(total, plan: Plan, seed: int, packed, meta, stream=None) -> None:
+    """total: device float32 tensor of n elements (the reduced chunk)."""
+    _check(lib().cgx_requantize(total.data_ptr(), *plan.args, seed & (2**64 - 1), packed.data_ptr(),
+                                meta.data_ptr(), _stream(stream)), "cgx_requantize")
+
+
+def cgx_dequant_reduce(packed: Sequence, meta: Sequence, plan: Plan, total, stream=None) -> None:
+    """packed / meta: W device tensors each; total: device float32 tensor of n elements (output)."""
+    W = len(packed)
+    if len(meta) != W:
+        raise ValueError("as many meta tensors as packed tensors")
+    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
+    _check(lib().cgx_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
+           "cgx_dequant_reduce")
+
+
+def cgx_shutdown() -> None:
+    _check(lib().cgx_shutdown(), "cgx_shutdown")

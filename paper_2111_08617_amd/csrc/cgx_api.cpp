@@ -1,0 +1,222 @@
+// extern "C" entry points of libcgx.so (see include/cgx.h): argument checks,
+// the per-plan tile table cache, and kernel launches on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <vector>
+
+#include "cgx_kernels.h"
+#include "cgx_plan.h"
+
+namespace {
+
+using cgx::Tile;
+
+struct CachedPlan {
+    // identity
+    int device = 0;
+    int32_t bucket = 0;
+    int dt = 0;
+    int chunks_per_tile = 0;
+    std::vector<int64_t> off;
+    std::vector<uint8_t> bits;
+    // content
+    cgx::PlanShape shape;
+    int64_t n_tiles = 0;
+    Tile *d_tiles = nullptr;
+};
+
+std::mutex g_mutex;
+std::vector<std::unique_ptr<CachedPlan>> g_plans;
+cgx::LaunchConfig g_cfg;
+bool g_cfg_read = false;
+
+int env_int(const char *name, int fallback)
+{
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+// Launch-shape tunables, for experiments: CGX_CHUNKS_PER_TILE, CGX_MAX_BLOCKS.
+const cgx::LaunchConfig &launch_config()
+{
+    if (!g_cfg_read) {
+        g_cfg.chunks_per_tile = env_int("CGX_CHUNKS_PER_TILE", g_cfg.chunks_per_tile);
+        g_cfg.max_blocks = env_int("CGX_MAX_BLOCKS", g_cfg.max_blocks);
+        g_cfg_read = true;
+    }
+    return g_cfg;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Finds or builds the device-resident tile table of a (valid) plan.
+int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, const CachedPlan **out)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const cgx::LaunchConfig &cfg = launch_config();
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return CGX_ERR_HIP;
+    for (const auto &p : g_plans) {
+        if (p->device == device && p->bucket == bucket && p->dt == dt &&
+            p->chunks_per_tile == cfg.chunks_per_tile && p->bits.size() == size_t(L) &&
+            std::memcmp(p->bits.data(), bits, size_t(L)) == 0 &&
+            std::memcmp(p->off.data(), off, sizeof(int64_t) * (size_t(L) + 1)) == 0) {
+            *out = p.get();
+            return CGX_OK;
+        }
+    }
+    auto plan = std::make_unique<CachedPlan>();
+    plan->device = device;
+    plan->bucket = bucket;
+    plan->dt = dt;
+    plan->chunks_per_tile = cfg.chunks_per_tile;
+    plan->off.assign(off, off + L + 1);
+    plan->bits.assign(bits, bits + L);
+    plan->shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    std::vector<Tile> tiles;
+    cgx::build_tiles(L, off, bits, bucket, dt, cfg.chunks_per_tile, tiles);
+    plan->n_tiles = int64_t(tiles.size());
+    if (!tiles.empty()) {
+        const size_t bytes = tiles.size() * sizeof(Tile);
+        if (hipMalloc(reinterpret_cast<void **>(&plan->d_tiles), bytes) != hipSuccess) return CGX_ERR_HIP;
+        if (hipMemcpy(plan->d_tiles, tiles.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(plan->d_tiles);
+            return CGX_ERR_HIP;
+        }
+    }
+    *out = plan.get();
+    g_plans.push_back(std::move(plan));
+    return CGX_OK;
+}
+
+int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
+                  uint64_t seed, int dt, void *packed, void *meta, void *stream)
+{
+    int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    if (rc != CGX_OK) return rc;
+    if (n == 0) return CGX_OK;
+    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    if (!grad || !packed || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
+    if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
+    const CachedPlan *plan = nullptr;
+    rc = get_plan(L, off, bits, bucket, dt, &plan);
+    if (rc != CGX_OK) return rc;
+    const hipError_t e = cgx::launch_quantize(grad, dt, plan->d_tiles, plan->n_tiles, bucket, seed, packed, meta,
+                                              launch_config(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cgx_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+              cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes)
+{
+    const int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (rc != CGX_OK) return rc;
+    const cgx::PlanShape s = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (packed_bytes) *packed_bytes = s.packed_bytes;
+    if (meta_bytes) *meta_bytes = s.meta_bytes;
+    return CGX_OK;
+}
+
+int cgx_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                 const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt, void *packed,
+                 void *meta, void *stream)
+{
+    return quantize_impl(grad, n, L, layer_offsets, bits_per_layer, bucket, seed, int(dt), packed, meta, stream);
+}
+
+int cgx_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
+                   const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, void *packed, void *meta,
+                   void *stream)
+{
+    return quantize_impl(sum, n, L, layer_offsets, bits_per_layer, bucket, seed, CGX_F32, packed, meta, stream);
+}
+
+int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
+                       const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
+                       float *sum, void *stream)
+{
+    int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (rc != CGX_OK) return rc;
+    if (W < 1 || W > CGX_MAX_PEERS) return CGX_ERR_PEERS;
+    if (n == 0) return CGX_OK;
+    const cgx::PlanShape shape = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (!packed || !meta || !sum) return CGX_ERR_NULL;
+    for (int w = 0; w < W; w++) {
+        if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
+        if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
+    }
+    if (misaligned(sum)) return CGX_ERR_ALIGN;
+    const CachedPlan *plan = nullptr;
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, int(dt), &plan);
+    if (rc != CGX_OK) return rc;
+    // peers are folded in order, kPeersPerLaunch at a time, so the sum order is w = 0, 1, ..., W-1
+    for (int w0 = 0; w0 < W; w0 += cgx::kPeersPerLaunch) {
+        const int k = W - w0 < cgx::kPeersPerLaunch ? W - w0 : cgx::kPeersPerLaunch;
+        cgx::PeerPtrs peers{};
+        for (int i = 0; i < k; i++) {
+            peers.packed[i] = static_cast<const uint8_t *>(packed[w0 + i]);
+            peers.meta[i] = static_cast<const float2 *>(meta[w0 + i]);
+        }
+        const hipError_t e = cgx::launch_dequant_reduce(peers, k, int(dt), plan->d_tiles, plan->n_tiles, bucket,
+                                                        w0 > 0, sum, launch_config(),
+                                                        static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return CGX_ERR_HIP;
+    }
+    return CGX_OK;
+}
+
+int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                   int32_t bucket, cgx_dtype dt, void *tiles_out, int64_t capacity, int64_t *n_tiles)
+{
+    const int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (rc != CGX_OK) return rc;
+    if (!n_tiles || (capacity > 0 && !tiles_out)) return CGX_ERR_NULL;
+    std::vector<Tile> tiles;
+    int chunks = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        chunks = launch_config().chunks_per_tile;
+    }
+    cgx::build_tiles(L, layer_offsets, bits_per_layer, bucket, int(dt), chunks, tiles);
+    *n_tiles = int64_t(tiles.size());
+    const int64_t k = capacity < *n_tiles ? capacity : *n_tiles;
+    if (k > 0) std::memcpy(tiles_out, tiles.data(), size_t(k) * sizeof(Tile));
+    return CGX_OK;
+}
+
+const char *cgx_status_string(int status)
+{
+    switch (status) {
+    case CGX_OK: return "ok";
+    case CGX_ERR_NULL: return "a required pointer is NULL";
+    case CGX_ERR_SIZE: return "n or L is negative, too large, or n does not match layer_offsets[L]";
+    case CGX_ERR_OFFSETS: return "layer_offsets must start at 0 and never decrease";
+    case CGX_ERR_BITS: return "bits_per_layer entries must be 0 (pass-through) or 1..8";
+    case CGX_ERR_BUCKET: return "bucket must be a multiple of 32 in [32, 8192]";
+    case CGX_ERR_PEERS: return "W must be in [1, 64]";
+    case CGX_ERR_DTYPE: return "unknown storage type";
+    case CGX_ERR_HIP: return "the HIP runtime reported an error";
+    case CGX_ERR_ALIGN: return "device pointers must be 16-byte aligned";
+    default: return "unknown status";
+    }
+}
+
+int cgx_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int rc = CGX_OK;
+    for (auto &p : g_plans)
+        if (p->d_tiles && hipFree(p->d_tiles) != hipSuccess) rc = CGX_ERR_HIP;
+    g_plans.clear();
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,32 @@
+// Launchers of the gfx950 kernels (implemented in cgx_kernels.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "cgx_plan.h"
+
+namespace cgx {
+
+constexpr int kPeersPerLaunch = 16;   // chunks one reduce launch reads; more peers take more launches
+
+struct PeerPtrs {
+    const uint8_t *packed[kPeersPerLaunch];
+    const float2 *meta[kPeersPerLaunch];
+};
+
+// Tunables (set once from the environment at first use; see cgx_api.cpp).
+struct LaunchConfig {
+    int chunks_per_tile = 1;   // fast-tile length in chunks of kChunk elements
+    int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
+};
+
+hipError_t launch_quantize(const void *grad, int dt, const Tile *tiles, int64_t n_tiles, int32_t bucket,
+                           uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
+                           hipStream_t stream);
+
+// sum = (accumulate ? sum : 0) + deq_0 + ... + deq_{W-1}, W <= kPeersPerLaunch.
+hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+                                 int32_t bucket, bool accumulate, float *sum, const LaunchConfig &cfg,
+                                 hipStream_t stream);
+
+}  // namespace cgx

@@ -1,0 +1,130 @@
+// Plan validation, sizes and tile table (host only; no HIP calls here).
+#include "cgx_plan.h"
+
+namespace cgx {
+
+static inline uint64_t round_up16(uint64_t v) { return (v + 15u) & ~uint64_t(15); }
+static inline int elem_size(int dt) { return dt == CGX_F16 ? 2 : 4; }
+
+int validate_plan(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt)
+{
+    if (n < 0 || L < 0) return CGX_ERR_SIZE;
+    if (L > 0 && (!off || !bits)) return CGX_ERR_NULL;
+    if (dt != CGX_F32 && dt != CGX_F16) return CGX_ERR_DTYPE;
+    if (bucket < 32 || bucket > 8192 || bucket % 32) return CGX_ERR_BUCKET;
+    if (L == 0) return n == 0 ? CGX_OK : CGX_ERR_SIZE;
+    if (off[0] != 0) return CGX_ERR_OFFSETS;
+    for (int32_t l = 0; l < L; l++) {
+        if (off[l + 1] < off[l]) return CGX_ERR_OFFSETS;
+        if (bits[l] > 8) return CGX_ERR_BITS;
+    }
+    if (off[L] != n) return CGX_ERR_SIZE;
+    // bucket indices are 32-bit in the tile table
+    if (n / 32 > int64_t(0xfffffff0u)) return CGX_ERR_SIZE;
+    return CGX_OK;
+}
+
+// Payload bytes (before padding) and buckets of one layer.
+static inline void layer_extent(int64_t len, int b, int32_t bucket, int dt, uint64_t &payload, uint64_t &buckets)
+{
+    if (b == 0) {
+        payload = uint64_t(len) * elem_size(dt);
+        buckets = 0;
+    } else {
+        payload = (uint64_t(len) * b + 7) / 8;
+        buckets = (uint64_t(len) + bucket - 1) / bucket;
+    }
+}
+
+PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt)
+{
+    PlanShape s;
+    for (int32_t l = 0; l < L; l++) {
+        int64_t len = off[l + 1] - off[l];
+        if (len == 0) continue;
+        uint64_t payload, buckets;
+        layer_extent(len, bits[l], bucket, dt, payload, buckets);
+        s.packed_bytes += round_up16(payload);
+        s.n_buckets += buckets;
+    }
+    s.meta_bytes = size_t(8 * s.n_buckets);
+    return s;
+}
+
+static inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+static inline int log2i(int v) { int k = 0; while ((1 << k) < v) k++; return k; }
+
+// All element pairs of [e0, e0 + count) share the upper 32 bits of their pair
+// index, so the generator's key is uniform over the tile.
+static inline bool same_key_block(int64_t e0, int64_t count)
+{
+    return ((uint64_t(e0) >> 1) >> 32) == ((uint64_t(e0 + count - 1) >> 1) >> 32);
+}
+
+void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+                 int chunks_per_tile, std::vector<Tile> &tiles)
+{
+    tiles.clear();
+    if (chunks_per_tile < 1) chunks_per_tile = 1;
+    const int S = elem_size(dt);
+    const bool fast_bucket = is_pow2(bucket) && bucket <= kChunk;
+    // 64 lanes x 4 groups x 8 elements = kChunk, so a bucket spans bucket/32 lanes
+    const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(bucket / 32)) : 0u;
+    uint64_t seg = 0, bucket0 = 0;
+    for (int32_t l = 0; l < L; l++) {
+        const int64_t first = off[l], len = off[l + 1] - off[l];
+        if (len == 0) continue;
+        const int b = bits[l];
+        uint64_t payload, buckets;
+        layer_extent(len, b, bucket, dt, payload, buckets);
+        const uint32_t pad = uint32_t(round_up16(payload) - payload);
+        const bool aligned = (first % 8) == 0;
+        const size_t first_tile = tiles.size();
+        if (b == 0) {
+            for (int64_t j = 0; j < len; j += kCopyTile) {
+                Tile t{};
+                t.elem0 = first + j;
+                t.packed_off = int64_t(seg + uint64_t(j) * S);
+                t.count = uint32_t(len - j < kCopyTile ? len - j : kCopyTile);
+                t.info = uint32_t(aligned ? kCopyFast : kCopySlow) << 4;
+                tiles.push_back(t);
+            }
+        } else {
+            int64_t j = 0;
+            if (fast_bucket && aligned) {
+                const int64_t full_chunks = len / kChunk;
+                for (int64_t c = 0; c < full_chunks;) {
+                    int64_t k = full_chunks - c < chunks_per_tile ? full_chunks - c : chunks_per_tile;
+                    // a tile must not straddle a 2^33-element block of the generator's key
+                    while (k > 1 && !same_key_block(first + c * kChunk, k * kChunk)) k--;
+                    Tile t{};
+                    t.elem0 = first + c * kChunk;
+                    t.packed_off = int64_t(seg + uint64_t(c) * kChunk * b / 8);
+                    t.bucket0 = uint32_t(bucket0 + uint64_t(c) * kChunk / bucket);
+                    t.count = uint32_t(k * kChunk);
+                    const bool fast = same_key_block(t.elem0, t.count);
+                    t.info = uint32_t(b) | uint32_t(fast ? kQuantFast : kQuantSlow) << 4 | lpb_log2 << 8;
+                    tiles.push_back(t);
+                    c += k;
+                }
+                j = full_chunks * kChunk;
+            }
+            // what is left (or the whole layer): whole buckets, about a chunk per tile
+            const int64_t step = bucket >= kChunk ? bucket : int64_t(kChunk / bucket) * bucket;
+            for (; j < len; j += step) {
+                Tile t{};
+                t.elem0 = first + j;
+                t.packed_off = int64_t(seg + uint64_t(j) * b / 8);
+                t.bucket0 = uint32_t(bucket0 + uint64_t(j) / bucket);
+                t.count = uint32_t(len - j < step ? len - j : step);
+                t.info = uint32_t(b) | uint32_t(kQuantSlow) << 4;
+                tiles.push_back(t);
+            }
+        }
+        if (tiles.size() > first_tile) tiles.back().pad = pad;
+        seg += round_up16(payload);
+        bucket0 += buckets;
+    }
+}
+
+}  // namespace cgx

@@ -1,0 +1,67 @@
+// Host-side plan: validation of the layer table, sizes of the packed stream
+// and meta array, and the tile table the kernels walk.
+//
+// A tile is a contiguous run of elements of ONE layer that one wavefront
+// processes: whole buckets of a quantized layer (paper Sec. 4.3: buckets are
+// compressed independently; Sec. 4.1: layers are never mixed) or a piece of a
+// pass-through layer.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/cgx.h"
+
+#if defined(__HIPCC__)
+#define CGX_HOST_DEVICE __host__ __device__
+#else
+#define CGX_HOST_DEVICE
+#endif
+
+namespace cgx {
+
+// Elements a wavefront handles per pass of the fast path: 64 lanes x 4 groups
+// of 8 consecutive elements.  A fast tile is a whole number of chunks.
+constexpr int kChunk = 2048;
+// Elements per pass-through tile.
+constexpr int kCopyTile = 8192;
+
+enum TileKind : uint32_t {
+    kQuantSlow = 0,  // any bucket size, any alignment, ragged last bucket
+    kQuantFast = 1,  // power-of-two bucket <= kChunk, 8-element aligned start, whole chunks
+    kCopySlow = 2,   // pass-through, element-wise
+    kCopyFast = 3    // pass-through, 16-byte vectors
+};
+
+struct Tile {               // 32 bytes, read by the kernels with scalar loads
+    int64_t elem0;          // first element, index in the fused buffer
+    int64_t packed_off;     // byte offset of the tile's payload in the packed stream
+    uint32_t bucket0;       // index of the tile's first bucket in the meta array
+    uint32_t count;         // elements in the tile
+    uint32_t info;          // bits [0:3] bit width, [4:7] TileKind, [8:11] log2(lanes per bucket)
+    uint32_t pad;           // zero bytes to append after the payload (last tile of a layer)
+};
+static_assert(sizeof(Tile) == 32, "tile layout is shared with the kernels");
+
+CGX_HOST_DEVICE inline uint32_t tile_bits(const Tile &t) { return t.info & 15u; }
+CGX_HOST_DEVICE inline uint32_t tile_kind(const Tile &t) { return (t.info >> 4) & 15u; }
+CGX_HOST_DEVICE inline uint32_t tile_lpb_log2(const Tile &t) { return (t.info >> 8) & 15u; }
+
+struct PlanShape {
+    size_t packed_bytes = 0;
+    size_t meta_bytes = 0;
+    uint64_t n_buckets = 0;
+};
+
+// Returns CGX_OK or the status code of the first violated rule.
+int validate_plan(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt);
+
+// Sizes only (layout rules of cgx.h).  The plan must be valid.
+PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt);
+
+// Tile table.  `chunks_per_tile` bounds the length of fast tiles.
+void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+                 int chunks_per_tile, std::vector<Tile> &tiles);
+
+}  // namespace cgx

@@ -1,0 +1,224 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bar: packed stream and meta bit-exact; reduced sums bit-exact against the
+oracle's ordered binary32 sum and within 1e-6 * sum_w |deq_w| of its binary64
+sum.  Inputs are seeded and synthetic (paper_2111_08617_amd.workloads); inputs of
+the reduce step come from the oracle's quantizer, never from the GPU.
+"""
+import numpy as np
+import pytest
+
+from paper_2111_08617_amd import binding as cgx
+from paper_2111_08617_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    cgx.lib()                       # fails loudly if libcgx.so has not been built
+    return t
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_quantize(torch, grad, offsets, bits, bucket, seed, dt, requant=False):
+    plan = cgx.Plan(offsets, bits, bucket, dt)
+    pb, mb = cgx.cgx_sizes(plan)
+    # canaries after the buffers catch writes past the sizes cgx_sizes reports
+    packed = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    meta = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+    g = grad if isinstance(grad, torch.Tensor) else dev(torch, grad)
+    if requant:
+        cgx.cgx_requantize(g, plan, seed, packed, meta)
+    else:
+        cgx.cgx_quantize(g, plan, seed, packed, meta)
+    torch.cuda.synchronize()
+    p, m = packed.cpu().numpy(), meta.cpu().numpy()
+    assert (p[pb:] == 0xA5).all() and (m[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+    return p[:pb], m[:mb // 4].reshape(-1, 2)
+
+
+def gpu_reduce(torch, chunks, metas, offsets, bits, bucket, dt):
+    plan = cgx.Plan(offsets, bits, bucket, dt)
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m.reshape(-1)) if m.size else torch.zeros(4, device="cuda") for m in metas]
+    total = torch.full((plan.n + 16,), 123.0, dtype=torch.float32, device="cuda")
+    cgx.cgx_dequant_reduce(dp, dm, plan, total)
+    torch.cuda.synchronize()
+    out = total.cpu().numpy()
+    assert (out[plan.n:] == 123.0).all(), "wrote past the end of the sum"
+    return out[:plan.n], total
+
+
+def assert_same_chunk(gp, gm, op, om, what=""):
+    assert gm.tobytes() == om.tobytes(), f"{what}: meta differs in {int((gm.view(np.uint32) != om.view(np.uint32)).sum())} words"
+    if not np.array_equal(gp, op):
+        bad = np.nonzero(gp != op)[0]
+        raise AssertionError(f"{what}: packed differs in {bad.size} bytes, first at {bad[:5]}")
+
+
+def assert_sum_parity(got, ref, what=""):
+    g, r = got.view(np.uint32), ref["sum32"].view(np.uint32)
+    assert np.array_equal(g, r), f"{what}: {int((g != r).sum())} sums differ from the ordered binary32 sum"
+    err = np.abs(got.astype(np.float64) - ref["sum64"])
+    assert (err <= 1e-6 * ref["abs64"] + 1e-45).all(), f"{what}: worst relative error {np.max(err / (ref['abs64'] + 1e-300))}"
+
+
+def full_cycle(torch, oracle, w, W, seed_shift=0, what=""):
+    """quantize, reduce over W oracle-made chunks, requantize of the GPU's own sum."""
+    chunks, metas = [], []
+    for peer in range(W):
+        g = w.gradient(peer)
+        seed = w.quant_seed(peer) + seed_shift
+        op, om = oracle.quantize(g, w.offsets, w.bits, w.bucket, seed, w.dt)
+        if peer < 2:
+            gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, seed, w.dt)
+            assert_same_chunk(gp, gm, op, om, f"{what} quantize peer {peer}")
+        chunks.append(op)
+        metas.append(om)
+    ref = oracle.dequant_reduce(chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
+    got, total = gpu_reduce(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
+    assert_sum_parity(got, ref, f"{what} reduce")
+    # requantize: the definition is quantize(sum) on binary32 input, so compare on the GPU's own sum
+    rp, rm = gpu_quantize(torch, total[:w.n], w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32, requant=True)
+    op, om = oracle.quantize(got, w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32)
+    assert_same_chunk(rp, rm, op, om, f"{what} requantize")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [32, 64, 96, 128, 512, 2048, 4096, 8192])
+def test_edge_case_plan(torch, oracle, bucket, dt):
+    """All bit widths, pass-through, empty, tiny and ragged layers, odd offsets."""
+    w = wl.tiny_mixed(seed=bucket + dt, dt=dt, bucket=bucket)
+    full_cycle(torch, oracle, w, W=3, what=f"tiny_mixed B={bucket}")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [32, 64, 128, 256, 512, 1024, 2048])
+def test_vectorised_path_all_bit_widths(torch, oracle, bucket, dt):
+    """Aligned layers of whole chunks (the fast tiles) plus ragged tails, every bit width."""
+    sizes = [2048 * 3, 2048 * 2 + 40, 8, 2048, 2048 * 5 + 1000, 2048 * 4, 16384, 2048 + bucket, 6144, 8192 * 2 + 24]
+    bits = [1, 2, 0, 3, 4, 5, 0, 6, 7, 8]
+    w = wl.Workload("chunks", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 4, 1000 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    kinds = (cgx.cgx_plan_tiles(plan)["info"] >> 4) & 15
+    assert (kinds == 1).sum() >= 20 and (kinds == 3).any() and (kinds == 0).any()
+    full_cycle(torch, oracle, w, W=4, what=f"chunks B={bucket}")
+
+
+def test_single_tensor_config(torch, oracle):
+    """2^20 elements ~ N(0, 0.01^2), 4 bit, bucket 128, seed 0, reduce over W = 2."""
+    w = wl.single_tensor(seed=0)
+    full_cycle(torch, oracle, w, W=2, what="single_1m")
+
+
+def test_many_peers_take_several_launches(torch, oracle):
+    w = wl.tiny_mixed(seed=77, bucket=128)
+    for W in (1, 16, 17, 37, 64):
+        chunks, metas = zip(*[oracle.quantize(w.gradient(p), w.offsets, w.bits, w.bucket, p) for p in range(W)])
+        ref = oracle.dequant_reduce(list(chunks), list(metas), w.offsets, w.bits, w.bucket)
+        got, _ = gpu_reduce(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
+        assert_sum_parity(got, ref, f"W={W}")
+
+
+def test_degenerate_values(torch, oracle):
+    """Constant, zero, signed-zero, subnormal and huge buckets; exact grids."""
+    B, n = 128, 128 * 24
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal(n).astype(np.float32)
+    x[0:128] = 0.37
+    x[128:256] = 0.0
+    x[130] = -0.0
+    x[256:384] = -0.0
+    x[384:512] = 1e-42
+    x[512:640] = np.float32(1e-42) * rng.integers(0, 50, 128).astype(np.float32)     # subnormal range
+    x[640:768] = rng.standard_normal(128).astype(np.float32) * np.float32(1e37)      # near the top of the range
+    x[768:896] = np.float32(-3.25) + rng.integers(0, 16, 128).astype(np.float32) * np.float32(2.0 ** -7)
+    x[768], x[769] = np.float32(-3.25), np.float32(-3.25) + np.float32(15 * 2.0 ** -7)
+    x[896:1024] = np.abs(x[896:1024])
+    x[896] = -0.0                                            # minimum is -0 with positive values
+    x[1024:1152] = np.float32(1e-30) * rng.standard_normal(128).astype(np.float32)
+    x[1152:1280] = np.float32(1.0) + np.float32(2.0 ** -23) * rng.integers(0, 3, 128).astype(np.float32)
+    for b in (1, 2, 3, 4, 8):
+        off, bits = np.array([0, n], np.int64), np.array([b], np.uint8)
+        for seed in (0, 2**64 - 1, 2**32, 12345678901234567):
+            gp, gm = gpu_quantize(torch, x, off, bits, B, seed, wl.F32)
+            op, om = oracle.quantize(x, off, bits, B, seed, wl.F32)
+            assert_same_chunk(gp, gm, op, om, f"degenerate b={b} seed={seed}")
+        got, _ = gpu_reduce(torch, [op, op], [om, om], off, bits, B, wl.F32)
+        assert_sum_parity(got, oracle.dequant_reduce([op, op], [om, om], off, bits, B), f"degenerate b={b}")
+    # binary16 storage with subnormal halves
+    h = (rng.standard_normal(4096) * 1e-3).astype(np.float16)
+    h[:64] = np.arange(64, dtype=np.float32) * np.float32(6e-8)
+    h[2048:2048 + 128] = 0
+    off, bits = np.array([0, 4096], np.int64), np.array([4], np.uint8)
+    gp, gm = gpu_quantize(torch, h, off, bits, 128, 5, wl.F16)
+    op, om = oracle.quantize(h, off, bits, 128, 5, wl.F16)
+    assert_same_chunk(gp, gm, op, om, "binary16 subnormals")
+
+
+def test_repeatable_and_seed_sensitive(torch, oracle):
+    w = wl.tiny_mixed(seed=5, bucket=256)
+    g = w.gradient()
+    a = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, 42, w.dt)
+    b = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, 42, w.dt)
+    c = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, 43, w.dt)
+    assert np.array_equal(a[0], b[0]) and a[1].tobytes() == b[1].tobytes()
+    assert not np.array_equal(a[0], c[0]) and a[1].tobytes() == c[1].tobytes()
+
+
+def test_non_default_stream(torch, oracle):
+    w = wl.tiny_mixed(seed=6, bucket=128)
+    g = w.gradient()
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    pb, mb = cgx.cgx_sizes(plan)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        dg = dev(torch, g)
+        packed = torch.empty(pb, dtype=torch.uint8, device="cuda")
+        meta = torch.empty(mb // 4, dtype=torch.float32, device="cuda")
+        cgx.cgx_quantize(dg, plan, 3, packed, meta, stream=s)
+    s.synchronize()
+    op, om = oracle.quantize(g, w.offsets, w.bits, w.bucket, 3)
+    assert_same_chunk(packed.cpu().numpy(), meta.cpu().numpy().reshape(-1, 2), op, om, "side stream")
+
+
+def test_resnet50_config_full_size(torch, oracle):
+    """161 tensors, 25.6M elements, 4 bit, bucket 1024, small tensors pass-through, W = 8."""
+    w = wl.resnet50()
+    full_cycle(torch, oracle, w, W=8, what="resnet50")
+
+
+def test_bert_base_config_full_size(torch, oracle):
+    """199 tensors, 109M elements, bits in {2,3,4,8}, bucket 512; reduce over W = 8 on a 1/8 share."""
+    w = wl.bert_base()
+    g = w.gradient(0)
+    gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    op, om = oracle.quantize(g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    assert_same_chunk(gp, gm, op, om, "bert_base quantize")
+    del g, gp, op
+    share_cycle(torch, oracle, w, rank=3, what="bert_base")
+
+
+def share_cycle(torch, oracle, w, rank, what):
+    """Reduce and requantize on one rank's share of a W-way scatter-reduce."""
+    first, sub_off, sub_bits = wl.share_subplan(w.offsets, w.bits, w.bucket, w.W, rank)
+    m = int(sub_off[-1])
+    chunks, metas = [], []
+    for peer in range(w.W):
+        g = w.gradient(peer, first, first + m)
+        op, om = oracle.quantize(g, sub_off, sub_bits, w.bucket, w.quant_seed(peer), w.dt)
+        chunks.append(op)
+        metas.append(om)
+    ref = oracle.dequant_reduce(chunks, metas, sub_off, sub_bits, w.bucket, w.dt)
+    got, total = gpu_reduce(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt)
+    assert_sum_parity(got, ref, f"{what} share reduce")
+    rp, rm = gpu_quantize(torch, total[:m], sub_off, sub_bits, w.bucket, 7, wl.F32, requant=True)
+    op, om = oracle.quantize(got, sub_off, sub_bits, w.bucket, 7, wl.F32)
+    assert_same_chunk(rp, rm, op, om, f"{what} share requantize")

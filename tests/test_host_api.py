@@ -1,0 +1,203 @@
+"""Host-side tests of libcgx.so: no kernel is launched, no GPU is needed.
+
+They cover the exported symbols, the argument checks of every entry point, the
+sizes of the packed stream / meta array (against the oracle's layout rules) and
+the tile table the kernels walk (paper Sec. 4.1: per-layer compression from the
+layer offsets of the fused buffer; Sec. 4.3: whole buckets).
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2111_08617_amd import binding as cgx
+from paper_2111_08617_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(cgx.LIB_PATH):
+        from paper_2111_08617_amd import build
+        build.build()
+    return cgx.lib()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "cgx.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(cgx_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(cgx.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    seen = {cgx.status_string(s) for s in range(0, -10, -1)}
+    assert len(seen) == 10 and "unknown status" not in seen
+    assert cgx.status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("name", ["single_1m", "resnet50", "bert_base", "gpt2_medium", "decoder_1p3b"])
+def test_sizes_match_the_oracle_layout(lib, oracle, name):
+    w = wl.WORKLOADS[name]()
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    assert cgx.cgx_sizes(plan) == oracle.sizes(w.offsets, w.bits, w.bucket, w.dt)
+
+
+def test_sizes_of_edge_plans(lib, oracle):
+    for dt in (wl.F32, wl.F16):
+        for bucket in (32, 64, 96, 1024, 8192):
+            w = wl.tiny_mixed(dt=dt, bucket=bucket)
+            plan = cgx.Plan(w.offsets, w.bits, bucket, dt)
+            assert cgx.cgx_sizes(plan) == oracle.sizes(w.offsets, w.bits, bucket, dt)
+    empty = cgx.Plan(np.zeros(1, np.int64), np.zeros(0, np.uint8), 128)
+    assert cgx.cgx_sizes(empty) == (0, 0)
+    only_empty_layers = cgx.Plan(np.zeros(4, np.int64), np.array([4, 0, 8], np.uint8), 128)
+    assert cgx.cgx_sizes(only_empty_layers) == (0, 0)
+
+
+def _status(fn, *args):
+    return fn(*args)
+
+
+def test_argument_errors_are_found_on_the_host(lib):
+    c = ctypes
+    off = np.array([0, 100, 300], np.int64)
+    bits = np.array([4, 0], np.uint8)
+    pb, mb = c.c_size_t(), c.c_size_t()
+
+    def sizes(n, L, o, b, bucket, dt=0):
+        return lib.cgx_sizes(n, L, o.ctypes.data if o is not None else None,
+                             b.ctypes.data if b is not None else None, bucket, dt, c.byref(pb), c.byref(mb))
+
+    assert sizes(300, 2, off, bits, 128) == 0
+    assert sizes(-1, 2, off, bits, 128) == -2
+    assert sizes(300, -1, off, bits, 128) == -2
+    assert sizes(301, 2, off, bits, 128) == -2                       # n != offsets[L]
+    assert sizes(300, 2, None, bits, 128) == -1
+    assert sizes(300, 2, off, None, 128) == -1
+    assert sizes(300, 2, np.array([1, 100, 300], np.int64), bits, 128) == -3
+    assert sizes(300, 2, np.array([0, 400, 300], np.int64), bits, 128) == -3
+    assert sizes(300, 2, off, np.array([9, 0], np.uint8), 128) == -4
+    for bad in (0, 16, 33, 100, 8192 + 32, -128):
+        assert sizes(300, 2, off, bits, bad) == -5
+    assert sizes(300, 2, off, bits, 128, 2) == -7
+    assert sizes(5, 0, off, bits, 128) == -2                         # no layers but n > 0
+
+    # the compute entry points reject bad arguments before touching the device
+    o, b = off.ctypes.data, bits.ctypes.data
+    buf = 0x1000                                                      # never dereferenced
+    assert lib.cgx_quantize(buf, 300, 2, o, b, 100, 0, 0, buf, buf, None) == -5
+    assert lib.cgx_quantize(None, 300, 2, o, b, 128, 0, 0, buf, buf, None) == -1
+    assert lib.cgx_quantize(buf, 300, 2, o, b, 128, 0, 0, None, buf, None) == -1
+    assert lib.cgx_quantize(buf, 300, 2, o, b, 128, 0, 0, buf, None, None) == -1
+    assert lib.cgx_quantize(buf + 4, 300, 2, o, b, 128, 0, 0, buf, buf, None) == -9
+    assert lib.cgx_quantize(buf, 300, 2, o, b, 128, 0, 0, buf + 8, buf, None) == -9
+    assert lib.cgx_quantize(buf, 300, 2, o, b, 128, 0, 3, buf, buf, None) == -7
+    assert lib.cgx_requantize(None, 300, 2, o, b, 128, 0, buf, buf, None) == -1
+    assert lib.cgx_requantize(buf, 299, 2, o, b, 128, 0, buf, buf, None) == -2
+    ptrs = (c.c_void_p * 2)(buf, buf)
+    nulls = (c.c_void_p * 2)(buf, None)
+    assert lib.cgx_dequant_reduce(ptrs, ptrs, 0, 300, 2, o, b, 128, 0, buf, None) == -6
+    assert lib.cgx_dequant_reduce(ptrs, ptrs, 65, 300, 2, o, b, 128, 0, buf, None) == -6
+    assert lib.cgx_dequant_reduce(None, ptrs, 2, 300, 2, o, b, 128, 0, buf, None) == -1
+    assert lib.cgx_dequant_reduce(nulls, ptrs, 2, 300, 2, o, b, 128, 0, buf, None) == -1
+    assert lib.cgx_dequant_reduce(ptrs, nulls, 2, 300, 2, o, b, 128, 0, buf, None) == -1
+    assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, None, None) == -1
+    assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, buf + 4, None) == -9
+    assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 48, 0, buf, None) == -5
+    # empty buffers are accepted and do nothing
+    z = np.zeros(1, np.int64)
+    assert lib.cgx_quantize(None, 0, 0, z.ctypes.data, None, 128, 0, 0, None, None, None) == 0
+    assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 0, 0, z.ctypes.data, None, 128, 0, None, None) == 0
+
+
+def layer_segments(w):
+    """(segment start, payload bytes, first bucket) per layer from the layout rules."""
+    seg, g, out = 0, 0, []
+    es = 2 if w.dt else 4
+    for l in range(w.L):
+        ln = int(w.offsets[l + 1] - w.offsets[l])
+        b = int(w.bits[l])
+        payload = ln * es if b == 0 else -(-ln * b // 8)
+        out.append((seg, payload, g))
+        if ln:
+            seg += (payload + 15) // 16 * 16
+            g += 0 if b == 0 else -(-ln // w.bucket)
+    return out
+
+
+@pytest.mark.parametrize("make", [
+    lambda: wl.tiny_mixed(), lambda: wl.tiny_mixed(dt=wl.F16, bucket=128), lambda: wl.tiny_mixed(bucket=96),
+    lambda: wl.tiny_mixed(bucket=4096), wl.resnet50, wl.bert_base, wl.gpt2_medium,
+])
+def test_tiles_cover_every_layer_exactly_once(lib, make):
+    w = make()
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    tiles = cgx.cgx_plan_tiles(plan)
+    segs = layer_segments(w)
+    es = 2 if w.dt else 4
+    order = np.argsort(tiles["elem0"], kind="stable")
+    assert np.array_equal(order, np.arange(tiles.size))               # tiles come in buffer order
+    starts, counts = tiles["elem0"], tiles["count"].astype(np.int64)
+    assert (counts > 0).all()
+    covered = np.zeros(w.n, np.int8)
+    for t in tiles:
+        covered[t["elem0"]:t["elem0"] + t["count"]] += 1
+    assert (covered == 1).all()
+    layer_of = np.searchsorted(w.offsets, tiles["elem0"], side="right") - 1
+    for t, l in zip(tiles, layer_of):
+        while w.offsets[l + 1] == w.offsets[l]:                       # skip empty layers at the same offset
+            l += 1
+        a, e = int(w.offsets[l]), int(w.offsets[l + 1])
+        assert a <= t["elem0"] and t["elem0"] + t["count"] <= e       # never crosses a layer
+        b = int(w.bits[l])
+        kind = (int(t["info"]) >> 4) & 15
+        assert int(t["info"]) & 15 == b
+        seg, payload, g0 = segs[l]
+        j = int(t["elem0"]) - a
+        last = t["elem0"] + t["count"] == e
+        assert int(t["pad"]) == ((-payload) % 16 if last else 0)
+        if b == 0:
+            assert kind in (2, 3)
+            assert t["packed_off"] == seg + j * es
+            if kind == 3:
+                assert t["elem0"] % 8 == 0
+        else:
+            assert kind in (0, 1)
+            assert j % w.bucket == 0                                  # tiles start on a bucket
+            assert last or t["count"] % w.bucket == 0                 # and hold whole buckets
+            assert t["packed_off"] == seg + j * b // 8
+            assert t["bucket0"] == g0 + j // w.bucket
+            if kind == 1:
+                assert t["count"] % 2048 == 0 and t["elem0"] % 8 == 0
+                assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= 2048
+                assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket // 32))
+
+
+def test_large_plans_use_the_vectorised_path(lib):
+    for make in (wl.resnet50, wl.decoder_1p3b):
+        w = make()
+        plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+        tiles = cgx.cgx_plan_tiles(plan)
+        kind = (tiles["info"] >> 4) & 15
+        fast = tiles["count"][(kind == 1) | (kind == 3)].astype(np.int64).sum()
+        assert fast / w.n > 0.999
+
+
+def test_tiles_do_not_straddle_a_generator_key_block(lib):
+    """Vectorised tiles lie inside one 2^33-element block (the generator's key is
+    uniform there); a tile that would straddle is handed to the generic path."""
+    n = (1 << 33) + 8192
+    plan = cgx.Plan(np.array([0, n], np.int64), np.array([2], np.uint8), 1024)
+    old = os.environ.get("CGX_CHUNKS_PER_TILE")
+    tiles = cgx.cgx_plan_tiles(plan)
+    lo, hi = tiles["elem0"] >> 33, (tiles["elem0"] + tiles["count"].astype(np.int64) - 1) >> 33
+    kind = (tiles["info"] >> 4) & 15
+    assert ((lo == hi) | (kind == 0)).all()
+    assert tiles["count"].astype(np.int64).sum() == n
+    assert old == os.environ.get("CGX_CHUNKS_PER_TILE")
