@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the CGX hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: cgx_quantize of
+a fused gradient buffer, cgx_dequant_reduce over W compressed chunks, and
+cgx_requantize of the sum.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line (see --help for the knobs).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(tiles, bucket, elem_bytes, W):
+    """Bytes the method itself must move per launch, evaluated from the plan:
+    quantize reads S and writes b/8 per element plus 8 per bucket (pass-through:
+    S in, S out); dequant-reduce reads W times the packed stream and meta and
+    writes 4 per element."""
+    import numpy as np
+    bits = (tiles["info"] & 15).astype(np.int64)
+    count = tiles["count"].astype(np.int64)
+    q = bits > 0
+    payload = np.where(q, (count * bits + 7) // 8, count * elem_bytes).sum()
+    buckets = np.where(q, (count + bucket - 1) // bucket, 0).sum()
+    n = int(count.sum())
+    packed_meta = int(payload + 8 * buckets)
+    return {
+        "quantize": n * elem_bytes + packed_meta,
+        "dequant_reduce": W * packed_meta + 4 * n,
+        "requantize": 4 * n + int(np.where(q, (count * bits + 7) // 8, count * 4).sum() + 8 * buckets),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet50",
+                    choices=["single_1m", "resnet50", "bert_base", "gpt2_medium", "decoder_1p3b"])
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="distinct buffer sets cycled through so that launches do not re-hit the 256 MB "
+                         "memory-side cache (0 = enough for 1 GB of traffic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the W peers of the reduce step are W compressed "
+                 "chunks resident in HBM); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2111_08617_amd import binding as cgx
+    from paper_2111_08617_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    cgx.lib()
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS[args.workload]()
+    W = w.W
+    S = 2 if w.dt == wl.F16 else 4
+    tdtype = torch.float16 if w.dt == wl.F16 else torch.float32
+
+    # the reduce step runs on one rank's share when the buffer is large (1/W of it), else on the full buffer
+    on_share = args.workload in ("gpt2_medium", "decoder_1p3b", "bert_base")
+    if on_share:
+        first, r_off, r_bits = wl.share_subplan(w.offsets, w.bits, w.bucket, W, W // 2)
+    else:
+        first, r_off, r_bits = 0, w.offsets, w.bits
+    q_plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    r_plan = cgx.Plan(r_off, r_bits, w.bucket, w.dt)         # reduce: chunks in the storage type's layout
+    rq_plan = cgx.Plan(r_off, r_bits, w.bucket, wl.F32)       # requantize: binary32 sum in
+    m = r_plan.n
+    q_pb, q_mb = cgx.cgx_sizes(q_plan)
+    r_pb, r_mb = cgx.cgx_sizes(r_plan)
+    rq_pb, rq_mb = cgx.cgx_sizes(rq_plan)
+
+    q_alg = algorithmic_bytes(cgx.cgx_plan_tiles(q_plan), w.bucket, S, W)["quantize"]
+    r_algs = algorithmic_bytes(cgx.cgx_plan_tiles(r_plan), w.bucket, S, W)
+    alg = {"quantize": q_alg, "dequant_reduce": r_algs["dequant_reduce"], "requantize": r_algs["requantize"]}
+
+    traffic = q_alg + alg["dequant_reduce"] + alg["requantize"]
+    R = args.rotate if args.rotate > 0 else max(2, min(8, int(np.ceil(1.0e9 / traffic))))
+
+    # ---- inputs, resident in HBM before timing
+    t0 = time.time()
+    host_grad = w.gradient(0, threads=16)
+    grads = [torch.from_numpy(host_grad).to(dev)]
+    for _ in range(1, R):
+        grads.append(grads[0].clone())
+    share_grads = [torch.from_numpy(w.gradient(p, first, first + m, threads=16)).to(dev) for p in range(W)]
+    chunk_sets = []
+    for r in range(R):
+        ps, ms = [], []
+        for p in range(W):
+            packed = torch.empty(r_pb, dtype=torch.uint8, device=dev)
+            meta = torch.empty(max(r_mb // 4, 4), dtype=torch.float32, device=dev)
+            cgx.cgx_quantize(share_grads[p], r_plan, w.quant_seed(p) + 1000 * r, packed, meta)
+            ps.append(packed)
+            ms.append(meta)
+        chunk_sets.append((ps, ms))
+    del share_grads
+    q_out = [(torch.empty(q_pb, dtype=torch.uint8, device=dev),
+              torch.empty(max(q_mb // 4, 4), dtype=torch.float32, device=dev)) for _ in range(R)]
+    sums = [torch.empty(m, dtype=torch.float32, device=dev) for _ in range(R)]
+    rq_out = [(torch.empty(rq_pb, dtype=torch.uint8, device=dev),
+               torch.empty(max(rq_mb // 4, 4), dtype=torch.float32, device=dev)) for _ in range(R)]
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step(i, ev=None):
+        r = i % R
+        if ev:
+            ev[0].record()
+        cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1])
+        if ev:
+            ev[1].record()
+        cgx.cgx_dequant_reduce(chunk_sets[r][0], chunk_sets[r][1], r_plan, sums[r])
+        if ev:
+            ev[2].record()
+        cgx.cgx_requantize(sums[r], rq_plan, 29 + i, rq_out[r][0], rq_out[r][1])
+        if ev:
+            ev[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    names = ["quantize", "dequant_reduce", "requantize"]
+    kern_ms = {k: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)]))
+               for j, k in enumerate(names)}
+    raw_bytes = {"quantize": w.n * S, "dequant_reduce": 4 * m, "requantize": 4 * m}
+    kernels = {}
+    for k in names:
+        kernels[k] = {
+            "ms": round(kern_ms[k], 5),
+            "raw_gradient_GBps": round(raw_bytes[k] / kern_ms[k] / 1e6, 1),
+            "algorithmic_bytes": int(alg[k]),
+            "algorithmic_GBps": round(alg[k] / kern_ms[k] / 1e6, 1),
+            "hbm_frac": round(alg[k] / kern_ms[k] / 1e6 / HBM_PEAK_GBPS, 4),
+        }
+    dominant = max(names, key=lambda k: kern_ms[k])
+    achieved = alg[dominant] / kern_ms[dominant] / 1e6
+    value = sum(raw_bytes.values()) / (ms_per_step * 1e6)
+
+    result = {
+        "metric": "GB/s of fp32 gradient quantized and dequant-reduced (W=8); % of HBM peak",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16" if w.dt == wl.F16 else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name,
+            "description": w.description,
+            "elements": w.n,
+            "reduce_elements": m,
+            "reduce_on": "1/%d share of the buffer" % W if on_share else "full buffer",
+            "W": W,
+            "bucket": w.bucket,
+            "step": "cgx_quantize(full buffer) + cgx_dequant_reduce(W chunks) + cgx_requantize(sum)",
+            "value_definition": "raw gradient bytes entering quantize + leaving dequant_reduce + entering "
+                                "requantize, per second of step wall time",
+            "buffer_sets_rotated": R,
+        },
+        "kernels": kernels,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": dominant,
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+        },
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = oracle.get_max_threads()
+        # bounded sample: whole step for small workloads, else the first tensors up to ~64M elements
+        cap = 64_000_000
+        L_s = int(np.searchsorted(w.offsets, cap, side="right")) - 1 if w.n > cap else w.L
+        L_s = max(L_s, 1)
+        off_s, bits_s = w.offsets[:L_s + 1], w.bits[:L_s]
+        n_s = int(off_s[-1])
+        g_s = host_grad[:n_s]
+        t0 = time.perf_counter()
+        cp, cm = oracle.quantize(g_s, off_s, bits_s, w.bucket, 17, w.dt)
+        t_q = time.perf_counter() - t0
+        chunks = [cp] * W
+        metas = [cm] * W
+        t0 = time.perf_counter()
+        s32 = oracle.dequant_reduce(chunks, metas, off_s, bits_s, w.bucket, w.dt, want=("sum32",))["sum32"]
+        t_r = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.quantize(s32, off_s, bits_s, w.bucket, 29, wl.F32)
+        t_rq = time.perf_counter() - t0
+        cpu_bytes = n_s * S + 4 * n_s + 4 * n_s
+        result["cpu_baseline"] = {
+            "value": round(cpu_bytes / (t_q + t_r + t_rq) / 1e9, 3),
+            "unit": "GB/s",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": "one step (quantize + dequant_reduce W=%d + requantize) on the first %d tensors / %d "
+                      "elements of %s, OpenMP over buckets" % (W, L_s, n_s, w.name),
+            "seconds": {"quantize": round(t_q, 3), "dequant_reduce": round(t_r, 3), "requantize": round(t_rq, 3)},
+        }
+    else:
+        result["cpu_baseline"] = None
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,6 +1,8 @@
 // Plan validation, sizes and tile table (host only; no HIP calls here).
 #include "cgx_plan.h"
 
+#include <algorithm>
+
 namespace cgx {
 
 static inline uint64_t round_up16(uint64_t v) { return (v + 15u) & ~uint64_t(15); }
@@ -68,8 +70,8 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     if (chunks_per_tile < 1) chunks_per_tile = 1;
     const int S = elem_size(dt);
     const bool fast_bucket = is_pow2(bucket) && bucket <= kChunk;
-    // 64 lanes x 4 groups x 8 elements = kChunk, so a bucket spans bucket/32 lanes
-    const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(bucket / 32)) : 0u;
+    // 64 lanes x kGroups groups x 8 elements = kChunk, so a bucket spans bucket / (8 * kGroups) lanes
+    const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(bucket / (8 * kGroups))) : 0u;
     uint64_t seg = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         const int64_t first = off[l], len = off[l + 1] - off[l];
@@ -125,6 +127,10 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
         seg += round_up16(payload);
         bucket0 += buckets;
     }
+    // Waves take tiles in table order.  The generic and pass-through tiles cost several
+    // dependent memory round trips each, so they go first and overlap with the stream
+    // of vectorised tiles instead of forming the tail of the launch.
+    std::stable_partition(tiles.begin(), tiles.end(), [](const Tile &t) { return tile_kind(t) != kQuantFast; });
 }
 
 }  // namespace cgx

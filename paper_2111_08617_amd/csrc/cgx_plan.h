@@ -21,9 +21,13 @@
 
 namespace cgx {
 
-// Elements a wavefront handles per pass of the fast path: 64 lanes x 4 groups
-// of 8 consecutive elements.  A fast tile is a whole number of chunks.
-constexpr int kChunk = 2048;
+// Elements a wavefront handles per pass of the fast path: 64 lanes x kGroups
+// groups of 8 consecutive elements.  A fast tile is a whole number of chunks.
+#ifndef CGX_GROUPS
+#define CGX_GROUPS 4
+#endif
+constexpr int kGroups = CGX_GROUPS;
+constexpr int kChunk = 64 * 8 * kGroups;
 // Elements per pass-through tile.
 constexpr int kCopyTile = 8192;
 

@@ -16,6 +16,7 @@ from paper_2111_08617_amd import binding as cgx
 from paper_2111_08617_amd import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CHUNK = 2048            # elements a wavefront takes per pass of the vectorised path
 
 
 @pytest.fixture(scope="module")
@@ -141,18 +142,19 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
     tiles = cgx.cgx_plan_tiles(plan)
     segs = layer_segments(w)
     es = 2 if w.dt else 4
-    order = np.argsort(tiles["elem0"], kind="stable")
-    assert np.array_equal(order, np.arange(tiles.size))               # tiles come in buffer order
-    starts, counts = tiles["elem0"], tiles["count"].astype(np.int64)
+    # generic and pass-through tiles first, then the vectorised ones; buffer order within each class
+    vectorised = ((tiles["info"] >> 4) & 15) == 1
+    assert not vectorised[:int((~vectorised).sum())].any()
+    for cls in (tiles[~vectorised], tiles[vectorised]):
+        assert (np.diff(cls["elem0"]) > 0).all()
+    counts = tiles["count"].astype(np.int64)
     assert (counts > 0).all()
     covered = np.zeros(w.n, np.int8)
     for t in tiles:
         covered[t["elem0"]:t["elem0"] + t["count"]] += 1
     assert (covered == 1).all()
-    layer_of = np.searchsorted(w.offsets, tiles["elem0"], side="right") - 1
+    layer_of = np.searchsorted(w.offsets, tiles["elem0"], side="right") - 1     # last layer starting at or before
     for t, l in zip(tiles, layer_of):
-        while w.offsets[l + 1] == w.offsets[l]:                       # skip empty layers at the same offset
-            l += 1
         a, e = int(w.offsets[l]), int(w.offsets[l + 1])
         assert a <= t["elem0"] and t["elem0"] + t["count"] <= e       # never crosses a layer
         b = int(w.bits[l])
@@ -174,9 +176,9 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
             assert t["packed_off"] == seg + j * b // 8
             assert t["bucket0"] == g0 + j // w.bucket
             if kind == 1:
-                assert t["count"] % 2048 == 0 and t["elem0"] % 8 == 0
-                assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= 2048
-                assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket // 32))
+                assert t["count"] % CHUNK == 0 and t["elem0"] % 8 == 0
+                assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= CHUNK
+                assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket * 64 // CHUNK))
 
 
 def test_large_plans_use_the_vectorised_path(lib):
