@@ -39,6 +39,21 @@ def algorithmic_bytes(tiles, bucket, elem_bytes, W):
     }
 
 
+def read_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary of this workload
+    (profiles/hbm_traffic_<workload>.txt: lines `kernel fetch_bytes write_bytes`), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == kernel:
+                    return int(float(parts[1]) + float(parts[2]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__)
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +65,10 @@ def main():
                     help="distinct buffer sets cycled through so that launches do not re-hit the 256 MB "
                          "memory-side cache (0 = enough for 1 GB of traffic)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB three times: "
+                         "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its known size gives the factor "
+                         "that scales the counters to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the W peers of the reduce step are W compressed "
@@ -143,6 +162,15 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    if args.calibration_copy:
+        # an elementwise kernel that reads 1 GiB and writes 1 GiB (grid unlike any cgx launch)
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     names = ["quantize", "dequant_reduce", "requantize"]
     kern_ms = {k: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)]))
                for j, k in enumerate(names)}
@@ -158,6 +186,7 @@ def main():
         }
     dominant = max(names, key=lambda k: kern_ms[k])
     achieved = alg[dominant] / kern_ms[dominant] / 1e6
+    traffic = read_traffic(w.name, dominant)
     value = sum(raw_bytes.values()) / (ms_per_step * 1e6)
 
     result = {
@@ -194,7 +223,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": traffic,
         },
         "setup_s": round(setup_s, 1),
     }

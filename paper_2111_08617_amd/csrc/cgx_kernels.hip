@@ -1,8 +1,8 @@
 // gfx950 kernels: bucketed stochastic quantization of a fused gradient buffer
 // and dequantize-and-reduce of W compressed chunks.
 //
-// One wavefront (64 lanes) owns one tile of the plan at a time.  In the fast
-// path a wave takes a chunk of 2048 elements per pass: each lane holds 4 groups
+// One wavefront (64 lanes) owns one tile of the plan.  In the vectorised path a
+// wave takes a chunk of kChunk = 2048 elements per pass: each lane holds 4 groups
 // of 8 consecutive elements, all of the same bucket (a bucket of B elements
 // spans B/32 neighbouring lanes), so
 //   - the bucket minimum / maximum is a lane-local reduction over 32 values
@@ -12,7 +12,10 @@
 //   - 8 consecutive codes pack into exactly b bytes, so no code straddles lanes.
 // The gradient is read from HBM once; a bucket lives in registers between the
 // reduction and the rounding (paper Sec. 4.3: parallel bucket norm computation,
-// vectorized loads and stores).
+// vectorized loads and stores).  All streaming traffic is non-temporal and every
+// store instruction writes whole lines: packed codes and sums are staged in LDS
+// and leave lane-contiguous; the reduce fetches each peer's packed bytes straight
+// into LDS (global_load_lds_dwordx4).
 //
 // The arithmetic of the code decision is binary32 without contraction and must
 // stay as written: the packed output is compared bit for bit with a CPU

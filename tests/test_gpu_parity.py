@@ -222,3 +222,28 @@ def share_cycle(torch, oracle, w, rank, what):
     rp, rm = gpu_quantize(torch, total[:m], sub_off, sub_bits, w.bucket, 7, wl.F32, requant=True)
     op, om = oracle.quantize(got, sub_off, sub_bits, w.bucket, 7, wl.F32)
     assert_same_chunk(rp, rm, op, om, f"{what} share requantize")
+
+
+def test_gpt2_medium_config_full_size(torch, oracle):
+    """292 tensors, 355M elements in binary16 storage, 20% exact zeros, 4 bit, bucket 128:
+    quantize the full buffer; reduce over W = 8 and requantize on one rank's 1/8 share."""
+    w = wl.gpt2_medium()
+    g = w.gradient(0, threads=16)
+    gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    op, om = oracle.quantize(g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    assert_same_chunk(gp, gm, op, om, "gpt2_medium quantize")
+    del g, gp, op
+    share_cycle(torch, oracle, w, rank=5, what="gpt2_medium")
+
+
+def test_decoder_1p3b_config_full_size(torch, oracle):
+    """292 tensors, 1.316G elements, Laplace values with outliers, bits in {2,4,8}, bucket 1024:
+    quantize the full buffer (the launch bench.py times); reduce over W = 8 and requantize on
+    one rank's 1/8 share."""
+    w = wl.decoder_1p3b()
+    g = w.gradient(0, threads=16)
+    gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    op, om = oracle.quantize(g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    assert_same_chunk(gp, gm, op, om, "decoder_1p3b quantize")
+    del g, gp, op
+    share_cycle(torch, oracle, w, rank=4, what="decoder_1p3b")
