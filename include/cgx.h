@@ -67,6 +67,7 @@ typedef enum {
 } cgx_dtype;
 
 #define CGX_MAX_PEERS 64
+#define CGX_MAX_FUSED_PEERS 16   /* cgx_dequant_reduce_requantize takes at most this many chunks */
 
 /*
  * Sizes of the packed stream and of the meta array for a plan (pure host
@@ -117,6 +118,22 @@ int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32
 int cgx_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
                    const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed,
                    void *packed, void *meta, void *stream);
+
+/*
+ * cgx_dequant_reduce followed by cgx_requantize in one pass: the binary32 sums stay in
+ * registers and never reach memory (paper Sec. 4.1, Scatter-Reduce-Allgather: a rank
+ * aggregates its chunk and compresses the aggregate again before broadcasting it).  The
+ * output is byte for byte what cgx_dequant_reduce into a buffer and cgx_requantize of that
+ * buffer with the same seed would give: packed_out has the layout of the plan with dt =
+ * CGX_F32 (pass-through layers hold the binary32 sums), meta_out its meta.
+ *   packed, meta          host arrays of W device pointers, chunks of the plan with storage dt
+ *   packed_out, meta_out  device, sizes from cgx_sizes(..., CGX_F32, ...)
+ * W must be in [1, CGX_MAX_FUSED_PEERS] (CGX_ERR_PEERS otherwise).
+ */
+int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W,
+                                  int64_t n, int32_t L, const int64_t *layer_offsets,
+                                  const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
+                                  uint64_t seed, void *packed_out, void *meta_out, void *stream);
 
 /*
  * Diagnostic: the table of wavefront work items ("tiles") the kernels walk for

@@ -18,8 +18,10 @@ LIB_PATH = os.path.join(HERE, "libcgx.so")
 
 F32, F16 = 0, 1
 MAX_PEERS = 64
+MAX_FUSED_PEERS = 16
 
-EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_requantize", "cgx_plan_tiles",
+EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_requantize",
+           "cgx_dequant_reduce_requantize", "cgx_plan_tiles",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -49,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.cgx_quantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_requantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + [c.c_int, c.c_void_p, c.c_void_p]
+        L.cgx_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
+            [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_status_string.restype = c.c_char_p
         L.cgx_status_string.argtypes = [c.c_int]
@@ -133,6 +137,20 @@ def cgx_dequant_reduce(packed: Sequence, meta: Sequence, plan: Plan, total, stre
     mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
     _check(lib().cgx_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
            "cgx_dequant_reduce")
+
+
+def cgx_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, seed: int, packed_out, meta_out,
+                                  stream=None) -> None:
+    """packed / meta: W <= 16 device tensors each (chunks of `plan`); packed_out / meta_out: device
+    tensors sized by cgx_sizes of the same plan with dt = F32."""
+    W = len(packed)
+    if len(meta) != W:
+        raise ValueError("as many meta tensors as packed tensors")
+    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
+    _check(lib().cgx_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
+                                               packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
+           "cgx_dequant_reduce_requantize")
 
 
 def cgx_shutdown() -> None:

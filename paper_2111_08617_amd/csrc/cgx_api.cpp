@@ -173,6 +173,39 @@ int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32
     return CGX_OK;
 }
 
+int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                                  int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                  int32_t bucket, cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
+                                  void *stream)
+{
+    int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (rc != CGX_OK) return rc;
+    if (W < 1 || W > CGX_MAX_FUSED_PEERS) return CGX_ERR_PEERS;
+    if (n == 0) return CGX_OK;
+    const cgx::PlanShape shape = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (!packed || !meta || !packed_out || (shape.meta_bytes && !meta_out)) return CGX_ERR_NULL;
+    for (int w = 0; w < W; w++) {
+        if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
+        if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
+    }
+    if (misaligned(packed_out) || misaligned(meta_out)) return CGX_ERR_ALIGN;
+    const CachedPlan *in = nullptr, *out = nullptr;
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, int(dt), &in);
+    if (rc != CGX_OK) return rc;
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, &out);
+    if (rc != CGX_OK) return rc;
+    if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
+    cgx::PeerPtrs peers{};
+    for (int i = 0; i < W; i++) {
+        peers.packed[i] = static_cast<const uint8_t *>(packed[i]);
+        peers.meta[i] = static_cast<const float2 *>(meta[i]);
+    }
+    const hipError_t e = cgx::launch_dequant_reduce_requantize(peers, W, int(dt), in->d_tiles, out->d_tiles,
+                                                               in->n_tiles, bucket, seed, packed_out, meta_out,
+                                                               launch_config(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                    int32_t bucket, cgx_dtype dt, void *tiles_out, int64_t capacity, int64_t *n_tiles)
 {

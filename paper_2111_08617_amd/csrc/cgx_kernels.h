@@ -29,4 +29,12 @@ hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Til
                                  int32_t bucket, bool accumulate, float *sum, const LaunchConfig &cfg,
                                  hipStream_t stream);
 
+// packed_out / meta_out = quantize(deq_0 + ... + deq_{W-1}) without the binary32 sum ever
+// reaching memory; tiles_in describes the chunks (storage type dt), tiles_out the output
+// (binary32 pass-through); W <= kPeersPerLaunch.
+hipError_t launch_dequant_reduce_requantize(const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
+                                            const Tile *tiles_out, int64_t n_tiles, int32_t bucket,
+                                            uint64_t seed, void *packed_out, void *meta_out,
+                                            const LaunchConfig &cfg, hipStream_t stream);
+
 }  // namespace cgx

@@ -1,5 +1,5 @@
-// gfx950 kernels: bucketed stochastic quantization of a fused gradient buffer
-// and dequantize-and-reduce of W compressed chunks.
+// gfx950 kernels: bucketed stochastic quantization of a fused gradient buffer,
+// dequantize-and-reduce of W compressed chunks, and the two fused into one pass.
 //
 // One wavefront (64 lanes) owns one tile of the plan.  In the vectorised path a
 // wave takes a chunk of kChunk = 2048 elements per pass: each lane holds 4 groups
@@ -30,11 +30,9 @@ namespace cgx {
 namespace {
 
 constexpr int kWave = 64;
-#ifndef CGX_WAVES_PER_BLOCK
-#define CGX_WAVES_PER_BLOCK 4
-#endif
-constexpr int kWavesPerBlock = CGX_WAVES_PER_BLOCK;
+constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int G = kGroups;               // groups of 8 elements per lane and chunk
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
@@ -60,7 +58,7 @@ __device__ __forceinline__ uint32_t rng_key(uint32_t seed_lo, uint32_t seed_hi, 
     return mix32(seed_lo ^ mix32(seed_hi ^ 0x9e3779b9U ^ pair_hi));
 }
 
-// 16-bit draw of element i (slow path: key recomputed per element).
+// 16-bit draw of element i (generic path: key recomputed per element).
 __device__ __forceinline__ uint32_t draw16(uint32_t seed_lo, uint32_t seed_hi, uint64_t i)
 {
     const uint64_t pair = i >> 1;
@@ -149,63 +147,28 @@ __device__ __forceinline__ uint32_t code_of(float x, const Scale &s, uint32_t dr
     return q < levels ? q : levels;
 }
 
-// ---------------------------------------------------------------- element access
+// ---------------------------------------------------------------- memory helpers
+
+// Streaming data is touched once: non-temporal loads and stores keep it from
+// displacing anything and (measured) raise the sustained HBM rate, provided each
+// instruction covers whole lines.
+template <typename T>
+__device__ __forceinline__ T stream_load(const T *p)
+{
+    return __builtin_nontemporal_load(p);
+}
+
+template <typename T>
+__device__ __forceinline__ void stream_store(T *p, T v)
+{
+    __builtin_nontemporal_store(v, p);
+}
 
 template <int DT>
 __device__ __forceinline__ float load_elem(const void *buf, int64_t i)
 {
     if (DT == CGX_F16) return float(reinterpret_cast<const _Float16 *>(buf)[i]);
     return reinterpret_cast<const float *>(buf)[i];
-}
-
-#ifndef CGX_NT_LOAD
-#define CGX_NT_LOAD 1
-#endif
-#ifndef CGX_NT_STORE
-#define CGX_NT_STORE 1
-#endif
-#ifndef CGX_PIPELINE
-#define CGX_PIPELINE 0
-#endif
-
-template <typename T>
-__device__ __forceinline__ T stream_load(const T *p)
-{
-#if CGX_NT_LOAD
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
-}
-
-template <typename T>
-__device__ __forceinline__ void stream_store(T *p, T v)
-{
-#if CGX_NT_STORE
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
-}
-
-#ifndef CGX_STAGE_OUT
-#define CGX_STAGE_OUT 1
-#endif
-
-// Orders this wave's LDS writes before its later LDS reads (a wave's LDS operations
-// execute in order; this only keeps the compiler from moving them).
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Streams `vecs` 16-byte vectors from the wave's LDS staging area to global memory,
-// lane-contiguous (each store instruction writes 1 KB of consecutive addresses).
-__device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, int vecs, int lane)
-{
-    for (int v = lane; v < vecs; v += kWave) stream_store(dst + v, stage[v]);
 }
 
 // 8 consecutive elements starting at element e (16-byte aligned address), as stored.
@@ -251,23 +214,38 @@ __device__ __forceinline__ void load8(const void *buf, int64_t e, float (&x)[8])
     raw.widen(x);
 }
 
-// b bytes holding 8 codes, to a b-byte aligned address.
-template <int BITS>
-__device__ __forceinline__ void store_codes(uint8_t *p, uint64_t acc)
+// Orders this wave's LDS writes before its later LDS reads (a wave's LDS operations
+// execute in order; this only keeps the compiler from moving them).
+__device__ __forceinline__ void wave_lds_fence()
 {
-    if (BITS == 8) {
-        stream_store(reinterpret_cast<uint64_t *>(p), acc);
-    } else if (BITS == 4) {
-        stream_store(reinterpret_cast<uint32_t *>(p), uint32_t(acc));
-    } else if (BITS == 2) {
-        stream_store(reinterpret_cast<uint16_t *>(p), uint16_t(acc));
-    } else {
-#pragma unroll
-        for (int k = 0; k < BITS; k++) p[k] = uint8_t(acc >> (8 * k));
-    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Same, into the LDS staging area (plain stores).
+// Streams `vecs` 16-byte vectors from the wave's LDS staging area to global memory,
+// lane-contiguous (each store instruction writes 1 KB of consecutive addresses).
+__device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, int vecs, int lane)
+{
+    for (int v = lane; v < vecs; v += kWave) stream_store(dst + v, stage[v]);
+}
+
+// One 16-byte vector per lane from global memory straight into LDS, without passing
+// through registers: lane l's vector lands at lds_base + 16 * l (lds_base is wave-uniform).
+__device__ __forceinline__ void load_to_lds16(const uint4v *gptr, uint4v *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 2 /* nt */);
+}
+
+// Waits until every outstanding vector-memory operation of this wave has completed
+// (s_waitcnt vmcnt(0); the export and LDS counters are left alone).
+__device__ __forceinline__ void wait_vector_memory()
+{
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+}
+
+// b bytes holding 8 codes, into / out of the LDS staging area (b-byte aligned).
 template <int BITS>
 __device__ __forceinline__ void stage_codes(uint8_t *p, uint64_t acc)
 {
@@ -284,117 +262,130 @@ __device__ __forceinline__ void stage_codes(uint8_t *p, uint64_t acc)
 }
 
 template <int BITS>
-__device__ __forceinline__ uint64_t load_codes(const uint8_t *p)
+__device__ __forceinline__ uint64_t staged_codes(const uint8_t *p)
 {
-    if (BITS == 8) return stream_load(reinterpret_cast<const uint64_t *>(p));
-    if (BITS == 4) return stream_load(reinterpret_cast<const uint32_t *>(p));
-    if (BITS == 2) return stream_load(reinterpret_cast<const uint16_t *>(p));
+    if (BITS == 8) return *reinterpret_cast<const uint64_t *>(p);
+    if (BITS == 4) return *reinterpret_cast<const uint32_t *>(p);
+    if (BITS == 2) return *reinterpret_cast<const uint16_t *>(p);
     uint64_t acc = 0;
 #pragma unroll
     for (int k = 0; k < BITS; k++) acc |= uint64_t(p[k]) << (8 * k);
     return acc;
 }
 
+// Calls f(w0, std::integral_constant<int, WB>) for consecutive blocks of at most MAXB
+// (8, 4, 2, 1) peers covering 0..W-1 in order, so that a block's loads can be issued together.
+template <int MAXB, typename F>
+__device__ __forceinline__ void for_peer_blocks(int W, F f)
+{
+    int w = 0;
+    if (MAXB >= 8)
+        for (; w + 8 <= W; w += 8) f(w, std::integral_constant<int, 8>());
+    if (MAXB >= 4)
+        for (; w + 4 <= W; w += 4) f(w, std::integral_constant<int, 4>());
+    if (MAXB >= 2)
+        for (; w + 2 <= W; w += 2) f(w, std::integral_constant<int, 2>());
+    for (; w < W; w++) f(w, std::integral_constant<int, 1>());
+}
+
+// Where a lane's groups sit inside a chunk of the vectorised path.
+struct LaneMap {
+    int lg;          // log2(lanes per bucket)
+    int bi;          // bucket of this lane within the chunk
+    int lp;          // lane within the bucket
+    int row;         // elements between a lane's groups = bucket / G
+    int e_lane;      // first element of the lane's group 0, relative to the chunk
+    __device__ __forceinline__ LaneMap(const Tile &tile, int bucket, int lane)
+    {
+        lg = int(tile_lpb_log2(tile));
+        bi = lane >> lg;
+        lp = lane & ((1 << lg) - 1);
+        row = 8 << lg;
+        e_lane = bi * bucket + lp * 8;
+    }
+    __device__ __forceinline__ int group(int r) const { return e_lane + r * row; }
+};
+
 // ---------------------------------------------------------------- quantize
+
+// One chunk held in registers (x) -> meta of its buckets and its packed codes.
+// first = buffer index of the chunk's first element; key = generator key of the tile.
+template <int BITS>
+__device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const LaneMap &map, int lane, int64_t first,
+                                               uint32_t key, float2 *__restrict__ meta_chunk,
+                                               uint8_t *__restrict__ out, uint4v *stage)
+{
+    constexpr uint32_t kLevels = (1u << BITS) - 1u;
+    float mn = x[0][0], mx = x[0][0];
+#pragma unroll
+    for (int r = 0; r < G; r++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            mn = __builtin_fminf(mn, x[r][j]);
+            mx = __builtin_fmaxf(mx, x[r][j]);
+        }
+    group_minmax(mn, mx, map.lg, lane);
+    const Scale s = bucket_scale(mn, mx, BITS);
+    if (map.lp == 0) meta_chunk[map.bi] = make_float2(s.unit, s.mn);
+
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const uint32_t pair0 = uint32_t(uint64_t(first + map.group(r)) >> 1);
+        uint64_t acc = 0;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const uint32_t w = mix32((pair0 + k) ^ key);
+            const uint64_t q0 = code_of(x[r][2 * k], s, w & 0xffffU, kLevels);
+            const uint64_t q1 = code_of(x[r][2 * k + 1], s, w >> 16, kLevels);
+            acc |= q0 << (2 * k * BITS);
+            acc |= q1 << ((2 * k + 1) * BITS);
+        }
+        stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (map.group(r) >> 3) * BITS, acc);
+    }
+    // the chunk's codes leave as whole 16-byte vectors, consecutive across lanes
+    wave_lds_fence();
+    flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
+    wave_lds_fence();
+}
 
 template <int DT, int BITS>
 __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uint8_t *__restrict__ packed,
                                               float2 *__restrict__ meta, const Tile &tile, int bucket,
                                               uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
 {
-    constexpr uint32_t kLevels = (1u << BITS) - 1u;
-    constexpr int G = kGroups;
-    const int lg = int(tile_lpb_log2(tile));
-    const int bi = lane >> lg;                       // bucket of this lane within the chunk
-    const int lp = lane & ((1 << lg) - 1);           // lane within the bucket
-    const int row = 8 << lg;                         // elements between a lane's groups = bucket / G
-    const int e_lane = bi * bucket + lp * 8;
+    const LaneMap map(tile, bucket, lane);
     const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
     const int chunks = int(tile.count / kChunk);
     const int buckets_per_chunk = kChunk / bucket;
-
-    Raw8<DT> raw[G];
-#pragma unroll
-    for (int r = 0; r < G; r++) raw[r].load(grad, tile.elem0 + e_lane + r * row);
-
     for (int c = 0; c < chunks; c++) {
-        const int64_t e0 = tile.elem0 + int64_t(c) * kChunk + e_lane;
+        const int64_t first = tile.elem0 + int64_t(c) * kChunk;
         float x[G][8];
 #pragma unroll
-        for (int r = 0; r < G; r++) raw[r].widen(x[r]);
-#if CGX_PIPELINE
-        if (c + 1 < chunks) {                        // next chunk's loads fly while this one is processed
-#pragma unroll
-            for (int r = 0; r < G; r++) raw[r].load(grad, e0 + kChunk + r * row);
-        }
-#endif
-
-        float mn = x[0][0], mx = x[0][0];
-#pragma unroll
-        for (int r = 0; r < G; r++)
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                mn = __builtin_fminf(mn, x[r][j]);
-                mx = __builtin_fmaxf(mx, x[r][j]);
-            }
-        group_minmax(mn, mx, lg, lane);
-        const Scale s = bucket_scale(mn, mx, BITS);
-        if (lp == 0) meta[tile.bucket0 + c * buckets_per_chunk + bi] = make_float2(s.unit, s.mn);
-
-        uint8_t *out = packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8);
-#pragma unroll
-        for (int r = 0; r < G; r++) {
-            const uint32_t pair0 = uint32_t(uint64_t(e0 + r * row) >> 1);
-            uint64_t acc = 0;
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                const uint32_t w = mix32((pair0 + k) ^ key);
-                const uint64_t q0 = code_of(x[r][2 * k], s, w & 0xffffU, kLevels);
-                const uint64_t q1 = code_of(x[r][2 * k + 1], s, w >> 16, kLevels);
-                acc |= q0 << (2 * k * BITS);
-                acc |= q1 << ((2 * k + 1) * BITS);
-            }
-#if CGX_STAGE_OUT
-            stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + ((e_lane + r * row) >> 3) * BITS, acc);
-#else
-            store_codes<BITS>(out + ((e_lane + r * row) >> 3) * BITS, acc);
-#endif
-        }
-#if CGX_STAGE_OUT
-        // the chunk's codes leave as whole 16-byte vectors, consecutive across lanes
-        wave_lds_fence();
-        flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
-        wave_lds_fence();
-#endif
-#if !CGX_PIPELINE
-        if (c + 1 < chunks) {
-#pragma unroll
-            for (int r = 0; r < G; r++) raw[r].load(grad, e0 + kChunk + r * row);
-        }
-#endif
+        for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
+        quantize_chunk<BITS>(x, map, lane, first, key, meta + tile.bucket0 + c * buckets_per_chunk,
+                             packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8), stage);
     }
 }
 
 // Any bucket size, any alignment, ragged last bucket: one bucket at a time, two passes.
-// Loads are issued in batches of 8 so that a pass costs few memory round trips.
-template <int DT>
-__device__ void quantize_slow(const void *__restrict__ grad, uint8_t *__restrict__ packed,
-                              float2 *__restrict__ meta, const Tile &tile, int bucket, uint32_t seed_lo,
-                              uint32_t seed_hi, int lane)
+// value(j) gives element j of the tile (called twice per element); loads are issued in
+// batches of 8 so that a pass costs few memory round trips.
+template <typename Value>
+__device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restrict__ out,
+                                                 float2 *__restrict__ meta, const Tile &tile, uint32_t pad,
+                                                 int bucket, uint32_t seed_lo, uint32_t seed_hi, int lane)
 {
     const int b = int(tile_bits(tile));
     const uint32_t levels = (1u << b) - 1u;
-    uint8_t *out = packed + tile.packed_off;
     for (uint32_t k0 = 0; k0 < tile.count; k0 += uint32_t(bucket)) {
         const uint32_t cnt = tile.count - k0 < uint32_t(bucket) ? tile.count - k0 : uint32_t(bucket);
-        const int64_t base = tile.elem0 + k0;
         float mn = __builtin_inff(), mx = -__builtin_inff();
         for (uint32_t j0 = 0; j0 < cnt; j0 += 8 * kWave) {
             float x[8];
 #pragma unroll
             for (int u = 0; u < 8; u++) {
                 const uint32_t j = j0 + u * kWave + lane;
-                x[u] = load_elem<DT>(grad, base + (j < cnt ? j : 0));     // clamped: element 0 again
+                x[u] = value(k0 + (j < cnt ? j : 0));               // clamped: the bucket's first element again
             }
 #pragma unroll
             for (int u = 0; u < 8; u++) {
@@ -411,11 +402,11 @@ __device__ void quantize_slow(const void *__restrict__ grad, uint8_t *__restrict
             const uint32_t valid = cnt - g * 8 < 8 ? cnt - g * 8 : 8;
             float x[8];
 #pragma unroll
-            for (uint32_t j = 0; j < 8; j++) x[j] = load_elem<DT>(grad, base + g * 8 + (j < valid ? j : 0));
+            for (uint32_t j = 0; j < 8; j++) x[j] = value(k0 + g * 8 + (j < valid ? j : 0));
             uint64_t acc = 0;
 #pragma unroll
             for (uint32_t j = 0; j < 8; j++) {
-                const uint64_t i = uint64_t(base + g * 8 + j);
+                const uint64_t i = uint64_t(tile.elem0) + k0 + g * 8 + j;
                 const uint64_t q = code_of(x[j], s, draw16(seed_lo, seed_hi, i), levels);
                 if (j < valid) acc |= q << (j * b);
             }
@@ -424,9 +415,9 @@ __device__ void quantize_slow(const void *__restrict__ grad, uint8_t *__restrict
             for (uint32_t k = 0; k < nbytes; k++) p[k] = uint8_t(acc >> (8 * k));
         }
     }
-    if (tile.pad) {
+    if (pad) {
         const uint64_t end = (uint64_t(tile.count) * b + 7) / 8;
-        if (uint32_t(lane) < tile.pad) out[end + lane] = 0;
+        if (uint32_t(lane) < pad) out[end + lane] = 0;
     }
 }
 
@@ -457,6 +448,18 @@ __device__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ p
     for (uint32_t k = done + lane; k < bytes + tile.pad; k += kWave) dst[k] = k < bytes ? src[k] : uint8_t(0);
 }
 
+#define CGX_FOR_BITS(bits, CALL)                      \
+    switch (bits) {                                   \
+    case 1: { constexpr int BITS = 1; CALL; } break;  \
+    case 2: { constexpr int BITS = 2; CALL; } break;  \
+    case 3: { constexpr int BITS = 3; CALL; } break;  \
+    case 4: { constexpr int BITS = 4; CALL; } break;  \
+    case 5: { constexpr int BITS = 5; CALL; } break;  \
+    case 6: { constexpr int BITS = 6; CALL; } break;  \
+    case 7: { constexpr int BITS = 7; CALL; } break;  \
+    default: { constexpr int BITS = 8; CALL; } break; \
+    }
+
 template <int DT>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
                                                            const Tile *__restrict__ tiles, int64_t n_tiles,
@@ -474,18 +477,11 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         if (kind == kQuantFast) {
-            switch (tile_bits(tile)) {
-            case 1: quantize_fast<DT, 1>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            case 2: quantize_fast<DT, 2>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            case 3: quantize_fast<DT, 3>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            case 4: quantize_fast<DT, 4>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            case 5: quantize_fast<DT, 5>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            case 6: quantize_fast<DT, 6>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            case 7: quantize_fast<DT, 7>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            default: quantize_fast<DT, 8>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage); break;
-            }
+            CGX_FOR_BITS(tile_bits(tile), (quantize_fast<DT, BITS>(grad, packed, meta, tile, bucket, seed_lo,
+                                                                     seed_hi, lane, stage)))
         } else if (kind == kQuantSlow) {
-            quantize_slow<DT>(grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane);
+            quantize_generic([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
+                             packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo, seed_hi, lane);
         } else {
             copy_tile<DT>(grad, packed, tile, kind == kCopyFast, lane);
         }
@@ -528,42 +524,13 @@ __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
     }
 }
 
-// b bytes holding 8 codes, read back from the LDS staging area.
-template <int BITS>
-__device__ __forceinline__ uint64_t staged_codes(const uint8_t *p)
-{
-    if (BITS == 8) return *reinterpret_cast<const uint64_t *>(p);
-    if (BITS == 4) return *reinterpret_cast<const uint32_t *>(p);
-    if (BITS == 2) return *reinterpret_cast<const uint16_t *>(p);
-    uint64_t acc = 0;
-#pragma unroll
-    for (int k = 0; k < BITS; k++) acc |= uint64_t(p[k]) << (8 * k);
-    return acc;
-}
-
-// One 16-byte vector per lane from global memory straight into LDS, without passing
-// through registers: lane l's vector lands at lds_base + 16 * l (lds_base is wave-uniform).
-__device__ __forceinline__ void load_to_lds16(const uint4v *gptr, uint4v *lds_base)
-{
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
-                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0,
-                                     CGX_NT_LOAD ? 2 : 0);
-}
-
-// Waits until every outstanding vector-memory operation of this wave has completed
-// (s_waitcnt vmcnt(0); the export and LDS counters are left alone).
-__device__ __forceinline__ void wait_vector_memory()
-{
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-}
-
 // Folds peers w0 .. w0+WB-1 into acc.  Each peer's share of the chunk (kChunk*BITS/8 bytes)
 // is fetched as whole 16-byte vectors, consecutive across lanes, directly into the wave's
 // LDS staging area, and read back by the lanes that own the codes.
 template <int BITS, int WB>
 __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int64_t in_off, uint32_t g,
-                                             const int (&code_off)[kGroups], float (&acc)[kGroups][8],
-                                             uint4v *stage, int lane)
+                                             const int (&code_off)[G], float (&acc)[G][8], uint4v *stage,
+                                             int lane)
 {
     constexpr int kBytes = kChunk * BITS / 8;        // per peer
     constexpr int kVecs = kBytes / 16;
@@ -585,19 +552,46 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
 #pragma unroll
     for (int i = 0; i < WB; i++) {
 #pragma unroll
-        for (int r = 0; r < kGroups; r++) {
+        for (int r = 0; r < G; r++) {
             float f[8];
             codes_to_float<BITS>(staged_codes<BITS>(codes + i * kBytes + code_off[r]), f);
 #pragma unroll
             for (int j = 0; j < 8; j++) acc[r][j] = __fadd_rn(acc[r][j], __builtin_fmaf(f[j], m[i].x, m[i].y));
         }
-#ifndef CGX_SCHED_PEERS
-#define CGX_SCHED_PEERS 2
-#endif
         // keep the scheduler from hoisting every peer's LDS reads to the top (registers)
-        if (CGX_SCHED_PEERS && (i % CGX_SCHED_PEERS) == CGX_SCHED_PEERS - 1) __builtin_amdgcn_sched_barrier(0);
+        if (i % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
     wave_lds_fence();
+}
+
+// Sum over the W peers of one chunk's dequantized values, added to acc in peer order.
+template <int BITS>
+__device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64_t in_off, uint32_t g,
+                                             const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane)
+{
+    // peers staged together: their packed bytes fit the staging area (one chunk of sums,
+    // kChunk * 4 bytes); bit widths whose codes are read back byte by byte take fewer peers
+    // at a time (the byte reads of a block are in flight together, each holding a register)
+    constexpr int kBytes = kChunk * BITS / 8;
+    constexpr bool kByteReads = BITS != 1 && BITS != 2 && BITS != 4 && BITS != 8;
+    constexpr int kWide = kByteReads ? (BITS == 3 ? 2 : 1) : (8 * kBytes <= kChunk * 4 ? 8 : 4);
+    static_assert(kWide * kBytes <= kChunk * 4, "staging area too small");
+    int code_off[G];
+#pragma unroll
+    for (int r = 0; r < G; r++) code_off[r] = (map.group(r) >> 3) * BITS;
+    for_peer_blocks<kWide>(W, [&](int w0, auto wb) {
+        reduce_peers<BITS, decltype(wb)::value>(peers, w0, in_off, g, code_off, acc, stage, lane);
+    });
+}
+
+// -0 is the identity of binary32 addition for every addend, signed zeros included, so
+// the first peer's value enters the sum unchanged.
+__device__ __forceinline__ void clear_sums(float (&acc)[G][8])
+{
+#pragma unroll
+    for (int r = 0; r < G; r++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[r][j] = -0.0f;
 }
 
 template <int BITS>
@@ -605,167 +599,140 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, bool a
                                             float *__restrict__ sum, const Tile &tile, int bucket, int lane,
                                             uint4v *stage)
 {
-    constexpr int G = kGroups;
-    // peers staged together: their packed bytes fit the staging area (one chunk of sums,
-    // kChunk * 4 bytes)
-    constexpr int kBytes = kChunk * BITS / 8;
-    // (bit widths whose codes are read back byte by byte take fewer peers at a time: the
-    // byte reads of a whole block are in flight together and each holds a register)
-    constexpr bool kByteReads = BITS != 1 && BITS != 2 && BITS != 4 && BITS != 8;
-    constexpr int kWide = kByteReads ? (BITS == 3 ? 2 : 1) : (8 * kBytes <= kChunk * 4 ? 8 : 4);
-    static_assert(kWide * kBytes <= kChunk * 4, "staging area too small");
-    const int lg = int(tile_lpb_log2(tile));
-    const int bi = lane >> lg;
-    const int lp = lane & ((1 << lg) - 1);
-    const int row = 8 << lg;
-    const int e_lane = bi * bucket + lp * 8;
+    const LaneMap map(tile, bucket, lane);
     const int chunks = int(tile.count / kChunk);
     const int buckets_per_chunk = kChunk / bucket;
-    int code_off[G];
-#pragma unroll
-    for (int r = 0; r < G; r++) code_off[r] = ((e_lane + r * row) >> 3) * BITS;
-
     for (int c = 0; c < chunks; c++) {
-        const int64_t e_chunk = tile.elem0 + int64_t(c) * kChunk;
-        const int64_t in_off = tile.packed_off + int64_t(c) * kBytes;
-        const uint32_t g = tile.bucket0 + c * buckets_per_chunk + bi;
-        // -0 is the identity of binary32 addition for every addend, signed zeros included,
-        // so the first peer's value enters the sum unchanged
+        const int64_t first = tile.elem0 + int64_t(c) * kChunk;
         float acc[G][8];
         if (accumulate) {
 #pragma unroll
-            for (int r = 0; r < G; r++) load8<CGX_F32>(sum, e_chunk + e_lane + r * row, acc[r]);
+            for (int r = 0; r < G; r++) load8<CGX_F32>(sum, first + map.group(r), acc[r]);
         } else {
-#pragma unroll
-            for (int r = 0; r < G; r++)
-#pragma unroll
-                for (int j = 0; j < 8; j++) acc[r][j] = -0.0f;
+            clear_sums(acc);
         }
-        int w = 0;
-        if (kWide >= 8)
-            for (; w + 8 <= W; w += 8) reduce_peers<BITS, 8>(peers, w, in_off, g, code_off, acc, stage, lane);
-        if (kWide >= 4)
-            for (; w + 4 <= W; w += 4) reduce_peers<BITS, 4>(peers, w, in_off, g, code_off, acc, stage, lane);
-        if (kWide >= 2)
-            for (; w + 2 <= W; w += 2) reduce_peers<BITS, 2>(peers, w, in_off, g, code_off, acc, stage, lane);
-        for (; w < W; w++) reduce_peers<BITS, 1>(peers, w, in_off, g, code_off, acc, stage, lane);
-
+        reduce_chunk<BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                           tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
         // the sums leave through LDS as well, so that every store instruction writes 1 KB of
         // consecutive addresses
 #pragma unroll
         for (int r = 0; r < G; r++) {
-            float4v *p = reinterpret_cast<float4v *>(stage) + ((e_lane + r * row) >> 2);
+            float4v *p = reinterpret_cast<float4v *>(stage) + (map.group(r) >> 2);
             p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
             p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
         }
         wave_lds_fence();
-        flush_stage(stage, reinterpret_cast<uint4v *>(sum + e_chunk), kChunk / 4, lane);
+        flush_stage(stage, reinterpret_cast<uint4v *>(sum + first), kChunk / 4, lane);
         wave_lds_fence();
     }
 }
 
-// Calls f(w0, std::integral_constant<int, WB>) for consecutive blocks of 8, 4, 2, 1 peers
-// covering 0..W-1 in order, so that a block's loads can be issued together.
-template <typename F>
-__device__ __forceinline__ void for_peer_blocks(int W, F f)
+// Ordered sum over the peers of element j of a generic quantized tile (start = the value
+// the sum starts from).
+__device__ __forceinline__ float generic_sum(const PeerPtrs &peers, int W, const Tile &tile, int bucket,
+                                             uint32_t j, float start)
 {
-    int w = 0;
-    for (; w + 8 <= W; w += 8) f(w, std::integral_constant<int, 8>());
-    if (w + 4 <= W) {
-        f(w, std::integral_constant<int, 4>());
-        w += 4;
-    }
-    if (w + 2 <= W) {
-        f(w, std::integral_constant<int, 2>());
-        w += 2;
-    }
-    if (w < W) f(w, std::integral_constant<int, 1>());
+    const int b = int(tile_bits(tile));
+    const uint32_t mask = (1u << b) - 1u;
+    const uint32_t g = tile.bucket0 + j / uint32_t(bucket);
+    const uint64_t bit = uint64_t(j) * b;
+    const int64_t at = tile.packed_off + int64_t(bit >> 3);
+    const uint32_t shift = uint32_t(bit & 7);
+    const bool two = shift + b > 8;                  // a code spans at most two bytes
+    float acc = start;
+    for_peer_blocks<8>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+        uint32_t lo[WB], hi[WB];
+        float2 m[WB];
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            const uint8_t *p = peers.packed[w0 + i] + at;
+            lo[i] = p[0];
+            hi[i] = two ? p[1] : 0u;
+            m[i] = peers.meta[w0 + i][g];
+        }
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            const uint32_t q = ((lo[i] | (hi[i] << 8)) >> shift) & mask;
+            acc = __fadd_rn(acc, __builtin_fmaf(float(q), m[i].x, m[i].y));
+        }
+    });
+    return acc;
 }
 
 // Any bucket size, any alignment, ragged tiles: one element per lane and pass.
 __device__ void reduce_slow(const PeerPtrs &peers, int W, bool accumulate, float *__restrict__ sum,
                             const Tile &tile, int bucket, int lane)
 {
-    const int b = int(tile_bits(tile));
-    const uint32_t mask = (1u << b) - 1u;
-    for (uint32_t j = lane; j < tile.count; j += kWave) {
-        const uint32_t g = tile.bucket0 + j / uint32_t(bucket);
-        const uint64_t bit = uint64_t(j) * b;
-        const int64_t at = tile.packed_off + int64_t(bit >> 3);
-        const uint32_t shift = uint32_t(bit & 7);
-        const bool two = shift + b > 8;                  // a code spans at most two bytes
-        float acc = accumulate ? sum[tile.elem0 + j] : -0.0f;
-        for_peer_blocks(W, [&](int w0, auto wb) {
-            constexpr int WB = decltype(wb)::value;
-            uint32_t lo[WB], hi[WB];
-            float2 m[WB];
-#pragma unroll
-            for (int i = 0; i < WB; i++) {
-                const uint8_t *p = peers.packed[w0 + i] + at;
-                lo[i] = p[0];
-                hi[i] = two ? p[1] : 0u;
-                m[i] = peers.meta[w0 + i][g];
-            }
-#pragma unroll
-            for (int i = 0; i < WB; i++) {
-                const uint32_t q = ((lo[i] | (hi[i] << 8)) >> shift) & mask;
-                acc = __fadd_rn(acc, __builtin_fmaf(float(q), m[i].x, m[i].y));
-            }
-        });
-        sum[tile.elem0 + j] = acc;
-    }
+    for (uint32_t j = lane; j < tile.count; j += kWave)
+        sum[tile.elem0 + j] = generic_sum(peers, W, tile, bucket, j, accumulate ? sum[tile.elem0 + j] : -0.0f);
 }
 
-// Pass-through tile of the reduce kernel: plain ordered sum of the stored values.
+// Ordered sum over the peers of 8 consecutive elements of a pass-through tile (16-byte
+// aligned) and of a single element.
 template <int DT>
-__device__ void reduce_copy(const PeerPtrs &peers, int W, bool accumulate, float *__restrict__ sum,
+__device__ __forceinline__ void copy_sum8(const PeerPtrs &peers, int W, const Tile &tile, uint32_t g,
+                                          float (&acc)[8])
+{
+    for_peer_blocks<8>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+        Raw8<DT> raw[WB];
+#pragma unroll
+        for (int i = 0; i < WB; i++) raw[i].load(peers.packed[w0 + i] + tile.packed_off, int64_t(g) * 8);
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            float x[8];
+            raw[i].widen(x);
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[j] = __fadd_rn(acc[j], x[j]);
+        }
+    });
+}
+
+template <int DT>
+__device__ __forceinline__ float copy_sum1(const PeerPtrs &peers, int W, const Tile &tile, uint32_t j, float start)
+{
+    float acc = start;
+    for_peer_blocks<8>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+        float x[WB];
+#pragma unroll
+        for (int i = 0; i < WB; i++) x[i] = load_elem<DT>(peers.packed[w0 + i] + tile.packed_off, j);
+#pragma unroll
+        for (int i = 0; i < WB; i++) acc = __fadd_rn(acc, x[i]);
+    });
+    return acc;
+}
+
+// Pass-through tile of the reduce kernels: plain ordered sum of the stored values, written
+// as binary32 to dst (dst[j] for element j of the tile).
+template <int DT>
+__device__ void reduce_copy(const PeerPtrs &peers, int W, bool accumulate, float *__restrict__ dst,
                             const Tile &tile, bool fast, int lane)
 {
     const uint32_t groups = fast ? tile.count / 8 : 0;
     for (uint32_t g = lane; g < groups; g += kWave) {
         float acc[8];
         if (accumulate) {
-            load8<CGX_F32>(sum, tile.elem0 + g * 8, acc);
+            load8<CGX_F32>(dst, int64_t(g) * 8, acc);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; j++) acc[j] = -0.0f;
         }
-        for_peer_blocks(W, [&](int w0, auto wb) {
-            constexpr int WB = decltype(wb)::value;
-            Raw8<DT> raw[WB];
-#pragma unroll
-            for (int i = 0; i < WB; i++) raw[i].load(peers.packed[w0 + i] + tile.packed_off, int64_t(g) * 8);
-#pragma unroll
-            for (int i = 0; i < WB; i++) {
-                float x[8];
-                raw[i].widen(x);
-#pragma unroll
-                for (int j = 0; j < 8; j++) acc[j] = __fadd_rn(acc[j], x[j]);
-            }
-        });
-        float4v *p = reinterpret_cast<float4v *>(sum + tile.elem0 + g * 8);
+        copy_sum8<DT>(peers, W, tile, g, acc);
+        float4v *p = reinterpret_cast<float4v *>(dst + g * 8);
         p[0] = float4v{acc[0], acc[1], acc[2], acc[3]};
         p[1] = float4v{acc[4], acc[5], acc[6], acc[7]};
     }
-    for (uint32_t j = groups * 8 + lane; j < tile.count; j += kWave) {
-        float acc = accumulate ? sum[tile.elem0 + j] : -0.0f;
-        for_peer_blocks(W, [&](int w0, auto wb) {
-            constexpr int WB = decltype(wb)::value;
-            float x[WB];
-#pragma unroll
-            for (int i = 0; i < WB; i++) x[i] = load_elem<DT>(peers.packed[w0 + i] + tile.packed_off, j);
-#pragma unroll
-            for (int i = 0; i < WB; i++) acc = __fadd_rn(acc, x[i]);
-        });
-        sum[tile.elem0 + j] = acc;
-    }
+    for (uint32_t j = groups * 8 + lane; j < tile.count; j += kWave)
+        dst[j] = copy_sum1<DT>(peers, W, tile, j, accumulate ? dst[j] : -0.0f);
 }
 
 __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, int W, int dt, bool accumulate,
                                                          const Tile *__restrict__ tiles, int64_t n_tiles,
                                                          int bucket, float *__restrict__ sum)
 {
-    // per-wave staging area for a chunk of binary32 sums
+    // per-wave staging area: a chunk of binary32 sums, or the packed bytes of a block of peers
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     const int lane = int(threadIdx.x) & 63;
@@ -775,22 +742,75 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         if (kind == kQuantFast) {
-            switch (tile_bits(tile)) {
-            case 1: reduce_fast<1>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            case 2: reduce_fast<2>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            case 3: reduce_fast<3>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            case 4: reduce_fast<4>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            case 5: reduce_fast<5>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            case 6: reduce_fast<6>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            case 7: reduce_fast<7>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            default: reduce_fast<8>(peers, W, accumulate, sum, tile, bucket, lane, stage); break;
-            }
+            CGX_FOR_BITS(tile_bits(tile), (reduce_fast<BITS>(peers, W, accumulate, sum, tile, bucket, lane, stage)))
         } else if (kind == kQuantSlow) {
             reduce_slow(peers, W, accumulate, sum, tile, bucket, lane);
         } else if (dt == CGX_F16) {
-            reduce_copy<CGX_F16>(peers, W, accumulate, sum, tile, kind == kCopyFast, lane);
+            reduce_copy<CGX_F16>(peers, W, accumulate, sum + tile.elem0, tile, kind == kCopyFast, lane);
         } else {
-            reduce_copy<CGX_F32>(peers, W, accumulate, sum, tile, kind == kCopyFast, lane);
+            reduce_copy<CGX_F32>(peers, W, accumulate, sum + tile.elem0, tile, kind == kCopyFast, lane);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- fused reduce + requantize
+
+// The sums of a chunk never leave the registers: reduce_chunk feeds quantize_chunk.
+template <int BITS>
+__device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
+                                           int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                           uint8_t *__restrict__ packed_out, float2 *__restrict__ meta_out,
+                                           int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    const int chunks = int(tile.count / kChunk);
+    const int buckets_per_chunk = kChunk / bucket;
+    for (int c = 0; c < chunks; c++) {
+        float acc[G][8];
+        clear_sums(acc);
+        reduce_chunk<BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                           tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
+        quantize_chunk<BITS>(acc, map, lane, tile.elem0 + int64_t(c) * kChunk, key,
+                             meta_out + tile.bucket0 + c * buckets_per_chunk,
+                             packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage);
+    }
+}
+
+// tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
+// output (binary32 pass-through layers); the two tables list the same tiles in the same order.
+__global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int W, int dt,
+                                                        const Tile *__restrict__ tiles_in,
+                                                        const Tile *__restrict__ tiles_out, int64_t n_tiles,
+                                                        int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                                        uint8_t *__restrict__ packed_out,
+                                                        float2 *__restrict__ meta_out)
+{
+    __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    uint4v *stage = stage_all[wave];
+    const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+        const Tile tile = tiles_in[t];
+        const int64_t out_off = tiles_out[t].packed_off;
+        const uint32_t out_pad = tiles_out[t].pad;
+        const uint32_t kind = tile_kind(tile);
+        if (kind == kQuantFast) {
+            CGX_FOR_BITS(tile_bits(tile), (fused_fast<BITS>(peers, W, tile, out_off, bucket, seed_lo, seed_hi,
+                                                             packed_out, meta_out, lane, stage)))
+        } else if (kind == kQuantSlow) {
+            quantize_generic([&](uint32_t j) { return generic_sum(peers, W, tile, bucket, j, -0.0f); },
+                             packed_out + out_off, meta_out, tile, out_pad, bucket, seed_lo, seed_hi, lane);
+        } else {
+            // pass-through: the sum is written as binary32 into the output stream, then its padding
+            float *dst = reinterpret_cast<float *>(packed_out + out_off);
+            if (dt == CGX_F16)
+                reduce_copy<CGX_F16>(peers, W, false, dst, tile, kind == kCopyFast, lane);
+            else
+                reduce_copy<CGX_F32>(peers, W, false, dst, tile, kind == kCopyFast, lane);
+            uint8_t *end = packed_out + out_off + uint64_t(tile.count) * 4;
+            if (uint32_t(lane) < out_pad) end[lane] = 0;
         }
     }
 }
@@ -829,6 +849,19 @@ hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Til
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     hipLaunchKernelGGL(reduce_kernel, grid, block, 0, stream, peers, W, dt, accumulate, tiles, n_tiles,
                        int(bucket), sum);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_reduce_requantize(const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
+                                            const Tile *tiles_out, int64_t n_tiles, int32_t bucket,
+                                            uint64_t seed, void *packed_out, void *meta_out,
+                                            const LaunchConfig &cfg, hipStream_t stream)
+{
+    if (n_tiles == 0) return hipSuccess;
+    const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
+    hipLaunchKernelGGL(fused_kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles,
+                       int(bucket), uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
+                       static_cast<float2 *>(meta_out));
     return hipGetLastError();
 }
 

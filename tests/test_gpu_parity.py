@@ -55,6 +55,21 @@ def gpu_reduce(torch, chunks, metas, offsets, bits, bucket, dt):
     return out[:plan.n], total
 
 
+def gpu_fused(torch, chunks, metas, offsets, bits, bucket, dt, seed):
+    """cgx_dequant_reduce_requantize on host-made chunks; returns (packed, meta) of the requantized sum."""
+    plan = cgx.Plan(offsets, bits, bucket, dt)
+    pb, mb = cgx.cgx_sizes(cgx.Plan(offsets, bits, bucket, wl.F32))
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m.reshape(-1)) if m.size else torch.zeros(4, device="cuda") for m in metas]
+    packed = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    meta = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+    cgx.cgx_dequant_reduce_requantize(dp, dm, plan, seed, packed, meta)
+    torch.cuda.synchronize()
+    p, m = packed.cpu().numpy(), meta.cpu().numpy()
+    assert (p[pb:] == 0xA5).all() and (m[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+    return p[:pb], m[:mb // 4].reshape(-1, 2)
+
+
 def assert_same_chunk(gp, gm, op, om, what=""):
     assert gm.tobytes() == om.tobytes(), f"{what}: meta differs in {int((gm.view(np.uint32) != om.view(np.uint32)).sum())} words"
     if not np.array_equal(gp, op):
@@ -88,6 +103,11 @@ def full_cycle(torch, oracle, w, W, seed_shift=0, what=""):
     rp, rm = gpu_quantize(torch, total[:w.n], w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32, requant=True)
     op, om = oracle.quantize(got, w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32)
     assert_same_chunk(rp, rm, op, om, f"{what} requantize")
+    # fused reduce + requantize: expected value from the oracle alone (its ordered binary32 sum, quantized)
+    if W <= cgx.MAX_FUSED_PEERS:
+        fp, fm = gpu_fused(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt, 99 + seed_shift)
+        op, om = oracle.quantize(ref["sum32"], w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32)
+        assert_same_chunk(fp, fm, op, om, f"{what} fused reduce+requantize")
 
 
 @pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
@@ -125,6 +145,19 @@ def test_many_peers_take_several_launches(torch, oracle):
         ref = oracle.dequant_reduce(list(chunks), list(metas), w.offsets, w.bits, w.bucket)
         got, _ = gpu_reduce(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
         assert_sum_parity(got, ref, f"W={W}")
+
+
+def test_fused_peer_counts(torch, oracle):
+    """Every chunk count the fused entry point accepts, on the edge-case plan in binary16 storage."""
+    w = wl.tiny_mixed(seed=91, dt=wl.F16, bucket=64)
+    chunks, metas = zip(*[oracle.quantize(w.gradient(p), w.offsets, w.bits, w.bucket, p, w.dt) for p in range(16)])
+    for W in (1, 2, 3, 5, 8, 11, 16):
+        ref = oracle.dequant_reduce(list(chunks[:W]), list(metas[:W]), w.offsets, w.bits, w.bucket, w.dt)
+        fp, fm = gpu_fused(torch, chunks[:W], metas[:W], w.offsets, w.bits, w.bucket, w.dt, 1000 + W)
+        op, om = oracle.quantize(ref["sum32"], w.offsets, w.bits, w.bucket, 1000 + W, wl.F32)
+        assert_same_chunk(fp, fm, op, om, f"fused W={W}")
+    with pytest.raises(cgx.CgxError):
+        gpu_fused(torch, list(chunks) + [chunks[0]], list(metas) + [metas[0]], w.offsets, w.bits, w.bucket, w.dt, 1)
 
 
 def test_degenerate_values(torch, oracle):
@@ -222,6 +255,10 @@ def share_cycle(torch, oracle, w, rank, what):
     rp, rm = gpu_quantize(torch, total[:m], sub_off, sub_bits, w.bucket, 7, wl.F32, requant=True)
     op, om = oracle.quantize(got, sub_off, sub_bits, w.bucket, 7, wl.F32)
     assert_same_chunk(rp, rm, op, om, f"{what} share requantize")
+    del rp, got, total
+    fp, fm = gpu_fused(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt, 7)
+    op, om = oracle.quantize(ref["sum32"], sub_off, sub_bits, w.bucket, 7, wl.F32)
+    assert_same_chunk(fp, fm, op, om, f"{what} share fused reduce+requantize")
 
 
 def test_gpt2_medium_config_full_size(torch, oracle):

@@ -111,6 +111,15 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, None, None) == -1
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, buf + 4, None) == -9
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 48, 0, buf, None) == -5
+    fused = lib.cgx_dequant_reduce_requantize
+    assert fused(ptrs, ptrs, 0, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
+    assert fused(ptrs, ptrs, 17, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
+    assert fused(ptrs, nulls, 2, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -1
+    assert fused(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, 1, None, buf, None) == -1
+    assert fused(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, 1, buf, None, None) == -1
+    assert fused(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, 1, buf + 8, buf, None) == -9
+    assert fused(ptrs, ptrs, 2, 300, 2, o, b, 128, 5, 1, buf, buf, None) == -7
+    assert fused(ptrs, ptrs, 2, 300, 2, o, b, 160 + 8, 0, 1, buf, buf, None) == -5
     # empty buffers are accepted and do nothing
     z = np.zeros(1, np.int64)
     assert lib.cgx_quantize(None, 0, 0, z.ctypes.data, None, 128, 0, 0, None, None, None) == 0
