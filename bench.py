@@ -162,6 +162,43 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    # the same rank's work with the fused entry point: quantize + dequant_reduce_requantize
+    def fused_step(i):
+        r = i % R
+        cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1])
+        cgx.cgx_dequant_reduce_requantize(chunk_sets[r][0], chunk_sets[r][1], r_plan, 29 + i, rq_out[r][0],
+                                          rq_out[r][1])
+
+    fused = None
+    if W <= cgx.MAX_FUSED_PEERS:
+        for i in range(args.warmup):
+            fused_step(i)
+        fe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            r = i % R
+            cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1])
+            fe[i][0].record()
+            cgx.cgx_dequant_reduce_requantize(chunk_sets[r][0], chunk_sets[r][1], r_plan, 29 + i, rq_out[r][0],
+                                              rq_out[r][1])
+            fe[i][1].record()
+        torch.cuda.synchronize()
+        fused_wall = (time.perf_counter() - t0) * 1e3 / args.steps
+        fused_kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in fe]))
+        fused_alg = alg["dequant_reduce"] - 4 * m + (alg["requantize"] - 4 * m)
+        fused = {
+            "step": "cgx_quantize(full buffer) + cgx_dequant_reduce_requantize(W chunks)",
+            "ms_per_step": round(fused_wall, 5),
+            "dequant_reduce_requantize": {
+                "ms": round(fused_kernel_ms, 5),
+                "algorithmic_bytes": int(fused_alg),
+                "algorithmic_GBps": round(fused_alg / fused_kernel_ms / 1e6, 1),
+                "hbm_frac": round(fused_alg / fused_kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                "raw_gradient_GBps": round(4 * m / fused_kernel_ms / 1e6, 1),
+            },
+        }
+
     if args.calibration_copy:
         # an elementwise kernel that reads 1 GiB and writes 1 GiB (grid unlike any cgx launch)
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
@@ -225,6 +262,7 @@ def main():
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": traffic,
         },
+        "fused": fused,
         "setup_s": round(setup_s, 1),
     }
 

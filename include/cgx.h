@@ -111,6 +111,30 @@ int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32
                        float *sum, void *stream);
 
 /*
+ * The same reduction when the rank's own contribution to its share is still uncompressed
+ * (paper Sec. 4.1, Scatter-Reduce-Allgather: a node receives its chunk from all OTHER
+ * nodes and aggregates it with its own): sum[i] = local[i] + deq_0[i] + ... + deq_{W-1}[i],
+ * in that order in binary32, local widened to binary32 first.
+ *   local  device, n elements of local_dt (binary32 or binary16), 16-byte aligned
+ */
+int cgx_dequant_reduce_add(const void *local, cgx_dtype local_dt, const void *const *packed,
+                           const void *const *meta, int32_t W, int64_t n, int32_t L,
+                           const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                           cgx_dtype dt, float *sum, void *stream);
+
+/*
+ * Decompress one chunk into the gradient's storage type (paper Sec. 4.1,
+ * Scatter-Reduce-Allgather, after the second round: every rank decompresses the
+ * aggregated chunks it gathered): out[i] = fma(code, unit, min), or the stored value for
+ * pass-through layers, rounded to nearest even when out_dt is CGX_F16.
+ *   packed, meta  device, one chunk of the plan (pass-through layers stored as dt)
+ *   out           device, n elements of out_dt
+ */
+int cgx_dequantize(const void *packed, const void *meta, int64_t n, int32_t L,
+                   const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                   cgx_dtype dt, cgx_dtype out_dt, void *out, void *stream);
+
+/*
  * Compress the aggregated chunk again before it is broadcast (paper Sec. 4.1,
  * Scatter-Reduce-Allgather, second round): cgx_quantize on binary32 input.
  * Pass-through layers are written as binary32.

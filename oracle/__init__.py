@@ -52,6 +52,10 @@ def _load():
         lib.oracle_quantize_with_draws.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_dequant_reduce_add.argtypes = [c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_int32] + plan + \
+            [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_float_to_half.restype = None
+        lib.oracle_float_to_half.argtypes = [c.c_void_p, c.c_int64, c.c_void_p]
         lib.oracle_unpack_codes.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p]
         _lib = lib
     return _lib
@@ -137,9 +141,24 @@ def quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=N
     return packed, meta
 
 
+def float_to_half(x) -> np.ndarray:
+    """binary32 -> binary16 (as uint16 bit patterns), round to nearest even."""
+    a = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.zeros(a.size, dtype=np.uint16)
+    _load().oracle_float_to_half(_ptr(a), a.size, _ptr(out))
+    return out.reshape(a.shape)
+
+
+def dequantize(packed, meta, offsets, bits, bucket: int, dt: int = F32, out_dt: int = F32) -> np.ndarray:
+    """One chunk decompressed into binary32, or into binary16 (rounded to nearest even)."""
+    d = dequant_reduce([packed], [meta], offsets, bits, bucket, dt, want=("sum32",))["sum32"]
+    return float_to_half(d).view(np.float16) if out_dt == F16 else d
+
+
 def dequant_reduce(packed_list, meta_list, offsets, bits, bucket: int, dt: int = F32,
-                   want=("sum32", "sum64", "abs64")):
-    """Returns a dict with the requested arrays (see cgx_oracle.c)."""
+                   want=("sum32", "sum64", "abs64"), local=None):
+    """Returns a dict with the requested arrays (see cgx_oracle.c).  `local` (float32 or
+    float16 array of n elements) is the rank's own uncompressed term, added first."""
     off, bt, n, L = _plan(offsets, bits)
     W = len(packed_list)
     if W < 1 or len(meta_list) != W:
@@ -157,8 +176,14 @@ def dequant_reduce(packed_list, meta_list, offsets, bits, bucket: int, dt: int =
         "sum64": np.zeros(n, dtype=np.float64) if "sum64" in want else None,
         "abs64": np.zeros(n, dtype=np.float64) if "abs64" in want else None,
     }
-    rc = _load().oracle_dequant_reduce(pp, mp, W, n, L, _ptr(off), _ptr(bt), bucket, dt,
-                                       _ptr(out["sum32"]), _ptr(out["sum64"]), _ptr(out["abs64"]))
+    loc, loc_dt = None, F32
+    if local is not None:
+        loc = np.ascontiguousarray(local)
+        if loc.dtype not in (np.float32, np.float16) or loc.size != n:
+            raise ValueError("local must be float32 or float16 with n elements")
+        loc_dt = F16 if loc.dtype == np.float16 else F32
+    rc = _load().oracle_dequant_reduce_add(_ptr(loc), loc_dt, pp, mp, W, n, L, _ptr(off), _ptr(bt), bucket, dt,
+                                           _ptr(out["sum32"]), _ptr(out["sum64"]), _ptr(out["abs64"]))
     _check(rc, "dequant_reduce")
     return {k: v for k, v in out.items() if v is not None}
 

@@ -75,6 +75,31 @@ static float half_to_float(uint16_t h)
     return sign ? -v : v;
 }
 
+/* binary32 -> binary16, round to nearest, ties to even, from the format definition:
+ * normal results are (1024 + m) * 2^(e-10) with e in [-14, 15], subnormal ones m * 2^-24. */
+static uint16_t float_to_half(float f)
+{
+    uint16_t sign = signbit(f) ? 0x8000u : 0u;
+    float a = fabsf(f);
+    if (isnan(f)) return (uint16_t)(sign | 0x7e00u);
+    if (a >= 65520.0f) return (uint16_t)(sign | 0x7c00u);   /* half way between the largest half and 2^16, or above */
+    if (a < 6.103515625e-05f) {                              /* below 2^-14: subnormal, units of 2^-24 */
+        int m = (int)nearbyintf(ldexpf(a, 24));              /* exact scaling; ties to even */
+        return (uint16_t)(sign | m);                         /* m == 1024 is the smallest normal */
+    }
+    int e;
+    float frac = frexpf(a, &e);                              /* a = frac * 2^e, frac in [0.5, 1) */
+    int m = (int)nearbyintf(ldexpf(frac, 11));               /* in [1024, 2048] */
+    e -= 1;                                                  /* a = (m / 1024) * 2^e */
+    if (m == 2048) { m = 1024; e += 1; }
+    return (uint16_t)(sign | ((e + 15) << 10) | (m - 1024));
+}
+
+void oracle_float_to_half(const float *in, int64_t count, uint16_t *out)
+{
+    for (int64_t k = 0; k < count; k++) out[k] = float_to_half(in[k]);
+}
+
 static float load_elem(const void *buf, int64_t i, int dt)
 {
     if (dt == DT_F16)
@@ -295,19 +320,23 @@ int oracle_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int
 
 /*
  * For every element of the buffer: sum over the W peers of the dequantized
- * value (pass-through layers: of the stored value).
- *   sum32[i]: binary32, deq_w = fmaf(q, unit, mn), added in order w = 0..W-1.
- *   sum64[i]: binary64 evaluation of sum_w (mn_w + q_w * unit_w).
- *   abs64[i]: binary64 sum_w |mn_w + q_w * unit_w|, the scale of the tolerance.
+ * value (pass-through layers: of the stored value), optionally preceded by the
+ * rank's own uncompressed value local[i] (local == NULL: no such term).
+ *   sum32[i]: binary32; terms are local[i] widened to binary32, then
+ *             deq_w = fmaf(q, unit, mn) for w = 0..W-1, added in that order.
+ *   sum64[i]: binary64 evaluation of local + sum_w (mn_w + q_w * unit_w).
+ *   abs64[i]: binary64 sum of the absolute values of the terms, the scale of the tolerance.
  * Any of the three outputs may be NULL.
  */
-int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W,
-                          int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
-                          int32_t bucket, int32_t dt, float *sum32, double *sum64, double *abs64)
+int oracle_dequant_reduce_add(const void *local, int32_t local_dt, const uint8_t *const *packed,
+                              const float *const *meta, int32_t W, int64_t n, int32_t L, const int64_t *off,
+                              const uint8_t *bits, int32_t bucket, int32_t dt, float *sum32, double *sum64,
+                              double *abs64)
 {
     int rc = check_plan(n, L, off, bits, bucket, dt);
     if (rc) return rc;
     if (W < 1 || !packed || !meta) return ORACLE_ERR_ARG;
+    if (local && local_dt != DT_F32 && local_dt != DT_F16) return ORACLE_ERR_ARG;
     uint64_t seg_start = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         int64_t first = off[l], len = off[l + 1] - off[l];
@@ -319,6 +348,13 @@ int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta
         for (int64_t j = 0; j < len; j++) {
             float acc32 = 0.0f;
             double acc64 = 0.0, accabs = 0.0;
+            int started = 0;
+            if (local) {
+                acc32 = load_elem(local, first + j, local_dt);
+                acc64 = (double)acc32;
+                accabs = fabs(acc64);
+                started = 1;
+            }
             for (int32_t w = 0; w < W; w++) {
                 const uint8_t *seg = packed[w] + seg_start;
                 float v32;
@@ -333,7 +369,8 @@ int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta
                     v32 = fmaf((float)q, unit, mn);
                     v64 = (double)mn + (double)q * (double)unit;
                 }
-                acc32 = (w == 0) ? v32 : acc32 + v32;
+                acc32 = started ? acc32 + v32 : v32;
+                started = 1;
                 acc64 += v64;
                 accabs += fabs(v64);
             }
@@ -345,6 +382,14 @@ int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta
         bucket0 += n_buckets;
     }
     return ORACLE_OK;
+}
+
+int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W,
+                          int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                          int32_t bucket, int32_t dt, float *sum32, double *sum64, double *abs64)
+{
+    return oracle_dequant_reduce_add(NULL, DT_F32, packed, meta, W, n, L, off, bits, bucket, dt, sum32, sum64,
+                                     abs64);
 }
 
 /* Codes of a quantized buffer, one byte per element (pass-through layers give 0xff). */

@@ -20,7 +20,8 @@ F32, F16 = 0, 1
 MAX_PEERS = 64
 MAX_FUSED_PEERS = 16
 
-EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_requantize",
+EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduce_add", "cgx_dequantize",
+           "cgx_requantize",
            "cgx_dequant_reduce_requantize", "cgx_plan_tiles",
            "cgx_status_string", "cgx_shutdown")
 
@@ -51,6 +52,9 @@ def lib() -> ctypes.CDLL:
         L.cgx_quantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_requantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + [c.c_int, c.c_void_p, c.c_void_p]
+        L.cgx_dequant_reduce_add.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_void_p, c.c_int32] + plan + \
+            [c.c_int, c.c_void_p, c.c_void_p]
+        L.cgx_dequantize.argtypes = [c.c_void_p, c.c_void_p] + plan + [c.c_int, c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
             [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
@@ -137,6 +141,23 @@ def cgx_dequant_reduce(packed: Sequence, meta: Sequence, plan: Plan, total, stre
     mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
     _check(lib().cgx_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
            "cgx_dequant_reduce")
+
+
+def cgx_dequant_reduce_add(local, local_dt: int, packed: Sequence, meta: Sequence, plan: Plan, total, stream=None) -> None:
+    """total = local + sum of the W dequantized chunks; local: device tensor of n elements (float32 / float16)."""
+    W = len(packed)
+    if len(meta) != W:
+        raise ValueError("as many meta tensors as packed tensors")
+    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
+    _check(lib().cgx_dequant_reduce_add(local.data_ptr(), local_dt, pp, mp, W, *plan.args, plan.dt, total.data_ptr(),
+                                        _stream(stream)), "cgx_dequant_reduce_add")
+
+
+def cgx_dequantize(packed, meta, plan: Plan, out_dt: int, out, stream=None) -> None:
+    """out: device tensor of n elements of out_dt (float32 or float16) receiving the decompressed chunk."""
+    _check(lib().cgx_dequantize(packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt, out_dt, out.data_ptr(),
+                                _stream(stream)), "cgx_dequantize")
 
 
 def cgx_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, seed: int, packed_out, meta_out,

@@ -110,6 +110,45 @@ int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off, co
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }
 
+// Shared body of the dequantize / reduce entry points: out = [local +] deq_0 + ... + deq_{W-1}.
+int reduce_impl(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
+                const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, const void *local, int local_dt,
+                bool want_local, void *out, int out_dt, void *stream)
+{
+    int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    if (rc != CGX_OK) return rc;
+    if (W < 1 || W > CGX_MAX_PEERS) return CGX_ERR_PEERS;
+    if (n == 0) return CGX_OK;
+    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    if (!packed || !meta || !out || (want_local && !local)) return CGX_ERR_NULL;
+    for (int w = 0; w < W; w++) {
+        if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
+        if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
+    }
+    if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
+    const CachedPlan *plan = nullptr;
+    rc = get_plan(L, off, bits, bucket, dt, &plan);
+    if (rc != CGX_OK) return rc;
+    // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
+    // a later launch starts from the binary32 result of the one before (W <= kPeersPerLaunch
+    // whenever the output is not binary32: only cgx_dequantize asks for that, with W = 1)
+    for (int w0 = 0; w0 < W; w0 += cgx::kPeersPerLaunch) {
+        const int k = W - w0 < cgx::kPeersPerLaunch ? W - w0 : cgx::kPeersPerLaunch;
+        cgx::PeerPtrs peers{};
+        for (int i = 0; i < k; i++) {
+            peers.packed[i] = static_cast<const uint8_t *>(packed[w0 + i]);
+            peers.meta[i] = static_cast<const float2 *>(meta[w0 + i]);
+        }
+        const void *init = w0 == 0 ? local : out;
+        const int init_dt = w0 == 0 ? local_dt : CGX_F32;
+        const hipError_t e = cgx::launch_dequant_reduce(peers, k, dt, plan->d_tiles, plan->n_tiles, bucket, init,
+                                                        init_dt, out, out_dt, launch_config(),
+                                                        static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return CGX_ERR_HIP;
+    }
+    return CGX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -143,34 +182,28 @@ int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32
                        const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
                        float *sum, void *stream)
 {
-    int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
-    if (rc != CGX_OK) return rc;
-    if (W < 1 || W > CGX_MAX_PEERS) return CGX_ERR_PEERS;
-    if (n == 0) return CGX_OK;
-    const cgx::PlanShape shape = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
-    if (!packed || !meta || !sum) return CGX_ERR_NULL;
-    for (int w = 0; w < W; w++) {
-        if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
-        if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
-    }
-    if (misaligned(sum)) return CGX_ERR_ALIGN;
-    const CachedPlan *plan = nullptr;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, int(dt), &plan);
-    if (rc != CGX_OK) return rc;
-    // peers are folded in order, kPeersPerLaunch at a time, so the sum order is w = 0, 1, ..., W-1
-    for (int w0 = 0; w0 < W; w0 += cgx::kPeersPerLaunch) {
-        const int k = W - w0 < cgx::kPeersPerLaunch ? W - w0 : cgx::kPeersPerLaunch;
-        cgx::PeerPtrs peers{};
-        for (int i = 0; i < k; i++) {
-            peers.packed[i] = static_cast<const uint8_t *>(packed[w0 + i]);
-            peers.meta[i] = static_cast<const float2 *>(meta[w0 + i]);
-        }
-        const hipError_t e = cgx::launch_dequant_reduce(peers, k, int(dt), plan->d_tiles, plan->n_tiles, bucket,
-                                                        w0 > 0, sum, launch_config(),
-                                                        static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return CGX_ERR_HIP;
-    }
-    return CGX_OK;
+    return reduce_impl(packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32,
+                       false, sum, CGX_F32, stream);
+}
+
+int cgx_dequant_reduce_add(const void *local, cgx_dtype local_dt, const void *const *packed,
+                           const void *const *meta, int32_t W, int64_t n, int32_t L,
+                           const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                           cgx_dtype dt, float *sum, void *stream)
+{
+    if (local_dt != CGX_F32 && local_dt != CGX_F16) return CGX_ERR_DTYPE;
+    return reduce_impl(packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), local, int(local_dt),
+                       true, sum, CGX_F32, stream);
+}
+
+int cgx_dequantize(const void *packed, const void *meta, int64_t n, int32_t L, const int64_t *layer_offsets,
+                   const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt, cgx_dtype out_dt, void *out,
+                   void *stream)
+{
+    if (out_dt != CGX_F32 && out_dt != CGX_F16) return CGX_ERR_DTYPE;
+    const void *const p[1] = {packed}, *const m[1] = {meta};
+    return reduce_impl(p, m, 1, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32, false, out,
+                       int(out_dt), stream);
 }
 
 int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W, int64_t n,

@@ -24,10 +24,11 @@ hipError_t launch_quantize(const void *grad, int dt, const Tile *tiles, int64_t 
                            uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
                            hipStream_t stream);
 
-// sum = (accumulate ? sum : 0) + deq_0 + ... + deq_{W-1}, W <= kPeersPerLaunch.
+// out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
+// term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
 hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
-                                 int32_t bucket, bool accumulate, float *sum, const LaunchConfig &cfg,
-                                 hipStream_t stream);
+                                 int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
+                                 const LaunchConfig &cfg, hipStream_t stream);
 
 // packed_out / meta_out = quantize(deq_0 + ... + deq_{W-1}) without the binary32 sum ever
 // reaching memory; tiles_in describes the chunks (storage type dt), tiles_out the output

@@ -368,9 +368,10 @@ __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uin
 }
 
 // Any bucket size, any alignment, ragged last bucket: one bucket at a time, two passes.
-// value(j) gives element j of the tile (called twice per element); loads are issued in
-// batches of 8 so that a pass costs few memory round trips.
-template <typename Value>
+// value(j) gives element j of the tile (called twice per element).  With BATCH the values
+// of a pass are fetched 8 at a time so that plain loads overlap; without it (value() is
+// itself a reduction over the peers) they are taken one by one.
+template <bool BATCH, typename Value>
 __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restrict__ out,
                                                  float2 *__restrict__ meta, const Tile &tile, uint32_t pad,
                                                  int bucket, uint32_t seed_lo, uint32_t seed_hi, int lane)
@@ -380,17 +381,25 @@ __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restric
     for (uint32_t k0 = 0; k0 < tile.count; k0 += uint32_t(bucket)) {
         const uint32_t cnt = tile.count - k0 < uint32_t(bucket) ? tile.count - k0 : uint32_t(bucket);
         float mn = __builtin_inff(), mx = -__builtin_inff();
-        for (uint32_t j0 = 0; j0 < cnt; j0 += 8 * kWave) {
-            float x[8];
+        if (BATCH) {
+            for (uint32_t j0 = 0; j0 < cnt; j0 += 8 * kWave) {
+                float x[8];
 #pragma unroll
-            for (int u = 0; u < 8; u++) {
-                const uint32_t j = j0 + u * kWave + lane;
-                x[u] = value(k0 + (j < cnt ? j : 0));               // clamped: the bucket's first element again
+                for (int u = 0; u < 8; u++) {
+                    const uint32_t j = j0 + u * kWave + lane;
+                    x[u] = value(k0 + (j < cnt ? j : 0));           // clamped: the bucket's first element again
+                }
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    mn = __builtin_fminf(mn, x[u]);
+                    mx = __builtin_fmaxf(mx, x[u]);
+                }
             }
-#pragma unroll
-            for (int u = 0; u < 8; u++) {
-                mn = __builtin_fminf(mn, x[u]);
-                mx = __builtin_fmaxf(mx, x[u]);
+        } else {
+            for (uint32_t j = lane; j < cnt; j += kWave) {
+                const float x = value(k0 + j);
+                mn = __builtin_fminf(mn, x);
+                mx = __builtin_fmaxf(mx, x);
             }
         }
         group_minmax(mn, mx, 6, lane);
@@ -400,15 +409,22 @@ __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restric
         const uint32_t groups = (cnt + 7) / 8;
         for (uint32_t g = lane; g < groups; g += kWave) {
             const uint32_t valid = cnt - g * 8 < 8 ? cnt - g * 8 : 8;
-            float x[8];
-#pragma unroll
-            for (uint32_t j = 0; j < 8; j++) x[j] = value(k0 + g * 8 + (j < valid ? j : 0));
+            const uint64_t i0 = uint64_t(tile.elem0) + k0 + g * 8;
             uint64_t acc = 0;
+            if (BATCH) {
+                float x[8];
 #pragma unroll
-            for (uint32_t j = 0; j < 8; j++) {
-                const uint64_t i = uint64_t(tile.elem0) + k0 + g * 8 + j;
-                const uint64_t q = code_of(x[j], s, draw16(seed_lo, seed_hi, i), levels);
-                if (j < valid) acc |= q << (j * b);
+                for (uint32_t j = 0; j < 8; j++) x[j] = value(k0 + g * 8 + (j < valid ? j : 0));
+#pragma unroll
+                for (uint32_t j = 0; j < 8; j++) {
+                    const uint64_t q = code_of(x[j], s, draw16(seed_lo, seed_hi, i0 + j), levels);
+                    if (j < valid) acc |= q << (j * b);
+                }
+            } else {
+                for (uint32_t j = 0; j < valid; j++) {
+                    const uint64_t q = code_of(value(k0 + g * 8 + j), s, draw16(seed_lo, seed_hi, i0 + j), levels);
+                    acc |= q << (j * b);
+                }
             }
             const uint32_t nbytes = (valid * b + 7) / 8;
             uint8_t *p = out + uint64_t(k0 / 8 + g) * b;
@@ -480,7 +496,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
             CGX_FOR_BITS(tile_bits(tile), (quantize_fast<DT, BITS>(grad, packed, meta, tile, bucket, seed_lo,
                                                                      seed_hi, lane, stage)))
         } else if (kind == kQuantSlow) {
-            quantize_generic([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
+            quantize_generic<true>([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
                              packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo, seed_hi, lane);
         } else {
             copy_tile<DT>(grad, packed, tile, kind == kCopyFast, lane);
@@ -594,10 +610,60 @@ __device__ __forceinline__ void clear_sums(float (&acc)[G][8])
         for (int j = 0; j < 8; j++) acc[r][j] = -0.0f;
 }
 
+// What a reduction starts from and where it goes: element e of the tile's buffer is
+// init[e] (binary32 or binary16; init == nullptr: nothing) and is written to out[e]
+// (binary32, or binary16 rounded to nearest even).
+struct SumIo {
+    const void *init;
+    int init_dt;
+    void *out;
+    int out_dt;
+};
+
+__device__ __forceinline__ void init8(const SumIo &io, int64_t e, float (&acc)[8])
+{
+    if (!io.init) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] = -0.0f;
+    } else if (io.init_dt == CGX_F16) {
+        load8<CGX_F16>(io.init, e, acc);
+    } else {
+        load8<CGX_F32>(io.init, e, acc);
+    }
+}
+
+__device__ __forceinline__ float init1(const SumIo &io, int64_t e)
+{
+    if (!io.init) return -0.0f;
+    return io.init_dt == CGX_F16 ? load_elem<CGX_F16>(io.init, e) : load_elem<CGX_F32>(io.init, e);
+}
+
+__device__ __forceinline__ void store1(const SumIo &io, int64_t e, float v)
+{
+    if (io.out_dt == CGX_F16)
+        reinterpret_cast<_Float16 *>(io.out)[e] = _Float16(v);
+    else
+        reinterpret_cast<float *>(io.out)[e] = v;
+}
+
+// 8 consecutive results to a 16-byte aligned position.
+__device__ __forceinline__ void store8(const SumIo &io, int64_t e, const float (&acc)[8])
+{
+    if (io.out_dt == CGX_F16) {
+        half8v h;
+#pragma unroll
+        for (int j = 0; j < 8; j++) h[j] = _Float16(acc[j]);
+        *reinterpret_cast<half8v *>(reinterpret_cast<_Float16 *>(io.out) + e) = h;
+    } else {
+        float4v *p = reinterpret_cast<float4v *>(reinterpret_cast<float *>(io.out) + e);
+        p[0] = float4v{acc[0], acc[1], acc[2], acc[3]};
+        p[1] = float4v{acc[4], acc[5], acc[6], acc[7]};
+    }
+}
+
 template <int BITS>
-__device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, bool accumulate,
-                                            float *__restrict__ sum, const Tile &tile, int bucket, int lane,
-                                            uint4v *stage)
+__device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const SumIo &io, const Tile &tile,
+                                            int bucket, int lane, uint4v *stage)
 {
     const LaneMap map(tile, bucket, lane);
     const int chunks = int(tile.count / kChunk);
@@ -605,24 +671,34 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, bool a
     for (int c = 0; c < chunks; c++) {
         const int64_t first = tile.elem0 + int64_t(c) * kChunk;
         float acc[G][8];
-        if (accumulate) {
 #pragma unroll
-            for (int r = 0; r < G; r++) load8<CGX_F32>(sum, first + map.group(r), acc[r]);
-        } else {
-            clear_sums(acc);
-        }
+        for (int r = 0; r < G; r++) init8(io, first + map.group(r), acc[r]);
         reduce_chunk<BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
                            tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
-        // the sums leave through LDS as well, so that every store instruction writes 1 KB of
+        // the results leave through LDS as well, so that every store instruction writes 1 KB of
         // consecutive addresses
+        if (io.out_dt == CGX_F16) {
 #pragma unroll
-        for (int r = 0; r < G; r++) {
-            float4v *p = reinterpret_cast<float4v *>(stage) + (map.group(r) >> 2);
-            p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
-            p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
+            for (int r = 0; r < G; r++) {
+                half8v h;
+#pragma unroll
+                for (int j = 0; j < 8; j++) h[j] = _Float16(acc[r][j]);
+                reinterpret_cast<half8v *>(stage)[map.group(r) >> 3] = h;
+            }
+            wave_lds_fence();
+            flush_stage(stage, reinterpret_cast<uint4v *>(reinterpret_cast<_Float16 *>(io.out) + first), kChunk / 8,
+                        lane);
+        } else {
+#pragma unroll
+            for (int r = 0; r < G; r++) {
+                float4v *p = reinterpret_cast<float4v *>(stage) + (map.group(r) >> 2);
+                p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+                p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
+            }
+            wave_lds_fence();
+            flush_stage(stage, reinterpret_cast<uint4v *>(reinterpret_cast<float *>(io.out) + first), kChunk / 4,
+                        lane);
         }
-        wave_lds_fence();
-        flush_stage(stage, reinterpret_cast<uint4v *>(sum + first), kChunk / 4, lane);
         wave_lds_fence();
     }
 }
@@ -661,11 +737,10 @@ __device__ __forceinline__ float generic_sum(const PeerPtrs &peers, int W, const
 }
 
 // Any bucket size, any alignment, ragged tiles: one element per lane and pass.
-__device__ void reduce_slow(const PeerPtrs &peers, int W, bool accumulate, float *__restrict__ sum,
-                            const Tile &tile, int bucket, int lane)
+__device__ void reduce_slow(const PeerPtrs &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
 {
     for (uint32_t j = lane; j < tile.count; j += kWave)
-        sum[tile.elem0 + j] = generic_sum(peers, W, tile, bucket, j, accumulate ? sum[tile.elem0 + j] : -0.0f);
+        store1(io, tile.elem0 + j, generic_sum(peers, W, tile, bucket, j, init1(io, tile.elem0 + j)));
 }
 
 // Ordered sum over the peers of 8 consecutive elements of a pass-through tile (16-byte
@@ -704,35 +779,28 @@ __device__ __forceinline__ float copy_sum1(const PeerPtrs &peers, int W, const T
     return acc;
 }
 
-// Pass-through tile of the reduce kernels: plain ordered sum of the stored values, written
-// as binary32 to dst (dst[j] for element j of the tile).
+// Pass-through tile of the reduce kernels: plain ordered sum of the stored values; element j
+// of the tile starts from / goes to position e0 + j of io.
 template <int DT>
-__device__ void reduce_copy(const PeerPtrs &peers, int W, bool accumulate, float *__restrict__ dst,
-                            const Tile &tile, bool fast, int lane)
+__device__ void reduce_copy(const PeerPtrs &peers, int W, const SumIo &io, int64_t e0, const Tile &tile, bool fast,
+                            int lane)
 {
     const uint32_t groups = fast ? tile.count / 8 : 0;
     for (uint32_t g = lane; g < groups; g += kWave) {
         float acc[8];
-        if (accumulate) {
-            load8<CGX_F32>(dst, int64_t(g) * 8, acc);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; j++) acc[j] = -0.0f;
-        }
+        init8(io, e0 + int64_t(g) * 8, acc);
         copy_sum8<DT>(peers, W, tile, g, acc);
-        float4v *p = reinterpret_cast<float4v *>(dst + g * 8);
-        p[0] = float4v{acc[0], acc[1], acc[2], acc[3]};
-        p[1] = float4v{acc[4], acc[5], acc[6], acc[7]};
+        store8(io, e0 + int64_t(g) * 8, acc);
     }
     for (uint32_t j = groups * 8 + lane; j < tile.count; j += kWave)
-        dst[j] = copy_sum1<DT>(peers, W, tile, j, accumulate ? dst[j] : -0.0f);
+        store1(io, e0 + j, copy_sum1<DT>(peers, W, tile, j, init1(io, e0 + j)));
 }
 
-__global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, int W, int dt, bool accumulate,
+__global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, int W, int dt, const SumIo io,
                                                          const Tile *__restrict__ tiles, int64_t n_tiles,
-                                                         int bucket, float *__restrict__ sum)
+                                                         int bucket)
 {
-    // per-wave staging area: a chunk of binary32 sums, or the packed bytes of a block of peers
+    // per-wave staging area: a chunk of binary32 results, or the packed bytes of a block of peers
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     const int lane = int(threadIdx.x) & 63;
@@ -742,13 +810,13 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         if (kind == kQuantFast) {
-            CGX_FOR_BITS(tile_bits(tile), (reduce_fast<BITS>(peers, W, accumulate, sum, tile, bucket, lane, stage)))
+            CGX_FOR_BITS(tile_bits(tile), (reduce_fast<BITS>(peers, W, io, tile, bucket, lane, stage)))
         } else if (kind == kQuantSlow) {
-            reduce_slow(peers, W, accumulate, sum, tile, bucket, lane);
+            reduce_slow(peers, W, io, tile, bucket, lane);
         } else if (dt == CGX_F16) {
-            reduce_copy<CGX_F16>(peers, W, accumulate, sum + tile.elem0, tile, kind == kCopyFast, lane);
+            reduce_copy<CGX_F16>(peers, W, io, tile.elem0, tile, kind == kCopyFast, lane);
         } else {
-            reduce_copy<CGX_F32>(peers, W, accumulate, sum + tile.elem0, tile, kind == kCopyFast, lane);
+            reduce_copy<CGX_F32>(peers, W, io, tile.elem0, tile, kind == kCopyFast, lane);
         }
     }
 }
@@ -800,15 +868,15 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int
             CGX_FOR_BITS(tile_bits(tile), (fused_fast<BITS>(peers, W, tile, out_off, bucket, seed_lo, seed_hi,
                                                              packed_out, meta_out, lane, stage)))
         } else if (kind == kQuantSlow) {
-            quantize_generic([&](uint32_t j) { return generic_sum(peers, W, tile, bucket, j, -0.0f); },
+            quantize_generic<false>([&](uint32_t j) { return generic_sum(peers, W, tile, bucket, j, -0.0f); },
                              packed_out + out_off, meta_out, tile, out_pad, bucket, seed_lo, seed_hi, lane);
         } else {
             // pass-through: the sum is written as binary32 into the output stream, then its padding
-            float *dst = reinterpret_cast<float *>(packed_out + out_off);
+            const SumIo io{nullptr, CGX_F32, packed_out + out_off, CGX_F32};
             if (dt == CGX_F16)
-                reduce_copy<CGX_F16>(peers, W, false, dst, tile, kind == kCopyFast, lane);
+                reduce_copy<CGX_F16>(peers, W, io, 0, tile, kind == kCopyFast, lane);
             else
-                reduce_copy<CGX_F32>(peers, W, false, dst, tile, kind == kCopyFast, lane);
+                reduce_copy<CGX_F32>(peers, W, io, 0, tile, kind == kCopyFast, lane);
             uint8_t *end = packed_out + out_off + uint64_t(tile.count) * 4;
             if (uint32_t(lane) < out_pad) end[lane] = 0;
         }
@@ -842,13 +910,13 @@ hipError_t launch_quantize(const void *grad, int dt, const Tile *tiles, int64_t 
 }
 
 hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
-                                 int32_t bucket, bool accumulate, float *sum, const LaunchConfig &cfg,
-                                 hipStream_t stream)
+                                 int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
+                                 const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
-    hipLaunchKernelGGL(reduce_kernel, grid, block, 0, stream, peers, W, dt, accumulate, tiles, n_tiles,
-                       int(bucket), sum);
+    const SumIo io{init, init_dt, out, out_dt};
+    hipLaunchKernelGGL(reduce_kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles, int(bucket));
     return hipGetLastError();
 }
 

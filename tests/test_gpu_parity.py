@@ -160,6 +160,38 @@ def test_fused_peer_counts(torch, oracle):
         gpu_fused(torch, list(chunks) + [chunks[0]], list(metas) + [metas[0]], w.offsets, w.bits, w.bucket, w.dt, 1)
 
 
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+def test_dequantize_and_local_addend(torch, oracle, dt):
+    """cgx_dequantize into binary32 / binary16 and cgx_dequant_reduce_add with a binary32 / binary16
+    local term, on a plan with vectorised, generic and pass-through tiles."""
+    sizes = [2048 * 3, 100, 2048 + 700, 8, 4096, 33, 2048 * 2]
+    bits = [4, 0, 3, 0, 8, 2, 1]
+    w = wl.Workload("mix", [(s,) for s in sizes], np.array(bits, np.uint8), 128, dt, 4, 321, wl._normal,
+                    np.linspace(0.01, 2.0, len(sizes)))
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    chunks, metas = zip(*[oracle.quantize(w.gradient(p), w.offsets, w.bits, w.bucket, 50 + p, w.dt) for p in range(20)])
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m.reshape(-1)) for m in metas]
+    for out_dt, tdt in ((wl.F32, torch.float32), (wl.F16, torch.float16)):
+        out = torch.full((w.n + 16,), 9.0, dtype=tdt, device="cuda")
+        cgx.cgx_dequantize(dp[0], dm[0], plan, out_dt, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert (got[w.n:] == 9.0).all()
+        want = oracle.dequantize(chunks[0], metas[0], w.offsets, w.bits, w.bucket, w.dt, out_dt)
+        assert got[:w.n].tobytes() == want.tobytes(), f"dequantize to {'f16' if out_dt else 'f32'}"
+    for W in (3, 20):
+        for local in (w.gradient(99).astype(np.float32), w.gradient(99).astype(np.float16)):
+            total = torch.full((w.n + 16,), 9.0, dtype=torch.float32, device="cuda")
+            cgx.cgx_dequant_reduce_add(dev(torch, local), wl.F16 if local.dtype == np.float16 else wl.F32,
+                                       dp[:W], dm[:W], plan, total)
+            torch.cuda.synchronize()
+            got = total.cpu().numpy()
+            assert (got[w.n:] == 9.0).all()
+            ref = oracle.dequant_reduce(list(chunks[:W]), list(metas[:W]), w.offsets, w.bits, w.bucket, w.dt, local=local)
+            assert_sum_parity(got[:w.n], ref, f"local addend W={W} {local.dtype}")
+
+
 def test_degenerate_values(torch, oracle):
     """Constant, zero, signed-zero, subnormal and huge buckets; exact grids."""
     B, n = 128, 128 * 24

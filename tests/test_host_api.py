@@ -111,6 +111,12 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, None, None) == -1
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 128, 0, buf + 4, None) == -9
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 300, 2, o, b, 48, 0, buf, None) == -5
+    assert lib.cgx_dequant_reduce_add(None, 0, ptrs, ptrs, 2, 300, 2, o, b, 128, 0, buf, None) == -1
+    assert lib.cgx_dequant_reduce_add(buf, 2, ptrs, ptrs, 2, 300, 2, o, b, 128, 0, buf, None) == -7
+    assert lib.cgx_dequant_reduce_add(buf + 2, 1, ptrs, ptrs, 2, 300, 2, o, b, 128, 0, buf, None) == -9
+    assert lib.cgx_dequantize(None, buf, 300, 2, o, b, 128, 0, 0, buf, None) == -1
+    assert lib.cgx_dequantize(buf, buf, 300, 2, o, b, 128, 0, 4, buf, None) == -7
+    assert lib.cgx_dequantize(buf, buf, 300, 2, o, b, 128, 0, 1, None, None) == -1
     fused = lib.cgx_dequant_reduce_requantize
     assert fused(ptrs, ptrs, 0, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
     assert fused(ptrs, ptrs, 17, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6

@@ -392,6 +392,44 @@ def test_mean_of_sums_converges(oracle):
     assert 3.0 < spread[1] / spread[16] < 5.5           # sqrt(16) = 4
 
 
+def test_half_conversion_matches_ieee_rounding(oracle):
+    """binary32 -> binary16 with ties to even: numpy's conversion is the reference routine."""
+    rng = np.random.default_rng(0)
+    x = np.concatenate([
+        rng.standard_normal(200000).astype(np.float32) * np.float32(10.0) ** rng.integers(-9, 5, 200000).astype(np.float32),
+        np.arange(0, 70000, 0.25, dtype=np.float32),                       # around the overflow threshold
+        np.float32(2.0 ** -24) * np.arange(0, 4096, 0.125, dtype=np.float32),   # subnormal halves and their ties
+        np.array([0.0, -0.0, np.inf, -np.inf, 65504.0, 65519.99, 65520.0, 1e-10, -1e-10], np.float32),
+        np.arange(2048, 4096, 0.5, dtype=np.float32),                      # exact ties in the normal range
+    ])
+    x = np.concatenate([x, -x])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.float_to_half(x), want)
+    assert oracle.float_to_half(np.array([np.nan], np.float32))[0] & 0x7c00 == 0x7c00
+
+
+def test_local_addend_comes_first(oracle):
+    """sum = local + deq_0 + deq_1 ...: equals the plain reduce when local is -0, and
+    equals numpy's ordered binary32 sum of the separately dequantized terms."""
+    w = wl.tiny_mixed(seed=12)
+    chunks, metas = zip(*[oracle.quantize(w.gradient(p), w.offsets, w.bits, w.bucket, p) for p in range(3)])
+    plain = oracle.dequant_reduce(list(chunks), list(metas), w.offsets, w.bits, w.bucket)
+    zero = np.full(w.n, -0.0, np.float32)
+    same = oracle.dequant_reduce(list(chunks), list(metas), w.offsets, w.bits, w.bucket, local=zero)
+    assert np.array_equal(plain["sum32"].view(np.uint32), same["sum32"].view(np.uint32))
+    for local in (w.gradient(7), w.gradient(7).astype(np.float16)):
+        got = oracle.dequant_reduce(list(chunks), list(metas), w.offsets, w.bits, w.bucket, local=local)
+        terms = [oracle.dequantize(c, m, w.offsets, w.bits, w.bucket) for c, m in zip(chunks, metas)]
+        acc = local.astype(np.float32)
+        acc64 = local.astype(np.float64)
+        for t in terms:
+            acc = acc + t
+        assert np.array_equal(got["sum32"], acc)
+        approx = acc64 + sum(t.astype(np.float64) for t in terms)          # terms rounded to binary32 once
+        assert (np.abs(got["sum64"] - approx) <= 1e-6 * got["abs64"] + 1e-30).all()
+
+
 def test_oracle_is_deterministic_and_thread_independent(oracle):
     w = wl.tiny_mixed(seed=1)
     g = w.gradient()
