@@ -199,6 +199,29 @@ def main():
             },
         }
 
+    # what the memory system gives a plain streaming kernel with each call's read:write mix at its size
+    def probe_ms(read_bytes, write_bytes):
+        rb, wb = read_bytes // 16 * 16, write_bytes // 16 * 16
+        srcs = [torch.empty(rb, dtype=torch.uint8, device=dev) for _ in range(R)]
+        dsts = [torch.empty(max(wb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
+        for i in range(max(args.warmup // 2, 2)):
+            cgx.cgx_stream_probe(srcs[i % R], rb, dsts[i % R], wb)
+        reps = max(args.steps // 2, 5)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+        torch.cuda.synchronize()
+        for i in range(reps):
+            evs[i][0].record()
+            cgx.cgx_stream_probe(srcs[i % R], rb, dsts[i % R], wb)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+    probe = {
+        "quantize": probe_ms(w.n * S, alg["quantize"] - w.n * S),
+        "dequant_reduce": probe_ms(alg["dequant_reduce"] - 4 * m, 4 * m),
+        "requantize": probe_ms(4 * m, alg["requantize"] - 4 * m),
+    }
+
     if args.calibration_copy:
         # an elementwise kernel that reads 1 GiB and writes 1 GiB (grid unlike any cgx launch)
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
@@ -220,6 +243,9 @@ def main():
             "algorithmic_bytes": int(alg[k]),
             "algorithmic_GBps": round(alg[k] / kern_ms[k] / 1e6, 1),
             "hbm_frac": round(alg[k] / kern_ms[k] / 1e6 / HBM_PEAK_GBPS, 4),
+            "stream_probe_ms": round(probe[k], 5),
+            "stream_probe_GBps": round(alg[k] // 16 * 16 / probe[k] / 1e6, 1),
+            "frac_of_stream_probe": round(probe[k] / kern_ms[k], 4),
         }
     dominant = max(names, key=lambda k: kern_ms[k])
     achieved = alg[dominant] / kern_ms[dominant] / 1e6

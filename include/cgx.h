@@ -174,6 +174,16 @@ int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uin
                    int32_t bucket, cgx_dtype dt, void *tiles_out /* host */, int64_t capacity,
                    int64_t *n_tiles);
 
+/*
+ * Measurement aid, not part of the method: one launch that reads read_bytes from src and
+ * writes write_bytes to dst (both device, 16-byte aligned, sizes multiples of 16) with the
+ * kernels' access style (one wavefront per 8 KB slice, non-temporal 16-byte vectors,
+ * lane-contiguous) and no arithmetic.  Its rate is what the memory system gives a kernel with
+ * that read:write mix at that size; the benchmark reports it next to each kernel.  What is
+ * written to dst is unspecified.
+ */
+int cgx_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *cgx_status_string(int status);
 

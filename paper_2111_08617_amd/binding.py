@@ -22,7 +22,7 @@ MAX_FUSED_PEERS = 16
 
 EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduce_add", "cgx_dequantize",
            "cgx_requantize",
-           "cgx_dequant_reduce_requantize", "cgx_plan_tiles",
+           "cgx_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -57,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.cgx_dequantize.argtypes = [c.c_void_p, c.c_void_p] + plan + [c.c_int, c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
             [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_stream_probe.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_status_string.restype = c.c_char_p
         L.cgx_status_string.argtypes = [c.c_int]
@@ -172,6 +173,12 @@ def cgx_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, 
     _check(lib().cgx_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
                                                packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
            "cgx_dequant_reduce_requantize")
+
+
+def cgx_stream_probe(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:
+    """Measurement aid: one launch reading read_bytes from src and writing write_bytes to dst."""
+    _check(lib().cgx_stream_probe(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes, _stream(stream)),
+           "cgx_stream_probe")
 
 
 def cgx_shutdown() -> None:

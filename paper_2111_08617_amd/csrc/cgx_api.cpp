@@ -258,6 +258,15 @@ int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uin
     return CGX_OK;
 }
 
+int cgx_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream)
+{
+    if ((read_bytes && !src) || (write_bytes && !dst)) return CGX_ERR_NULL;
+    if (read_bytes % 16 || write_bytes % 16) return CGX_ERR_SIZE;
+    if (misaligned(src) || misaligned(dst)) return CGX_ERR_ALIGN;
+    const hipError_t e = cgx::launch_stream_probe(src, read_bytes, dst, write_bytes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
 const char *cgx_status_string(int status)
 {
     switch (status) {

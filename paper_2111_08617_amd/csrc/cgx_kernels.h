@@ -38,4 +38,9 @@ hipError_t launch_dequant_reduce_requantize(const PeerPtrs &peers, int W, int dt
                                             uint64_t seed, void *packed_out, void *meta_out,
                                             const LaunchConfig &cfg, hipStream_t stream);
 
+// Measurement aid: streams read_bytes in and write_bytes out (multiples of 16) with the access
+// style of the kernels and no arithmetic; see cgx_stream_probe in cgx.h.
+hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes,
+                               hipStream_t stream);
+
 }  // namespace cgx

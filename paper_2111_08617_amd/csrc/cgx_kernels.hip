@@ -883,6 +883,35 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int
     }
 }
 
+// ---------------------------------------------------------------- streaming probe
+
+// Measurement aid: moves read_bytes in and write_bytes out with the access style of the
+// kernels above (one wave per slice, lane-contiguous non-temporal 16-byte vectors) and no
+// arithmetic to speak of.  Its rate is what the memory system gives a kernel with that
+// read:write mix at that size.
+__global__ __launch_bounds__(kBlock) void stream_probe_kernel(const uint4v *__restrict__ src, int64_t read_vecs,
+                                                               uint4v *__restrict__ dst, int64_t write_vecs,
+                                                               int64_t waves)
+{
+    const int64_t wave = int64_t(blockIdx.x) * kWavesPerBlock + (int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    if (wave >= waves) return;
+    const int64_t r0 = read_vecs * wave / waves, r1 = read_vecs * (wave + 1) / waves;
+    const int64_t w0 = write_vecs * wave / waves, w1 = write_vecs * (wave + 1) / waves;
+    uint4v acc = {0u, 0u, 0u, 0u};
+    for (int64_t v = r0 + lane; v < r1; v += 8 * kWave) {
+        uint4v x[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const int64_t i = v + u * kWave;
+            x[u] = i < r1 ? stream_load(src + i) : uint4v{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc += x[u];
+    }
+    for (int64_t v = w0 + lane; v < w1; v += kWave) stream_store(dst + v, acc + uint32_t(v));
+}
+
 inline unsigned grid_for(int64_t n_tiles, const LaunchConfig &cfg)
 {
     int64_t blocks = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -930,6 +959,18 @@ hipError_t launch_dequant_reduce_requantize(const PeerPtrs &peers, int W, int dt
     hipLaunchKernelGGL(fused_kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles,
                        int(bucket), uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
                        static_cast<float2 *>(meta_out));
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, hipStream_t stream)
+{
+    const int64_t read_vecs = int64_t(read_bytes / 16), write_vecs = int64_t(write_bytes / 16);
+    const int64_t larger = read_vecs > write_vecs ? read_vecs : write_vecs;
+    const int64_t waves = (larger + 511) / 512;                 // 8 KB of the larger side per wave
+    if (waves == 0) return hipSuccess;
+    const dim3 grid(unsigned((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(kBlock);
+    hipLaunchKernelGGL(stream_probe_kernel, grid, block, 0, stream, static_cast<const uint4v *>(src), read_vecs,
+                       static_cast<uint4v *>(dst), write_vecs, waves);
     return hipGetLastError();
 }
 

@@ -117,6 +117,9 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.cgx_dequantize(None, buf, 300, 2, o, b, 128, 0, 0, buf, None) == -1
     assert lib.cgx_dequantize(buf, buf, 300, 2, o, b, 128, 0, 4, buf, None) == -7
     assert lib.cgx_dequantize(buf, buf, 300, 2, o, b, 128, 0, 1, None, None) == -1
+    assert lib.cgx_stream_probe(None, 1024, buf, 1024, None) == -1
+    assert lib.cgx_stream_probe(buf, 1000, buf, 1024, None) == -2
+    assert lib.cgx_stream_probe(buf + 4, 1024, buf, 1024, None) == -9
     fused = lib.cgx_dequant_reduce_requantize
     assert fused(ptrs, ptrs, 0, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
     assert fused(ptrs, ptrs, 17, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
