@@ -49,6 +49,7 @@ def _load():
         plan = [c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int32]
         lib.oracle_sizes.argtypes = plan + [c.c_int32, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64)]
         lib.oracle_quantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int32, c.c_void_p, c.c_void_p]
+        lib.oracle_quantize_window.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int32, c.c_uint64, c.c_void_p, c.c_void_p]
         lib.oracle_quantize_with_draws.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -120,8 +121,9 @@ def _grad(grad, n, dt):
     return g
 
 
-def quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=None):
-    """Returns (packed uint8[packed_bytes], meta float32[n_buckets, 2] = (unit, mn))."""
+def quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=None, index_base: int = 0):
+    """Returns (packed uint8[packed_bytes], meta float32[n_buckets, 2] = (unit, mn)).
+    index_base: position of grad[0] in the whole buffer when grad is a window of it."""
     off, bt, n, L = _plan(offsets, bits)
     g = _grad(grad, n, dt)
     pb, mb = sizes(off, bt, bucket, dt)
@@ -129,8 +131,8 @@ def quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=N
     meta = np.zeros((mb // 8, 2), dtype=np.float32)
     lib = _load()
     if draws is None:
-        rc = lib.oracle_quantize(_ptr(g), n, L, _ptr(off), _ptr(bt), bucket, seed & (2**64 - 1), dt,
-                                 _ptr(packed), _ptr(meta))
+        rc = lib.oracle_quantize_window(_ptr(g), n, L, _ptr(off), _ptr(bt), bucket, seed & (2**64 - 1), dt,
+                                        index_base, _ptr(packed), _ptr(meta))
     else:
         d = np.ascontiguousarray(draws, dtype=np.uint16)
         if d.size != n:

@@ -261,7 +261,7 @@ static uint32_t get_bits(const uint8_t *stream, uint64_t bitpos, int b)
  */
 static int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off,
                          const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
-                         const uint16_t *draws, uint8_t *packed, float *meta)
+                         const uint16_t *draws, uint64_t index_base, uint8_t *packed, float *meta)
 {
     int rc = check_plan(n, L, off, bits, bucket, dt);
     if (rc) return rc;
@@ -288,8 +288,8 @@ static int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *
                 meta[2 * (bucket0 + k) + 0] = unit;
                 meta[2 * (bucket0 + k) + 1] = mn;
                 for (int64_t j = j0; j < j0 + count; j++) {
-                    uint64_t i = (uint64_t)(first + j);      /* index in the whole buffer */
-                    uint32_t u16 = draws ? draws[i] : oracle_u16(seed, i);
+                    uint64_t i = (uint64_t)(first + j);      /* index in the buffer handed in */
+                    uint32_t u16 = draws ? draws[i] : oracle_u16(seed, index_base + i);
                     uint32_t q = quantize_elem(load_elem(grad, first + j, dt), mn, inv16, b, u16);
                     put_bits(seg, (uint64_t)j * b, q, b);
                 }
@@ -305,7 +305,20 @@ int oracle_quantize(const void *grad, int64_t n, int32_t L, const int64_t *off,
                     const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
                     uint8_t *packed, float *meta)
 {
-    return quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, packed, meta);
+    return quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, 0, packed, meta);
+}
+
+/*
+ * The same for a window of a larger buffer: element i of `grad` is element
+ * index_base + i of that buffer, which only matters for the draws (they are keyed on
+ * the position in the whole buffer).  Lets a test check a slice of a buffer too
+ * large to hand to the oracle in one piece.
+ */
+int oracle_quantize_window(const void *grad, int64_t n, int32_t L, const int64_t *off,
+                           const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
+                           uint64_t index_base, uint8_t *packed, float *meta)
+{
+    return quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, index_base, packed, meta);
 }
 
 int oracle_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int64_t *off,
@@ -313,7 +326,7 @@ int oracle_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int
                                const uint16_t *draws, uint8_t *packed, float *meta)
 {
     if (!draws) return ORACLE_ERR_ARG;
-    return quantize_impl(grad, n, L, off, bits, bucket, 0, dt, draws, packed, meta);
+    return quantize_impl(grad, n, L, off, bits, bucket, 0, dt, draws, 0, packed, meta);
 }
 
 /* ---- dequantize and reduce ---------------------------------------------- */

@@ -316,3 +316,105 @@ def test_decoder_1p3b_config_full_size(torch, oracle):
     assert_same_chunk(gp, gm, op, om, "decoder_1p3b quantize")
     del g, gp, op
     share_cycle(torch, oracle, w, rank=4, what="decoder_1p3b")
+
+
+def test_indices_beyond_2_to_33(torch, oracle):
+    """Maximum sizes: a binary16 buffer of 2^33 + 3 M elements.  Element indices need more than
+    32 bits, the generator's key changes at element 2^33, and one tile straddles that point
+    (it takes the generic path).  Windows at the start, around 2^33 and at the ragged end are
+    compared with the oracle run on the same slices."""
+    B, b, seed = 1024, 2, 2**40 + 7
+    head = 1024                                   # shifts the big layer so that 2^33 falls inside a chunk
+    n = (1 << 33) + 3 * (1 << 20) + 1000
+    offsets = np.array([0, head, n], np.int64)
+    bits = np.array([4, b], np.uint8)
+    plan = cgx.Plan(offsets, bits, B, wl.F16)
+    tiles = cgx.cgx_plan_tiles(plan)
+    straddle = tiles[(tiles["elem0"] < (1 << 33)) & (tiles["elem0"] + tiles["count"].astype(np.int64) > (1 << 33))]
+    assert straddle.size == 1 and (int(straddle["info"][0]) >> 4) & 15 == 0
+    grad = torch.empty(n, dtype=torch.float16, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    step = 1 << 28
+    for a in range(0, n, step):
+        e = min(a + step, n)
+        grad[a:e] = torch.randn(e - a, device="cuda", generator=gen, dtype=torch.float32).to(torch.float16)
+    pb, mb = cgx.cgx_sizes(plan)
+    packed = torch.empty(pb, dtype=torch.uint8, device="cuda")
+    meta = torch.empty(mb // 4, dtype=torch.float32, device="cuda")
+    cgx.cgx_quantize(grad, plan, seed, packed, meta)
+    torch.cuda.synchronize()
+    seg1 = head * 4 // 8                          # first layer: 512 bytes, already a multiple of 16
+    windows = [(head, head + (1 << 20)), ((1 << 33) - (1 << 20) + head, (1 << 33) + (1 << 20) + head),
+               (n - ((n - head) % B) - 512 * B, n)]
+    for a, e in windows:
+        assert (a - head) % B == 0
+        x = grad[a:e].cpu().numpy()
+        op, om = oracle.quantize(x, np.array([0, e - a], np.int64), np.array([b], np.uint8), B, seed, wl.F16,
+                                 index_base=a)
+        nbytes = -(-(e - a) * b // 8)
+        lo = seg1 + (a - head) * b // 8
+        gp = packed[lo:lo + nbytes].cpu().numpy()
+        g0 = 1 + (a - head) // B                  # one bucket in the first layer
+        gm = meta[2 * g0:2 * (g0 + om.shape[0])].cpu().numpy().reshape(-1, 2)
+        assert_same_chunk(gp, gm, op[:nbytes], om, f"window [{a}, {e})")
+    # the reduce side reads the same positions: dequantize the last window's chunk region and compare
+    del grad
+    out = torch.empty(n, dtype=torch.float16, device="cuda")
+    cgx.cgx_dequantize(packed, meta, plan, wl.F16, out)
+    torch.cuda.synchronize()
+    a, e = windows[1]
+    x_codes = packed[seg1 + (a - head) * b // 8: seg1 + (e - head) * b // 8].cpu().numpy()
+    m_win = meta[2 * (1 + (a - head) // B):2 * (1 + (e - head) // B)].cpu().numpy().reshape(-1, 2)
+    want = oracle.dequantize(np.concatenate([x_codes, np.zeros((-x_codes.size) % 16, np.uint8)]), m_win,
+                             np.array([0, e - a], np.int64), np.array([b], np.uint8), B, wl.F16, wl.F16)
+    assert out[a:e].cpu().numpy().tobytes() == want.tobytes()
+
+
+def test_non_finite_inputs_do_not_disturb_other_buckets(torch, oracle):
+    """NaN and infinities violate the precondition: their own buckets are unspecified, but
+    nothing is written out of bounds and every other bucket still matches the oracle."""
+    rng = np.random.default_rng(11)
+    B, n = 128, 128 * 64 + 77
+    x = rng.standard_normal(n).astype(np.float32)
+    bad = {3: np.nan, 10: np.inf, 20: -np.inf, 33: np.nan, 64: np.inf}
+    for k, v in bad.items():
+        x[k * B + 5] = v
+    x[33 * B + 6] = np.inf
+    for b in (2, 4, 8):
+        off, bits = np.array([0, n], np.int64), np.array([b], np.uint8)
+        gp, gm = gpu_quantize(torch, x, off, bits, B, 9, wl.F32)         # checks the canaries
+        op, om = oracle.quantize(x, off, bits, B, 9, wl.F32)
+        good = np.array([k not in bad for k in range(om.shape[0])])
+        assert gm[good].tobytes() == om[good].tobytes()
+        per = B * b // 8
+        nb_full = n // B
+        gpb, opb = gp[:nb_full * per].reshape(nb_full, per), op[:nb_full * per].reshape(nb_full, per)
+        assert np.array_equal(gpb[good[:nb_full]], opb[good[:nb_full]])
+        assert np.array_equal(gp[nb_full * per:], op[nb_full * per:])
+
+
+def test_result_does_not_depend_on_launch_geometry(torch, oracle):
+    """Counter-based draws: tiles of several chunks and a small persistent grid give the same bytes."""
+    import hashlib
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys, hashlib, numpy as np, torch; sys.path.insert(0, %r)\n"
+        "from paper_2111_08617_amd import binding as cgx, workloads as wl\n"
+        "w = wl.Workload('g', [(2048 * 37 + 300,), (500,), (2048 * 64,)], np.array([4, 0, 2], np.uint8), 256, wl.F32, 2, 5,\n"
+        "                wl._normal, np.array([1.0, 1.0, 0.1]))\n"
+        "plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt); pb, mb = cgx.cgx_sizes(plan)\n"
+        "p = torch.zeros(pb, dtype=torch.uint8, device='cuda'); m = torch.zeros(mb // 4, device='cuda')\n"
+        "cgx.cgx_quantize(torch.from_numpy(w.gradient()).cuda(), plan, 77, p, m); torch.cuda.synchronize()\n"
+        "s = torch.zeros(w.n, device='cuda'); cgx.cgx_dequant_reduce([p, p], [m, m], plan, s); torch.cuda.synchronize()\n"
+        "print(hashlib.sha256(p.cpu().numpy().tobytes() + m.cpu().numpy().tobytes() + s.cpu().numpy().tobytes()).hexdigest())\n"
+    ) % root
+    digests = set()
+    for env in ({}, {"CGX_CHUNKS_PER_TILE": "3"}, {"CGX_CHUNKS_PER_TILE": "8", "CGX_MAX_BLOCKS": "5"}):
+        out = subprocess.run([sys.executable, "-c", code], env={**os.environ, **env}, capture_output=True, text=True,
+                             timeout=300)
+        assert out.returncode == 0, out.stderr[-2000:]
+        digests.add(out.stdout.strip().splitlines()[-1])
+    assert len(digests) == 1

@@ -430,6 +430,20 @@ def test_local_addend_comes_first(oracle):
         assert (np.abs(got["sum64"] - approx) <= 1e-6 * got["abs64"] + 1e-30).all()
 
 
+def test_window_of_a_buffer_equals_the_slice_of_the_whole(oracle):
+    """Quantizing elements [a, b) of a layer as a window (bucket aligned) gives the bytes the
+    whole buffer gives for that range."""
+    rng = np.random.default_rng(3)
+    n, B, b = 64 * 40, 64, 3
+    x = rng.standard_normal(n).astype(np.float32)
+    off, bits = one_layer(n, b)
+    p, m = oracle.quantize(x, off, bits, B, seed=17)
+    a, e = 64 * 7, 64 * 23
+    pw, mw = oracle.quantize(x[a:e], *one_layer(e - a, b), B, seed=17, index_base=a)
+    assert np.array_equal(pw[:(e - a) * b // 8], p[a * b // 8:e * b // 8])
+    assert mw.tobytes() == m[a // B:e // B].tobytes()
+
+
 def test_oracle_is_deterministic_and_thread_independent(oracle):
     w = wl.tiny_mixed(seed=1)
     g = w.gradient()
