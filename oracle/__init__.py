@@ -57,6 +57,11 @@ def _load():
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_float_to_half.restype = None
         lib.oracle_float_to_half.argtypes = [c.c_void_p, c.c_int64, c.c_void_p]
+        lib.oracle_qsgd_sizes.argtypes = plan + [c.c_int32, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64)]
+        lib.oracle_qsgd_quantize.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int32, c.c_void_p, c.c_void_p]
+        lib.oracle_qsgd_quantize_with_draws.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_qsgd_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
+            [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_unpack_codes.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p]
         _lib = lib
     return _lib
@@ -197,3 +202,59 @@ def unpack_codes(packed, offsets, bits, bucket: int, dt: int = F32):
     codes = np.zeros(n, dtype=np.uint8)
     _check(_load().oracle_unpack_codes(_ptr(p), n, L, _ptr(off), _ptr(bt), bucket, dt, _ptr(codes)), "unpack_codes")
     return codes
+
+
+# ---- the norm-and-sign form (see the second half of cgx_oracle.c)
+
+def qsgd_sizes(offsets, bits, bucket: int, dt: int = F32):
+    off, bt, n, L = _plan(offsets, bits)
+    pb, mb = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(_load().oracle_qsgd_sizes(n, L, _ptr(off), _ptr(bt), bucket, dt, ctypes.byref(pb), ctypes.byref(mb)),
+           "qsgd_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def qsgd_quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=None):
+    """Returns (packed uint8[packed_bytes], meta float32[n_buckets] = unit)."""
+    off, bt, n, L = _plan(offsets, bits)
+    g = _grad(grad, n, dt)
+    pb, mb = qsgd_sizes(off, bt, bucket, dt)
+    packed = np.zeros(pb, dtype=np.uint8)
+    meta = np.zeros(mb // 4, dtype=np.float32)
+    lib = _load()
+    if draws is None:
+        rc = lib.oracle_qsgd_quantize(_ptr(g), n, L, _ptr(off), _ptr(bt), bucket, seed & (2**64 - 1), dt,
+                                      _ptr(packed), _ptr(meta))
+    else:
+        d = np.ascontiguousarray(draws, dtype=np.uint16)
+        if d.size != n:
+            raise ValueError("one draw per element")
+        rc = lib.oracle_qsgd_quantize_with_draws(_ptr(g), n, L, _ptr(off), _ptr(bt), bucket, dt, _ptr(d),
+                                                 _ptr(packed), _ptr(meta))
+    _check(rc, "qsgd_quantize")
+    return packed, meta
+
+
+def qsgd_dequant_reduce(packed_list, meta_list, offsets, bits, bucket: int, dt: int = F32,
+                        want=("sum32", "sum64", "abs64")):
+    off, bt, n, L = _plan(offsets, bits)
+    W = len(packed_list)
+    if W < 1 or len(meta_list) != W:
+        raise ValueError("need W >= 1 packed chunks and as many meta arrays")
+    pb, mb = qsgd_sizes(off, bt, bucket, dt)
+    pk = [np.ascontiguousarray(p, dtype=np.uint8) for p in packed_list]
+    mt = [np.ascontiguousarray(m, dtype=np.float32) for m in meta_list]
+    for p, m in zip(pk, mt):
+        if p.size != pb or m.size * 4 != mb:
+            raise ValueError("chunk sizes do not match the plan")
+    pp = (ctypes.c_void_p * W)(*[p.ctypes.data for p in pk])
+    mp = (ctypes.c_void_p * W)(*[m.ctypes.data for m in mt])
+    out = {
+        "sum32": np.zeros(n, dtype=np.float32) if "sum32" in want else None,
+        "sum64": np.zeros(n, dtype=np.float64) if "sum64" in want else None,
+        "abs64": np.zeros(n, dtype=np.float64) if "abs64" in want else None,
+    }
+    rc = _load().oracle_qsgd_dequant_reduce(pp, mp, W, n, L, _ptr(off), _ptr(bt), bucket, dt,
+                                            _ptr(out["sum32"]), _ptr(out["sum64"]), _ptr(out["abs64"]))
+    _check(rc, "qsgd_dequant_reduce")
+    return {k: v for k, v in out.items() if v is not None}

@@ -44,6 +44,9 @@
  *   - dequantized value = fma(q, unit, mn) in binary32; the reduce adds the
  *     peers in ascending order in binary32 (sum32) and, separately, evaluates
  *     sum_w (mn_w + q_w * unit_w) in binary64 (sum64).
+ *   - the second half of the file holds the norm-and-sign form of the same
+ *     quantizer (the formula Q_s of Sec. 2.2 taken literally), with its own
+ *     header comment.
  *
  * Build:  gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  */
@@ -420,6 +423,161 @@ int oracle_unpack_codes(const uint8_t *packed, int64_t n, int32_t L, const int64
         for (int64_t j = 0; j < len; j++)
             codes[first + j] = b ? (uint8_t)get_bits(packed + seg_start, (uint64_t)j * b, b) : 0xff;
         seg_start += seg_bytes;
+    }
+    return ORACLE_OK;
+}
+
+/* ======================================================================== *
+ * The norm-and-sign form of the quantizer, as the paper prints it
+ * (Sec. 2.2: Q_s(v_i) = ||v|| * sign(v_i) * q(|v_i| / ||v||, s)), per bucket.
+ *
+ * Readings: the norm is the maximum absolute value of the bucket (so that
+ * |v_i| / ||v|| covers [0, 1] and no summation order enters the result); a
+ * b-bit code is one sign bit (the top bit; set when the sign bit of v_i is
+ * set) and b-1 bits of level, s = 2^(b-1) - 1 intervals, b >= 2; meta is ONE
+ * float per bucket, unit = ||v|| / s; the level is drawn exactly as in the
+ * min/max form: inv16 = (s * 65536) / ||v||, T = trunc(|v_i| * inv16),
+ * level = min(floor((T + u) / 65536), s); the value of a code is level * unit
+ * (one binary32 multiplication), negated when the sign bit is set.  Layout,
+ * draws, pass-through layers and the order of the sum are those of the
+ * min/max form.
+ * ======================================================================== */
+
+static int check_qsgd_bits(int32_t L, const uint8_t *bits)
+{
+    for (int32_t l = 0; l < L; l++)
+        if (bits[l] == 1) return ORACLE_ERR_ARG;     /* a sign bit alone carries no level */
+    return ORACLE_OK;
+}
+
+int oracle_qsgd_sizes(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                      int32_t bucket, int32_t dt, uint64_t *packed_bytes, uint64_t *meta_bytes)
+{
+    uint64_t mb = 0;
+    int rc = oracle_sizes(n, L, off, bits, bucket, dt, packed_bytes, &mb);
+    if (rc) return rc;
+    if (check_qsgd_bits(L, bits)) return ORACLE_ERR_ARG;
+    if (meta_bytes) *meta_bytes = mb / 2;            /* one float per bucket instead of two */
+    return ORACLE_OK;
+}
+
+static int qsgd_quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off,
+                              const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
+                              const uint16_t *draws, uint8_t *packed, float *meta)
+{
+    int rc = check_plan(n, L, off, bits, bucket, dt);
+    if (rc) return rc;
+    if (check_qsgd_bits(L, bits)) return ORACLE_ERR_ARG;
+    uint64_t seg_start = 0, bucket0 = 0;
+    for (int32_t l = 0; l < L; l++) {
+        int64_t first = off[l], len = off[l + 1] - off[l];
+        int b = bits[l];
+        uint64_t seg_bytes, n_buckets;
+        layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
+        if (len == 0) continue;
+        uint8_t *seg = packed + seg_start;
+        memset(seg, 0, seg_bytes);
+        if (b == 0) {
+            memcpy(seg, (const uint8_t *)grad + (uint64_t)first * elem_size(dt), (uint64_t)len * elem_size(dt));
+        } else {
+            const uint32_t s = (1u << (b - 1)) - 1u;         /* intervals of the level grid */
+#pragma omp parallel for schedule(static)
+            for (int64_t k = 0; k < (int64_t)n_buckets; k++) {
+                int64_t j0 = k * bucket;
+                int64_t count = len - j0 < bucket ? len - j0 : bucket;
+                float norm = 0.0f;
+                for (int64_t j = j0; j < j0 + count; j++) {
+                    float a = fabsf(load_elem(grad, first + j, dt));
+                    if (a > norm) norm = a;
+                }
+                float unit = norm / (float)s;
+                float inv16 = (float)(s * 65536u) / norm;
+                if (!(unit > 0.0f) || !isfinite(unit) || !isfinite(inv16)) {
+                    unit = 0.0f;
+                    inv16 = 0.0f;
+                }
+                meta[bucket0 + k] = unit;
+                for (int64_t j = j0; j < j0 + count; j++) {
+                    uint64_t i = (uint64_t)(first + j);
+                    uint32_t u16 = draws ? draws[i] : oracle_u16(seed, i);
+                    float x = load_elem(grad, first + j, dt);
+                    float S = fabsf(x) * inv16;
+                    uint64_t T;
+                    if (!(S >= 0.0f)) T = 0;
+                    else if (S >= 4294967296.0f) T = 0xffffffffu;
+                    else T = (uint64_t)S;
+                    uint64_t level = (T + u16) >> 16;
+                    if (level > s) level = s;
+                    uint32_t code = (uint32_t)level | ((signbit(x) ? 1u : 0u) << (b - 1));
+                    put_bits(seg, (uint64_t)j * b, code, b);
+                }
+            }
+        }
+        seg_start += seg_bytes;
+        bucket0 += n_buckets;
+    }
+    return ORACLE_OK;
+}
+
+int oracle_qsgd_quantize(const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                         int32_t bucket, uint64_t seed, int32_t dt, uint8_t *packed, float *meta)
+{
+    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, packed, meta);
+}
+
+int oracle_qsgd_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int64_t *off,
+                                    const uint8_t *bits, int32_t bucket, int32_t dt, const uint16_t *draws,
+                                    uint8_t *packed, float *meta)
+{
+    if (!draws) return ORACLE_ERR_ARG;
+    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, 0, dt, draws, packed, meta);
+}
+
+/* Sum over the W peers of the decoded values; outputs as in oracle_dequant_reduce. */
+int oracle_qsgd_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W, int64_t n,
+                               int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int32_t dt,
+                               float *sum32, double *sum64, double *abs64)
+{
+    int rc = check_plan(n, L, off, bits, bucket, dt);
+    if (rc) return rc;
+    if (check_qsgd_bits(L, bits) || W < 1 || !packed || !meta) return ORACLE_ERR_ARG;
+    uint64_t seg_start = 0, bucket0 = 0;
+    for (int32_t l = 0; l < L; l++) {
+        int64_t first = off[l], len = off[l + 1] - off[l];
+        int b = bits[l];
+        uint64_t seg_bytes, n_buckets;
+        layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
+        if (len == 0) continue;
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < len; j++) {
+            float acc32 = 0.0f;
+            double acc64 = 0.0, accabs = 0.0;
+            for (int32_t w = 0; w < W; w++) {
+                const uint8_t *seg = packed[w] + seg_start;
+                float v32;
+                double v64;
+                if (b == 0) {
+                    v32 = load_elem(seg, j, dt);
+                    v64 = (double)v32;
+                } else {
+                    float unit = meta[w][bucket0 + (uint64_t)(j / bucket)];
+                    uint32_t code = get_bits(seg, (uint64_t)j * b, b);
+                    uint32_t level = code & ((1u << (b - 1)) - 1u);
+                    int negative = (int)(code >> (b - 1));
+                    v32 = (float)level * unit;
+                    v64 = (double)level * (double)unit;
+                    if (negative) { v32 = -v32; v64 = -v64; }
+                }
+                acc32 = (w == 0) ? v32 : acc32 + v32;
+                acc64 += v64;
+                accabs += fabs(v64);
+            }
+            if (sum32) sum32[first + j] = acc32;
+            if (sum64) sum64[first + j] = acc64;
+            if (abs64) abs64[first + j] = accabs;
+        }
+        seg_start += seg_bytes;
+        bucket0 += n_buckets;
     }
     return ORACLE_OK;
 }
