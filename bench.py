@@ -19,11 +19,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(tiles, bucket, elem_bytes, W):
+def algorithmic_bytes(tiles, bucket, elem_bytes, W, meta_per_bucket=8):
     """Bytes the method itself must move per launch, evaluated from the plan:
-    quantize reads S and writes b/8 per element plus 8 per bucket (pass-through:
-    S in, S out); dequant-reduce reads W times the packed stream and meta and
-    writes 4 per element."""
+    quantize reads S and writes b/8 per element plus 8 per bucket (4 for the
+    norm-and-sign form; pass-through: S in, S out); dequant-reduce reads W times
+    the packed stream and meta and writes 4 per element."""
     import numpy as np
     bits = (tiles["info"] & 15).astype(np.int64)
     count = tiles["count"].astype(np.int64)
@@ -31,11 +31,11 @@ def algorithmic_bytes(tiles, bucket, elem_bytes, W):
     payload = np.where(q, (count * bits + 7) // 8, count * elem_bytes).sum()
     buckets = np.where(q, (count + bucket - 1) // bucket, 0).sum()
     n = int(count.sum())
-    packed_meta = int(payload + 8 * buckets)
+    packed_meta = int(payload + meta_per_bucket * buckets)
     return {
         "quantize": n * elem_bytes + packed_meta,
         "dequant_reduce": W * packed_meta + 4 * n,
-        "requantize": 4 * n + int(np.where(q, (count * bits + 7) // 8, count * 4).sum() + 8 * buckets),
+        "requantize": 4 * n + int(np.where(q, (count * bits + 7) // 8, count * 4).sum() + meta_per_bucket * buckets),
     }
 
 
@@ -199,6 +199,60 @@ def main():
             },
         }
 
+    # the same step with the norm-and-sign form of the quantizer (Sec. 2.2, Q_s), timed per kernel
+    norm_sign = None
+    if not (w.bits == 1).any():
+        ns_meta = lambda mb: torch.empty(max(mb // 8, 4), dtype=torch.float32, device=dev)
+        ns_chunks = []
+        share = [torch.from_numpy(w.gradient(p, first, first + m, threads=16)).to(dev) for p in range(W)]
+        for r in range(R):
+            ps, ms = [], []
+            for p in range(W):
+                packed = torch.empty(r_pb, dtype=torch.uint8, device=dev)
+                meta = ns_meta(r_mb)
+                cgx.cgx_qsgd_quantize(share[p], r_plan, w.quant_seed(p) + 1000 * r, packed, meta)
+                ps.append(packed)
+                ms.append(meta)
+            ns_chunks.append((ps, ms))
+        del share
+        ns_q = [ns_meta(q_mb) for _ in range(R)]
+        ns_rq = [ns_meta(rq_mb) for _ in range(R)]
+
+        def ns_step(i, ev=None):
+            r = i % R
+            if ev:
+                ev[0].record()
+            cgx.cgx_qsgd_quantize(grads[r], q_plan, 17 + i, q_out[r][0], ns_q[r])
+            if ev:
+                ev[1].record()
+            cgx.cgx_qsgd_dequant_reduce(ns_chunks[r][0], ns_chunks[r][1], r_plan, sums[r])
+            if ev:
+                ev[2].record()
+            cgx.cgx_qsgd_quantize(sums[r], rq_plan, 29 + i, rq_out[r][0], ns_rq[r])
+            if ev:
+                ev[3].record()
+
+        for i in range(args.warmup):
+            ns_step(i)
+        ne = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            ns_step(i, ne[i])
+        torch.cuda.synchronize()
+        ns_wall = (time.perf_counter() - t0) * 1e3 / args.steps
+        ns_alg = {"quantize": algorithmic_bytes(cgx.cgx_plan_tiles(q_plan), w.bucket, S, W, 4)["quantize"]}
+        ns_r = algorithmic_bytes(cgx.cgx_plan_tiles(r_plan), w.bucket, S, W, 4)
+        ns_alg.update(dequant_reduce=ns_r["dequant_reduce"], requantize=ns_r["requantize"])
+        norm_sign = {"step": "cgx_qsgd_quantize + cgx_qsgd_dequant_reduce + cgx_qsgd_quantize(sum)",
+                     "ms_per_step": round(ns_wall, 5)}
+        for j, k in enumerate(["quantize", "dequant_reduce", "requantize"]):
+            ms = float(np.mean([ne[i][j].elapsed_time(ne[i][j + 1]) for i in range(args.steps)]))
+            norm_sign[k] = {"ms": round(ms, 5), "algorithmic_bytes": int(ns_alg[k]),
+                            "algorithmic_GBps": round(ns_alg[k] / ms / 1e6, 1),
+                            "hbm_frac": round(ns_alg[k] / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        del ns_chunks
+
     # what the memory system gives a plain streaming kernel with each call's read:write mix at its size
     def probe_ms(read_bytes, write_bytes):
         rb, wb = read_bytes // 16 * 16, write_bytes // 16 * 16
@@ -289,6 +343,7 @@ def main():
             "traffic": traffic,
         },
         "fused": fused,
+        "norm_sign": norm_sign,
         "setup_s": round(setup_s, 1),
     }
 

@@ -160,6 +160,41 @@ int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *
                                   uint64_t seed, void *packed_out, void *meta_out, void *stream);
 
 /*
+ * The norm-and-sign form of the quantizer, Q_s as printed in paper Sec. 2.2
+ * (Q_s(v_i) = ||v|| sign(v_i) q(|v_i| / ||v||, s)), applied per bucket (Sec. 4.3)
+ * with per-layer widths (Sec. 4.1).  Same plan, layout of the packed stream,
+ * draws, pass-through layers, summation order and error codes as the calls
+ * above; what differs:
+ *   - the norm of a bucket is its largest magnitude (so that |v_i| / ||v||
+ *     covers [0, 1] and no summation order enters the result);
+ *   - level = min((trunc(|x| * inv16) + u) >> 16, s), s = 2^(b-1) - 1; b must
+ *     be in 2..8 (CGX_ERR_BITS for a 1-bit layer);
+ *   - a b-bit code is the signed level sign(x) * level in -s..s as a two's
+ *     complement number (the sign is that of the value's sign bit; level 0 has
+ *     the one code 0);
+ *   - meta is ONE float per bucket, unit = ||v|| / s (0 for an all-zero or
+ *     degenerate bucket, as is inv16 = (s * 65536) / ||v||);
+ *   - the value of a code is (float)signed_level * unit, one binary32
+ *     multiplication.
+ * cgx_qsgd_sizes: packed_bytes as cgx_sizes, meta_bytes = 4 * buckets.
+ * cgx_qsgd_quantize: as cgx_quantize (dt = CGX_F32 serves as the requantize
+ * of a reduced chunk).  cgx_qsgd_dequant_reduce: as cgx_dequant_reduce.
+ * cgx_qsgd_dequant_reduce_requantize: as cgx_dequant_reduce_requantize.
+ */
+int cgx_qsgd_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                   int32_t bucket, cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes);
+int cgx_qsgd_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                      const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt,
+                      void *packed, void *meta, void *stream);
+int cgx_qsgd_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                            int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                            int32_t bucket, cgx_dtype dt, float *sum, void *stream);
+int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W,
+                                       int64_t n, int32_t L, const int64_t *layer_offsets,
+                                       const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
+                                       uint64_t seed, void *packed_out, void *meta_out, void *stream);
+
+/*
  * Diagnostic: the table of wavefront work items ("tiles") the kernels walk for
  * a plan, written to host memory as 32-byte records
  *   { int64 first_element; int64 packed_byte_offset; uint32 first_bucket;

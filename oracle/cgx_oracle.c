@@ -432,15 +432,16 @@ int oracle_unpack_codes(const uint8_t *packed, int64_t n, int32_t L, const int64
  * (Sec. 2.2: Q_s(v_i) = ||v|| * sign(v_i) * q(|v_i| / ||v||, s)), per bucket.
  *
  * Readings: the norm is the maximum absolute value of the bucket (so that
- * |v_i| / ||v|| covers [0, 1] and no summation order enters the result); a
- * b-bit code is one sign bit (the top bit; set when the sign bit of v_i is
- * set) and b-1 bits of level, s = 2^(b-1) - 1 intervals, b >= 2; meta is ONE
- * float per bucket, unit = ||v|| / s; the level is drawn exactly as in the
- * min/max form: inv16 = (s * 65536) / ||v||, T = trunc(|v_i| * inv16),
- * level = min(floor((T + u) / 65536), s); the value of a code is level * unit
- * (one binary32 multiplication), negated when the sign bit is set.  Layout,
- * draws, pass-through layers and the order of the sum are those of the
- * min/max form.
+ * |v_i| / ||v|| covers [0, 1] and no summation order enters the result);
+ * s = 2^(b-1) - 1 intervals, b >= 2; meta is ONE float per bucket,
+ * unit = ||v|| / s; the level is drawn exactly as in the min/max form:
+ * inv16 = (s * 65536) / ||v||, T = trunc(|v_i| * inv16),
+ * level = min(floor((T + u) / 65536), s).  The paper gives no bit format for
+ * sign(v_i) * level: the b-bit code is that product, the signed level in
+ * -s..s, in two's complement (so sign(0) * 0 = 0 has one code, and a negative
+ * v_i whose level is 0 decodes to +0).  The value of a code is
+ * (float)signed_level * unit, one binary32 multiplication.  Layout, draws,
+ * pass-through layers and the order of the sum are those of the min/max form.
  * ======================================================================== */
 
 static int check_qsgd_bits(int32_t L, const uint8_t *bits)
@@ -508,7 +509,8 @@ static int qsgd_quantize_impl(const void *grad, int64_t n, int32_t L, const int6
                     else T = (uint64_t)S;
                     uint64_t level = (T + u16) >> 16;
                     if (level > s) level = s;
-                    uint32_t code = (uint32_t)level | ((signbit(x) ? 1u : 0u) << (b - 1));
+                    int32_t signed_level = signbit(x) ? -(int32_t)level : (int32_t)level;
+                    uint32_t code = (uint32_t)signed_level & ((1u << b) - 1u);
                     put_bits(seg, (uint64_t)j * b, code, b);
                 }
             }
@@ -562,11 +564,10 @@ int oracle_qsgd_dequant_reduce(const uint8_t *const *packed, const float *const 
                 } else {
                     float unit = meta[w][bucket0 + (uint64_t)(j / bucket)];
                     uint32_t code = get_bits(seg, (uint64_t)j * b, b);
-                    uint32_t level = code & ((1u << (b - 1)) - 1u);
-                    int negative = (int)(code >> (b - 1));
+                    /* two's complement of width b: the top bit weighs -2^(b-1) */
+                    int32_t level = (int32_t)code - (int32_t)((code >> (b - 1)) << b);
                     v32 = (float)level * unit;
                     v64 = (double)level * (double)unit;
-                    if (negative) { v32 = -v32; v64 = -v64; }
                 }
                 acc32 = (w == 0) ? v32 : acc32 + v32;
                 acc64 += v64;

@@ -22,7 +22,8 @@ MAX_FUSED_PEERS = 16
 
 EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduce_add", "cgx_dequantize",
            "cgx_requantize",
-           "cgx_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
+           "cgx_dequant_reduce_requantize", "cgx_qsgd_sizes", "cgx_qsgd_quantize", "cgx_qsgd_dequant_reduce",
+           "cgx_qsgd_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -57,6 +58,10 @@ def lib() -> ctypes.CDLL:
         L.cgx_dequantize.argtypes = [c.c_void_p, c.c_void_p] + plan + [c.c_int, c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
             [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_qsgd_sizes.argtypes = L.cgx_sizes.argtypes
+        L.cgx_qsgd_quantize.argtypes = L.cgx_quantize.argtypes
+        L.cgx_qsgd_dequant_reduce.argtypes = L.cgx_dequant_reduce.argtypes
+        L.cgx_qsgd_dequant_reduce_requantize.argtypes = L.cgx_dequant_reduce_requantize.argtypes
         L.cgx_stream_probe.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_status_string.restype = c.c_char_p
@@ -173,6 +178,44 @@ def cgx_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, 
     _check(lib().cgx_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
                                                packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
            "cgx_dequant_reduce_requantize")
+
+
+def _peer_arrays(packed: Sequence, meta: Sequence):
+    W = len(packed)
+    if len(meta) != W:
+        raise ValueError("as many meta tensors as packed tensors")
+    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
+    return W, pp, mp
+
+
+def cgx_qsgd_sizes(plan: Plan) -> Tuple[int, int]:
+    """(packed_bytes, meta_bytes) of a plan under the norm-and-sign quantizer (one float of meta per bucket)."""
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().cgx_qsgd_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_qsgd_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def cgx_qsgd_quantize(grad, plan: Plan, seed: int, packed, meta, stream=None) -> None:
+    """As cgx_quantize, norm-and-sign codes; buffers sized by cgx_qsgd_sizes."""
+    _check(lib().cgx_qsgd_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
+                                   meta.data_ptr(), _stream(stream)), "cgx_qsgd_quantize")
+
+
+def cgx_qsgd_dequant_reduce(packed: Sequence, meta: Sequence, plan: Plan, total, stream=None) -> None:
+    """As cgx_dequant_reduce, for chunks written by cgx_qsgd_quantize."""
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_qsgd_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
+           "cgx_qsgd_dequant_reduce")
+
+
+def cgx_qsgd_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, seed: int, packed_out,
+                                       meta_out, stream=None) -> None:
+    """As cgx_dequant_reduce_requantize, norm-and-sign codes on both sides."""
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_qsgd_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
+                                                    packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
+           "cgx_qsgd_dequant_reduce_requantize")
 
 
 def cgx_stream_probe(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:

@@ -93,10 +93,22 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     return CGX_OK;
 }
 
-int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
-                  uint64_t seed, int dt, void *packed, void *meta, void *stream)
+// Plan check of an entry point: the common rules, and for the norm-and-sign quantizer no
+// 1-bit layers (a sign bit alone carries no level).
+int check_plan(int scheme, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt)
 {
-    int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    const int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    if (rc != CGX_OK) return rc;
+    if (scheme == cgx::kSchemeNormSign)
+        for (int32_t l = 0; l < L; l++)
+            if (bits[l] == 1) return CGX_ERR_BITS;
+    return CGX_OK;
+}
+
+int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                  int32_t bucket, uint64_t seed, int dt, void *packed, void *meta, void *stream)
+{
+    int rc = check_plan(scheme, n, L, off, bits, bucket, dt);
     if (rc != CGX_OK) return rc;
     if (n == 0) return CGX_OK;
     const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
@@ -105,17 +117,17 @@ int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off, co
     const CachedPlan *plan = nullptr;
     rc = get_plan(L, off, bits, bucket, dt, &plan);
     if (rc != CGX_OK) return rc;
-    const hipError_t e = cgx::launch_quantize(grad, dt, plan->d_tiles, plan->n_tiles, bucket, seed, packed, meta,
+    const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, bucket, seed, packed, meta,
                                               launch_config(), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }
 
 // Shared body of the dequantize / reduce entry points: out = [local +] deq_0 + ... + deq_{W-1}.
-int reduce_impl(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
+int reduce_impl(int scheme, const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
                 const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, const void *local, int local_dt,
                 bool want_local, void *out, int out_dt, void *stream)
 {
-    int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    int rc = check_plan(scheme, n, L, off, bits, bucket, dt);
     if (rc != CGX_OK) return rc;
     if (W < 1 || W > CGX_MAX_PEERS) return CGX_ERR_PEERS;
     if (n == 0) return CGX_OK;
@@ -137,16 +149,48 @@ int reduce_impl(const void *const *packed, const void *const *meta, int32_t W, i
         cgx::PeerPtrs peers{};
         for (int i = 0; i < k; i++) {
             peers.packed[i] = static_cast<const uint8_t *>(packed[w0 + i]);
-            peers.meta[i] = static_cast<const float2 *>(meta[w0 + i]);
+            peers.meta[i] = static_cast<const float *>(meta[w0 + i]);
         }
         const void *init = w0 == 0 ? local : out;
         const int init_dt = w0 == 0 ? local_dt : CGX_F32;
-        const hipError_t e = cgx::launch_dequant_reduce(peers, k, dt, plan->d_tiles, plan->n_tiles, bucket, init,
+        const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles, bucket, init,
                                                         init_dt, out, out_dt, launch_config(),
                                                         static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return CGX_ERR_HIP;
     }
     return CGX_OK;
+}
+
+int fused_impl(int scheme, const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
+               const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, int dt, uint64_t seed,
+               void *packed_out, void *meta_out, void *stream)
+{
+    int rc = check_plan(scheme, n, L, layer_offsets, bits_per_layer, bucket, dt);
+    if (rc != CGX_OK) return rc;
+    if (W < 1 || W > CGX_MAX_FUSED_PEERS) return CGX_ERR_PEERS;
+    if (n == 0) return CGX_OK;
+    const cgx::PlanShape shape = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, dt);
+    if (!packed || !meta || !packed_out || (shape.meta_bytes && !meta_out)) return CGX_ERR_NULL;
+    for (int w = 0; w < W; w++) {
+        if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
+        if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
+    }
+    if (misaligned(packed_out) || misaligned(meta_out)) return CGX_ERR_ALIGN;
+    const CachedPlan *in = nullptr, *out = nullptr;
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, dt, &in);
+    if (rc != CGX_OK) return rc;
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, &out);
+    if (rc != CGX_OK) return rc;
+    if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
+    cgx::PeerPtrs peers{};
+    for (int i = 0; i < W; i++) {
+        peers.packed[i] = static_cast<const uint8_t *>(packed[i]);
+        peers.meta[i] = static_cast<const float *>(meta[i]);
+    }
+    const hipError_t e = cgx::launch_dequant_reduce_requantize(scheme, peers, W, dt, in->d_tiles, out->d_tiles,
+                                                               in->n_tiles, bucket, seed, packed_out, meta_out,
+                                                               launch_config(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }
 
 }  // namespace
@@ -168,21 +212,21 @@ int cgx_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_of
                  const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt, void *packed,
                  void *meta, void *stream)
 {
-    return quantize_impl(grad, n, L, layer_offsets, bits_per_layer, bucket, seed, int(dt), packed, meta, stream);
+    return quantize_impl(cgx::kSchemeMinMax, grad, n, L, layer_offsets, bits_per_layer, bucket, seed, int(dt), packed, meta, stream);
 }
 
 int cgx_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
                    const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, void *packed, void *meta,
                    void *stream)
 {
-    return quantize_impl(sum, n, L, layer_offsets, bits_per_layer, bucket, seed, CGX_F32, packed, meta, stream);
+    return quantize_impl(cgx::kSchemeMinMax, sum, n, L, layer_offsets, bits_per_layer, bucket, seed, CGX_F32, packed, meta, stream);
 }
 
 int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
                        const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
                        float *sum, void *stream)
 {
-    return reduce_impl(packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32,
+    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32,
                        false, sum, CGX_F32, stream);
 }
 
@@ -192,7 +236,7 @@ int cgx_dequant_reduce_add(const void *local, cgx_dtype local_dt, const void *co
                            cgx_dtype dt, float *sum, void *stream)
 {
     if (local_dt != CGX_F32 && local_dt != CGX_F16) return CGX_ERR_DTYPE;
-    return reduce_impl(packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), local, int(local_dt),
+    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), local, int(local_dt),
                        true, sum, CGX_F32, stream);
 }
 
@@ -202,7 +246,7 @@ int cgx_dequantize(const void *packed, const void *meta, int64_t n, int32_t L, c
 {
     if (out_dt != CGX_F32 && out_dt != CGX_F16) return CGX_ERR_DTYPE;
     const void *const p[1] = {packed}, *const m[1] = {meta};
-    return reduce_impl(p, m, 1, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32, false, out,
+    return reduce_impl(cgx::kSchemeMinMax, p, m, 1, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32, false, out,
                        int(out_dt), stream);
 }
 
@@ -211,32 +255,44 @@ int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *
                                   int32_t bucket, cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
                                   void *stream)
 {
-    int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
+    return fused_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), seed,
+                      packed_out, meta_out, stream);
+}
+
+int cgx_qsgd_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                   int32_t bucket, cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes)
+{
+    const int rc = check_plan(cgx::kSchemeNormSign, n, L, layer_offsets, bits_per_layer, bucket, int(dt));
     if (rc != CGX_OK) return rc;
-    if (W < 1 || W > CGX_MAX_FUSED_PEERS) return CGX_ERR_PEERS;
-    if (n == 0) return CGX_OK;
-    const cgx::PlanShape shape = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
-    if (!packed || !meta || !packed_out || (shape.meta_bytes && !meta_out)) return CGX_ERR_NULL;
-    for (int w = 0; w < W; w++) {
-        if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
-        if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
-    }
-    if (misaligned(packed_out) || misaligned(meta_out)) return CGX_ERR_ALIGN;
-    const CachedPlan *in = nullptr, *out = nullptr;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, int(dt), &in);
-    if (rc != CGX_OK) return rc;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, &out);
-    if (rc != CGX_OK) return rc;
-    if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
-    cgx::PeerPtrs peers{};
-    for (int i = 0; i < W; i++) {
-        peers.packed[i] = static_cast<const uint8_t *>(packed[i]);
-        peers.meta[i] = static_cast<const float2 *>(meta[i]);
-    }
-    const hipError_t e = cgx::launch_dequant_reduce_requantize(peers, W, int(dt), in->d_tiles, out->d_tiles,
-                                                               in->n_tiles, bucket, seed, packed_out, meta_out,
-                                                               launch_config(), static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+    const cgx::PlanShape s = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
+    if (packed_bytes) *packed_bytes = s.packed_bytes;
+    if (meta_bytes) *meta_bytes = s.meta_bytes / 2;            // one float per bucket
+    return CGX_OK;
+}
+
+int cgx_qsgd_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                      const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt, void *packed,
+                      void *meta, void *stream)
+{
+    return quantize_impl(cgx::kSchemeNormSign, grad, n, L, layer_offsets, bits_per_layer, bucket, seed, int(dt),
+                         packed, meta, stream);
+}
+
+int cgx_qsgd_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
+                            const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                            cgx_dtype dt, float *sum, void *stream)
+{
+    return reduce_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt),
+                       nullptr, CGX_F32, false, sum, CGX_F32, stream);
+}
+
+int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                                       int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                       int32_t bucket, cgx_dtype dt, uint64_t seed, void *packed_out,
+                                       void *meta_out, void *stream)
+{
+    return fused_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt),
+                      seed, packed_out, meta_out, stream);
 }
 
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
@@ -274,7 +330,7 @@ const char *cgx_status_string(int status)
     case CGX_ERR_NULL: return "a required pointer is NULL";
     case CGX_ERR_SIZE: return "n or L is negative, too large, or n does not match layer_offsets[L]";
     case CGX_ERR_OFFSETS: return "layer_offsets must start at 0 and never decrease";
-    case CGX_ERR_BITS: return "bits_per_layer entries must be 0 (pass-through) or 1..8";
+    case CGX_ERR_BITS: return "bits_per_layer entries must be 0 (pass-through) or 1..8 (2..8 for the cgx_qsgd_ calls)";
     case CGX_ERR_BUCKET: return "bucket must be a multiple of 32 in [32, 8192]";
     case CGX_ERR_PEERS: return "W must be in [1, 64]";
     case CGX_ERR_DTYPE: return "unknown storage type";

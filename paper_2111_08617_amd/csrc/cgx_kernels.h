@@ -9,9 +9,14 @@ namespace cgx {
 
 constexpr int kPeersPerLaunch = 16;   // chunks one reduce launch reads; more peers take more launches
 
+// The two quantizers the kernels implement (`scheme` below): affine between the bucket's
+// minimum and maximum (meta: two floats per bucket), and sign plus level of |x| / max|x|
+// (meta: one float per bucket).
+enum { kSchemeMinMax = 0, kSchemeNormSign = 1 };
+
 struct PeerPtrs {
     const uint8_t *packed[kPeersPerLaunch];
-    const float2 *meta[kPeersPerLaunch];
+    const float *meta[kPeersPerLaunch];
 };
 
 // Tunables (set once from the environment at first use; see cgx_api.cpp).
@@ -20,20 +25,20 @@ struct LaunchConfig {
     int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
 };
 
-hipError_t launch_quantize(const void *grad, int dt, const Tile *tiles, int64_t n_tiles, int32_t bucket,
+hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, int32_t bucket,
                            uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
                            hipStream_t stream);
 
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
 // term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
-hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
                                  const LaunchConfig &cfg, hipStream_t stream);
 
 // packed_out / meta_out = quantize(deq_0 + ... + deq_{W-1}) without the binary32 sum ever
 // reaching memory; tiles_in describes the chunks (storage type dt), tiles_out the output
 // (binary32 pass-through); W <= kPeersPerLaunch.
-hipError_t launch_dequant_reduce_requantize(const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
+hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
                                             const Tile *tiles_out, int64_t n_tiles, int32_t bucket,
                                             uint64_t seed, void *packed_out, void *meta_out,
                                             const LaunchConfig &cfg, hipStream_t stream);

@@ -116,7 +116,39 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int lg, int l
     }
 }
 
-// ---------------------------------------------------------------- bucket scale
+// Maximum alone, same exchange pattern.
+__device__ __forceinline__ void group_max(float &mx, int lg, int lane)
+{
+    if (lg >= 1) mx = __builtin_fmaxf(mx, dpp_move<0xB1>(mx));
+    if (lg >= 2) mx = __builtin_fmaxf(mx, dpp_move<0x4E>(mx));
+    if (lg >= 3) mx = __builtin_fmaxf(mx, dpp_move<0x141>(mx));
+    if (lg >= 4) mx = __builtin_fmaxf(mx, dpp_move<0x140>(mx));
+    if (lg >= 5) mx = __builtin_fmaxf(mx, swizzle_xor16(mx));
+    if (lg >= 6) mx = __builtin_fmaxf(mx, permute_xor32(mx, lane));
+}
+
+// ---------------------------------------------------------------- the two quantizers
+//
+// kMinMax: affine per bucket.  A b-bit code is a level 0..2^b-1 between the bucket's minimum
+// and maximum; meta = {unit, minimum} (float2 per bucket); value = fma(level, unit, minimum).
+// kNormSign: the norm-and-sign form printed in Sec. 2.2 (Q_s), with the bucket's largest
+// magnitude as the norm.  A b-bit code (b >= 2) is sign(x) times a level 0..s,
+// s = 2^(b-1)-1, of |x| / norm, as a two's complement number (decoding, done once per peer
+// and element, is then a sign-extending conversion and a multiplication; encoding, done once
+// per element, pays the negation); meta = unit = norm / s (one float per bucket);
+// value = float(signed level) * unit.
+// Both resolve the rounding probability to 16 bits with the same draws.
+enum Scheme { kMinMax = kSchemeMinMax, kNormSign = kSchemeNormSign };
+
+template <int SCHEME>
+__device__ __forceinline__ constexpr uint32_t top_level(int bits)
+{
+    return SCHEME == kNormSign ? (1u << (bits - 1)) - 1u : (1u << bits) - 1u;
+}
+
+// floats of meta per bucket
+template <int SCHEME>
+constexpr int kMetaFloats = SCHEME == kNormSign ? 1 : 2;
 
 struct Scale {
     float unit, mn, inv16;
@@ -124,9 +156,9 @@ struct Scale {
 
 // unit = (mx - mn) / Lv, inv16 = (Lv * 65536) / (mx - mn), both IEEE divisions;
 // a constant or degenerate bucket gets unit = inv16 = 0; a zero minimum is +0.
-__device__ __forceinline__ Scale bucket_scale(float mn, float mx, int bits)
+// (kNormSign calls it with mn = +0 and mx = the largest magnitude.)
+__device__ __forceinline__ Scale bucket_scale(float mn, float mx, int levels)
 {
-    const int levels = (1 << bits) - 1;
     if (mn == 0.0f) mn = 0.0f;
     const float range = mx - mn;
     float unit = __fdiv_rn(range, float(levels));
@@ -138,13 +170,45 @@ __device__ __forceinline__ Scale bucket_scale(float mn, float mx, int bits)
     return Scale{unit, mn, inv16};
 }
 
-__device__ __forceinline__ uint32_t code_of(float x, const Scale &s, uint32_t draw, uint32_t levels)
+// bits is the code width (only kNormSign uses it, to cut the two's complement code).
+template <int SCHEME>
+__device__ __forceinline__ uint32_t code_of(float x, const Scale &s, uint32_t draw, uint32_t levels, int bits)
 {
-    const float d = __fsub_rn(x, s.mn);
+    const float d = SCHEME == kNormSign ? __builtin_fabsf(x) : __fsub_rn(x, s.mn);
     const float S = __fmul_rn(d, s.inv16);
     const uint32_t T = uint32_t(S);                 // v_cvt_u32_f32: truncates, saturates
     const uint32_t q = (T + draw) >> 16;
-    return q < levels ? q : levels;
+    const uint32_t level = q < levels ? q : levels;
+    if (SCHEME == kNormSign) {
+        const uint32_t neg = uint32_t(__builtin_bit_cast(int32_t, x) >> 31);    // all ones for a set sign bit
+        return ((level ^ neg) - neg) & ((1u << bits) - 1u);
+    }
+    return level;
+}
+
+template <int SCHEME>
+__device__ __forceinline__ void store_meta(float *meta, uint32_t g, const Scale &s)
+{
+    if (SCHEME == kNormSign)
+        meta[g] = s.unit;
+    else
+        reinterpret_cast<float2 *>(meta)[g] = make_float2(s.unit, s.mn);
+}
+
+// {unit, offset} of bucket g (kNormSign: offset unused).
+template <int SCHEME>
+__device__ __forceinline__ float2 load_meta(const float *meta, uint32_t g)
+{
+    if (SCHEME == kNormSign) return make_float2(meta[g], 0.0f);
+    return reinterpret_cast<const float2 *>(meta)[g];
+}
+
+// Value of a code whose (kNormSign: signed) level is f.
+template <int SCHEME>
+__device__ __forceinline__ float decode(float f, float2 m)
+{
+    if (SCHEME == kNormSign) return __fmul_rn(f, m.x);
+    return __builtin_fmaf(f, m.x, m.y);
 }
 
 // ---------------------------------------------------------------- memory helpers
@@ -310,23 +374,36 @@ struct LaneMap {
 
 // One chunk held in registers (x) -> meta of its buckets and its packed codes.
 // first = buffer index of the chunk's first element; key = generator key of the tile.
-template <int BITS>
+// meta_chunk points at the meta of the chunk's first bucket.
+template <int SCHEME, int BITS>
 __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const LaneMap &map, int lane, int64_t first,
-                                               uint32_t key, float2 *__restrict__ meta_chunk,
+                                               uint32_t key, float *__restrict__ meta_chunk,
                                                uint8_t *__restrict__ out, uint4v *stage)
 {
-    constexpr uint32_t kLevels = (1u << BITS) - 1u;
-    float mn = x[0][0], mx = x[0][0];
+    constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    float mn, mx;
+    if (SCHEME == kNormSign) {
+        mn = 0.0f;
+        mx = 0.0f;
 #pragma unroll
-    for (int r = 0; r < G; r++)
+        for (int r = 0; r < G; r++)
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            mn = __builtin_fminf(mn, x[r][j]);
-            mx = __builtin_fmaxf(mx, x[r][j]);
-        }
-    group_minmax(mn, mx, map.lg, lane);
-    const Scale s = bucket_scale(mn, mx, BITS);
-    if (map.lp == 0) meta_chunk[map.bi] = make_float2(s.unit, s.mn);
+            for (int j = 0; j < 8; j++) mx = __builtin_fmaxf(mx, __builtin_fabsf(x[r][j]));
+        group_max(mx, map.lg, lane);
+    } else {
+        mn = x[0][0];
+        mx = x[0][0];
+#pragma unroll
+        for (int r = 0; r < G; r++)
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                mn = __builtin_fminf(mn, x[r][j]);
+                mx = __builtin_fmaxf(mx, x[r][j]);
+            }
+        group_minmax(mn, mx, map.lg, lane);
+    }
+    const Scale s = bucket_scale(mn, mx, int(kLevels));
+    if (map.lp == 0) store_meta<SCHEME>(meta_chunk, map.bi, s);
 
 #pragma unroll
     for (int r = 0; r < G; r++) {
@@ -335,8 +412,8 @@ __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const Lan
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t w = mix32((pair0 + k) ^ key);
-            const uint64_t q0 = code_of(x[r][2 * k], s, w & 0xffffU, kLevels);
-            const uint64_t q1 = code_of(x[r][2 * k + 1], s, w >> 16, kLevels);
+            const uint64_t q0 = code_of<SCHEME>(x[r][2 * k], s, w & 0xffffU, kLevels, BITS);
+            const uint64_t q1 = code_of<SCHEME>(x[r][2 * k + 1], s, w >> 16, kLevels, BITS);
             acc |= q0 << (2 * k * BITS);
             acc |= q1 << ((2 * k + 1) * BITS);
         }
@@ -348,9 +425,9 @@ __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const Lan
     wave_lds_fence();
 }
 
-template <int DT, int BITS>
+template <int SCHEME, int DT, int BITS>
 __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uint8_t *__restrict__ packed,
-                                              float2 *__restrict__ meta, const Tile &tile, int bucket,
+                                              float *__restrict__ meta, const Tile &tile, int bucket,
                                               uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
 {
     const LaneMap map(tile, bucket, lane);
@@ -362,8 +439,9 @@ __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uin
         float x[G][8];
 #pragma unroll
         for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
-        quantize_chunk<BITS>(x, map, lane, first, key, meta + tile.bucket0 + c * buckets_per_chunk,
-                             packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8), stage);
+        quantize_chunk<SCHEME, BITS>(x, map, lane, first, key,
+                                     meta + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
+                                     packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8), stage);
     }
 }
 
@@ -371,16 +449,18 @@ __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uin
 // value(j) gives element j of the tile (called twice per element).  With BATCH the values
 // of a pass are fetched 8 at a time so that plain loads overlap; without it (value() is
 // itself a reduction over the peers) they are taken one by one.
-template <bool BATCH, typename Value>
+template <int SCHEME, bool BATCH, typename Value>
 __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restrict__ out,
-                                                 float2 *__restrict__ meta, const Tile &tile, uint32_t pad,
+                                                 float *__restrict__ meta, const Tile &tile, uint32_t pad,
                                                  int bucket, uint32_t seed_lo, uint32_t seed_hi, int lane)
 {
     const int b = int(tile_bits(tile));
-    const uint32_t levels = (1u << b) - 1u;
+    const uint32_t levels = top_level<SCHEME>(b);
+    // kNormSign: the maximum runs over magnitudes and the minimum stays +0
+    const auto seen = [](float x) { return SCHEME == kNormSign ? __builtin_fabsf(x) : x; };
     for (uint32_t k0 = 0; k0 < tile.count; k0 += uint32_t(bucket)) {
         const uint32_t cnt = tile.count - k0 < uint32_t(bucket) ? tile.count - k0 : uint32_t(bucket);
-        float mn = __builtin_inff(), mx = -__builtin_inff();
+        float mn = SCHEME == kNormSign ? 0.0f : __builtin_inff(), mx = SCHEME == kNormSign ? 0.0f : -__builtin_inff();
         if (BATCH) {
             for (uint32_t j0 = 0; j0 < cnt; j0 += 8 * kWave) {
                 float x[8];
@@ -391,20 +471,23 @@ __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restric
                 }
 #pragma unroll
                 for (int u = 0; u < 8; u++) {
-                    mn = __builtin_fminf(mn, x[u]);
-                    mx = __builtin_fmaxf(mx, x[u]);
+                    if (SCHEME != kNormSign) mn = __builtin_fminf(mn, x[u]);
+                    mx = __builtin_fmaxf(mx, seen(x[u]));
                 }
             }
         } else {
             for (uint32_t j = lane; j < cnt; j += kWave) {
                 const float x = value(k0 + j);
-                mn = __builtin_fminf(mn, x);
-                mx = __builtin_fmaxf(mx, x);
+                if (SCHEME != kNormSign) mn = __builtin_fminf(mn, x);
+                mx = __builtin_fmaxf(mx, seen(x));
             }
         }
-        group_minmax(mn, mx, 6, lane);
-        const Scale s = bucket_scale(mn, mx, b);
-        if (lane == 0) meta[tile.bucket0 + k0 / uint32_t(bucket)] = make_float2(s.unit, s.mn);
+        if (SCHEME == kNormSign)
+            group_max(mx, 6, lane);
+        else
+            group_minmax(mn, mx, 6, lane);
+        const Scale s = bucket_scale(mn, mx, int(levels));
+        if (lane == 0) store_meta<SCHEME>(meta, tile.bucket0 + k0 / uint32_t(bucket), s);
 
         const uint32_t groups = (cnt + 7) / 8;
         for (uint32_t g = lane; g < groups; g += kWave) {
@@ -417,12 +500,13 @@ __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restric
                 for (uint32_t j = 0; j < 8; j++) x[j] = value(k0 + g * 8 + (j < valid ? j : 0));
 #pragma unroll
                 for (uint32_t j = 0; j < 8; j++) {
-                    const uint64_t q = code_of(x[j], s, draw16(seed_lo, seed_hi, i0 + j), levels);
+                    const uint64_t q = code_of<SCHEME>(x[j], s, draw16(seed_lo, seed_hi, i0 + j), levels, b);
                     if (j < valid) acc |= q << (j * b);
                 }
             } else {
                 for (uint32_t j = 0; j < valid; j++) {
-                    const uint64_t q = code_of(value(k0 + g * 8 + j), s, draw16(seed_lo, seed_hi, i0 + j), levels);
+                    const uint64_t q =
+                        code_of<SCHEME>(value(k0 + g * 8 + j), s, draw16(seed_lo, seed_hi, i0 + j), levels, b);
                     acc |= q << (j * b);
                 }
             }
@@ -464,9 +548,11 @@ __device__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ p
     for (uint32_t k = done + lane; k < bytes + tile.pad; k += kWave) dst[k] = k < bytes ? src[k] : uint8_t(0);
 }
 
+// Runs CALL with BITS = bits as a constant (kNormSign has no 1-bit codes: the entry points
+// reject such plans, and nothing is instantiated for them).
 #define CGX_FOR_BITS(bits, CALL)                      \
     switch (bits) {                                   \
-    case 1: { constexpr int BITS = 1; CALL; } break;  \
+    case 1: { constexpr int BITS = 1; if constexpr (SCHEME != kNormSign) { CALL; } } break;  \
     case 2: { constexpr int BITS = 2; CALL; } break;  \
     case 3: { constexpr int BITS = 3; CALL; } break;  \
     case 4: { constexpr int BITS = 4; CALL; } break;  \
@@ -476,12 +562,12 @@ __device__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ p
     default: { constexpr int BITS = 8; CALL; } break; \
     }
 
-template <int DT>
+template <int SCHEME, int DT>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
                                                            const Tile *__restrict__ tiles, int64_t n_tiles,
                                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                                            uint8_t *__restrict__ packed,
-                                                           float2 *__restrict__ meta)
+                                                           float *__restrict__ meta)
 {
     // per-wave staging area for a chunk's packed codes (at most kChunk bytes, at 8 bits)
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 16];
@@ -493,11 +579,12 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         if (kind == kQuantFast) {
-            CGX_FOR_BITS(tile_bits(tile), (quantize_fast<DT, BITS>(grad, packed, meta, tile, bucket, seed_lo,
-                                                                     seed_hi, lane, stage)))
+            CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
+                                                                             seed_lo, seed_hi, lane, stage)))
         } else if (kind == kQuantSlow) {
-            quantize_generic<true>([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
-                             packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo, seed_hi, lane);
+            quantize_generic<SCHEME, true>([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
+                                           packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo,
+                                           seed_hi, lane);
         } else {
             copy_tile<DT>(grad, packed, tile, kind == kCopyFast, lane);
         }
@@ -506,11 +593,24 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
 
 // ---------------------------------------------------------------- dequantize + reduce
 
-// Codes of one group of 8 elements as floats.
-template <int BITS>
+// Levels of one group of 8 codes as floats (kNormSign: signed levels).
+template <int SCHEME, int BITS>
 __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
 {
-    if (BITS == 8) {
+    if (SCHEME == kNormSign) {
+        if (BITS == 8) {
+            const uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                f[j] = float(int32_t(int8_t(lo >> (8 * j))));
+                f[4 + j] = float(int32_t(int8_t(hi >> (8 * j))));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++)      // sign-extending field extract
+                f[j] = float(int32_t(uint32_t(v >> (j * BITS)) << (32 - BITS)) >> (32 - BITS));
+        }
+    } else if (BITS == 8) {
         const uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
 #pragma unroll
         for (int j = 0; j < 4; j++) {
@@ -543,7 +643,7 @@ __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
 // Folds peers w0 .. w0+WB-1 into acc.  Each peer's share of the chunk (kChunk*BITS/8 bytes)
 // is fetched as whole 16-byte vectors, consecutive across lanes, directly into the wave's
 // LDS staging area, and read back by the lanes that own the codes.
-template <int BITS, int WB>
+template <int SCHEME, int BITS, int WB>
 __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int64_t in_off, uint32_t g,
                                              const int (&code_off)[G], float (&acc)[G][8], uint4v *stage,
                                              int lane)
@@ -560,7 +660,7 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
             const int v = lane + k * kWave;
             if (kVecs % kWave == 0 || v < kVecs) load_to_lds16(in + v, stage + i * kVecs + k * kWave);
         }
-        m[i] = peers.meta[w0 + i][g];
+        m[i] = load_meta<SCHEME>(peers.meta[w0 + i], g);
     }
     wait_vector_memory();
     wave_lds_fence();
@@ -570,9 +670,9 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
 #pragma unroll
         for (int r = 0; r < G; r++) {
             float f[8];
-            codes_to_float<BITS>(staged_codes<BITS>(codes + i * kBytes + code_off[r]), f);
+            codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes + i * kBytes + code_off[r]), f);
 #pragma unroll
-            for (int j = 0; j < 8; j++) acc[r][j] = __fadd_rn(acc[r][j], __builtin_fmaf(f[j], m[i].x, m[i].y));
+            for (int j = 0; j < 8; j++) acc[r][j] = __fadd_rn(acc[r][j], decode<SCHEME>(f[j], m[i]));
         }
         // keep the scheduler from hoisting every peer's LDS reads to the top (registers)
         if (i % 2 == 1) __builtin_amdgcn_sched_barrier(0);
@@ -581,7 +681,7 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
 }
 
 // Sum over the W peers of one chunk's dequantized values, added to acc in peer order.
-template <int BITS>
+template <int SCHEME, int BITS>
 __device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64_t in_off, uint32_t g,
                                              const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane)
 {
@@ -596,7 +696,7 @@ __device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64
 #pragma unroll
     for (int r = 0; r < G; r++) code_off[r] = (map.group(r) >> 3) * BITS;
     for_peer_blocks<kWide>(W, [&](int w0, auto wb) {
-        reduce_peers<BITS, decltype(wb)::value>(peers, w0, in_off, g, code_off, acc, stage, lane);
+        reduce_peers<SCHEME, BITS, decltype(wb)::value>(peers, w0, in_off, g, code_off, acc, stage, lane);
     });
 }
 
@@ -661,7 +761,7 @@ __device__ __forceinline__ void store8(const SumIo &io, int64_t e, const float (
     }
 }
 
-template <int BITS>
+template <int SCHEME, int BITS>
 __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const SumIo &io, const Tile &tile,
                                             int bucket, int lane, uint4v *stage)
 {
@@ -673,8 +773,8 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const 
         float acc[G][8];
 #pragma unroll
         for (int r = 0; r < G; r++) init8(io, first + map.group(r), acc[r]);
-        reduce_chunk<BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
-                           tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
+        reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                                   tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
         // the results leave through LDS as well, so that every store instruction writes 1 KB of
         // consecutive addresses
         if (io.out_dt == CGX_F16) {
@@ -705,6 +805,7 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const 
 
 // Ordered sum over the peers of element j of a generic quantized tile (start = the value
 // the sum starts from).
+template <int SCHEME>
 __device__ __forceinline__ float generic_sum(const PeerPtrs &peers, int W, const Tile &tile, int bucket,
                                              uint32_t j, float start)
 {
@@ -725,22 +826,24 @@ __device__ __forceinline__ float generic_sum(const PeerPtrs &peers, int W, const
             const uint8_t *p = peers.packed[w0 + i] + at;
             lo[i] = p[0];
             hi[i] = two ? p[1] : 0u;
-            m[i] = peers.meta[w0 + i][g];
+            m[i] = load_meta<SCHEME>(peers.meta[w0 + i], g);
         }
 #pragma unroll
         for (int i = 0; i < WB; i++) {
-            const uint32_t q = ((lo[i] | (hi[i] << 8)) >> shift) & mask;
-            acc = __fadd_rn(acc, __builtin_fmaf(float(q), m[i].x, m[i].y));
+            const uint32_t code = ((lo[i] | (hi[i] << 8)) >> shift) & mask;
+            const float level = SCHEME == kNormSign ? float(int32_t(code << (32 - b)) >> (32 - b)) : float(code);
+            acc = __fadd_rn(acc, decode<SCHEME>(level, m[i]));
         }
     });
     return acc;
 }
 
 // Any bucket size, any alignment, ragged tiles: one element per lane and pass.
+template <int SCHEME>
 __device__ void reduce_slow(const PeerPtrs &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
 {
     for (uint32_t j = lane; j < tile.count; j += kWave)
-        store1(io, tile.elem0 + j, generic_sum(peers, W, tile, bucket, j, init1(io, tile.elem0 + j)));
+        store1(io, tile.elem0 + j, generic_sum<SCHEME>(peers, W, tile, bucket, j, init1(io, tile.elem0 + j)));
 }
 
 // Ordered sum over the peers of 8 consecutive elements of a pass-through tile (16-byte
@@ -796,6 +899,7 @@ __device__ void reduce_copy(const PeerPtrs &peers, int W, const SumIo &io, int64
         store1(io, e0 + j, copy_sum1<DT>(peers, W, tile, j, init1(io, e0 + j)));
 }
 
+template <int SCHEME>
 __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, int W, int dt, const SumIo io,
                                                          const Tile *__restrict__ tiles, int64_t n_tiles,
                                                          int bucket)
@@ -810,9 +914,9 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         if (kind == kQuantFast) {
-            CGX_FOR_BITS(tile_bits(tile), (reduce_fast<BITS>(peers, W, io, tile, bucket, lane, stage)))
+            CGX_FOR_BITS(tile_bits(tile), (reduce_fast<SCHEME, BITS>(peers, W, io, tile, bucket, lane, stage)))
         } else if (kind == kQuantSlow) {
-            reduce_slow(peers, W, io, tile, bucket, lane);
+            reduce_slow<SCHEME>(peers, W, io, tile, bucket, lane);
         } else if (dt == CGX_F16) {
             reduce_copy<CGX_F16>(peers, W, io, tile.elem0, tile, kind == kCopyFast, lane);
         } else {
@@ -824,10 +928,10 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
 // ---------------------------------------------------------------- fused reduce + requantize
 
 // The sums of a chunk never leave the registers: reduce_chunk feeds quantize_chunk.
-template <int BITS>
+template <int SCHEME, int BITS>
 __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
-                                           uint8_t *__restrict__ packed_out, float2 *__restrict__ meta_out,
+                                           uint8_t *__restrict__ packed_out, float *__restrict__ meta_out,
                                            int lane, uint4v *stage)
 {
     const LaneMap map(tile, bucket, lane);
@@ -837,22 +941,23 @@ __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const T
     for (int c = 0; c < chunks; c++) {
         float acc[G][8];
         clear_sums(acc);
-        reduce_chunk<BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
-                           tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
-        quantize_chunk<BITS>(acc, map, lane, tile.elem0 + int64_t(c) * kChunk, key,
-                             meta_out + tile.bucket0 + c * buckets_per_chunk,
-                             packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage);
+        reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                                   tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
+        quantize_chunk<SCHEME, BITS>(acc, map, lane, tile.elem0 + int64_t(c) * kChunk, key,
+                                     meta_out + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
+                                     packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage);
     }
 }
 
 // tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
 // output (binary32 pass-through layers); the two tables list the same tiles in the same order.
+template <int SCHEME>
 __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int W, int dt,
                                                         const Tile *__restrict__ tiles_in,
                                                         const Tile *__restrict__ tiles_out, int64_t n_tiles,
                                                         int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                                         uint8_t *__restrict__ packed_out,
-                                                        float2 *__restrict__ meta_out)
+                                                        float *__restrict__ meta_out)
 {
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
@@ -865,11 +970,12 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int
         const uint32_t out_pad = tiles_out[t].pad;
         const uint32_t kind = tile_kind(tile);
         if (kind == kQuantFast) {
-            CGX_FOR_BITS(tile_bits(tile), (fused_fast<BITS>(peers, W, tile, out_off, bucket, seed_lo, seed_hi,
-                                                             packed_out, meta_out, lane, stage)))
+            CGX_FOR_BITS(tile_bits(tile), (fused_fast<SCHEME, BITS>(peers, W, tile, out_off, bucket, seed_lo,
+                                                                     seed_hi, packed_out, meta_out, lane, stage)))
         } else if (kind == kQuantSlow) {
-            quantize_generic<false>([&](uint32_t j) { return generic_sum(peers, W, tile, bucket, j, -0.0f); },
-                             packed_out + out_off, meta_out, tile, out_pad, bucket, seed_lo, seed_hi, lane);
+            quantize_generic<SCHEME, false>(
+                [&](uint32_t j) { return generic_sum<SCHEME>(peers, W, tile, bucket, j, -0.0f); },
+                packed_out + out_off, meta_out, tile, out_pad, bucket, seed_lo, seed_hi, lane);
         } else {
             // pass-through: the sum is written as binary32 into the output stream, then its padding
             const SumIo io{nullptr, CGX_F32, packed_out + out_off, CGX_F32};
@@ -922,43 +1028,44 @@ inline unsigned grid_for(int64_t n_tiles, const LaunchConfig &cfg)
 
 }  // namespace
 
-hipError_t launch_quantize(const void *grad, int dt, const Tile *tiles, int64_t n_tiles, int32_t bucket,
-                           uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
+hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles,
+                           int32_t bucket, uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
                            hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const uint32_t seed_lo = uint32_t(seed), seed_hi = uint32_t(seed >> 32);
-    if (dt == CGX_F16)
-        hipLaunchKernelGGL(quantize_kernel<CGX_F16>, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket),
-                           seed_lo, seed_hi, static_cast<uint8_t *>(packed), static_cast<float2 *>(meta));
-    else
-        hipLaunchKernelGGL(quantize_kernel<CGX_F32>, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket),
-                           seed_lo, seed_hi, static_cast<uint8_t *>(packed), static_cast<float2 *>(meta));
+    const auto kernel = scheme == kSchemeNormSign
+                            ? (dt == CGX_F16 ? quantize_kernel<kNormSign, CGX_F16> : quantize_kernel<kNormSign, CGX_F32>)
+                            : (dt == CGX_F16 ? quantize_kernel<kMinMax, CGX_F16> : quantize_kernel<kMinMax, CGX_F32>);
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket), seed_lo, seed_hi,
+                       static_cast<uint8_t *>(packed), static_cast<float *>(meta));
     return hipGetLastError();
 }
 
-hipError_t launch_dequant_reduce(const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
                                  const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const SumIo io{init, init_dt, out, out_dt};
-    hipLaunchKernelGGL(reduce_kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles, int(bucket));
+    const auto kernel = scheme == kSchemeNormSign ? reduce_kernel<kNormSign> : reduce_kernel<kMinMax>;
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles, int(bucket));
     return hipGetLastError();
 }
 
-hipError_t launch_dequant_reduce_requantize(const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
+hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
                                             const Tile *tiles_out, int64_t n_tiles, int32_t bucket,
                                             uint64_t seed, void *packed_out, void *meta_out,
                                             const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
-    hipLaunchKernelGGL(fused_kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles,
-                       int(bucket), uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
-                       static_cast<float2 *>(meta_out));
+    const auto kernel = scheme == kSchemeNormSign ? fused_kernel<kNormSign> : fused_kernel<kMinMax>;
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles, int(bucket),
+                       uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
+                       static_cast<float *>(meta_out));
     return hipGetLastError();
 }
 

@@ -1,0 +1,192 @@
+"""Parity of the norm-and-sign quantizer (cgx_qsgd_* through the C ABI) with the CPU oracle.
+
+Bar as for the min/max form: packed stream and meta bit-exact; sums bit-exact against
+the oracle's ordered binary32 sum and within 1e-6 * sum_w |deq_w| of its binary64 sum.
+Chunks fed to the reduce come from the oracle's quantizer, never from the GPU.
+"""
+import numpy as np
+import pytest
+
+from paper_2111_08617_amd import binding as cgx
+from paper_2111_08617_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    cgx.lib()
+    return t
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def no_one_bit(w):
+    """The same workload with its 1-bit layers widened to 2 bits (a sign bit alone carries no level)."""
+    w.bits = np.where(w.bits == 1, 2, w.bits).astype(np.uint8)
+    return w
+
+
+def gpu_quantize(torch, grad, offsets, bits, bucket, seed, dt):
+    plan = cgx.Plan(offsets, bits, bucket, dt)
+    pb, mb = cgx.cgx_qsgd_sizes(plan)
+    packed = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    meta = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+    g = grad if isinstance(grad, torch.Tensor) else dev(torch, grad)
+    cgx.cgx_qsgd_quantize(g, plan, seed, packed, meta)
+    torch.cuda.synchronize()
+    p, m = packed.cpu().numpy(), meta.cpu().numpy()
+    assert (p[pb:] == 0xA5).all() and (m[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+    return p[:pb], m[:mb // 4]
+
+
+def device_chunks(torch, chunks, metas):
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m) if m.size else torch.zeros(4, device="cuda") for m in metas]
+    return dp, dm
+
+
+def gpu_reduce(torch, chunks, metas, offsets, bits, bucket, dt):
+    plan = cgx.Plan(offsets, bits, bucket, dt)
+    dp, dm = device_chunks(torch, chunks, metas)
+    total = torch.full((plan.n + 16,), 123.0, dtype=torch.float32, device="cuda")
+    cgx.cgx_qsgd_dequant_reduce(dp, dm, plan, total)
+    torch.cuda.synchronize()
+    out = total.cpu().numpy()
+    assert (out[plan.n:] == 123.0).all(), "wrote past the end of the sum"
+    return out[:plan.n], total
+
+
+def gpu_fused(torch, chunks, metas, offsets, bits, bucket, dt, seed):
+    plan = cgx.Plan(offsets, bits, bucket, dt)
+    pb, mb = cgx.cgx_qsgd_sizes(cgx.Plan(offsets, bits, bucket, wl.F32))
+    dp, dm = device_chunks(torch, chunks, metas)
+    packed = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    meta = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+    cgx.cgx_qsgd_dequant_reduce_requantize(dp, dm, plan, seed, packed, meta)
+    torch.cuda.synchronize()
+    p, m = packed.cpu().numpy(), meta.cpu().numpy()
+    assert (p[pb:] == 0xA5).all() and (m[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+    return p[:pb], m[:mb // 4]
+
+
+def assert_same_chunk(gp, gm, op, om, what=""):
+    assert gm.tobytes() == om.tobytes(), f"{what}: meta differs in {int((gm.view(np.uint32) != om.view(np.uint32)).sum())} words"
+    if not np.array_equal(gp, op):
+        bad = np.nonzero(gp != op)[0]
+        raise AssertionError(f"{what}: packed differs in {bad.size} bytes, first at {bad[:5]}")
+
+
+def assert_sum_parity(got, ref, what=""):
+    g, r = got.view(np.uint32), ref["sum32"].view(np.uint32)
+    assert np.array_equal(g, r), f"{what}: {int((g != r).sum())} sums differ from the ordered binary32 sum"
+    err = np.abs(got.astype(np.float64) - ref["sum64"])
+    assert (err <= 1e-6 * ref["abs64"] + 1e-45).all(), f"{what}: worst relative error {np.max(err / (ref['abs64'] + 1e-300))}"
+
+
+def full_cycle(torch, oracle, w, W, what=""):
+    chunks, metas = [], []
+    for peer in range(W):
+        g = w.gradient(peer)
+        seed = w.quant_seed(peer)
+        op, om = oracle.qsgd_quantize(g, w.offsets, w.bits, w.bucket, seed, w.dt)
+        if peer < 2:
+            gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, seed, w.dt)
+            assert_same_chunk(gp, gm, op, om, f"{what} quantize peer {peer}")
+        chunks.append(op)
+        metas.append(om)
+    ref = oracle.qsgd_dequant_reduce(chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
+    got, total = gpu_reduce(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
+    assert_sum_parity(got, ref, f"{what} reduce")
+    rp, rm = gpu_quantize(torch, total[:w.n], w.offsets, w.bits, w.bucket, 99, wl.F32)
+    op, om = oracle.qsgd_quantize(got, w.offsets, w.bits, w.bucket, 99, wl.F32)
+    assert_same_chunk(rp, rm, op, om, f"{what} requantize")
+    if W <= cgx.MAX_FUSED_PEERS:
+        fp, fm = gpu_fused(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt, 99)
+        op, om = oracle.qsgd_quantize(ref["sum32"], w.offsets, w.bits, w.bucket, 99, wl.F32)
+        assert_same_chunk(fp, fm, op, om, f"{what} fused reduce+requantize")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [32, 96, 128, 512, 4096, 8192])
+def test_edge_case_plan(torch, oracle, bucket, dt):
+    """Bit widths 2..8, pass-through, empty, tiny and ragged layers, odd offsets."""
+    w = no_one_bit(wl.tiny_mixed(seed=bucket + dt, dt=dt, bucket=bucket))
+    full_cycle(torch, oracle, w, W=3, what=f"qsgd tiny_mixed B={bucket}")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [32, 64, 128, 256, 512, 1024, 2048])
+def test_vectorised_path_all_bit_widths(torch, oracle, bucket, dt):
+    sizes = [2048 * 3, 2048 * 2 + 40, 8, 2048, 2048 * 5 + 1000, 2048 * 4, 16384, 2048 + bucket, 6144, 8192 * 2 + 24]
+    bits = [2, 2, 0, 3, 4, 5, 0, 6, 7, 8]
+    w = wl.Workload("chunks", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 4, 2000 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    full_cycle(torch, oracle, w, W=4, what=f"qsgd chunks B={bucket}")
+
+
+@pytest.mark.parametrize("W", [1, 5, 16, 17, 40])
+def test_peer_counts(torch, oracle, W):
+    """Every peer-block size of a launch, and more peers than one launch takes."""
+    sizes = [2048 * 2, 2048 + 24, 2048 * 3, 100]
+    w = wl.Workload("peers", [(s,) for s in sizes], np.array([4, 3, 8, 0], np.uint8), 128, wl.F32, W, 77 + W,
+                    wl._normal, np.ones(len(sizes)))
+    full_cycle(torch, oracle, w, W=W, what=f"qsgd W={W}")
+
+
+def test_signed_zeros_constant_and_non_finite_values(torch, oracle):
+    """Zeros of either sign decode to +0; a non-finite value zeroes the bucket's unit; both
+    sides agree bit for bit."""
+    rng = np.random.default_rng(5)
+    n, B = 2048 * 3 + 200, 128
+    x = rng.standard_normal(n).astype(np.float32)
+    x[:B] = 0.0
+    x[5] = -0.0
+    x[B:2 * B] = -3.5                                   # constant bucket: every level is the top one
+    x[2 * B + 3] = np.inf
+    x[3 * B + 9] = -np.inf
+    x[4 * B + 1] = np.nan
+    x[5 * B:6 * B] = np.float32(1e-42) * rng.integers(-3, 4, B)   # subnormal magnitudes
+    x[-150:] = np.abs(x[-150:])                          # a one-signed ragged tail
+    off, bits = np.array([0, n], np.int64), np.array([4], np.uint8)
+    op, om = oracle.qsgd_quantize(x, off, bits, B, 11)
+    gp, gm = gpu_quantize(torch, x, off, bits, B, 11, wl.F32)
+    assert_same_chunk(gp, gm, op, om, "qsgd special values")
+    ref = oracle.qsgd_dequant_reduce([op, op], [om, om], off, bits, B)
+    got, _ = gpu_reduce(torch, [op, op], [om, om], off, bits, B, wl.F32)
+    assert np.array_equal(got.view(np.uint32), ref["sum32"].view(np.uint32))
+    assert not np.signbit(got[5]) and got[5] == 0.0 and (got[B:2 * B] == -7.0).all()
+
+
+def test_resnet50_config_full_size(torch, oracle):
+    """161 tensors, 25.6M elements, 4 bit, bucket 1024, small tensors pass-through, W = 8."""
+    full_cycle(torch, oracle, no_one_bit(wl.resnet50()), W=8, what="qsgd resnet50")
+
+
+def test_gpt2_medium_config_full_size(torch, oracle):
+    """355M elements in binary16 storage, 4 bit, bucket 128: quantize the full buffer; reduce over
+    W = 8, requantize and the fused form on one rank's 1/8 share."""
+    w = no_one_bit(wl.gpt2_medium())
+    g = w.gradient(0, threads=16)
+    gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    op, om = oracle.qsgd_quantize(g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
+    assert_same_chunk(gp, gm, op, om, "qsgd gpt2_medium quantize")
+    del g, gp, op
+    first, sub_off, sub_bits = wl.share_subplan(w.offsets, w.bits, w.bucket, w.W, 5)
+    m = int(sub_off[-1])
+    chunks, metas = [], []
+    for peer in range(w.W):
+        x = w.gradient(peer, first, first + m)
+        op, om = oracle.qsgd_quantize(x, sub_off, sub_bits, w.bucket, w.quant_seed(peer), w.dt)
+        chunks.append(op)
+        metas.append(om)
+    ref = oracle.qsgd_dequant_reduce(chunks, metas, sub_off, sub_bits, w.bucket, w.dt)
+    got, total = gpu_reduce(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt)
+    assert_sum_parity(got, ref, "qsgd gpt2_medium share reduce")
+    fp, fm = gpu_fused(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt, 7)
+    op, om = oracle.qsgd_quantize(ref["sum32"], sub_off, sub_bits, w.bucket, 7, wl.F32)
+    assert_same_chunk(fp, fm, op, om, "qsgd gpt2_medium share fused reduce+requantize")

@@ -135,6 +135,36 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 0, 0, z.ctypes.data, None, 128, 0, None, None) == 0
 
 
+def test_norm_and_sign_entry_points_check_their_arguments(lib, oracle):
+    c = ctypes
+    off = np.array([0, 100, 300, 1300], np.int64)
+    o = off.ctypes.data
+    pb, mb = c.c_size_t(), c.c_size_t()
+    ok = np.array([4, 0, 2], np.uint8)
+    one = np.array([4, 0, 1], np.uint8)
+    assert lib.cgx_qsgd_sizes(1300, 3, o, ok.ctypes.data, 128, 0, c.byref(pb), c.byref(mb)) == 0
+    assert (pb.value, mb.value) == oracle.qsgd_sizes(off, ok, 128)
+    assert mb.value == 4 * (1 + 8)                                    # one float per bucket
+    assert lib.cgx_qsgd_sizes(1300, 3, o, one.ctypes.data, 128, 0, c.byref(pb), c.byref(mb)) == -4
+    assert lib.cgx_qsgd_sizes(1300, 3, o, ok.ctypes.data, 100, 0, c.byref(pb), c.byref(mb)) == -5
+    buf = 0x1000                                                      # never dereferenced
+    ptrs = (c.c_void_p * 2)(buf, buf)
+    assert lib.cgx_qsgd_quantize(buf, 1300, 3, o, one.ctypes.data, 128, 0, 0, buf, buf, None) == -4
+    assert lib.cgx_qsgd_quantize(None, 1300, 3, o, ok.ctypes.data, 128, 0, 0, buf, buf, None) == -1
+    assert lib.cgx_qsgd_quantize(buf, 1300, 3, o, ok.ctypes.data, 128, 0, 0, buf + 4, buf, None) == -9
+    assert lib.cgx_qsgd_dequant_reduce(ptrs, ptrs, 2, 1300, 3, o, one.ctypes.data, 128, 0, buf, None) == -4
+    assert lib.cgx_qsgd_dequant_reduce(ptrs, ptrs, 65, 1300, 3, o, ok.ctypes.data, 128, 0, buf, None) == -6
+    assert lib.cgx_qsgd_dequant_reduce(ptrs, ptrs, 2, 1300, 3, o, ok.ctypes.data, 128, 0, None, None) == -1
+    fused = lib.cgx_qsgd_dequant_reduce_requantize
+    assert fused(ptrs, ptrs, 2, 1300, 3, o, one.ctypes.data, 128, 0, 1, buf, buf, None) == -4
+    assert fused(ptrs, ptrs, 17, 1300, 3, o, ok.ctypes.data, 128, 0, 1, buf, buf, None) == -6
+    assert fused(ptrs, ptrs, 2, 1300, 3, o, ok.ctypes.data, 128, 0, 1, buf, None, None) == -1
+    for name in ("resnet50", "gpt2_medium"):
+        w = wl.WORKLOADS[name]()
+        plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+        assert cgx.cgx_qsgd_sizes(plan) == oracle.qsgd_sizes(w.offsets, w.bits, w.bucket, w.dt)
+
+
 def layer_segments(w):
     """(segment start, payload bytes, first bucket) per layer from the layout rules."""
     seg, g, out = 0, 0, []

@@ -10,6 +10,12 @@ import pytest
 from paper_2111_08617_amd import workloads as wl
 
 
+def signed_levels(codes, b):
+    """b-bit two's complement codes -> signed levels."""
+    codes = np.asarray(codes).astype(np.int64)
+    return codes - ((codes >> (b - 1)) << b)
+
+
 def one_layer(n, b):
     return np.array([0, n], np.int64), np.array([b], np.uint8)
 
@@ -17,7 +23,7 @@ def one_layer(n, b):
 @pytest.mark.parametrize("b", [2, 3, 4, 8])
 def test_levels_follow_the_printed_rule_exactly_enumerated(oracle, b):
     """All 65536 draws for every element of a bucket: E[level] = |v| / ||v|| * s, levels are the two
-    neighbours, the sign bit is the sign of v, and the largest |v| always gets level s."""
+    neighbours, the code carries the sign of v, and the largest |v| always gets level s."""
     rng = np.random.default_rng(40 + b)
     B, s, K = 32, (1 << (b - 1)) - 1, 65536
     x = rng.standard_normal(B).astype(np.float32)
@@ -27,7 +33,9 @@ def test_levels_follow_the_printed_rule_exactly_enumerated(oracle, b):
     draws = np.repeat(np.arange(K, dtype=np.uint16), B)
     packed, meta = oracle.qsgd_quantize(grad, offsets, bits, B, seed=0, draws=draws)
     codes = oracle.unpack_codes(packed, offsets, bits, B).reshape(K, B).astype(np.int64)
-    level, sign = codes & s, codes >> (b - 1)
+    signed = signed_levels(codes, b)
+    level = np.abs(signed)
+    assert (codes != 1 << (b - 1)).all()                               # -2^(b-1) is never used
     norm = Fraction(float(np.abs(x).max()))
     tol = Fraction(1, 65536) + Fraction(4 * s, 1 << 24)
     for j in range(B):
@@ -36,7 +44,7 @@ def test_levels_follow_the_printed_rule_exactly_enumerated(oracle, b):
         assert seen.max() - seen.min() <= 1
         assert seen.min() >= int(np.floor(pos - tol)) and seen.max() <= int(np.ceil(pos + tol))
         assert abs(Fraction(int(level[:, j].sum()), K) - pos) <= tol
-        assert (sign[:, j] == (1 if x[j] < 0 else 0)).all()
+        assert (signed[:, j] * (-1 if x[j] < 0 else 1) >= 0).all()      # never the other sign
     top = level[:, int(np.abs(x).argmax())]
     assert (top >= s - 1).all() and (top == s).sum() >= K - 4
     assert np.allclose(meta, float(norm) / s, rtol=1e-6)
@@ -71,8 +79,8 @@ def test_exact_on_symmetric_power_of_two_grids(oracle):
         for seed in (0, 99):
             p, m = oracle.qsgd_quantize(x, off, bits, B, seed=seed)
             assert (m == np.float32(2.0 ** -9)).all()
-            codes = oracle.unpack_codes(p, off, bits, B).astype(np.int64)
-            assert np.array_equal(codes & s, np.abs(lv))
+            codes = oracle.unpack_codes(p, off, bits, B)
+            assert np.array_equal(signed_levels(codes, b), lv)
             d = oracle.qsgd_dequant_reduce([p], [m], off, bits, B)
             assert np.array_equal(d["sum32"], x) and np.array_equal(d["sum64"], x.astype(np.float64))
 
@@ -84,10 +92,16 @@ def test_zero_bucket_sizes_and_rejection_of_one_bit(oracle):
     off, bits = one_layer(n, 4)
     p, m = oracle.qsgd_quantize(x, off, bits, B, seed=1)
     assert not m.any()
-    codes = oracle.unpack_codes(p, off, bits, B)
-    assert codes[130] == 8 and codes.sum() == 8                 # only the sign bit of the -0
+    assert not oracle.unpack_codes(p, off, bits, B).any()      # sign(0) * 0 has the one code 0
     d = oracle.qsgd_dequant_reduce([p], [m], off, bits, B)["sum32"]
-    assert np.array_equal(d, x) and np.signbit(d[130])
+    assert np.array_equal(d, x) and not np.signbit(d).any()
+    y = np.full(n, -1e-30, np.float32)                          # negative values that round to level 0
+    y[::B] = 1.0
+    p, m = oracle.qsgd_quantize(y, off, bits, B, seed=2)
+    codes = oracle.unpack_codes(p, off, bits, B)
+    assert (codes[::B] == 7).all() and codes.sum() == 7 * (n // B)
+    d = oracle.qsgd_dequant_reduce([p], [m], off, bits, B)["sum32"]
+    assert (d[1:B] == 0).all() and not np.signbit(d[1:B]).any()
     pb, mb = oracle.qsgd_sizes(off, bits, B)
     pb2, mb2 = oracle.sizes(off, bits, B)
     assert pb == pb2 and 2 * mb == mb2                          # one float of meta per bucket
@@ -108,7 +122,7 @@ def test_reduce_is_exact_on_integer_grids_and_layout_is_shared(oracle):
         total += lv * (w + 1)
         p, m = oracle.qsgd_quantize((lv * (w + 1)).astype(np.float32), off, bits, B, seed=w)
         # the stream is the same LSB-first layout: code j in bits [4j, 4j+4)
-        codes = np.where(lv < 0, 8, 0) + np.abs(lv)
+        codes = lv & 15                                          # two's complement nibbles
         big = 0
         for j, c in enumerate(codes.tolist()):
             big |= c << (4 * j)
