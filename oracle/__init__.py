@@ -62,6 +62,9 @@ def _load():
         lib.oracle_qsgd_quantize_with_draws.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_qsgd_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_layer_sqnorms.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p, c.c_int32, c.c_void_p]
+        lib.oracle_layer_sqerrors.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p] + plan + \
+            [c.c_int32, c.c_void_p]
         lib.oracle_unpack_codes.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p]
         _lib = lib
     return _lib
@@ -258,3 +261,31 @@ def qsgd_dequant_reduce(packed_list, meta_list, offsets, bits, bucket: int, dt: 
                                             _ptr(out["sum32"]), _ptr(out["sum64"]), _ptr(out["abs64"]))
     _check(rc, "qsgd_dequant_reduce")
     return {k: v for k, v in out.items() if v is not None}
+
+
+# ---- per-layer statistics for the adaptive scheme
+
+def layer_sqnorms(buf, offsets, dt: int = F32):
+    """float64[L]: sum of squares of every layer of the buffer."""
+    off = np.ascontiguousarray(offsets, dtype=np.int64)
+    n, L = int(off[-1]), off.size - 1
+    g = _grad(buf, n, dt)
+    out = np.zeros(L, dtype=np.float64)
+    _check(_load().oracle_layer_sqnorms(_ptr(g), n, L, _ptr(off), dt, _ptr(out)), "layer_sqnorms")
+    return out
+
+
+def layer_sqerrors(grad, packed, meta, offsets, bits, bucket: int, dt: int = F32, scheme: int = 0):
+    """float64[L]: squared l2 norm of grad - dequantize(packed, meta) per layer
+    (scheme 0: min/max form, 1: norm-and-sign form)."""
+    off, bt, n, L = _plan(offsets, bits)
+    g = _grad(grad, n, dt)
+    pk = np.ascontiguousarray(packed, dtype=np.uint8)
+    mt = np.ascontiguousarray(meta, dtype=np.float32).reshape(-1)
+    pb, mb = (qsgd_sizes if scheme == 1 else sizes)(off, bt, bucket, dt)
+    if pk.size != pb or mt.size * 4 != mb:
+        raise ValueError("chunk sizes do not match the plan")
+    out = np.zeros(L, dtype=np.float64)
+    _check(_load().oracle_layer_sqerrors(scheme, _ptr(g), _ptr(pk), _ptr(mt), n, L, _ptr(off), _ptr(bt), bucket, dt,
+                                         _ptr(out)), "layer_sqerrors")
+    return out

@@ -582,3 +582,71 @@ int oracle_qsgd_dequant_reduce(const uint8_t *const *packed, const float *const 
     }
     return ORACLE_OK;
 }
+
+/* ======================================================================== *
+ * Per-layer statistics for the layer-wise adaptive scheme (Sec. "Layer-wise
+ * Adaptive Quantization"): the squared l2 norm of every layer of a fused
+ * buffer (the second coordinate of Algorithm 1's points is its square root)
+ * and the squared l2 norm of the compression error of every layer (the
+ * quantity the problem definition bounds by alpha * E_4).  Sums are carried in
+ * long double and rounded to binary64 once, so the oracle's own rounding is
+ * far below the tolerance the GPU sums are checked with.
+ * ======================================================================== */
+
+int oracle_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *off, int32_t dt, double *out)
+{
+    if (n < 0 || L < 0 || (L > 0 && (!off || !out)) || (dt != DT_F32 && dt != DT_F16)) return ORACLE_ERR_ARG;
+    if (L == 0) return n == 0 ? ORACLE_OK : ORACLE_ERR_ARG;
+    if (off[0] != 0 || off[L] != n) return ORACLE_ERR_ARG;
+    for (int32_t l = 0; l < L; l++) {
+        if (off[l + 1] < off[l]) return ORACLE_ERR_ARG;
+        long double acc = 0.0L;
+        for (int64_t i = off[l]; i < off[l + 1]; i++) {
+            long double x = (long double)load_elem(buf, i, dt);
+            acc += x * x;
+        }
+        out[l] = (double)acc;
+    }
+    return ORACLE_OK;
+}
+
+/* out[l] = sum over the layer of (x_i - value of its code)^2, the value being the binary32 one
+ * the dequantizer returns; 0 for pass-through layers.  scheme 0: min/max form (meta {unit, mn}),
+ * scheme 1: norm-and-sign form (meta unit). */
+int oracle_layer_sqerrors(int32_t scheme, const void *grad, const uint8_t *packed, const float *meta, int64_t n,
+                          int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int32_t dt,
+                          double *out)
+{
+    int rc = check_plan(n, L, off, bits, bucket, dt);
+    if (rc) return rc;
+    if ((scheme != 0 && scheme != 1) || (scheme == 1 && check_qsgd_bits(L, bits))) return ORACLE_ERR_ARG;
+    if (L > 0 && !out) return ORACLE_ERR_ARG;
+    uint64_t seg_start = 0, bucket0 = 0;
+    for (int32_t l = 0; l < L; l++) {
+        int64_t first = off[l], len = off[l + 1] - off[l];
+        int b = bits[l];
+        uint64_t seg_bytes, n_buckets;
+        layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
+        long double acc = 0.0L;
+        if (b != 0) {
+            const uint8_t *seg = packed + seg_start;
+            for (int64_t j = 0; j < len; j++) {
+                uint64_t g = bucket0 + (uint64_t)(j / bucket);
+                uint32_t code = get_bits(seg, (uint64_t)j * b, b);
+                float v;
+                if (scheme == 1) {
+                    int32_t level = (int32_t)code - (int32_t)((code >> (b - 1)) << b);
+                    v = (float)level * meta[g];
+                } else {
+                    v = fmaf((float)code, meta[2 * g], meta[2 * g + 1]);
+                }
+                long double d = (long double)load_elem(grad, first + j, dt) - (long double)v;
+                acc += d * d;
+            }
+        }
+        out[l] = (double)acc;
+        seg_start += seg_bytes;
+        bucket0 += n_buckets;
+    }
+    return ORACLE_OK;
+}
