@@ -195,6 +195,73 @@ int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *co
                                        uint64_t seed, void *packed_out, void *meta_out, void *stream);
 
 /*
+ * Per-layer statistics for the layer-wise adaptive scheme (paper Sec. "Layer-wise
+ * Adaptive Quantization").  Sums are binary64; squares of binary32 values and
+ * differences of two binary32 values are exact in binary64, so only the additions
+ * round, and their order is fixed (no atomics): a result is reproducible bit for bit
+ * and lies within (140 + tiles_of_the_layer / 64) * 2^-53, relative, of the exact sum.
+ *
+ * cgx_layer_sqnorms: sqnorm[l] = sum of x_i^2 over layer l of buf (n elements of dt):
+ * the squared "norm(G_l)" of Algorithm 1 when buf holds the accumulated gradient.
+ * cgx_layer_sqerrors / cgx_qsgd_layer_sqerrors: sqerr[l] = sum over layer l of
+ * (grad_i - value of its code)^2 for a chunk written by cgx_quantize /
+ * cgx_qsgd_quantize from grad with the same plan: the squared l2 norm of the
+ * compression error that the problem definition bounds by alpha * E_4; 0 for
+ * pass-through and empty layers.
+ *   sqnorm, sqerr  device, L doubles (8-byte aligned), every entry written
+ *   workspace      device, 16-byte aligned, at least the bytes cgx_layer_stats_workspace
+ *                  reports for the same plan (bits_per_layer = NULL and any valid bucket
+ *                  for cgx_layer_sqnorms); holds one partial sum per wavefront work item
+ *                  during the call, contents unspecified afterwards; CGX_ERR_SIZE if it
+ *                  is too small.  Calls that share a workspace must not overlap.
+ */
+int cgx_layer_stats_workspace(int64_t n, int32_t L, const int64_t *layer_offsets,
+                              const uint8_t *bits_per_layer /* NULL: for cgx_layer_sqnorms */,
+                              int32_t bucket, cgx_dtype dt, size_t *bytes);
+int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *layer_offsets, cgx_dtype dt,
+                      double *sqnorm, void *workspace, size_t workspace_bytes, void *stream);
+int cgx_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                       const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                       cgx_dtype dt, double *sqerr, void *workspace, size_t workspace_bytes, void *stream);
+int cgx_qsgd_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                            const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                            cgx_dtype dt, double *sqerr, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/*
+ * Bit-width assigners of the layer-wise adaptive scheme (same section; host only, no
+ * device work).  Inputs: the layer table, one non-negative number per layer
+ * (layer_norms: the l2 norm of the layer's accumulated gradient, i.e. the square root of
+ * cgx_layer_sqnorms' output), bits_in (0 marks a layer that stays uncompressed, as in
+ * every plan), and k candidate widths in 1..8 (any order; used in ascending order).
+ * bits_out[l] is 0 for layers with bits_in[l] == 0 or no elements, else one of the
+ * candidates; it is a valid bits_per_layer for every call above.
+ *
+ * cgx_assign_bits_kmeans (Algorithm 1): each taking-part layer is the point
+ * (size, norm), both axes scaled to [0, 1] by their minimum and maximum over those
+ * layers (an axis without spread becomes 0).  Lloyd's k-means with k clusters: the
+ * points are ordered by norm - size (ties: layer order), cluster c starts at the point
+ * of rank floor((c + 1/2) * M / k); every point goes to its nearest centroid (squared
+ * Euclidean distance, ties to the lowest index); centroids become the means of their
+ * points (an empty cluster keeps its centroid); stop when nothing moves or after
+ * max_iter rounds.  Non-empty clusters are ranked by centroid norm - size, ascending;
+ * rank r of m gets candidate number round_half_up(r * (k - 1) / (m - 1)) (m = 1: the
+ * largest), so large layers with small gradients get the fewest bits.  With M <= k
+ * points every point is its own cluster.
+ * cgx_assign_bits_linear (the sort-and-interpolate heuristic): layers ordered by
+ * norm / size, ascending (ties: layer order); rank r of M gets candidate number
+ * floor(r * k / M).
+ * Errors: CGX_ERR_NULL, CGX_ERR_SIZE (L < 0, k outside 1..64, max_iter < 1),
+ * CGX_ERR_OFFSETS, CGX_ERR_BITS (a candidate outside 1..8, bits_in above 8).
+ */
+int cgx_assign_bits_kmeans(int32_t L, const int64_t *layer_offsets /* host [L+1] */,
+                           const double *layer_norms /* host [L] */, const uint8_t *bits_in /* host [L] */,
+                           const uint8_t *candidates /* host [k] */, int32_t k, int32_t max_iter,
+                           uint8_t *bits_out /* host [L] */);
+int cgx_assign_bits_linear(int32_t L, const int64_t *layer_offsets, const double *layer_norms,
+                           const uint8_t *bits_in, const uint8_t *candidates, int32_t k, uint8_t *bits_out);
+
+/*
  * Diagnostic: the table of wavefront work items ("tiles") the kernels walk for
  * a plan, written to host memory as 32-byte records
  *   { int64 first_element; int64 packed_byte_offset; uint32 first_bucket;

@@ -23,7 +23,9 @@ MAX_FUSED_PEERS = 16
 EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduce_add", "cgx_dequantize",
            "cgx_requantize",
            "cgx_dequant_reduce_requantize", "cgx_qsgd_sizes", "cgx_qsgd_quantize", "cgx_qsgd_dequant_reduce",
-           "cgx_qsgd_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
+           "cgx_qsgd_dequant_reduce_requantize", "cgx_layer_stats_workspace", "cgx_layer_sqnorms",
+           "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
+           "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -62,6 +64,16 @@ def lib() -> ctypes.CDLL:
         L.cgx_qsgd_quantize.argtypes = L.cgx_quantize.argtypes
         L.cgx_qsgd_dequant_reduce.argtypes = L.cgx_dequant_reduce.argtypes
         L.cgx_qsgd_dequant_reduce_requantize.argtypes = L.cgx_dequant_reduce_requantize.argtypes
+        L.cgx_layer_stats_workspace.argtypes = plan + [c.c_int, c.POINTER(c.c_size_t)]
+        L.cgx_layer_sqnorms.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p, c.c_int, c.c_void_p, c.c_void_p,
+                                        c.c_size_t, c.c_void_p]
+        L.cgx_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + plan + \
+            [c.c_int, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.cgx_qsgd_layer_sqerrors.argtypes = L.cgx_layer_sqerrors.argtypes
+        L.cgx_assign_bits_kmeans.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                                             c.c_int32, c.c_void_p]
+        L.cgx_assign_bits_linear.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                                             c.c_void_p]
         L.cgx_stream_probe.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_status_string.restype = c.c_char_p
@@ -216,6 +228,57 @@ def cgx_qsgd_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: P
     _check(lib().cgx_qsgd_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
                                                     packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
            "cgx_qsgd_dequant_reduce_requantize")
+
+
+def cgx_layer_stats_workspace(plan: Plan, for_sqnorms: bool = False) -> int:
+    """Bytes of device workspace the per-layer statistics need for this plan."""
+    nbytes = ctypes.c_size_t()
+    bits = None if for_sqnorms else plan.bits.ctypes.data
+    _check(lib().cgx_layer_stats_workspace(plan.n, plan.L, plan.offsets.ctypes.data, bits, plan.bucket, plan.dt,
+                                           ctypes.byref(nbytes)), "cgx_layer_stats_workspace")
+    return int(nbytes.value)
+
+
+def cgx_layer_sqnorms(buf, plan: Plan, sqnorm, workspace, stream=None) -> None:
+    """sqnorm (device float64[L]) = per-layer sums of squares of buf; workspace: device uint8 tensor."""
+    _check(lib().cgx_layer_sqnorms(buf.data_ptr(), plan.n, plan.L, plan.offsets.ctypes.data, plan.dt,
+                                   sqnorm.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)), "cgx_layer_sqnorms")
+
+
+def cgx_layer_sqerrors(grad, packed, meta, plan: Plan, sqerr, workspace, stream=None, qsgd: bool = False) -> None:
+    """sqerr (device float64[L]) = per-layer squared l2 norm of grad - dequantize(packed, meta)."""
+    fn = lib().cgx_qsgd_layer_sqerrors if qsgd else lib().cgx_layer_sqerrors
+    _check(fn(grad.data_ptr(), packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt, sqerr.data_ptr(),
+              workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "cgx_qsgd_layer_sqerrors" if qsgd else "cgx_layer_sqerrors")
+
+
+def _assign_inputs(layer_offsets, layer_norms, bits_in, candidates):
+    off = np.ascontiguousarray(layer_offsets, dtype=np.int64)
+    norms = np.ascontiguousarray(layer_norms, dtype=np.float64)
+    bits = np.ascontiguousarray(bits_in, dtype=np.uint8)
+    cand = np.ascontiguousarray(candidates, dtype=np.uint8)
+    if off.size != bits.size + 1 or norms.size != bits.size:
+        raise ValueError("one norm and one bits_in entry per layer, one more offset")
+    return off, norms, bits, cand, np.zeros(bits.size, dtype=np.uint8)
+
+
+def cgx_assign_bits_kmeans(layer_offsets, layer_norms, bits_in, candidates, max_iter: int = 100) -> np.ndarray:
+    """bits_per_layer chosen by the k-means assigner (host arrays in, uint8[L] out)."""
+    off, norms, bits, cand, out = _assign_inputs(layer_offsets, layer_norms, bits_in, candidates)
+    _check(lib().cgx_assign_bits_kmeans(bits.size, off.ctypes.data, norms.ctypes.data, bits.ctypes.data,
+                                        cand.ctypes.data, cand.size, max_iter, out.ctypes.data),
+           "cgx_assign_bits_kmeans")
+    return out
+
+
+def cgx_assign_bits_linear(layer_offsets, layer_norms, bits_in, candidates) -> np.ndarray:
+    """bits_per_layer chosen by the sort-and-interpolate heuristic."""
+    off, norms, bits, cand, out = _assign_inputs(layer_offsets, layer_norms, bits_in, candidates)
+    _check(lib().cgx_assign_bits_linear(bits.size, off.ctypes.data, norms.ctypes.data, bits.ctypes.data,
+                                        cand.ctypes.data, cand.size, out.ctypes.data), "cgx_assign_bits_linear")
+    return out
 
 
 def cgx_stream_probe(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:

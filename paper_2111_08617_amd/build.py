@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcgx.so")
-SOURCES = ["cgx_plan.cpp", "cgx_api.cpp", "cgx_kernels.hip"]
+SOURCES = ["cgx_plan.cpp", "cgx_api.cpp", "cgx_adaptive.cpp", "cgx_kernels.hip"]
 
 # -ffp-contract=off: the code decision is binary32 without fused operations.
 # packed-fp32 instructions stay disabled for this target.

@@ -27,7 +27,29 @@ struct CachedPlan {
     cgx::PlanShape shape;
     int64_t n_tiles = 0;
     Tile *d_tiles = nullptr;
+    // per-layer numbering of the tiles (for the statistics): slot of every tile, first slot of every layer
+    uint32_t *d_slots = nullptr;
+    int64_t *d_layer_first = nullptr;
 };
+
+void free_plan(CachedPlan &p)
+{
+    if (p.d_tiles) (void)hipFree(p.d_tiles);
+    if (p.d_slots) (void)hipFree(p.d_slots);
+    if (p.d_layer_first) (void)hipFree(p.d_layer_first);
+    p.d_tiles = nullptr;
+    p.d_slots = nullptr;
+    p.d_layer_first = nullptr;
+}
+
+template <typename T>
+bool upload(T **dst, const std::vector<T> &src)
+{
+    if (src.empty()) return true;
+    const size_t bytes = src.size() * sizeof(T);
+    if (hipMalloc(reinterpret_cast<void **>(dst), bytes) != hipSuccess) return false;
+    return hipMemcpy(*dst, src.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+}
 
 std::mutex g_mutex;
 std::vector<std::unique_ptr<CachedPlan>> g_plans;
@@ -78,15 +100,15 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     plan->bits.assign(bits, bits + L);
     plan->shape = cgx::plan_shape(L, off, bits, bucket, dt);
     std::vector<Tile> tiles;
-    cgx::build_tiles(L, off, bits, bucket, dt, cfg.chunks_per_tile, tiles);
+    std::vector<uint32_t> slots;
+    std::vector<int64_t> layer_first;
+    cgx::build_tiles(L, off, bits, bucket, dt, cfg.chunks_per_tile, tiles, &slots, &layer_first);
+    if (tiles.size() > size_t(0xffffffffu)) return CGX_ERR_SIZE;
     plan->n_tiles = int64_t(tiles.size());
-    if (!tiles.empty()) {
-        const size_t bytes = tiles.size() * sizeof(Tile);
-        if (hipMalloc(reinterpret_cast<void **>(&plan->d_tiles), bytes) != hipSuccess) return CGX_ERR_HIP;
-        if (hipMemcpy(plan->d_tiles, tiles.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
-            (void)hipFree(plan->d_tiles);
-            return CGX_ERR_HIP;
-        }
+    if (!upload(&plan->d_tiles, tiles) || !upload(&plan->d_slots, slots) ||
+        !upload(&plan->d_layer_first, layer_first)) {
+        free_plan(*plan);
+        return CGX_ERR_HIP;
     }
     *out = plan.get();
     g_plans.push_back(std::move(plan));
@@ -193,6 +215,53 @@ int fused_impl(int scheme, const void *const *packed, const void *const *meta, i
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }
 
+// Number of tiles (= doubles of workspace) of the plan the statistics walk; bits == nullptr:
+// the all-pass-through plan cgx_layer_sqnorms uses.
+int stats_tiles(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+                int64_t *n_tiles)
+{
+    std::vector<uint8_t> zeros;
+    if (!bits) {
+        zeros.assign(size_t(L > 0 ? L : 0), 0);
+        bits = zeros.data();
+        bucket = 32;
+    }
+    const int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    if (rc != CGX_OK) return rc;
+    std::vector<Tile> tiles;
+    int chunks = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        chunks = launch_config().chunks_per_tile;
+    }
+    cgx::build_tiles(L, off, bits, bucket, dt, chunks, tiles);
+    *n_tiles = int64_t(tiles.size());
+    return CGX_OK;
+}
+
+int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                  const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, double *sqerr, void *workspace,
+                  size_t workspace_bytes, void *stream)
+{
+    int rc = check_plan(scheme, n, L, off, bits, bucket, dt);
+    if (rc != CGX_OK) return rc;
+    if (L == 0) return CGX_OK;
+    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    if (!sqerr || (n > 0 && (!grad || !packed || !workspace)) || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
+    if (misaligned(grad) || misaligned(packed) || misaligned(meta) || misaligned(workspace) ||
+        (reinterpret_cast<uintptr_t>(sqerr) & 7u))
+        return CGX_ERR_ALIGN;
+    const CachedPlan *plan = nullptr;
+    rc = get_plan(L, off, bits, bucket, dt, &plan);
+    if (rc != CGX_OK) return rc;
+    if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
+    const hipError_t e = cgx::launch_layer_sqerrors(scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots,
+                                                    plan->n_tiles, plan->d_layer_first, L, bucket,
+                                                    static_cast<double *>(workspace), sqerr, launch_config(),
+                                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -295,6 +364,52 @@ int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *co
                       seed, packed_out, meta_out, stream);
 }
 
+int cgx_layer_stats_workspace(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                              int32_t bucket, cgx_dtype dt, size_t *bytes)
+{
+    if (!bytes) return CGX_ERR_NULL;
+    int64_t n_tiles = 0;
+    const int rc = stats_tiles(n, L, layer_offsets, bits_per_layer, bucket, int(dt), &n_tiles);
+    if (rc != CGX_OK) return rc;
+    *bytes = size_t(n_tiles) * sizeof(double);
+    return CGX_OK;
+}
+
+int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *layer_offsets, cgx_dtype dt,
+                      double *sqnorm, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const std::vector<uint8_t> zeros(size_t(L > 0 ? L : 0), 0);
+    int rc = cgx::validate_plan(n, L, layer_offsets, zeros.data(), 32, int(dt));
+    if (rc != CGX_OK) return rc;
+    if (L == 0) return CGX_OK;
+    if (!sqnorm || (n > 0 && (!buf || !workspace))) return CGX_ERR_NULL;
+    if (misaligned(buf) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(sqnorm) & 7u)) return CGX_ERR_ALIGN;
+    const CachedPlan *plan = nullptr;
+    rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), &plan);
+    if (rc != CGX_OK) return rc;
+    if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
+    const hipError_t e = cgx::launch_layer_sqnorms(buf, int(dt), plan->d_tiles, plan->d_slots, plan->n_tiles,
+                                                   plan->d_layer_first, L, static_cast<double *>(workspace), sqnorm,
+                                                   launch_config(), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
+int cgx_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                       const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
+                       double *sqerr, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sqerrors_impl(cgx::kSchemeMinMax, grad, packed, meta, n, L, layer_offsets, bits_per_layer, bucket, int(dt),
+                         sqerr, workspace, workspace_bytes, stream);
+}
+
+int cgx_qsgd_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                            const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
+                            cgx_dtype dt, double *sqerr, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sqerrors_impl(cgx::kSchemeNormSign, grad, packed, meta, n, L, layer_offsets, bits_per_layer, bucket,
+                         int(dt), sqerr, workspace, workspace_bytes, stream);
+}
+
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                    int32_t bucket, cgx_dtype dt, void *tiles_out, int64_t capacity, int64_t *n_tiles)
 {
@@ -344,8 +459,11 @@ int cgx_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     int rc = CGX_OK;
-    for (auto &p : g_plans)
+    for (auto &p : g_plans) {
         if (p->d_tiles && hipFree(p->d_tiles) != hipSuccess) rc = CGX_ERR_HIP;
+        p->d_tiles = nullptr;
+        free_plan(*p);
+    }
     g_plans.clear();
     return rc;
 }

@@ -43,6 +43,18 @@ hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, i
                                             uint64_t seed, void *packed_out, void *meta_out,
                                             const LaunchConfig &cfg, hipStream_t stream);
 
+// Per-layer squared l2 norms of buf (tiles of a plan whose layers are all pass-through) and
+// of the compression error grad - dequantize(packed, meta) (tiles of the chunk's plan).
+// slots / layer_first number the tiles per layer (see build_tiles); partial holds one double
+// per tile; out one double per layer (all device memory).
+hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
+                                const int64_t *layer_first, int32_t L, double *partial, double *out,
+                                const LaunchConfig &cfg, hipStream_t stream);
+hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const void *packed, const void *meta,
+                                 const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
+                                 const int64_t *layer_first, int32_t L, int32_t bucket, double *partial,
+                                 double *out, const LaunchConfig &cfg, hipStream_t stream);
+
 // Measurement aid: streams read_bytes in and write_bytes out (multiples of 16) with the access
 // style of the kernels and no arithmetic; see cgx_stream_probe in cgx.h.
 hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes,

@@ -64,9 +64,11 @@ static inline bool same_key_block(int64_t e0, int64_t count)
 }
 
 void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
-                 int chunks_per_tile, std::vector<Tile> &tiles)
+                 int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots,
+                 std::vector<int64_t> *layer_first)
 {
     tiles.clear();
+    if (layer_first) layer_first->assign(size_t(L) + 1, 0);
     if (chunks_per_tile < 1) chunks_per_tile = 1;
     const int S = elem_size(dt);
     const bool fast_bucket = is_pow2(bucket) && bucket <= kChunk;
@@ -75,6 +77,7 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     uint64_t seg = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         const int64_t first = off[l], len = off[l + 1] - off[l];
+        if (layer_first) (*layer_first)[size_t(l)] = int64_t(tiles.size());
         if (len == 0) continue;
         const int b = bits[l];
         uint64_t payload, buckets;
@@ -130,7 +133,15 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     // Waves take tiles in table order.  The generic and pass-through tiles cost several
     // dependent memory round trips each, so they go first and overlap with the stream
     // of vectorised tiles instead of forming the tail of the launch.
-    std::stable_partition(tiles.begin(), tiles.end(), [](const Tile &t) { return tile_kind(t) != kQuantFast; });
+    if (layer_first) (*layer_first)[size_t(L)] = int64_t(tiles.size());
+    std::vector<uint32_t> order(tiles.size());
+    for (size_t i = 0; i < order.size(); i++) order[i] = uint32_t(i);
+    std::stable_partition(order.begin(), order.end(),
+                          [&](uint32_t i) { return tile_kind(tiles[i]) != kQuantFast; });
+    std::vector<Tile> sorted(tiles.size());
+    for (size_t i = 0; i < order.size(); i++) sorted[i] = tiles[order[i]];
+    tiles.swap(sorted);
+    if (slots) slots->swap(order);
 }
 
 }  // namespace cgx

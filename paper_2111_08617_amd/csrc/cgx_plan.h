@@ -65,7 +65,12 @@ int validate_plan(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
 PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt);
 
 // Tile table.  `chunks_per_tile` bounds the length of fast tiles.
+// With `slots` and `layer_first` (both or neither): numbering the tiles layer by layer and,
+// inside a layer, by first element, tile t of the table has number slots[t], and layer l owns
+// the numbers layer_first[l] .. layer_first[l + 1] - 1 (the per-layer statistics keep one
+// partial sum per tile and add them up in that order).
 void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
-                 int chunks_per_tile, std::vector<Tile> &tiles);
+                 int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots = nullptr,
+                 std::vector<int64_t> *layer_first = nullptr);
 
 }  // namespace cgx
