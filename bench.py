@@ -253,6 +253,40 @@ def main():
                             "hbm_frac": round(ns_alg[k] / ms / 1e6 / HBM_PEAK_GBPS, 4)}
         del ns_chunks
 
+    # per-layer statistics of the adaptive scheme: squared norms of the full buffer, squared
+    # compression error of the full buffer's chunk (read-only kernels: bytes in / time)
+    def timed(fn):
+        for i in range(max(args.warmup // 2, 2)):
+            fn(i)
+        reps = max(args.steps // 2, 5)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+        torch.cuda.synchronize()
+        for i in range(reps):
+            evs[i][0].record()
+            fn(i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+    ws_bytes = max(cgx.cgx_layer_stats_workspace(q_plan), cgx.cgx_layer_stats_workspace(q_plan, for_sqnorms=True), 16)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stat_out = torch.empty(w.L, dtype=torch.float64, device=dev)
+    for r in range(R):
+        cgx.cgx_quantize(grads[r], q_plan, 17 + r, q_out[r][0], q_out[r][1])
+    sqn_ms = timed(lambda i: cgx.cgx_layer_sqnorms(grads[i % R], q_plan, stat_out, ws))
+    sqe_ms = timed(lambda i: cgx.cgx_layer_sqerrors(grads[i % R], q_out[i % R][0], q_out[i % R][1], q_plan, stat_out, ws))
+    sqn_bytes, sqe_bytes = w.n * S, alg["quantize"]
+    layer_stats = {
+        "sqnorms": {"ms": round(sqn_ms, 5), "algorithmic_bytes": int(sqn_bytes),
+                    "algorithmic_GBps": round(sqn_bytes / sqn_ms / 1e6, 1),
+                    "hbm_frac": round(sqn_bytes / sqn_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+        "sqerrors": {"ms": round(sqe_ms, 5), "algorithmic_bytes": int(sqe_bytes),
+                     "algorithmic_GBps": round(sqe_bytes / sqe_ms / 1e6, 1),
+                     "hbm_frac": round(sqe_bytes / sqe_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+        "note": "each figure covers the tile kernel and the per-layer sum kernel (two launches)",
+    }
+    del ws
+
     # what the memory system gives a plain streaming kernel with each call's read:write mix at its size
     def probe_ms(read_bytes, write_bytes):
         rb, wb = read_bytes // 16 * 16, write_bytes // 16 * 16
@@ -344,6 +378,7 @@ def main():
         },
         "fused": fused,
         "norm_sign": norm_sign,
+        "layer_stats": layer_stats,
         "setup_s": round(setup_s, 1),
     }
 
