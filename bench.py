@@ -65,6 +65,9 @@ def main():
                     help="distinct buffer sets cycled through so that launches do not re-hit the 256 MB "
                          "memory-side cache (0 = enough for 1 GB of traffic)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--step-only", action="store_true",
+                    help="time the step alone: no fused / norm-and-sign / statistics / probe legs (for counter "
+                         "runs, where every dispatch is slow)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB three times: "
                          "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its known size gives the factor "
@@ -170,7 +173,7 @@ def main():
                                           rq_out[r][1])
 
     fused = None
-    if W <= cgx.MAX_FUSED_PEERS:
+    if W <= cgx.MAX_FUSED_PEERS and not args.step_only:
         for i in range(args.warmup):
             fused_step(i)
         fe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
@@ -201,7 +204,7 @@ def main():
 
     # the same step with the norm-and-sign form of the quantizer (Sec. 2.2, Q_s), timed per kernel
     norm_sign = None
-    if not (w.bits == 1).any():
+    if not (w.bits == 1).any() and not args.step_only:
         ns_meta = lambda mb: torch.empty(max(mb // 8, 4), dtype=torch.float32, device=dev)
         ns_chunks = []
         share = [torch.from_numpy(w.gradient(p, first, first + m, threads=16)).to(dev) for p in range(W)]
@@ -268,24 +271,26 @@ def main():
         torch.cuda.synchronize()
         return float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
-    ws_bytes = max(cgx.cgx_layer_stats_workspace(q_plan), cgx.cgx_layer_stats_workspace(q_plan, for_sqnorms=True), 16)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    stat_out = torch.empty(w.L, dtype=torch.float64, device=dev)
-    for r in range(R):
-        cgx.cgx_quantize(grads[r], q_plan, 17 + r, q_out[r][0], q_out[r][1])
-    sqn_ms = timed(lambda i: cgx.cgx_layer_sqnorms(grads[i % R], q_plan, stat_out, ws))
-    sqe_ms = timed(lambda i: cgx.cgx_layer_sqerrors(grads[i % R], q_out[i % R][0], q_out[i % R][1], q_plan, stat_out, ws))
-    sqn_bytes, sqe_bytes = w.n * S, alg["quantize"]
-    layer_stats = {
-        "sqnorms": {"ms": round(sqn_ms, 5), "algorithmic_bytes": int(sqn_bytes),
-                    "algorithmic_GBps": round(sqn_bytes / sqn_ms / 1e6, 1),
-                    "hbm_frac": round(sqn_bytes / sqn_ms / 1e6 / HBM_PEAK_GBPS, 4)},
-        "sqerrors": {"ms": round(sqe_ms, 5), "algorithmic_bytes": int(sqe_bytes),
-                     "algorithmic_GBps": round(sqe_bytes / sqe_ms / 1e6, 1),
-                     "hbm_frac": round(sqe_bytes / sqe_ms / 1e6 / HBM_PEAK_GBPS, 4)},
-        "note": "each figure covers the tile kernel and the per-layer sum kernel (two launches)",
-    }
-    del ws
+    layer_stats = None
+    if not args.step_only:
+        ws_bytes = max(cgx.cgx_layer_stats_workspace(q_plan), cgx.cgx_layer_stats_workspace(q_plan, for_sqnorms=True), 16)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        stat_out = torch.empty(w.L, dtype=torch.float64, device=dev)
+        for r in range(R):
+            cgx.cgx_quantize(grads[r], q_plan, 17 + r, q_out[r][0], q_out[r][1])
+        sqn_ms = timed(lambda i: cgx.cgx_layer_sqnorms(grads[i % R], q_plan, stat_out, ws))
+        sqe_ms = timed(lambda i: cgx.cgx_layer_sqerrors(grads[i % R], q_out[i % R][0], q_out[i % R][1], q_plan, stat_out, ws))
+        sqn_bytes, sqe_bytes = w.n * S, alg["quantize"]
+        layer_stats = {
+            "sqnorms": {"ms": round(sqn_ms, 5), "algorithmic_bytes": int(sqn_bytes),
+                        "algorithmic_GBps": round(sqn_bytes / sqn_ms / 1e6, 1),
+                        "hbm_frac": round(sqn_bytes / sqn_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+            "sqerrors": {"ms": round(sqe_ms, 5), "algorithmic_bytes": int(sqe_bytes),
+                         "algorithmic_GBps": round(sqe_bytes / sqe_ms / 1e6, 1),
+                         "hbm_frac": round(sqe_bytes / sqe_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+            "note": "each figure covers the tile kernel and the per-layer sum kernel (two launches)",
+        }
+        del ws
 
     # what the memory system gives a plain streaming kernel with each call's read:write mix at its size
     def probe_ms(read_bytes, write_bytes):
@@ -304,11 +309,13 @@ def main():
         torch.cuda.synchronize()
         return float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
-    probe = {
-        "quantize": probe_ms(w.n * S, alg["quantize"] - w.n * S),
-        "dequant_reduce": probe_ms(alg["dequant_reduce"] - 4 * m, 4 * m),
-        "requantize": probe_ms(4 * m, alg["requantize"] - 4 * m),
-    }
+    probe = None
+    if not args.step_only:
+        probe = {
+            "quantize": probe_ms(w.n * S, alg["quantize"] - w.n * S),
+            "dequant_reduce": probe_ms(alg["dequant_reduce"] - 4 * m, 4 * m),
+            "requantize": probe_ms(4 * m, alg["requantize"] - 4 * m),
+        }
 
     if args.calibration_copy:
         # an elementwise kernel that reads 1 GiB and writes 1 GiB (grid unlike any cgx launch)
@@ -331,10 +338,11 @@ def main():
             "algorithmic_bytes": int(alg[k]),
             "algorithmic_GBps": round(alg[k] / kern_ms[k] / 1e6, 1),
             "hbm_frac": round(alg[k] / kern_ms[k] / 1e6 / HBM_PEAK_GBPS, 4),
-            "stream_probe_ms": round(probe[k], 5),
-            "stream_probe_GBps": round(alg[k] // 16 * 16 / probe[k] / 1e6, 1),
-            "frac_of_stream_probe": round(probe[k] / kern_ms[k], 4),
         }
+        if probe:
+            kernels[k].update(stream_probe_ms=round(probe[k], 5),
+                              stream_probe_GBps=round(alg[k] // 16 * 16 / probe[k] / 1e6, 1),
+                              frac_of_stream_probe=round(probe[k] / kern_ms[k], 4))
     dominant = max(names, key=lambda k: kern_ms[k])
     achieved = alg[dominant] / kern_ms[dominant] / 1e6
     traffic = read_traffic(w.name, dominant)

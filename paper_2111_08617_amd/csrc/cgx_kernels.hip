@@ -1113,18 +1113,36 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const void *__restrict_
 }
 
 // out[l] = sum of the partials of layer l, numbers layer_first[l] .. layer_first[l + 1] - 1.
-__global__ __launch_bounds__(kBlock) void layer_sum_kernel(const double *__restrict__ partial,
-                                                            const int64_t *__restrict__ layer_first, int32_t L,
-                                                            double *__restrict__ out)
+// One block per layer: the largest layers own tens of thousands of partials, so the loads are
+// spread over 16 waves and issued four at a time; the order of the additions is fixed.
+constexpr int kSumBlock = 1024;
+
+__global__ __launch_bounds__(kSumBlock) void layer_sum_kernel(const double *__restrict__ partial,
+                                                               const int64_t *__restrict__ layer_first,
+                                                               double *__restrict__ out)
 {
-    const int64_t l = int64_t(blockIdx.x) * kWavesPerBlock + (int(threadIdx.x) >> 6);
-    const int lane = int(threadIdx.x) & 63;
-    if (l >= L) return;
+    __shared__ double wave_part[kSumBlock / kWave];
+    const int64_t l = blockIdx.x;
+    const int tid = int(threadIdx.x), lane = tid & 63, wave = tid >> 6;
     const int64_t a = layer_first[l], b = layer_first[l + 1];
     double s = 0.0;
-    for (int64_t i = a + lane; i < b; i += kWave) s += partial[i];
+    for (int64_t i0 = a; i0 < b; i0 += 4 * kSumBlock) {
+        double v[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int64_t i = i0 + u * kSumBlock + tid;
+            v[u] = i < b ? partial[i] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) s += v[u];
+    }
     s = wave_sum(s);
-    if (lane == 0) out[l] = s;
+    if (lane == 0) wave_part[wave] = s;
+    __syncthreads();
+    if (wave == 0) {
+        const double t = wave_sum(lane < kSumBlock / kWave ? wave_part[lane] : 0.0);
+        if (lane == 0) out[l] = t;
+    }
 }
 
 // ---------------------------------------------------------------- streaming probe
@@ -1218,9 +1236,8 @@ hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, cons
         const auto kernel = dt == CGX_F16 ? sqnorm_kernel<CGX_F16> : sqnorm_kernel<CGX_F32>;
         hipLaunchKernelGGL(kernel, grid, block, 0, stream, buf, tiles, slots, n_tiles, partial);
     }
-    const dim3 layers(unsigned((int64_t(L) + kWavesPerBlock - 1) / kWavesPerBlock));
-    hipLaunchKernelGGL(layer_sum_kernel, layers, block, 0, stream, static_cast<const double *>(partial), layer_first,
-                       L, out);
+    hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
+                       static_cast<const double *>(partial), layer_first, out);
     return hipGetLastError();
 }
 
@@ -1242,9 +1259,8 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
                 : (dt == CGX_F16 ? sqerror_kernel<kMinMax, CGX_F16> : sqerror_kernel<kMinMax, CGX_F32>);
         hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, chunk, tiles, slots, n_tiles, int(bucket), partial);
     }
-    const dim3 layers(unsigned((int64_t(L) + kWavesPerBlock - 1) / kWavesPerBlock));
-    hipLaunchKernelGGL(layer_sum_kernel, layers, block, 0, stream, static_cast<const double *>(partial), layer_first,
-                       L, out);
+    hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
+                       static_cast<const double *>(partial), layer_first, out);
     return hipGetLastError();
 }
 
