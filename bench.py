@@ -65,6 +65,9 @@ def main():
                     help="distinct buffer sets cycled through so that launches do not re-hit the 256 MB "
                          "memory-side cache (0 = enough for 1 GB of traffic)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--spin-up-ms", type=float, default=50.0,
+                    help="untimed steps run for this long before the warmup steps, so that the clocks have "
+                         "settled whatever --warmup is (the first ~10 ms of activity run slower)")
     ap.add_argument("--step-only", action="store_true",
                     help="time the step alone: no fused / norm-and-sign / statistics / probe legs (for counter "
                          "runs, where every dispatch is slow)")
@@ -138,32 +141,70 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
-    def step(i, ev=None):
+    names = ["quantize", "dequant_reduce", "requantize"]
+
+    def step(i, ev=None, only=None):
+        """One step; ev: four events recorded around the three calls (only = j: just the two around call j).
+        An event record costs about 3 us of stream time, so the timed region carries few of them."""
         r = i % R
-        if ev:
+        if ev and only in (None, 0):
             ev[0].record()
         cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1])
-        if ev:
+        if ev and only in (None, 0, 1):
             ev[1].record()
         cgx.cgx_dequant_reduce(chunk_sets[r][0], chunk_sets[r][1], r_plan, sums[r])
-        if ev:
+        if ev and only in (None, 1, 2):
             ev[2].record()
         cgx.cgx_requantize(sums[r], rq_plan, 29 + i, rq_out[r][0], rq_out[r][1])
-        if ev:
+        if ev and only in (None, 2):
             ev[3].record()
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
+    def new_events(k):
+        return [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(k)]
 
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    def mean_ms(evs, j):
+        return float(np.mean([e[j].elapsed_time(e[j + 1]) for e in evs]))
+
+    # spin-up (part of the set-up): the step itself, until the clocks have settled
+    spin_steps = 0
+    t_spin = time.perf_counter()
+    while (time.perf_counter() - t_spin) * 1e3 < args.spin_up_ms:
+        for _ in range(8):
+            step(spin_steps)
+            spin_steps += 1
+        torch.cuda.synchronize()
+
+    # warmup, with events on every call: it also tells which kernel dominates the step
+    warm_events = new_events(args.warmup)
+    for i in range(args.warmup):
+        step(i, warm_events[i])
+    torch.cuda.synchronize()
+    if args.warmup > 0:
+        dom = int(np.argmax([mean_ms(warm_events[args.warmup // 2:], j) for j in range(3)]))
+    else:
+        dom = int(np.argmax([alg[k] for k in names]))
+
+    # timed region: exactly `steps` steps; the dominant kernel is bracketed by two events on every
+    # `stride`-th step (about 25 samples), nothing else sits between the launches
+    stride = max(1, args.steps // 25)
+    events = new_events(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, events[i])
+        if i % stride == 0:
+            step(i, events[i], only=dom)
+        else:
+            step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    dominant_ms = mean_ms(events[::stride], dom)
+
+    # per-kernel breakdown, outside the timed region: the same steps with events around every call
+    all_events = new_events(args.steps)
+    for i in range(args.steps):
+        step(i, all_events[i])
+    torch.cuda.synchronize()
 
     # the same rank's work with the fused entry point: quantize + dequant_reduce_requantize
     def fused_step(i):
@@ -326,9 +367,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    names = ["quantize", "dequant_reduce", "requantize"]
-    kern_ms = {k: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)]))
-               for j, k in enumerate(names)}
+    kern_ms = {k: mean_ms(all_events, j) for j, k in enumerate(names)}
     raw_bytes = {"quantize": w.n * S, "dequant_reduce": 4 * m, "requantize": 4 * m}
     kernels = {}
     for k in names:
@@ -343,8 +382,8 @@ def main():
             kernels[k].update(stream_probe_ms=round(probe[k], 5),
                               stream_probe_GBps=round(alg[k] // 16 * 16 / probe[k] / 1e6, 1),
                               frac_of_stream_probe=round(probe[k] / kern_ms[k], 4))
-    dominant = max(names, key=lambda k: kern_ms[k])
-    achieved = alg[dominant] / kern_ms[dominant] / 1e6
+    dominant = names[dom]
+    achieved = alg[dominant] / dominant_ms / 1e6
     traffic = read_traffic(w.name, dominant)
     value = sum(raw_bytes.values()) / (ms_per_step * 1e6)
 
@@ -373,8 +412,10 @@ def main():
             "value_definition": "raw gradient bytes entering quantize + leaving dequant_reduce + entering "
                                 "requantize, per second of step wall time",
             "buffer_sets_rotated": R,
+            "spin_up_steps_before_warmup": spin_steps,
         },
         "kernels": kernels,
+        "kernels_timing": "a pass of the same steps after the timed region, HIP events around every call",
         "roofline": {
             "bound": "hbm",
             "kernel": dominant,
@@ -383,6 +424,9 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": traffic,
+            "launch_ms": round(dominant_ms, 5),
+            "timing": "HIP events around %d of the %d launches of the timed region (every %d-th step)"
+                      % (len(events[::stride]), args.steps, stride),
         },
         "fused": fused,
         "norm_sign": norm_sign,
