@@ -29,7 +29,9 @@
  *   Pointers marked "host" are read during the call and may be reused on
  *   return.  The library keeps a small device-resident table per distinct plan
  *   (built on first use, which may synchronise; later calls with the same plan
- *   only queue kernels) and frees them in cgx_shutdown().  No call synchronises
+ *   only queue kernels): at most 64 of them, the least recently used one being
+ *   dropped (which waits for the device) when a 65th plan arrives; cgx_shutdown()
+ *   frees them all.  No call synchronises
  *   the stream.  `stream` is a hipStream_t passed as void* (NULL = the default
  *   stream).
  *

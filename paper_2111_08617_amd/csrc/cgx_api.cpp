@@ -30,6 +30,7 @@ struct CachedPlan {
     // per-layer numbering of the tiles (for the statistics): slot of every tile, first slot of every layer
     uint32_t *d_slots = nullptr;
     int64_t *d_layer_first = nullptr;
+    uint64_t last_use = 0;      // cache clock at the latest look-up
 };
 
 void free_plan(CachedPlan &p)
@@ -52,7 +53,16 @@ bool upload(T **dst, const std::vector<T> &src)
 }
 
 std::mutex g_mutex;
-std::vector<std::unique_ptr<CachedPlan>> g_plans;
+// A caller that keeps changing its plan (new bit widths every so often) must not grow the
+// cache without bound: beyond kMaxPlans entries the least recently used one is dropped.  An
+// entry handed out stays alive while its call uses it (shared ownership); its device tables
+// are released when the last owner lets go, and hipFree waits for launches still reading them.
+// The cache object itself is never destroyed, so nothing is freed during process exit, when
+// the HIP runtime may already be gone.
+constexpr size_t kMaxPlans = 64;
+using PlanRef = std::shared_ptr<const CachedPlan>;
+std::vector<std::shared_ptr<CachedPlan>> &g_plans = *new std::vector<std::shared_ptr<CachedPlan>>();
+uint64_t g_clock = 0;
 cgx::LaunchConfig g_cfg;
 bool g_cfg_read = false;
 
@@ -76,7 +86,7 @@ const cgx::LaunchConfig &launch_config()
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Finds or builds the device-resident tile table of a (valid) plan.
-int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, const CachedPlan **out)
+int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, PlanRef *out)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     const cgx::LaunchConfig &cfg = launch_config();
@@ -87,11 +97,15 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
             p->chunks_per_tile == cfg.chunks_per_tile && p->bits.size() == size_t(L) &&
             std::memcmp(p->bits.data(), bits, size_t(L)) == 0 &&
             std::memcmp(p->off.data(), off, sizeof(int64_t) * (size_t(L) + 1)) == 0) {
-            *out = p.get();
+            p->last_use = ++g_clock;
+            *out = p;
             return CGX_OK;
         }
     }
-    auto plan = std::make_unique<CachedPlan>();
+    std::shared_ptr<CachedPlan> plan(new CachedPlan, [](CachedPlan *p) {
+        free_plan(*p);
+        delete p;
+    });
     plan->device = device;
     plan->bucket = bucket;
     plan->dt = dt;
@@ -110,7 +124,14 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
         free_plan(*plan);
         return CGX_ERR_HIP;
     }
-    *out = plan.get();
+    plan->last_use = ++g_clock;
+    if (g_plans.size() >= kMaxPlans) {
+        size_t oldest = 0;
+        for (size_t i = 1; i < g_plans.size(); i++)
+            if (g_plans[i]->last_use < g_plans[oldest]->last_use) oldest = i;
+        g_plans.erase(g_plans.begin() + long(oldest));
+    }
+    *out = plan;
     g_plans.push_back(std::move(plan));
     return CGX_OK;
 }
@@ -136,7 +157,7 @@ int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int6
     const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
     if (!grad || !packed || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
     if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
-    const CachedPlan *plan = nullptr;
+    PlanRef plan;
     rc = get_plan(L, off, bits, bucket, dt, &plan);
     if (rc != CGX_OK) return rc;
     const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, bucket, seed, packed, meta,
@@ -160,7 +181,7 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
-    const CachedPlan *plan = nullptr;
+    PlanRef plan;
     rc = get_plan(L, off, bits, bucket, dt, &plan);
     if (rc != CGX_OK) return rc;
     // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
@@ -198,7 +219,7 @@ int fused_impl(int scheme, const void *const *packed, const void *const *meta, i
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(packed_out) || misaligned(meta_out)) return CGX_ERR_ALIGN;
-    const CachedPlan *in = nullptr, *out = nullptr;
+    PlanRef in, out;
     rc = get_plan(L, layer_offsets, bits_per_layer, bucket, dt, &in);
     if (rc != CGX_OK) return rc;
     rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, &out);
@@ -251,7 +272,7 @@ int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *
     if (misaligned(grad) || misaligned(packed) || misaligned(meta) || misaligned(workspace) ||
         (reinterpret_cast<uintptr_t>(sqerr) & 7u))
         return CGX_ERR_ALIGN;
-    const CachedPlan *plan = nullptr;
+    PlanRef plan;
     rc = get_plan(L, off, bits, bucket, dt, &plan);
     if (rc != CGX_OK) return rc;
     if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
@@ -384,7 +405,7 @@ int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *laye
     if (L == 0) return CGX_OK;
     if (!sqnorm || (n > 0 && (!buf || !workspace))) return CGX_ERR_NULL;
     if (misaligned(buf) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(sqnorm) & 7u)) return CGX_ERR_ALIGN;
-    const CachedPlan *plan = nullptr;
+    PlanRef plan;
     rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), &plan);
     if (rc != CGX_OK) return rc;
     if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
@@ -459,11 +480,7 @@ int cgx_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     int rc = CGX_OK;
-    for (auto &p : g_plans) {
-        if (p->d_tiles && hipFree(p->d_tiles) != hipSuccess) rc = CGX_ERR_HIP;
-        p->d_tiles = nullptr;
-        free_plan(*p);
-    }
+    // the tables go away with their last owner; hipFree waits for work that still reads them
     g_plans.clear();
     return rc;
 }

@@ -418,3 +418,20 @@ def test_result_does_not_depend_on_launch_geometry(torch, oracle):
         assert out.returncode == 0, out.stderr[-2000:]
         digests.add(out.stdout.strip().splitlines()[-1])
     assert len(digests) == 1
+
+
+def test_plan_cache_keeps_working_beyond_its_capacity(torch, oracle):
+    """More distinct plans than the library caches (64): the least recently used tables are
+    dropped and rebuilt on demand, results stay exact."""
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal(8192 + 300).astype(np.float32)
+    plans = []
+    for k in range(70):
+        cut = 2048 + 8 * k
+        plans.append((np.array([0, cut, x.size], np.int64), np.array([4, 2 + k % 7], np.uint8)))
+    for rnd in range(2):                                  # the second round finds the early plans evicted
+        for k, (off, bits) in enumerate(plans):
+            gp, gm = gpu_quantize(torch, x, off, bits, 128, 3 + k, wl.F32)
+            if k % 9 == 0 or rnd == 1 and k < 8:
+                op, om = oracle.quantize(x, off, bits, 128, 3 + k, wl.F32)
+                assert_same_chunk(gp, gm, op, om, f"plan {k} round {rnd}")

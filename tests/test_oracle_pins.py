@@ -506,3 +506,33 @@ def test_generator_avalanche(oracle):
     flips = np.array(flips)
     assert 15.5 < flips.mean() < 16.5
     assert flips.min() >= 3
+
+
+def test_generator_equals_its_written_specification(oracle):
+    """The generator restated in Python from its specification: one 32-bit word per element pair,
+    r = mix(pair_lo ^ key), key = mix(seed_lo ^ mix(seed_hi ^ 0x9e3779b9 ^ pair_hi)), mix = xor-shift 16,
+    times 0x7feb352d, xor-shift 15, times 0x846ca68b, xor-shift 16; even elements take the low half."""
+    M = 0xffffffff
+
+    def mix(x):
+        x ^= x >> 16
+        x = (x * 0x7feb352d) & M
+        x ^= x >> 15
+        x = (x * 0x846ca68b) & M
+        return x ^ (x >> 16)
+
+    def word(seed, pair):
+        key = mix((seed & M) ^ mix(((seed >> 32) & M) ^ 0x9e3779b9 ^ ((pair >> 32) & M)))
+        return mix((pair & M) ^ key)
+
+    rng = np.random.default_rng(77)
+    seeds = [0, 1, 2**32 - 1, 2**32, 2**64 - 1] + [int(s) for s in rng.integers(0, 2**63, 20)]
+    idx = [0, 1, 2, 3, 2**32 - 1, 2**32, 2**33 - 2, 2**33 - 1, 2**33, 2**33 + 1, 2**40 + 5, 2**63 + 1] + \
+          [int(i) for i in rng.integers(0, 2**62, 50)]
+    for s in seeds:
+        for i in idx:
+            r = word(s, i >> 1)
+            assert oracle.rng32(s, i >> 1) == r
+            assert oracle.u16(s, i) == ((r >> 16) if i & 1 else (r & 0xffff))
+    d = oracle.draws(12345, 2**33 - 8, 16)                       # a run across a key-block boundary
+    assert [int(v) for v in d] == [oracle.u16(12345, 2**33 - 8 + k) for k in range(16)]
