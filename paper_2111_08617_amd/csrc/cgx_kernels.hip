@@ -30,7 +30,10 @@ namespace cgx {
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kWavesPerBlock = 4;
+#ifndef CGX_WAVES_PER_BLOCK
+#define CGX_WAVES_PER_BLOCK 4
+#endif
+constexpr int kWavesPerBlock = CGX_WAVES_PER_BLOCK;
 constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int G = kGroups;               // groups of 8 elements per lane and chunk
 
@@ -309,32 +312,39 @@ __device__ __forceinline__ void wait_vector_memory()
     __builtin_amdgcn_s_waitcnt(0x0f70);
 }
 
-// b bytes holding 8 codes, into / out of the LDS staging area (b-byte aligned).
+// b bytes holding 8 codes into the LDS staging area at a multiple of b bytes: exactly b bytes
+// are written (the neighbours belong to other lanes); for the odd widths the copy is lowered
+// to a few unaligned LDS stores (LDS accepts any alignment in this execution mode).
 template <int BITS>
 __device__ __forceinline__ void stage_codes(uint8_t *p, uint64_t acc)
 {
-    if (BITS == 8) {
-        *reinterpret_cast<uint64_t *>(p) = acc;
-    } else if (BITS == 4) {
-        *reinterpret_cast<uint32_t *>(p) = uint32_t(acc);
-    } else if (BITS == 2) {
-        *reinterpret_cast<uint16_t *>(p) = uint16_t(acc);
-    } else {
-#pragma unroll
-        for (int k = 0; k < BITS; k++) p[k] = uint8_t(acc >> (8 * k));
-    }
+    __builtin_memcpy(p, &acc, BITS);
 }
 
+// Bytes staged_codes may read past the b bytes of a group (their content is ignored).
 template <int BITS>
-__device__ __forceinline__ uint64_t staged_codes(const uint8_t *p)
+constexpr int kStagedOverRead = (BITS == 3 || BITS == 5 || BITS == 6 || BITS == 7) ? 8 : 0;
+
+// The b bytes holding 8 codes at byte offset off (a multiple of b) of a 4-byte aligned LDS
+// area; bits above 8 * b of the result are unspecified.  Power-of-two widths read their
+// naturally aligned unit.  The odd widths read the aligned dwords that cover the group and
+// shift: unaligned LDS reads work but run at a fraction of the aligned rate (measured: the
+// 3-bit reduce was LDS-bound with them).
+template <int BITS>
+__device__ __forceinline__ uint64_t staged_codes(const uint8_t *base, int off)
 {
-    if (BITS == 8) return *reinterpret_cast<const uint64_t *>(p);
-    if (BITS == 4) return *reinterpret_cast<const uint32_t *>(p);
-    if (BITS == 2) return *reinterpret_cast<const uint16_t *>(p);
-    uint64_t acc = 0;
-#pragma unroll
-    for (int k = 0; k < BITS; k++) acc |= uint64_t(p[k]) << (8 * k);
-    return acc;
+    if (BITS == 8) return *reinterpret_cast<const uint64_t *>(base + off);
+    if (BITS == 4) return *reinterpret_cast<const uint32_t *>(base + off);
+    if (BITS == 2) return *reinterpret_cast<const uint16_t *>(base + off);
+    if (BITS == 1) return base[off];
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(base) + (off >> 2);
+    const uint32_t shift = uint32_t(off & 3) * 8u;
+    const uint32_t d0 = w[0], d1 = w[1];
+    // 3 and 5 bits: shift + 8 * b <= 64, two dwords cover the group; 6 and 7 bits: three
+    const uint32_t d2 = (BITS == 6 || BITS == 7) ? w[2] : 0u;
+    const uint32_t lo = __builtin_amdgcn_alignbit(d1, d0, shift);      // ({d1, d0} >> shift), low 32 bits
+    const uint32_t hi = BITS == 3 ? 0u : __builtin_amdgcn_alignbit(d2, d1, shift);
+    return (uint64_t(hi) << 32) | lo;
 }
 
 // Calls f(w0, std::integral_constant<int, WB>) for consecutive blocks of at most MAXB
@@ -670,7 +680,7 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
 #pragma unroll
         for (int r = 0; r < G; r++) {
             float f[8];
-            codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes + i * kBytes + code_off[r]), f);
+            codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes + i * kBytes, code_off[r]), f);
 #pragma unroll
             for (int j = 0; j < 8; j++) acc[r][j] = __fadd_rn(acc[r][j], decode<SCHEME>(f[j], m[i]));
         }
@@ -685,13 +695,11 @@ template <int SCHEME, int BITS>
 __device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64_t in_off, uint32_t g,
                                              const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane)
 {
-    // peers staged together: their packed bytes fit the staging area (one chunk of sums,
-    // kChunk * 4 bytes); bit widths whose codes are read back byte by byte take fewer peers
-    // at a time (the byte reads of a block are in flight together, each holding a register)
+    // peers staged together: as many as fit the staging area (one chunk of sums, kChunk * 4
+    // bytes) with their packed bytes, 8 or 4
     constexpr int kBytes = kChunk * BITS / 8;
-    constexpr bool kByteReads = BITS != 1 && BITS != 2 && BITS != 4 && BITS != 8;
-    constexpr int kWide = kByteReads ? (BITS == 3 ? 2 : 1) : (8 * kBytes <= kChunk * 4 ? 8 : 4);
-    static_assert(kWide * kBytes <= kChunk * 4, "staging area too small");
+    constexpr int kWide = 8 * kBytes + kStagedOverRead<BITS> <= kChunk * 4 ? 8 : 4;
+    static_assert(kWide * kBytes + kStagedOverRead<BITS> <= kChunk * 4, "staging area too small");
     int code_off[G];
 #pragma unroll
     for (int r = 0; r < G; r++) code_off[r] = (map.group(r) >> 3) * BITS;
