@@ -250,6 +250,13 @@ struct Raw8<CGX_F32> {
         a = stream_load(p);
         b = stream_load(p + 1);
     }
+    // the same with ordinary loads: for data that is read again shortly
+    __device__ __forceinline__ void load_keep(const void *buf, int64_t e)
+    {
+        const float4v *p = reinterpret_cast<const float4v *>(reinterpret_cast<const float *>(buf) + e);
+        a = p[0];
+        b = p[1];
+    }
     __device__ __forceinline__ void widen(float (&x)[8]) const
     {
 #pragma unroll
@@ -265,6 +272,10 @@ struct Raw8<CGX_F16> {
     __device__ __forceinline__ void load(const void *buf, int64_t e)
     {
         h = stream_load(reinterpret_cast<const half8v *>(reinterpret_cast<const _Float16 *>(buf) + e));
+    }
+    __device__ __forceinline__ void load_keep(const void *buf, int64_t e)
+    {
+        h = *reinterpret_cast<const half8v *>(reinterpret_cast<const _Float16 *>(buf) + e);
     }
     __device__ __forceinline__ void widen(float (&x)[8]) const
     {
@@ -382,6 +393,59 @@ struct LaneMap {
 
 // ---------------------------------------------------------------- quantize
 
+// The 8 codes of one group, packed: element j of the group has buffer index 2 * pair0 + j
+// (groups start on even indices), key = generator key of the tile.
+template <int SCHEME, int BITS>
+__device__ __forceinline__ uint64_t encode_group(const float (&x)[8], const Scale &s, uint32_t pair0, uint32_t key)
+{
+    constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    uint64_t acc = 0;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const uint32_t w = mix32((pair0 + k) ^ key);
+        const uint64_t q0 = code_of<SCHEME>(x[2 * k], s, w & 0xffffU, kLevels, BITS);
+        const uint64_t q1 = code_of<SCHEME>(x[2 * k + 1], s, w >> 16, kLevels, BITS);
+        acc |= q0 << (2 * k * BITS);
+        acc |= q1 << ((2 * k + 1) * BITS);
+    }
+    return acc;
+}
+
+// Minimum and maximum (kNormSign: +0 and the largest magnitude) of a lane's chunk, folded into mn / mx.
+template <int SCHEME>
+__device__ __forceinline__ void lane_extent(const float (&x)[G][8], float &mn, float &mx)
+{
+#pragma unroll
+    for (int r = 0; r < G; r++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            if (SCHEME == kNormSign) {
+                mx = __builtin_fmaxf(mx, __builtin_fabsf(x[r][j]));
+            } else {
+                mn = __builtin_fminf(mn, x[r][j]);
+                mx = __builtin_fmaxf(mx, x[r][j]);
+            }
+        }
+}
+
+// Codes of a chunk whose elements all take the scale s: staged, then sent out.
+template <int SCHEME, int BITS>
+__device__ __forceinline__ void encode_chunk(const float (&x)[G][8], const Scale &s, const LaneMap &map,
+                                             int64_t first, uint32_t key, uint8_t *__restrict__ out,
+                                             uint4v *stage, int lane)
+{
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const uint32_t pair0 = uint32_t(uint64_t(first + map.group(r)) >> 1);
+        stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (map.group(r) >> 3) * BITS,
+                          encode_group<SCHEME, BITS>(x[r], s, pair0, key));
+    }
+    // the chunk's codes leave as whole 16-byte vectors, consecutive across lanes
+    wave_lds_fence();
+    flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
+    wave_lds_fence();
+}
+
 // One chunk held in registers (x) -> meta of its buckets and its packed codes.
 // first = buffer index of the chunk's first element; key = generator key of the tile.
 // meta_chunk points at the meta of the chunk's first bucket.
@@ -391,48 +455,15 @@ __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const Lan
                                                uint8_t *__restrict__ out, uint4v *stage)
 {
     constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
-    float mn, mx;
-    if (SCHEME == kNormSign) {
-        mn = 0.0f;
-        mx = 0.0f;
-#pragma unroll
-        for (int r = 0; r < G; r++)
-#pragma unroll
-            for (int j = 0; j < 8; j++) mx = __builtin_fmaxf(mx, __builtin_fabsf(x[r][j]));
+    float mn = SCHEME == kNormSign ? 0.0f : x[0][0], mx = mn;
+    lane_extent<SCHEME>(x, mn, mx);
+    if (SCHEME == kNormSign)
         group_max(mx, map.lg, lane);
-    } else {
-        mn = x[0][0];
-        mx = x[0][0];
-#pragma unroll
-        for (int r = 0; r < G; r++)
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                mn = __builtin_fminf(mn, x[r][j]);
-                mx = __builtin_fmaxf(mx, x[r][j]);
-            }
+    else
         group_minmax(mn, mx, map.lg, lane);
-    }
     const Scale s = bucket_scale(mn, mx, int(kLevels));
     if (map.lp == 0) store_meta<SCHEME>(meta_chunk, map.bi, s);
-
-#pragma unroll
-    for (int r = 0; r < G; r++) {
-        const uint32_t pair0 = uint32_t(uint64_t(first + map.group(r)) >> 1);
-        uint64_t acc = 0;
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            const uint32_t w = mix32((pair0 + k) ^ key);
-            const uint64_t q0 = code_of<SCHEME>(x[r][2 * k], s, w & 0xffffU, kLevels, BITS);
-            const uint64_t q1 = code_of<SCHEME>(x[r][2 * k + 1], s, w >> 16, kLevels, BITS);
-            acc |= q0 << (2 * k * BITS);
-            acc |= q1 << ((2 * k + 1) * BITS);
-        }
-        stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (map.group(r) >> 3) * BITS, acc);
-    }
-    // the chunk's codes leave as whole 16-byte vectors, consecutive across lanes
-    wave_lds_fence();
-    flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
-    wave_lds_fence();
+    encode_chunk<SCHEME, BITS>(x, s, map, first, key, out, stage, lane);
 }
 
 // The same for buckets of 32 or 64 elements, with the chunk held row by row: group r of lane l
@@ -474,18 +505,8 @@ __device__ __forceinline__ void quantize_chunk_rows(const float (&x)[G][8], int 
         if ((lane & ((1 << lg) - 1)) == 0) store_meta<SCHEME>(meta_chunk, r * buckets_per_row + (lane >> lg), s);
         const int e = r * kRow + lane * 8;           // the group's first element within the chunk
         const uint32_t pair0 = uint32_t(uint64_t(first + e) >> 1);
-        uint64_t acc = 0;
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            const uint32_t w = mix32((pair0 + k) ^ key);
-            const uint64_t q0 = code_of<SCHEME>(x[r][2 * k], s, w & 0xffffU, kLevels, BITS);
-            const uint64_t q1 = code_of<SCHEME>(x[r][2 * k + 1], s, w >> 16, kLevels, BITS);
-            acc |= q0 << (2 * k * BITS);
-            acc |= q1 << ((2 * k + 1) * BITS);
-        }
-        stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (e >> 3) * BITS, acc);
-        // one row at a time: interleaving the four rows' divisions costs 50 more registers
-        __builtin_amdgcn_sched_barrier(0);
+        stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (e >> 3) * BITS,
+                          encode_group<SCHEME, BITS>(x[r], s, pair0, key));
     }
     wave_lds_fence();
     flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
@@ -529,6 +550,45 @@ __device__ __forceinline__ void quantize_fast_rows(const void *__restrict__ grad
         quantize_chunk_rows<SCHEME, BITS>(x, bucket, lane, first, key,
                                           meta + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
                                           packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8), stage);
+    }
+}
+
+// A tile that is one whole bucket of 2 or 4 chunks: a first pass over the chunks finds the
+// scale, a second one reads them again (from the caches: 16 or 32 KB read a moment ago) and
+// cuts the codes.  Row-by-row mapping (LaneMap with the whole wave as one bucket).
+template <int SCHEME, int DT, int BITS>
+__device__ __forceinline__ void quantize_wide(const void *__restrict__ grad, uint8_t *__restrict__ packed,
+                                              float *__restrict__ meta, const Tile &tile, int bucket,
+                                              uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
+{
+    constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    const LaneMap map(tile, bucket, lane);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    const int chunks = int(tile.count / kChunk);
+    float mn = SCHEME == kNormSign ? 0.0f : __builtin_inff(), mx = SCHEME == kNormSign ? 0.0f : -__builtin_inff();
+    for (int c = 0; c < chunks; c++) {
+        float x[G][8];
+#pragma unroll
+        for (int r = 0; r < G; r++) {
+            Raw8<DT> raw;
+            raw.load_keep(grad, tile.elem0 + int64_t(c) * kChunk + map.group(r));   // read again below
+            raw.widen(x[r]);
+        }
+        lane_extent<SCHEME>(x, mn, mx);
+    }
+    if (SCHEME == kNormSign)
+        group_max(mx, 6, lane);
+    else
+        group_minmax(mn, mx, 6, lane);
+    const Scale s = bucket_scale(mn, mx, int(kLevels));
+    if (lane == 0) store_meta<SCHEME>(meta, tile.bucket0, s);
+    for (int c = 0; c < chunks; c++) {
+        const int64_t first = tile.elem0 + int64_t(c) * kChunk;
+        float x[G][8];
+#pragma unroll
+        for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
+        encode_chunk<SCHEME, BITS>(x, s, map, first, key, packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                                   stage, lane);
     }
 }
 
@@ -649,9 +709,15 @@ __device__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ p
     default: { constexpr int BITS = 8; CALL; } break; \
     }
 
-// ROWS: the plan's bucket is 32 or 64 elements (the vectorised tiles then take the row-by-row
-// mapping, which needs more registers: a kernel of its own keeps the others' occupancy).
-template <int SCHEME, int DT, bool ROWS>
+// MAP: how the vectorised tiles of the plan are laid over the lanes, fixed by the call's bucket
+// size: kMapBuckets for 128..2048 (bucket-major), kMapRows for 32 and 64 (row by row; needs more
+// registers, so a kernel of its own keeps the others' occupancy), kMapWide for 4096 and 8192
+// (a tile is one bucket of several chunks).
+enum LaneMapping { kMapBuckets = 0, kMapRows = 1, kMapWide = 2 };
+
+inline int mapping_of(int bucket) { return bucket <= 64 ? kMapRows : bucket > kChunk ? kMapWide : kMapBuckets; }
+
+template <int SCHEME, int DT, int MAP>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
                                                            const Tile *__restrict__ tiles, int64_t n_tiles,
                                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
@@ -667,10 +733,13 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
     for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
-        if (kind == kQuantFast) {
-            if constexpr (ROWS) {
+        if (is_vector_kind(kind)) {
+            if constexpr (MAP == kMapRows) {
                 CGX_FOR_BITS(tile_bits(tile), (quantize_fast_rows<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
                                                                                       seed_lo, seed_hi, lane, stage)))
+            } else if constexpr (MAP == kMapWide) {
+                CGX_FOR_BITS(tile_bits(tile), (quantize_wide<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
+                                                                                 seed_lo, seed_hi, lane, stage)))
             } else {
                 CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
                                                                                  seed_lo, seed_hi, lane, stage)))
@@ -1005,7 +1074,7 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
     for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
-        if (kind == kQuantFast) {
+        if (is_vector_kind(kind)) {      // a wide tile is chunks of one bucket: kChunk / bucket == 0 below
             CGX_FOR_BITS(tile_bits(tile), (reduce_fast<SCHEME, BITS>(peers, W, io, tile, bucket, lane, stage)))
         } else if (kind == kQuantSlow) {
             reduce_slow<SCHEME>(peers, W, io, tile, bucket, lane);
@@ -1041,9 +1110,50 @@ __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const T
     }
 }
 
+// A tile that is one whole bucket of 2 or 4 chunks: the sums are formed twice, once for the
+// scale and once for the codes (they would not fit the registers, and the chunks' bytes come
+// from the caches the second time).
+template <int SCHEME, int BITS>
+__device__ __forceinline__ void fused_wide(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
+                                           int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                           uint8_t *__restrict__ packed_out, float *__restrict__ meta_out,
+                                           int lane, uint4v *stage)
+{
+    constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    const LaneMap map(tile, bucket, lane);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    const int chunks = int(tile.count / kChunk);
+    float mn = SCHEME == kNormSign ? 0.0f : __builtin_inff(), mx = SCHEME == kNormSign ? 0.0f : -__builtin_inff();
+    Scale s{0.0f, 0.0f, 0.0f};
+    // both passes in one loop, so that the reduction is instantiated once
+    for (int it = 0; it < 2 * chunks; it++) {
+        const bool second = it >= chunks;
+        const int c = second ? it - chunks : it;
+        float acc[G][8];
+        clear_sums(acc);
+        reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8), tile.bucket0, map,
+                                   acc, stage, lane);
+        if (second) {
+            encode_chunk<SCHEME, BITS>(acc, s, map, tile.elem0 + int64_t(c) * kChunk, key,
+                                       packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage, lane);
+            continue;
+        }
+        lane_extent<SCHEME>(acc, mn, mx);
+        if (c == chunks - 1) {
+            if (SCHEME == kNormSign)
+                group_max(mx, 6, lane);
+            else
+                group_minmax(mn, mx, 6, lane);
+            s = bucket_scale(mn, mx, int(kLevels));
+            if (lane == 0) store_meta<SCHEME>(meta_out, tile.bucket0, s);
+        }
+    }
+}
+
 // tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
 // output (binary32 pass-through layers); the two tables list the same tiles in the same order.
-template <int SCHEME>
+// WIDE: the call's bucket is longer than a chunk (see quantize_kernel's MAP).
+template <int SCHEME, bool WIDE>
 __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int W, int dt,
                                                         const Tile *__restrict__ tiles_in,
                                                         const Tile *__restrict__ tiles_out, int64_t n_tiles,
@@ -1061,9 +1171,14 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int
         const int64_t out_off = tiles_out[t].packed_off;
         const uint32_t out_pad = tiles_out[t].pad;
         const uint32_t kind = tile_kind(tile);
-        if (kind == kQuantFast) {
-            CGX_FOR_BITS(tile_bits(tile), (fused_fast<SCHEME, BITS>(peers, W, tile, out_off, bucket, seed_lo,
-                                                                     seed_hi, packed_out, meta_out, lane, stage)))
+        if (is_vector_kind(kind)) {
+            if constexpr (WIDE) {
+                CGX_FOR_BITS(tile_bits(tile), (fused_wide<SCHEME, BITS>(peers, W, tile, out_off, bucket, seed_lo,
+                                                                         seed_hi, packed_out, meta_out, lane, stage)))
+            } else {
+                CGX_FOR_BITS(tile_bits(tile), (fused_fast<SCHEME, BITS>(peers, W, tile, out_off, bucket, seed_lo,
+                                                                         seed_hi, packed_out, meta_out, lane, stage)))
+            }
         } else if (kind == kQuantSlow) {
             quantize_generic<SCHEME, false>(
                 [&](uint32_t j) { return generic_sum<SCHEME>(peers, W, tile, bucket, j, -0.0f); },
@@ -1190,7 +1305,7 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const void *__restrict_
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         double s = 0.0;                              // pass-through tiles: no error
-        if (kind == kQuantFast) {
+        if (is_vector_kind(kind)) {
             CGX_FOR_BITS(tile_bits(tile), (s = sqerror_fast<SCHEME, DT, BITS>(grad, chunk, tile, bucket, lane, stage)))
         } else if (kind == kQuantSlow) {
             for (uint32_t j = lane; j < tile.count; j += kWave) {
@@ -1283,13 +1398,17 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const uint32_t seed_lo = uint32_t(seed), seed_hi = uint32_t(seed >> 32);
-    const bool rows = bucket <= 64;
-    const auto kernel =
-        scheme == kSchemeNormSign
-            ? (dt == CGX_F16 ? (rows ? quantize_kernel<kNormSign, CGX_F16, true> : quantize_kernel<kNormSign, CGX_F16, false>)
-                             : (rows ? quantize_kernel<kNormSign, CGX_F32, true> : quantize_kernel<kNormSign, CGX_F32, false>))
-            : (dt == CGX_F16 ? (rows ? quantize_kernel<kMinMax, CGX_F16, true> : quantize_kernel<kMinMax, CGX_F16, false>)
-                             : (rows ? quantize_kernel<kMinMax, CGX_F32, true> : quantize_kernel<kMinMax, CGX_F32, false>));
+    using Kernel = void (*)(const void *, const Tile *, int64_t, int, uint32_t, uint32_t, uint8_t *, float *);
+    static const Kernel table[2][2][3] = {
+        {{quantize_kernel<kMinMax, CGX_F32, kMapBuckets>, quantize_kernel<kMinMax, CGX_F32, kMapRows>,
+          quantize_kernel<kMinMax, CGX_F32, kMapWide>},
+         {quantize_kernel<kMinMax, CGX_F16, kMapBuckets>, quantize_kernel<kMinMax, CGX_F16, kMapRows>,
+          quantize_kernel<kMinMax, CGX_F16, kMapWide>}},
+        {{quantize_kernel<kNormSign, CGX_F32, kMapBuckets>, quantize_kernel<kNormSign, CGX_F32, kMapRows>,
+          quantize_kernel<kNormSign, CGX_F32, kMapWide>},
+         {quantize_kernel<kNormSign, CGX_F16, kMapBuckets>, quantize_kernel<kNormSign, CGX_F16, kMapRows>,
+          quantize_kernel<kNormSign, CGX_F16, kMapWide>}}};
+    const Kernel kernel = table[scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket)];
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket), seed_lo, seed_hi,
                        static_cast<uint8_t *>(packed), static_cast<float *>(meta));
     return hipGetLastError();
@@ -1314,7 +1433,9 @@ hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, i
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
-    const auto kernel = scheme == kSchemeNormSign ? fused_kernel<kNormSign> : fused_kernel<kMinMax>;
+    const bool wide = mapping_of(bucket) == kMapWide;
+    const auto kernel = scheme == kSchemeNormSign ? (wide ? fused_kernel<kNormSign, true> : fused_kernel<kNormSign, false>)
+                                                  : (wide ? fused_kernel<kMinMax, true> : fused_kernel<kMinMax, false>);
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles, int(bucket),
                        uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
                        static_cast<float *>(meta_out));

@@ -72,6 +72,7 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     if (chunks_per_tile < 1) chunks_per_tile = 1;
     const int S = elem_size(dt);
     const bool fast_bucket = is_pow2(bucket) && bucket <= kChunk;
+    const bool wide_bucket = is_pow2(bucket) && bucket > kChunk;       // a bucket is 2 or 4 chunks
     // 64 lanes x kGroups groups x 8 elements = kChunk, so a bucket spans bucket / (8 * kGroups) lanes
     const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(bucket / (8 * kGroups))) : 0u;
     uint64_t seg = 0, bucket0 = 0;
@@ -113,6 +114,20 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
                     c += k;
                 }
                 j = full_chunks * kChunk;
+            } else if (wide_bucket && aligned) {
+                // one tile per whole bucket: its scale needs all of it (lanes-per-bucket field: the whole wave)
+                const int64_t full = len / bucket;
+                for (int64_t k = 0; k < full; k++) {
+                    Tile t{};
+                    t.elem0 = first + k * bucket;
+                    t.packed_off = int64_t(seg + uint64_t(k) * bucket * b / 8);
+                    t.bucket0 = uint32_t(bucket0 + uint64_t(k));
+                    t.count = uint32_t(bucket);
+                    const bool fast = same_key_block(t.elem0, t.count);
+                    t.info = uint32_t(b) | uint32_t(fast ? kQuantWide : kQuantSlow) << 4 | 6u << 8;
+                    tiles.push_back(t);
+                }
+                j = full * bucket;
             }
             // what is left (or the whole layer): whole buckets, about a chunk per tile
             const int64_t step = bucket >= kChunk ? bucket : int64_t(kChunk / bucket) * bucket;
@@ -137,7 +152,7 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     std::vector<uint32_t> order(tiles.size());
     for (size_t i = 0; i < order.size(); i++) order[i] = uint32_t(i);
     std::stable_partition(order.begin(), order.end(),
-                          [&](uint32_t i) { return tile_kind(tiles[i]) != kQuantFast; });
+                          [&](uint32_t i) { return !is_vector_kind(tile_kind(tiles[i])); });
     std::vector<Tile> sorted(tiles.size());
     for (size_t i = 0; i < order.size(); i++) sorted[i] = tiles[order[i]];
     tiles.swap(sorted);

@@ -35,8 +35,12 @@ enum TileKind : uint32_t {
     kQuantSlow = 0,  // any bucket size, any alignment, ragged last bucket
     kQuantFast = 1,  // power-of-two bucket <= kChunk, 8-element aligned start, whole chunks
     kCopySlow = 2,   // pass-through, element-wise
-    kCopyFast = 3    // pass-through, 16-byte vectors
+    kCopyFast = 3,   // pass-through, 16-byte vectors
+    kQuantWide = 4   // one whole power-of-two bucket longer than a chunk (4096, 8192), 8-element aligned
 };
+
+// Vectorised quantized tiles (everything else costs several dependent memory round trips).
+CGX_HOST_DEVICE inline bool is_vector_kind(uint32_t kind) { return kind == kQuantFast || kind == kQuantWide; }
 
 struct Tile {               // 32 bytes, read by the kernels with scalar loads
     int64_t elem0;          // first element, index in the fused buffer

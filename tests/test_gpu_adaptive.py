@@ -98,9 +98,9 @@ def test_sqerrors_on_edge_case_plans(torch, oracle, bucket, dt, qsgd):
 
 @pytest.mark.parametrize("qsgd", [False, True], ids=["minmax", "normsign"])
 @pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
-@pytest.mark.parametrize("bucket", [64, 512, 2048])
+@pytest.mark.parametrize("bucket", [64, 512, 2048, 4096])
 def test_sqerrors_vectorised_path_all_bit_widths(torch, oracle, bucket, dt, qsgd):
-    sizes = [2048 * 3, 2048 * 2 + 40, 8, 2048, 2048 * 5 + 1000, 2048 * 4, 16384, 2048 + bucket, 6144, 8192 * 2 + 24]
+    sizes = [2048 * 4, 2048 * 2 + 40, 8, 4096, 2048 * 5 + 1000, 2048 * 4, 16384, 2048 + bucket, 8192, 8192 * 2 + 24]
     bits = [2 if qsgd else 1, 2, 0, 3, 4, 5, 0, 6, 7, 8]
     w = wl.Workload("chunks", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 1, 3000 + bucket,
                     wl._normal, np.linspace(0.01, 2.0, len(sizes)))

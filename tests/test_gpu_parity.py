@@ -435,3 +435,18 @@ def test_plan_cache_keeps_working_beyond_its_capacity(torch, oracle):
             if k % 9 == 0 or rnd == 1 and k < 8:
                 op, om = oracle.quantize(x, off, bits, 128, 3 + k, wl.F32)
                 assert_same_chunk(gp, gm, op, om, f"plan {k} round {rnd}")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [4096, 8192])
+def test_buckets_longer_than_a_chunk(torch, oracle, bucket, dt):
+    """Whole buckets of 4096 / 8192 elements take the two-pass vectorised tiles; tails and
+    unaligned layers the generic ones; every bit width."""
+    sizes = [bucket * 3, bucket + 40, 8, bucket * 2, bucket * 2 + 1000, 4, bucket, 16384, bucket * 4 + 24, 100, bucket * 2]
+    bits = [1, 2, 0, 3, 4, 5, 0, 6, 7, 8, 4]
+    w = wl.Workload("wide", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 3, 500 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    kinds = (cgx.cgx_plan_tiles(plan)["info"] >> 4) & 15
+    assert (kinds == 4).sum() >= 10 and (kinds == 0).any() and not (kinds == 1).any()
+    full_cycle(torch, oracle, w, W=3, what=f"wide B={bucket}")

@@ -190,3 +190,13 @@ def test_gpt2_medium_config_full_size(torch, oracle):
     fp, fm = gpu_fused(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt, 7)
     op, om = oracle.qsgd_quantize(ref["sum32"], sub_off, sub_bits, w.bucket, 7, wl.F32)
     assert_same_chunk(fp, fm, op, om, "qsgd gpt2_medium share fused reduce+requantize")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [4096, 8192])
+def test_buckets_longer_than_a_chunk(torch, oracle, bucket, dt):
+    sizes = [bucket * 3, bucket + 40, 8, bucket * 2, bucket * 2 + 1000, 4, bucket, 16384, bucket * 4 + 24, 100, bucket * 2]
+    bits = [2, 2, 0, 3, 4, 5, 0, 6, 7, 8, 4]
+    w = wl.Workload("wide", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 3, 600 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    full_cycle(torch, oracle, w, W=3, what=f"qsgd wide B={bucket}")

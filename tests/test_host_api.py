@@ -183,6 +183,10 @@ def layer_segments(w):
 @pytest.mark.parametrize("make", [
     lambda: wl.tiny_mixed(), lambda: wl.tiny_mixed(dt=wl.F16, bucket=128), lambda: wl.tiny_mixed(bucket=96),
     lambda: wl.tiny_mixed(bucket=4096), wl.resnet50, wl.bert_base, wl.gpt2_medium,
+    lambda: wl.Workload("wide", [(4096 * 3 + 100,), (4,), (8192 * 2,), (4096,), (5000,)], np.array([4, 0, 3, 8, 2], np.uint8),
+                        4096, wl.F32, 2, 1, wl._normal, np.ones(5)),
+    lambda: wl.Workload("wide16", [(8192 * 2 + 8,), (8192,), (100,)], np.array([4, 5, 1], np.uint8),
+                        8192, wl.F16, 2, 1, wl._normal, np.ones(3)),
 ])
 def test_tiles_cover_every_layer_exactly_once(lib, make):
     w = make()
@@ -191,7 +195,7 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
     segs = layer_segments(w)
     es = 2 if w.dt else 4
     # generic and pass-through tiles first, then the vectorised ones; buffer order within each class
-    vectorised = ((tiles["info"] >> 4) & 15) == 1
+    vectorised = np.isin((tiles["info"] >> 4) & 15, (1, 4))
     assert not vectorised[:int((~vectorised).sum())].any()
     for cls in (tiles[~vectorised], tiles[vectorised]):
         assert (np.diff(cls["elem0"]) > 0).all()
@@ -218,7 +222,7 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
             if kind == 3:
                 assert t["elem0"] % 8 == 0
         else:
-            assert kind in (0, 1)
+            assert kind in (0, 1, 4)
             assert j % w.bucket == 0                                  # tiles start on a bucket
             assert last or t["count"] % w.bucket == 0                 # and hold whole buckets
             assert t["packed_off"] == seg + j * b // 8
@@ -227,6 +231,11 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
                 assert t["count"] % CHUNK == 0 and t["elem0"] % 8 == 0
                 assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= CHUNK
                 assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket * 64 // CHUNK))
+            if kind == 4:                                             # one whole bucket of several chunks
+                assert t["count"] == w.bucket and w.bucket in (4096, 8192) and t["elem0"] % 8 == 0
+                assert (int(t["info"]) >> 8) & 15 == 6
+    if w.name.startswith("wide"):
+        assert (((tiles["info"] >> 4) & 15) == 4).sum() == (9 if w.name == "wide" else 3)
 
 
 def test_large_plans_use_the_vectorised_path(lib):
