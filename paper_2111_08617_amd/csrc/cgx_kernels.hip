@@ -40,6 +40,13 @@ constexpr int G = kGroups;               // groups of 8 elements per lane and ch
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+// The same vectors at the alignment of ONE element: a layer may start anywhere in the fused
+// buffer, so accesses on the gradient / sum side promise no more than that.  Global memory takes
+// 16-byte accesses at any alignment in this execution mode (the instructions are the same; only
+// the lines touched by an instruction shift), which keeps unaligned layers on the vectorised path.
+typedef float4v float4u __attribute__((aligned(4)));
+typedef half8v half8u __attribute__((aligned(2)));
+typedef uint4v uint4u2 __attribute__((aligned(2)));
 
 // ---------------------------------------------------------------- generator
 
@@ -230,6 +237,8 @@ __device__ __forceinline__ void stream_store(T *p, T v)
 {
     __builtin_nontemporal_store(v, p);
 }
+// (Pointers to the element-aligned vector types below must not go through these templates:
+// a template argument drops the alignment of the typedef.  Their accesses call the builtins.)
 
 template <int DT>
 __device__ __forceinline__ float load_elem(const void *buf, int64_t i)
@@ -246,14 +255,14 @@ struct Raw8<CGX_F32> {
     float4v a, b;
     __device__ __forceinline__ void load(const void *buf, int64_t e)
     {
-        const float4v *p = reinterpret_cast<const float4v *>(reinterpret_cast<const float *>(buf) + e);
-        a = stream_load(p);
-        b = stream_load(p + 1);
+        const float4u *p = reinterpret_cast<const float4u *>(reinterpret_cast<const float *>(buf) + e);
+        a = __builtin_nontemporal_load(p);
+        b = __builtin_nontemporal_load(p + 1);
     }
     // the same with ordinary loads: for data that is read again shortly
     __device__ __forceinline__ void load_keep(const void *buf, int64_t e)
     {
-        const float4v *p = reinterpret_cast<const float4v *>(reinterpret_cast<const float *>(buf) + e);
+        const float4u *p = reinterpret_cast<const float4u *>(reinterpret_cast<const float *>(buf) + e);
         a = p[0];
         b = p[1];
     }
@@ -271,11 +280,11 @@ struct Raw8<CGX_F16> {
     half8v h;
     __device__ __forceinline__ void load(const void *buf, int64_t e)
     {
-        h = stream_load(reinterpret_cast<const half8v *>(reinterpret_cast<const _Float16 *>(buf) + e));
+        h = __builtin_nontemporal_load(reinterpret_cast<const half8u *>(reinterpret_cast<const _Float16 *>(buf) + e));
     }
     __device__ __forceinline__ void load_keep(const void *buf, int64_t e)
     {
-        h = *reinterpret_cast<const half8v *>(reinterpret_cast<const _Float16 *>(buf) + e);
+        h = *reinterpret_cast<const half8u *>(reinterpret_cast<const _Float16 *>(buf) + e);
     }
     __device__ __forceinline__ void widen(float (&x)[8]) const
     {
@@ -306,6 +315,12 @@ __device__ __forceinline__ void wave_lds_fence()
 __device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, int vecs, int lane)
 {
     for (int v = lane; v < vecs; v += kWave) stream_store(dst + v, stage[v]);
+}
+
+// The same to an element-aligned destination (sums).
+__device__ __forceinline__ void flush_stage_to_elements(const uint4v *stage, uint4u2 *dst, int vecs, int lane)
+{
+    for (int v = lane; v < vecs; v += kWave) __builtin_nontemporal_store(stage[v], dst + v);
 }
 
 // One 16-byte vector per lane from global memory straight into LDS, without passing
@@ -393,16 +408,25 @@ struct LaneMap {
 
 // ---------------------------------------------------------------- quantize
 
-// The 8 codes of one group, packed: element j of the group has buffer index 2 * pair0 + j
-// (groups start on even indices), key = generator key of the tile.
+// The 8 codes of one group, packed: element j of the group has buffer index
+// 2 * pair0 + odd + j, key = generator key of the tile.  odd (0 or 1, uniform over a tile: groups
+// start 8 elements apart) tells whether the group starts on the upper half of a generator word;
+// then its 8 draws are the 16-bit halves 1..8 of words pair0 .. pair0 + 4 instead of halves
+// 0..7 of words pair0 .. pair0 + 3.
 template <int SCHEME, int BITS>
-__device__ __forceinline__ uint64_t encode_group(const float (&x)[8], const Scale &s, uint32_t pair0, uint32_t key)
+__device__ __forceinline__ uint64_t encode_group(const float (&x)[8], const Scale &s, uint32_t pair0, uint32_t key,
+                                                 uint32_t odd)
 {
     constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    uint32_t word[5];
+#pragma unroll
+    for (int k = 0; k < 4; k++) word[k] = mix32((pair0 + k) ^ key);
+    word[4] = 0;
+    if (odd) word[4] = mix32((pair0 + 4) ^ key);
     uint64_t acc = 0;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-        const uint32_t w = mix32((pair0 + k) ^ key);
+        const uint32_t w = __builtin_amdgcn_alignbit(word[k + 1], word[k], 16u * odd);   // the pair's two draws
         const uint64_t q0 = code_of<SCHEME>(x[2 * k], s, w & 0xffffU, kLevels, BITS);
         const uint64_t q1 = code_of<SCHEME>(x[2 * k + 1], s, w >> 16, kLevels, BITS);
         acc |= q0 << (2 * k * BITS);
@@ -438,7 +462,7 @@ __device__ __forceinline__ void encode_chunk(const float (&x)[G][8], const Scale
     for (int r = 0; r < G; r++) {
         const uint32_t pair0 = uint32_t(uint64_t(first + map.group(r)) >> 1);
         stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (map.group(r) >> 3) * BITS,
-                          encode_group<SCHEME, BITS>(x[r], s, pair0, key));
+                          encode_group<SCHEME, BITS>(x[r], s, pair0, key, uint32_t(first) & 1u));
     }
     // the chunk's codes leave as whole 16-byte vectors, consecutive across lanes
     wave_lds_fence();
@@ -506,7 +530,7 @@ __device__ __forceinline__ void quantize_chunk_rows(const float (&x)[G][8], int 
         const int e = r * kRow + lane * 8;           // the group's first element within the chunk
         const uint32_t pair0 = uint32_t(uint64_t(first + e) >> 1);
         stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (e >> 3) * BITS,
-                          encode_group<SCHEME, BITS>(x[r], s, pair0, key));
+                          encode_group<SCHEME, BITS>(x[r], s, pair0, key, uint32_t(first) & 1u));
     }
     wave_lds_fence();
     flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
@@ -681,7 +705,7 @@ __device__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ p
     if (fast) {
         const uint32_t vecs = bytes / 16;
         for (uint32_t v = lane; v < vecs; v += kWave)
-            reinterpret_cast<uint4v *>(dst)[v] = reinterpret_cast<const uint4v *>(src)[v];
+            reinterpret_cast<uint4v *>(dst)[v] = reinterpret_cast<const uint4u2 *>(src)[v];
         done = vecs * 16;
     } else if (DT == CGX_F16) {
         for (uint32_t e = lane; e < tile.count; e += kWave)
@@ -914,9 +938,9 @@ __device__ __forceinline__ void store8(const SumIo &io, int64_t e, const float (
         half8v h;
 #pragma unroll
         for (int j = 0; j < 8; j++) h[j] = _Float16(acc[j]);
-        *reinterpret_cast<half8v *>(reinterpret_cast<_Float16 *>(io.out) + e) = h;
+        *reinterpret_cast<half8u *>(reinterpret_cast<_Float16 *>(io.out) + e) = h;
     } else {
-        float4v *p = reinterpret_cast<float4v *>(reinterpret_cast<float *>(io.out) + e);
+        float4u *p = reinterpret_cast<float4u *>(reinterpret_cast<float *>(io.out) + e);
         p[0] = float4v{acc[0], acc[1], acc[2], acc[3]};
         p[1] = float4v{acc[4], acc[5], acc[6], acc[7]};
     }
@@ -947,8 +971,8 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const 
                 reinterpret_cast<half8v *>(stage)[map.group(r) >> 3] = h;
             }
             wave_lds_fence();
-            flush_stage(stage, reinterpret_cast<uint4v *>(reinterpret_cast<_Float16 *>(io.out) + first), kChunk / 8,
-                        lane);
+            flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<_Float16 *>(io.out) + first),
+                                    kChunk / 8, lane);
         } else {
 #pragma unroll
             for (int r = 0; r < G; r++) {
@@ -957,8 +981,8 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const 
                 p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
             }
             wave_lds_fence();
-            flush_stage(stage, reinterpret_cast<uint4v *>(reinterpret_cast<float *>(io.out) + first), kChunk / 4,
-                        lane);
+            flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<float *>(io.out) + first),
+                                    kChunk / 4, lane);
         }
         wave_lds_fence();
     }

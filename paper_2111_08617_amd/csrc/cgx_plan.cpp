@@ -84,7 +84,8 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
         uint64_t payload, buckets;
         layer_extent(len, b, bucket, dt, payload, buckets);
         const uint32_t pad = uint32_t(round_up16(payload) - payload);
-        const bool aligned = (first % 8) == 0;
+        // vector accesses on the gradient side are element-aligned, so a layer may start anywhere
+        const bool aligned = true;
         const size_t first_tile = tiles.size();
         if (b == 0) {
             for (int64_t j = 0; j < len; j += kCopyTile) {

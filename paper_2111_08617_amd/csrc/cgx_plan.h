@@ -33,10 +33,10 @@ constexpr int kCopyTile = 8192;
 
 enum TileKind : uint32_t {
     kQuantSlow = 0,  // any bucket size, any alignment, ragged last bucket
-    kQuantFast = 1,  // power-of-two bucket <= kChunk, 8-element aligned start, whole chunks
-    kCopySlow = 2,   // pass-through, element-wise
+    kQuantFast = 1,  // power-of-two bucket <= kChunk, whole chunks
+    kCopySlow = 2,   // pass-through, element-wise (no longer produced: every copy tile is vectorised)
     kCopyFast = 3,   // pass-through, 16-byte vectors
-    kQuantWide = 4   // one whole power-of-two bucket longer than a chunk (4096, 8192), 8-element aligned
+    kQuantWide = 4   // one whole power-of-two bucket longer than a chunk (4096, 8192)
 };
 
 // Vectorised quantized tiles (everything else costs several dependent memory round trips).

@@ -158,3 +158,16 @@ def test_adaptive_round_on_the_device(torch, oracle):
     size = np.diff(off)
     assert (bits * size).sum() < (bits_in * size).sum()          # fewer bits on the wire ...
     assert err.cpu().numpy().sum() > e4.sum()                    # ... paid with a larger error than E_4
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+def test_statistics_of_layers_that_start_anywhere(torch, oracle, dt):
+    sizes = [2048 * 3 + 1, 2048 * 2, 7, 8192 + 3, 2048 * 4 + 2, 1, 8192 * 2, 4096 + 5, 2048 * 5]
+    bits = [4, 1, 0, 3, 8, 0, 0, 5, 2]
+    w = wl.Workload("shifted", [(s,) for s in sizes], np.array(bits, np.uint8), 256, dt, 1, 900, wl._normal,
+                    np.linspace(0.01, 2.0, len(sizes)))
+    g = w.gradient()
+    assert_close(gpu_sqnorms(torch, g, w.offsets, dt), oracle.layer_sqnorms(g, w.offsets, dt), "shifted sqnorms")
+    p, m = oracle.quantize(g, w.offsets, w.bits, w.bucket, 2, dt)
+    assert_close(gpu_sqerrors(torch, g, p, m, w.offsets, w.bits, w.bucket, dt),
+                 oracle.layer_sqerrors(g, p, m, w.offsets, w.bits, w.bucket, dt), "shifted sqerrors")

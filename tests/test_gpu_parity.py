@@ -450,3 +450,20 @@ def test_buckets_longer_than_a_chunk(torch, oracle, bucket, dt):
     kinds = (cgx.cgx_plan_tiles(plan)["info"] >> 4) & 15
     assert (kinds == 4).sum() >= 10 and (kinds == 0).any() and not (kinds == 1).any()
     full_cycle(torch, oracle, w, W=3, what=f"wide B={bucket}")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [64, 128, 1024, 4096])
+def test_layers_that_start_anywhere(torch, oracle, bucket, dt):
+    """Odd-length tensors shift every later layer off the 8-element grid, onto odd element indices
+    and back: the vectorised tiles (quantized and pass-through) must take them as they come."""
+    sizes = [2048 * 3 + 1, 2048 * 2, 7, 8192 + 3, 2048 * 4 + 2, 1, 8192 * 2, 4096 + 5, 2048 * 5, 3, 8192 + 4096]
+    bits = [4, 1, 0, 3, 8, 0, 0, 5, 2, 0, 7]
+    w = wl.Workload("shifted", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 3, 700 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    tiles = cgx.cgx_plan_tiles(plan)
+    vec = np.isin((tiles["info"] >> 4) & 15, (1, 4))
+    assert (tiles["elem0"][vec] % 2 == 1).sum() >= 5 and (tiles["elem0"][vec] % 8 == 0).sum() >= 1
+    assert np.isin(tiles["elem0"][vec] % 8, (2, 4, 6)).any()
+    full_cycle(torch, oracle, w, W=3, what=f"shifted B={bucket}")

@@ -200,3 +200,13 @@ def test_buckets_longer_than_a_chunk(torch, oracle, bucket, dt):
     w = wl.Workload("wide", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 3, 600 + bucket,
                     wl._normal, np.linspace(0.01, 2.0, len(sizes)))
     full_cycle(torch, oracle, w, W=3, what=f"qsgd wide B={bucket}")
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [32, 512, 8192])
+def test_layers_that_start_anywhere(torch, oracle, bucket, dt):
+    sizes = [2048 * 3 + 1, 2048 * 2, 7, 8192 + 3, 2048 * 4 + 2, 1, 8192 * 2, 4096 + 5, 2048 * 5, 3, 8192 + 4096]
+    bits = [4, 2, 0, 3, 8, 0, 0, 5, 2, 0, 7]
+    w = wl.Workload("shifted", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 3, 800 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    full_cycle(torch, oracle, w, W=3, what=f"qsgd shifted B={bucket}")

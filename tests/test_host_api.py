@@ -217,10 +217,8 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
         last = t["elem0"] + t["count"] == e
         assert int(t["pad"]) == ((-payload) % 16 if last else 0)
         if b == 0:
-            assert kind in (2, 3)
+            assert kind == 3                                          # every copy tile is vectorised
             assert t["packed_off"] == seg + j * es
-            if kind == 3:
-                assert t["elem0"] % 8 == 0
         else:
             assert kind in (0, 1, 4)
             assert j % w.bucket == 0                                  # tiles start on a bucket
@@ -228,11 +226,11 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
             assert t["packed_off"] == seg + j * b // 8
             assert t["bucket0"] == g0 + j // w.bucket
             if kind == 1:
-                assert t["count"] % CHUNK == 0 and t["elem0"] % 8 == 0
+                assert t["count"] % CHUNK == 0
                 assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= CHUNK
                 assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket * 64 // CHUNK))
             if kind == 4:                                             # one whole bucket of several chunks
-                assert t["count"] == w.bucket and w.bucket in (4096, 8192) and t["elem0"] % 8 == 0
+                assert t["count"] == w.bucket and w.bucket in (4096, 8192)
                 assert (int(t["info"]) >> 8) & 15 == 6
     if w.name.startswith("wide"):
         assert (((tiles["info"] >> 4) & 15) == 4).sum() == (9 if w.name == "wide" else 3)
