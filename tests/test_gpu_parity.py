@@ -467,3 +467,92 @@ def test_layers_that_start_anywhere(torch, oracle, bucket, dt):
     assert (tiles["elem0"][vec] % 2 == 1).sum() >= 5 and (tiles["elem0"][vec] % 8 == 0).sum() >= 1
     assert np.isin(tiles["elem0"][vec] % 8, (2, 4, 6)).any()
     full_cycle(torch, oracle, w, W=3, what=f"shifted B={bucket}")
+
+
+def test_step_can_be_captured_in_a_graph_and_replayed(torch, oracle):
+    """Once a plan's tables exist the entry points only queue kernels, so a step can be captured;
+    every replay (with eager work and synchronisations in between) gives the eager result."""
+    w = wl.tiny_mixed(seed=12, bucket=128)
+    W = 3
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    plan32 = cgx.Plan(w.offsets, w.bits, w.bucket, wl.F32)
+    pb, mb = cgx.cgx_sizes(plan)
+    g = dev(torch, w.gradient(0))
+    chunks = [oracle.quantize(w.gradient(p), w.offsets, w.bits, w.bucket, w.quant_seed(p), w.dt) for p in range(W)]
+    dp = [dev(torch, c[0]) for c in chunks]
+    dm = [dev(torch, c[1].reshape(-1)) for c in chunks]
+
+    def buffers():
+        return (torch.zeros(pb, dtype=torch.uint8, device="cuda"), torch.zeros(max(mb // 4, 4), device="cuda"),
+                torch.zeros(w.n, device="cuda"), torch.zeros(pb, dtype=torch.uint8, device="cuda"),
+                torch.zeros(max(mb // 4, 4), device="cuda"))
+
+    def step(out):
+        cgx.cgx_quantize(g, plan, 5, out[0], out[1])
+        cgx.cgx_dequant_reduce(dp, dm, plan, out[2])
+        cgx.cgx_requantize(out[2], plan32, 6, out[3], out[4])
+
+    eager = buffers()
+    step(eager)                                   # also builds the plans' tables
+    torch.cuda.synchronize()
+    want = [t.cpu().numpy().copy() for t in eager]
+    op, om = oracle.quantize(w.gradient(0), w.offsets, w.bits, w.bucket, 5, w.dt)
+    assert np.array_equal(want[0], op) and want[1][:mb // 4].tobytes() == om.tobytes()
+
+    captured = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(captured)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in captured:
+            t.fill_(7 if t.dtype == torch.uint8 else 7.0)      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(captured, want):
+            assert got.cpu().numpy().tobytes() == ref.tobytes(), f"replay {replay}"
+
+
+def test_calls_from_several_host_threads_and_streams(torch, oracle):
+    """The plan cache is shared by host threads; concurrent calls on separate streams with
+    separate outputs give the same bytes as a single call."""
+    import threading
+    w = wl.tiny_mixed(seed=14, bucket=512)
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    pb, mb = cgx.cgx_sizes(plan)
+    g = dev(torch, w.gradient(0))
+    op, om = oracle.quantize(w.gradient(0), w.offsets, w.bits, w.bucket, 9, w.dt)
+    torch.cuda.synchronize()
+    results, errors = {}, []
+
+    def worker(k):
+        try:
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.default_stream())
+            for rep in range(5):
+                # a plan of its own (new tables) and the shared one, alternately
+                own = cgx.Plan(np.array([0, 4096 + 8 * k, w.n], np.int64), np.array([4, 2], np.uint8), 128, w.dt)
+                opb, omb = cgx.cgx_sizes(own)
+                a = torch.empty(opb, dtype=torch.uint8, device="cuda")
+                b = torch.empty(max(omb // 4, 4), device="cuda")
+                packed = torch.empty(pb, dtype=torch.uint8, device="cuda")
+                meta = torch.empty(max(mb // 4, 4), device="cuda")
+                cgx.cgx_quantize(g, own, k, a, b, stream=s)
+                cgx.cgx_quantize(g, plan, 9, packed, meta, stream=s)
+                s.synchronize()
+                results[(k, rep)] = (packed.cpu().numpy(), meta.cpu().numpy()[:mb // 4])
+        except Exception as e:                      # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(6)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert len(results) == 30
+    for p, m in results.values():
+        assert np.array_equal(p, op) and m.tobytes() == om.tobytes()
