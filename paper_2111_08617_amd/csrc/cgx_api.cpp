@@ -26,6 +26,7 @@ struct CachedPlan {
     // content
     cgx::PlanShape shape;
     int64_t n_tiles = 0;
+    bool odd_tiles = false;     // some vectorised quantized tile starts on an odd element index
     Tile *d_tiles = nullptr;
     // per-layer numbering of the tiles (for the statistics): slot of every tile, first slot of every layer
     uint32_t *d_slots = nullptr;
@@ -119,6 +120,8 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     cgx::build_tiles(L, off, bits, bucket, dt, cfg.chunks_per_tile, tiles, &slots, &layer_first);
     if (tiles.size() > size_t(0xffffffffu)) return CGX_ERR_SIZE;
     plan->n_tiles = int64_t(tiles.size());
+    for (const Tile &t : tiles)
+        if (cgx::is_vector_kind(cgx::tile_kind(t)) && (t.elem0 & 1)) plan->odd_tiles = true;
     if (!upload(&plan->d_tiles, tiles) || !upload(&plan->d_slots, slots) ||
         !upload(&plan->d_layer_first, layer_first)) {
         free_plan(*plan);
@@ -160,7 +163,8 @@ int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int6
     PlanRef plan;
     rc = get_plan(L, off, bits, bucket, dt, &plan);
     if (rc != CGX_OK) return rc;
-    const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, bucket, seed, packed, meta,
+    const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles, bucket,
+                                              seed, packed, meta,
                                               launch_config(), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }
@@ -231,7 +235,8 @@ int fused_impl(int scheme, const void *const *packed, const void *const *meta, i
         peers.meta[i] = static_cast<const float *>(meta[i]);
     }
     const hipError_t e = cgx::launch_dequant_reduce_requantize(scheme, peers, W, dt, in->d_tiles, out->d_tiles,
-                                                               in->n_tiles, bucket, seed, packed_out, meta_out,
+                                                               in->n_tiles, in->odd_tiles, bucket, seed, packed_out,
+                                                               meta_out,
                                                                launch_config(), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }

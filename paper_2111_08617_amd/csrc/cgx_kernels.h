@@ -25,8 +25,10 @@ struct LaunchConfig {
     int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
 };
 
-hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, int32_t bucket,
-                           uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
+// odd_tiles: some vectorised tile starts on an odd element index (the kernels then take the
+// variant that can draw across generator words; a property of the tile table).
+hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
+                           int32_t bucket, uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
                            hipStream_t stream);
 
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
@@ -39,7 +41,7 @@ hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int d
 // reaching memory; tiles_in describes the chunks (storage type dt), tiles_out the output
 // (binary32 pass-through); W <= kPeersPerLaunch.
 hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
-                                            const Tile *tiles_out, int64_t n_tiles, int32_t bucket,
+                                            const Tile *tiles_out, int64_t n_tiles, bool odd_tiles, int32_t bucket,
                                             uint64_t seed, void *packed_out, void *meta_out,
                                             const LaunchConfig &cfg, hipStream_t stream);
 

@@ -344,7 +344,14 @@ __device__ __forceinline__ void wait_vector_memory()
 template <int BITS>
 __device__ __forceinline__ void stage_codes(uint8_t *p, uint64_t acc)
 {
-    __builtin_memcpy(p, &acc, BITS);
+    if (BITS == 8)
+        *reinterpret_cast<uint64_t *>(p) = acc;
+    else if (BITS == 4)
+        *reinterpret_cast<uint32_t *>(p) = uint32_t(acc);
+    else if (BITS == 2)
+        *reinterpret_cast<uint16_t *>(p) = uint16_t(acc);
+    else
+        __builtin_memcpy(p, &acc, BITS);
 }
 
 // Bytes staged_codes may read past the b bytes of a group (their content is ignored).
@@ -412,21 +419,21 @@ struct LaneMap {
 // 2 * pair0 + odd + j, key = generator key of the tile.  odd (0 or 1, uniform over a tile: groups
 // start 8 elements apart) tells whether the group starts on the upper half of a generator word;
 // then its 8 draws are the 16-bit halves 1..8 of words pair0 .. pair0 + 4 instead of halves
-// 0..7 of words pair0 .. pair0 + 3.
-template <int SCHEME, int BITS>
+// 0..7 of words pair0 .. pair0 + 3.  ODD = false: the plan has no such tile (odd == 0 always),
+// and neither the fifth word nor the selection is paid; the host picks the instantiation.
+template <int SCHEME, int BITS, bool ODD>
 __device__ __forceinline__ uint64_t encode_group(const float (&x)[8], const Scale &s, uint32_t pair0, uint32_t key,
                                                  uint32_t odd)
 {
     constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
     uint32_t word[5];
 #pragma unroll
-    for (int k = 0; k < 4; k++) word[k] = mix32((pair0 + k) ^ key);
-    word[4] = 0;
-    if (odd) word[4] = mix32((pair0 + 4) ^ key);
+    for (int k = 0; k < 4 + int(ODD); k++) word[k] = mix32((pair0 + k) ^ key);
     uint64_t acc = 0;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-        const uint32_t w = __builtin_amdgcn_alignbit(word[k + 1], word[k], 16u * odd);   // the pair's two draws
+        // the pair's two draws
+        const uint32_t w = ODD ? __builtin_amdgcn_alignbit(word[k + 1], word[k], 16u * odd) : word[k];
         const uint64_t q0 = code_of<SCHEME>(x[2 * k], s, w & 0xffffU, kLevels, BITS);
         const uint64_t q1 = code_of<SCHEME>(x[2 * k + 1], s, w >> 16, kLevels, BITS);
         acc |= q0 << (2 * k * BITS);
@@ -453,7 +460,7 @@ __device__ __forceinline__ void lane_extent(const float (&x)[G][8], float &mn, f
 }
 
 // Codes of a chunk whose elements all take the scale s: staged, then sent out.
-template <int SCHEME, int BITS>
+template <int SCHEME, int BITS, bool ODD>
 __device__ __forceinline__ void encode_chunk(const float (&x)[G][8], const Scale &s, const LaneMap &map,
                                              int64_t first, uint32_t key, uint8_t *__restrict__ out,
                                              uint4v *stage, int lane)
@@ -462,7 +469,7 @@ __device__ __forceinline__ void encode_chunk(const float (&x)[G][8], const Scale
     for (int r = 0; r < G; r++) {
         const uint32_t pair0 = uint32_t(uint64_t(first + map.group(r)) >> 1);
         stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (map.group(r) >> 3) * BITS,
-                          encode_group<SCHEME, BITS>(x[r], s, pair0, key, uint32_t(first) & 1u));
+                          encode_group<SCHEME, BITS, ODD>(x[r], s, pair0, key, uint32_t(first) & 1u));
     }
     // the chunk's codes leave as whole 16-byte vectors, consecutive across lanes
     wave_lds_fence();
@@ -473,7 +480,7 @@ __device__ __forceinline__ void encode_chunk(const float (&x)[G][8], const Scale
 // One chunk held in registers (x) -> meta of its buckets and its packed codes.
 // first = buffer index of the chunk's first element; key = generator key of the tile.
 // meta_chunk points at the meta of the chunk's first bucket.
-template <int SCHEME, int BITS>
+template <int SCHEME, int BITS, bool ODD>
 __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const LaneMap &map, int lane, int64_t first,
                                                uint32_t key, float *__restrict__ meta_chunk,
                                                uint8_t *__restrict__ out, uint4v *stage)
@@ -487,7 +494,7 @@ __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const Lan
         group_minmax(mn, mx, map.lg, lane);
     const Scale s = bucket_scale(mn, mx, int(kLevels));
     if (map.lp == 0) store_meta<SCHEME>(meta_chunk, map.bi, s);
-    encode_chunk<SCHEME, BITS>(x, s, map, first, key, out, stage, lane);
+    encode_chunk<SCHEME, BITS, ODD>(x, s, map, first, key, out, stage, lane);
 }
 
 // The same for buckets of 32 or 64 elements, with the chunk held row by row: group r of lane l
@@ -497,7 +504,7 @@ __device__ __forceinline__ void quantize_chunk(const float (&x)[G][8], const Lan
 // 16 to 64 bytes of each: measured 21 % of the HBM peak at 32-element buckets).  A bucket is
 // bucket / 8 neighbouring lanes of one row; a lane serves four buckets and pays the two
 // divisions four times.
-template <int SCHEME, int BITS>
+template <int SCHEME, int BITS, bool ODD>
 __device__ __forceinline__ void quantize_chunk_rows(const float (&x)[G][8], int bucket, int lane, int64_t first,
                                                     uint32_t key, float *__restrict__ meta_chunk,
                                                     uint8_t *__restrict__ out, uint4v *stage)
@@ -530,14 +537,14 @@ __device__ __forceinline__ void quantize_chunk_rows(const float (&x)[G][8], int 
         const int e = r * kRow + lane * 8;           // the group's first element within the chunk
         const uint32_t pair0 = uint32_t(uint64_t(first + e) >> 1);
         stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (e >> 3) * BITS,
-                          encode_group<SCHEME, BITS>(x[r], s, pair0, key, uint32_t(first) & 1u));
+                          encode_group<SCHEME, BITS, ODD>(x[r], s, pair0, key, uint32_t(first) & 1u));
     }
     wave_lds_fence();
     flush_stage(stage, reinterpret_cast<uint4v *>(out), kChunk * BITS / 128, lane);
     wave_lds_fence();
 }
 
-template <int SCHEME, int DT, int BITS>
+template <int SCHEME, int DT, int BITS, bool ODD>
 __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uint8_t *__restrict__ packed,
                                               float *__restrict__ meta, const Tile &tile, int bucket,
                                               uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
@@ -551,14 +558,14 @@ __device__ __forceinline__ void quantize_fast(const void *__restrict__ grad, uin
         float x[G][8];
 #pragma unroll
         for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
-        quantize_chunk<SCHEME, BITS>(x, map, lane, first, key,
+        quantize_chunk<SCHEME, BITS, ODD>(x, map, lane, first, key,
                                      meta + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
                                      packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8), stage);
     }
 }
 
 // quantize_fast for buckets of 32 or 64 elements (row-by-row mapping).
-template <int SCHEME, int DT, int BITS>
+template <int SCHEME, int DT, int BITS, bool ODD>
 __device__ __forceinline__ void quantize_fast_rows(const void *__restrict__ grad, uint8_t *__restrict__ packed,
                                                    float *__restrict__ meta, const Tile &tile, int bucket,
                                                    uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
@@ -571,7 +578,7 @@ __device__ __forceinline__ void quantize_fast_rows(const void *__restrict__ grad
         float x[G][8];
 #pragma unroll
         for (int r = 0; r < G; r++) load8<DT>(grad, first + r * (kWave * 8) + lane * 8, x[r]);
-        quantize_chunk_rows<SCHEME, BITS>(x, bucket, lane, first, key,
+        quantize_chunk_rows<SCHEME, BITS, ODD>(x, bucket, lane, first, key,
                                           meta + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
                                           packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8), stage);
     }
@@ -580,7 +587,7 @@ __device__ __forceinline__ void quantize_fast_rows(const void *__restrict__ grad
 // A tile that is one whole bucket of 2 or 4 chunks: a first pass over the chunks finds the
 // scale, a second one reads them again (from the caches: 16 or 32 KB read a moment ago) and
 // cuts the codes.  Row-by-row mapping (LaneMap with the whole wave as one bucket).
-template <int SCHEME, int DT, int BITS>
+template <int SCHEME, int DT, int BITS, bool ODD>
 __device__ __forceinline__ void quantize_wide(const void *__restrict__ grad, uint8_t *__restrict__ packed,
                                               float *__restrict__ meta, const Tile &tile, int bucket,
                                               uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
@@ -611,7 +618,7 @@ __device__ __forceinline__ void quantize_wide(const void *__restrict__ grad, uin
         float x[G][8];
 #pragma unroll
         for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
-        encode_chunk<SCHEME, BITS>(x, s, map, first, key, packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+        encode_chunk<SCHEME, BITS, ODD>(x, s, map, first, key, packed + tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
                                    stage, lane);
     }
 }
@@ -741,7 +748,8 @@ enum LaneMapping { kMapBuckets = 0, kMapRows = 1, kMapWide = 2 };
 
 inline int mapping_of(int bucket) { return bucket <= 64 ? kMapRows : bucket > kChunk ? kMapWide : kMapBuckets; }
 
-template <int SCHEME, int DT, int MAP>
+// ODD: some vectorised tile of the plan starts on an odd element index (see encode_group).
+template <int SCHEME, int DT, int MAP, bool ODD>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
                                                            const Tile *__restrict__ tiles, int64_t n_tiles,
                                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
@@ -759,13 +767,13 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {
             if constexpr (MAP == kMapRows) {
-                CGX_FOR_BITS(tile_bits(tile), (quantize_fast_rows<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
+                CGX_FOR_BITS(tile_bits(tile), (quantize_fast_rows<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
                                                                                       seed_lo, seed_hi, lane, stage)))
             } else if constexpr (MAP == kMapWide) {
-                CGX_FOR_BITS(tile_bits(tile), (quantize_wide<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
+                CGX_FOR_BITS(tile_bits(tile), (quantize_wide<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
                                                                                  seed_lo, seed_hi, lane, stage)))
             } else {
-                CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS>(grad, packed, meta, tile, bucket,
+                CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
                                                                                  seed_lo, seed_hi, lane, stage)))
             }
         } else if (kind == kQuantSlow) {
@@ -872,10 +880,13 @@ template <int SCHEME, int BITS>
 __device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64_t in_off, uint32_t g,
                                              const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane)
 {
-    // peers staged together: as many as fit the staging area (one chunk of sums, kChunk * 4
-    // bytes) with their packed bytes, 8 or 4
+    // peers staged together: 8 if their packed bytes fit the staging area (one chunk of sums,
+    // kChunk * 4 bytes), else 4; the odd widths take 4 (their two or three dwords per group
+    // and peer are all in flight together: at 8 peers the 3-bit path alone raised the fused
+    // kernel from 106 to 125 registers, which cost every other width up to 50 % there)
     constexpr int kBytes = kChunk * BITS / 8;
-    constexpr int kWide = 8 * kBytes + kStagedOverRead<BITS> <= kChunk * 4 ? 8 : 4;
+    constexpr bool kOddWidth = kStagedOverRead<BITS> != 0;
+    constexpr int kWide = (kOddWidth || 8 * kBytes > kChunk * 4) ? 4 : 8;
     static_assert(kWide * kBytes + kStagedOverRead<BITS> <= kChunk * 4, "staging area too small");
     int code_off[G];
 #pragma unroll
@@ -1113,7 +1124,7 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
 // ---------------------------------------------------------------- fused reduce + requantize
 
 // The sums of a chunk never leave the registers: reduce_chunk feeds quantize_chunk.
-template <int SCHEME, int BITS>
+template <int SCHEME, int BITS, bool ODD>
 __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                            uint8_t *__restrict__ packed_out, float *__restrict__ meta_out,
@@ -1128,7 +1139,7 @@ __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const T
         clear_sums(acc);
         reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
                                    tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
-        quantize_chunk<SCHEME, BITS>(acc, map, lane, tile.elem0 + int64_t(c) * kChunk, key,
+        quantize_chunk<SCHEME, BITS, ODD>(acc, map, lane, tile.elem0 + int64_t(c) * kChunk, key,
                                      meta_out + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
                                      packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage);
     }
@@ -1137,7 +1148,7 @@ __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const T
 // A tile that is one whole bucket of 2 or 4 chunks: the sums are formed twice, once for the
 // scale and once for the codes (they would not fit the registers, and the chunks' bytes come
 // from the caches the second time).
-template <int SCHEME, int BITS>
+template <int SCHEME, int BITS, bool ODD>
 __device__ __forceinline__ void fused_wide(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                            uint8_t *__restrict__ packed_out, float *__restrict__ meta_out,
@@ -1158,7 +1169,7 @@ __device__ __forceinline__ void fused_wide(const PeerPtrs &peers, int W, const T
         reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8), tile.bucket0, map,
                                    acc, stage, lane);
         if (second) {
-            encode_chunk<SCHEME, BITS>(acc, s, map, tile.elem0 + int64_t(c) * kChunk, key,
+            encode_chunk<SCHEME, BITS, ODD>(acc, s, map, tile.elem0 + int64_t(c) * kChunk, key,
                                        packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage, lane);
             continue;
         }
@@ -1177,7 +1188,7 @@ __device__ __forceinline__ void fused_wide(const PeerPtrs &peers, int W, const T
 // tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
 // output (binary32 pass-through layers); the two tables list the same tiles in the same order.
 // WIDE: the call's bucket is longer than a chunk (see quantize_kernel's MAP).
-template <int SCHEME, bool WIDE>
+template <int SCHEME, bool WIDE, bool ODD>
 __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int W, int dt,
                                                         const Tile *__restrict__ tiles_in,
                                                         const Tile *__restrict__ tiles_out, int64_t n_tiles,
@@ -1197,10 +1208,10 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {
             if constexpr (WIDE) {
-                CGX_FOR_BITS(tile_bits(tile), (fused_wide<SCHEME, BITS>(peers, W, tile, out_off, bucket, seed_lo,
+                CGX_FOR_BITS(tile_bits(tile), (fused_wide<SCHEME, BITS, ODD>(peers, W, tile, out_off, bucket, seed_lo,
                                                                          seed_hi, packed_out, meta_out, lane, stage)))
             } else {
-                CGX_FOR_BITS(tile_bits(tile), (fused_fast<SCHEME, BITS>(peers, W, tile, out_off, bucket, seed_lo,
+                CGX_FOR_BITS(tile_bits(tile), (fused_fast<SCHEME, BITS, ODD>(peers, W, tile, out_off, bucket, seed_lo,
                                                                          seed_hi, packed_out, meta_out, lane, stage)))
             }
         } else if (kind == kQuantSlow) {
@@ -1415,7 +1426,7 @@ inline unsigned grid_for(int64_t n_tiles, const LaunchConfig &cfg)
 
 }  // namespace
 
-hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles,
+hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
                            int32_t bucket, uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
                            hipStream_t stream)
 {
@@ -1423,16 +1434,15 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const uint32_t seed_lo = uint32_t(seed), seed_hi = uint32_t(seed >> 32);
     using Kernel = void (*)(const void *, const Tile *, int64_t, int, uint32_t, uint32_t, uint8_t *, float *);
-    static const Kernel table[2][2][3] = {
-        {{quantize_kernel<kMinMax, CGX_F32, kMapBuckets>, quantize_kernel<kMinMax, CGX_F32, kMapRows>,
-          quantize_kernel<kMinMax, CGX_F32, kMapWide>},
-         {quantize_kernel<kMinMax, CGX_F16, kMapBuckets>, quantize_kernel<kMinMax, CGX_F16, kMapRows>,
-          quantize_kernel<kMinMax, CGX_F16, kMapWide>}},
-        {{quantize_kernel<kNormSign, CGX_F32, kMapBuckets>, quantize_kernel<kNormSign, CGX_F32, kMapRows>,
-          quantize_kernel<kNormSign, CGX_F32, kMapWide>},
-         {quantize_kernel<kNormSign, CGX_F16, kMapBuckets>, quantize_kernel<kNormSign, CGX_F16, kMapRows>,
-          quantize_kernel<kNormSign, CGX_F16, kMapWide>}}};
-    const Kernel kernel = table[scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket)];
+#define CGX_QUANTIZE_MAPS(S, D, O) \
+    {quantize_kernel<S, D, kMapBuckets, O>, quantize_kernel<S, D, kMapRows, O>, quantize_kernel<S, D, kMapWide, O>}
+    static const Kernel table[2][2][2][3] = {
+        {{CGX_QUANTIZE_MAPS(kMinMax, CGX_F32, false), CGX_QUANTIZE_MAPS(kMinMax, CGX_F16, false)},
+         {CGX_QUANTIZE_MAPS(kNormSign, CGX_F32, false), CGX_QUANTIZE_MAPS(kNormSign, CGX_F16, false)}},
+        {{CGX_QUANTIZE_MAPS(kMinMax, CGX_F32, true), CGX_QUANTIZE_MAPS(kMinMax, CGX_F16, true)},
+         {CGX_QUANTIZE_MAPS(kNormSign, CGX_F32, true), CGX_QUANTIZE_MAPS(kNormSign, CGX_F16, true)}}};
+#undef CGX_QUANTIZE_MAPS
+    const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket)];
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket), seed_lo, seed_hi,
                        static_cast<uint8_t *>(packed), static_cast<float *>(meta));
     return hipGetLastError();
@@ -1451,15 +1461,21 @@ hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int d
 }
 
 hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles_in,
-                                            const Tile *tiles_out, int64_t n_tiles, int32_t bucket,
+                                            const Tile *tiles_out, int64_t n_tiles, bool odd_tiles, int32_t bucket,
                                             uint64_t seed, void *packed_out, void *meta_out,
                                             const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const bool wide = mapping_of(bucket) == kMapWide;
-    const auto kernel = scheme == kSchemeNormSign ? (wide ? fused_kernel<kNormSign, true> : fused_kernel<kNormSign, false>)
-                                                  : (wide ? fused_kernel<kMinMax, true> : fused_kernel<kMinMax, false>);
+    using Kernel = void (*)(const PeerPtrs, int, int, const Tile *, const Tile *, int64_t, int, uint32_t, uint32_t,
+                            uint8_t *, float *);
+    static const Kernel table[2][2][2] = {
+        {{fused_kernel<kMinMax, false, false>, fused_kernel<kMinMax, true, false>},
+         {fused_kernel<kNormSign, false, false>, fused_kernel<kNormSign, true, false>}},
+        {{fused_kernel<kMinMax, false, true>, fused_kernel<kMinMax, true, true>},
+         {fused_kernel<kNormSign, false, true>, fused_kernel<kNormSign, true, true>}}};
+    const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][wide];
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles, int(bucket),
                        uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
                        static_cast<float *>(meta_out));
