@@ -556,3 +556,16 @@ def test_calls_from_several_host_threads_and_streams(torch, oracle):
     assert len(results) == 30
     for p, m in results.values():
         assert np.array_equal(p, op) and m.tobytes() == om.tobytes()
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+def test_thousands_of_small_layers(torch, oracle, dt):
+    """A layer table of 4000 short tensors of random length, width and alignment."""
+    rng = np.random.default_rng(31 + dt)
+    sizes = rng.integers(0, 3000, 4000)
+    sizes[rng.random(4000) < 0.02] = 0
+    sizes[::97] = rng.integers(5000, 40000, sizes[::97].size)
+    bits = rng.integers(0, 9, 4000).astype(np.uint8)
+    w = wl.Workload("small_layers", [(int(s),) for s in sizes], bits, 256, dt, 2, 4242, wl._normal,
+                    np.exp(rng.normal(-3, 1, 4000)))
+    full_cycle(torch, oracle, w, W=2, what="4000 layers")
