@@ -270,7 +270,8 @@ int cgx_assign_bits_linear(int32_t L, const int64_t *layer_offsets, const double
  *     uint32 elements; uint32 info; uint32 pad_bytes }
  * with info = bits | kind << 4 | log2(lanes per bucket) << 8 and kind 0 = generic
  * quantize, 1 = vectorised quantize, 2 = element-wise copy, 3 = vectorised copy,
- * 4 = vectorised quantize of one whole bucket of 4096 or 8192 elements.
+ * 4 = vectorised quantize of one whole bucket of 4096 or 8192 elements, 5 = the short end
+ * of a layer (less than a chunk of 2048 elements) with power-of-two buckets.
  * Every element of every non-empty layer lies in exactly one tile and tiles never
  * cross layers (paper Sec. 4.1).  At most `capacity` records are written;
  * *n_tiles receives the full count.  Pure host computation.

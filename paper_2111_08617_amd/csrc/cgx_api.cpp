@@ -27,6 +27,7 @@ struct CachedPlan {
     cgx::PlanShape shape;
     int64_t n_tiles = 0;
     bool odd_tiles = false;     // some vectorised quantized tile starts on an odd element index
+    bool many_tails = false;    // short ends of layers are at least 1/64 of the tiles, and at least 16
     Tile *d_tiles = nullptr;
     // per-layer numbering of the tiles (for the statistics): slot of every tile, first slot of every layer
     uint32_t *d_slots = nullptr;
@@ -121,7 +122,11 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     if (tiles.size() > size_t(0xffffffffu)) return CGX_ERR_SIZE;
     plan->n_tiles = int64_t(tiles.size());
     for (const Tile &t : tiles)
-        if (cgx::is_vector_kind(cgx::tile_kind(t)) && (t.elem0 & 1)) plan->odd_tiles = true;
+        if ((cgx::is_vector_kind(cgx::tile_kind(t)) || cgx::tile_kind(t) == cgx::kQuantTail) && (t.elem0 & 1))
+            plan->odd_tiles = true;
+    int64_t tails = 0;
+    for (const Tile &t : tiles) tails += cgx::tile_kind(t) == cgx::kQuantTail;
+    plan->many_tails = tails >= 16 && tails * 64 >= plan->n_tiles;
     if (!upload(&plan->d_tiles, tiles) || !upload(&plan->d_slots, slots) ||
         !upload(&plan->d_layer_first, layer_first)) {
         free_plan(*plan);
@@ -200,7 +205,8 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
         }
         const void *init = w0 == 0 ? local : out;
         const int init_dt = w0 == 0 ? local_dt : CGX_F32;
-        const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles, bucket, init,
+        const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
+                                                        plan->many_tails, bucket, init,
                                                         init_dt, out, out_dt, launch_config(),
                                                         static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return CGX_ERR_HIP;

@@ -33,7 +33,10 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
 
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
 // term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
+// many_tails: the short ends of layers are a real share of the plan's tiles (the kernel then
+// takes them through the masked chunk path instead of the generic one).
 hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+                                 bool many_tails,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
                                  const LaunchConfig &cfg, hipStream_t stream);
 

@@ -29,6 +29,18 @@
 namespace cgx {
 namespace {
 
+// The peers' pointer table is a kernel argument (256 bytes).  The kernels read it where the
+// dispatch packet put it, in the constant-address-space kernarg segment, with scalar loads at
+// computed offsets; taken as an ordinary by-value parameter it would be copied into 64 scalar
+// registers at entry and, in the larger kernels, spilled to scratch to be indexed.
+typedef const __attribute__((address_space(4))) PeerPtrs KernargPeers;
+
+// The table when it is the kernel's FIRST parameter (offset 0 of the kernarg segment).
+__device__ __forceinline__ KernargPeers &first_kernel_argument()
+{
+    return *(KernargPeers *)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
 constexpr int kWave = 64;
 #ifndef CGX_WAVES_PER_BLOCK
 #define CGX_WAVES_PER_BLOCK 4
@@ -623,6 +635,91 @@ __device__ __forceinline__ void quantize_wide(const void *__restrict__ grad, uin
     }
 }
 
+// The short end of a layer (fewer elements than a chunk, whole buckets and possibly a ragged last
+// one) goes through the chunk code with the missing elements masked.
+struct TailShape {
+    int count;       // elements of the tile
+    int buckets;     // its buckets (the last one may be short)
+    int nvecs;       // 16-byte vectors of its packed bytes (the layer's zero padding included)
+    template <int BITS>
+    __device__ __forceinline__ static TailShape of(const Tile &tile, int bucket)
+    {
+        TailShape t;
+        t.count = int(tile.count);
+        t.buckets = (t.count + bucket - 1) / bucket;
+        t.nvecs = ((t.count * BITS + 7) / 8 + 15) / 16;
+        return t;
+    }
+    // how many of the 8 elements of the group that starts at chunk element e exist
+    __device__ __forceinline__ int valid(int e) const { return count - e >= 8 ? 8 : count - e > 0 ? count - e : 0; }
+};
+
+// x holds the tile's elements in the chunk mapping, 0 where there is none -> meta and codes.
+template <int SCHEME, int BITS, bool ODD>
+__device__ __forceinline__ void quantize_tail_regs(const float (&x)[G][8], const TailShape &shape, const LaneMap &map,
+                                                   int lane, int64_t first, uint32_t key, float *__restrict__ meta,
+                                                   uint8_t *__restrict__ out, uint4v *stage)
+{
+    constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    // kNormSign: the zeros of the missing elements are neutral for the largest magnitude
+    float mn = SCHEME == kNormSign ? 0.0f : __builtin_inff(), mx = SCHEME == kNormSign ? 0.0f : -__builtin_inff();
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int v = shape.valid(map.group(r));
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            if (SCHEME == kNormSign) {
+                mx = __builtin_fmaxf(mx, __builtin_fabsf(x[r][j]));
+            } else {
+                mn = __builtin_fminf(mn, j < v ? x[r][j] : __builtin_inff());
+                mx = __builtin_fmaxf(mx, j < v ? x[r][j] : -__builtin_inff());
+            }
+        }
+    }
+    if (SCHEME == kNormSign)
+        group_max(mx, map.lg, lane);
+    else
+        group_minmax(mn, mx, map.lg, lane);
+    const Scale s = bucket_scale(mn, mx, int(kLevels));
+    if (map.lp == 0 && map.bi < shape.buckets) store_meta<SCHEME>(meta, map.bi, s);
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int v = shape.valid(map.group(r));
+        const uint32_t pair0 = uint32_t(uint64_t(first + map.group(r)) >> 1);
+        uint64_t codes = encode_group<SCHEME, BITS, ODD>(x[r], s, pair0, key, uint32_t(first) & 1u);
+        codes &= v == 8 ? ~uint64_t(0) : (uint64_t(1) << (v * BITS)) - 1u;       // nothing past the layer's end
+        stage_codes<BITS>(reinterpret_cast<uint8_t *>(stage) + (map.group(r) >> 3) * BITS, codes);
+    }
+    // every group of the chunk has been staged (zeros past the end), so whole vectors can leave:
+    // they carry the zero padding of the layer's segment with them
+    wave_lds_fence();
+    flush_stage(stage, reinterpret_cast<uint4v *>(out), shape.nvecs, lane);
+    wave_lds_fence();
+}
+
+template <int SCHEME, int DT, int BITS, bool ODD>
+__device__ __forceinline__ void quantize_tail(const void *__restrict__ grad, uint8_t *__restrict__ packed,
+                                              float *__restrict__ meta, const Tile &tile, int bucket,
+                                              uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const TailShape shape = TailShape::of<BITS>(tile, bucket);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    float x[G][8];
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int e = map.group(r), v = shape.valid(e);
+        if (v == 8) {
+            load8<DT>(grad, tile.elem0 + e, x[r]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++) x[r][j] = j < v ? load_elem<DT>(grad, tile.elem0 + e + j) : 0.0f;
+        }
+    }
+    quantize_tail_regs<SCHEME, BITS, ODD>(x, shape, map, lane, tile.elem0, key,
+                                          meta + kMetaFloats<SCHEME> * tile.bucket0, packed + tile.packed_off, stage);
+}
+
 // Any bucket size, any alignment, ragged last bucket: one bucket at a time, two passes.
 // value(j) gives element j of the tile (called twice per element).  With BATCH the values
 // of a pass are fetched 8 at a time so that plain loads overlap; without it (value() is
@@ -776,6 +873,9 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
                 CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
                                                                                  seed_lo, seed_hi, lane, stage)))
             }
+        } else if (kind == kQuantTail) {
+            CGX_FOR_BITS(tile_bits(tile), (quantize_tail<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
+                                                                                  seed_lo, seed_hi, lane, stage)))
         } else if (kind == kQuantSlow) {
             quantize_generic<SCHEME, true>([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
                                            packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo,
@@ -838,10 +938,13 @@ __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
 // Folds peers w0 .. w0+WB-1 into acc.  Each peer's share of the chunk (kChunk*BITS/8 bytes)
 // is fetched as whole 16-byte vectors, consecutive across lanes, directly into the wave's
 // LDS staging area, and read back by the lanes that own the codes.
-template <int SCHEME, int BITS, int WB>
-__device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int64_t in_off, uint32_t g,
+// TAIL: the chunk is the short end of a layer; only its first nvecs 16-byte vectors exist in the
+// packed streams (what lies behind them in LDS is stale, and so are the sums of elements past
+// the end: the caller drops them).
+template <int SCHEME, int BITS, int WB, bool TAIL, typename Peers>
+__device__ __forceinline__ void reduce_peers(Peers &peers, int w0, int64_t in_off, uint32_t g,
                                              const int (&code_off)[G], float (&acc)[G][8], uint4v *stage,
-                                             int lane)
+                                             int lane, int nvecs)
 {
     constexpr int kBytes = kChunk * BITS / 8;        // per peer
     constexpr int kVecs = kBytes / 16;
@@ -853,7 +956,7 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
 #pragma unroll
         for (int k = 0; k < kPerLane; k++) {
             const int v = lane + k * kWave;
-            if (kVecs % kWave == 0 || v < kVecs) load_to_lds16(in + v, stage + i * kVecs + k * kWave);
+            if (TAIL ? v < nvecs : (kVecs % kWave == 0 || v < kVecs)) load_to_lds16(in + v, stage + i * kVecs + k * kWave);
         }
         m[i] = load_meta<SCHEME>(peers.meta[w0 + i], g);
     }
@@ -876,9 +979,10 @@ __device__ __forceinline__ void reduce_peers(const PeerPtrs &peers, int w0, int6
 }
 
 // Sum over the W peers of one chunk's dequantized values, added to acc in peer order.
-template <int SCHEME, int BITS>
-__device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64_t in_off, uint32_t g,
-                                             const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane)
+template <int SCHEME, int BITS, bool TAIL = false, typename Peers>
+__device__ __forceinline__ void reduce_chunk(Peers &peers, int W, int64_t in_off, uint32_t g,
+                                             const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane,
+                                             int nvecs = 0)
 {
     // peers staged together: 8 if their packed bytes fit the staging area (one chunk of sums,
     // kChunk * 4 bytes), else 4; the odd widths take 4 (their two or three dwords per group
@@ -892,7 +996,7 @@ __device__ __forceinline__ void reduce_chunk(const PeerPtrs &peers, int W, int64
 #pragma unroll
     for (int r = 0; r < G; r++) code_off[r] = (map.group(r) >> 3) * BITS;
     for_peer_blocks<kWide>(W, [&](int w0, auto wb) {
-        reduce_peers<SCHEME, BITS, decltype(wb)::value>(peers, w0, in_off, g, code_off, acc, stage, lane);
+        reduce_peers<SCHEME, BITS, decltype(wb)::value, TAIL>(peers, w0, in_off, g, code_off, acc, stage, lane, nvecs);
     });
 }
 
@@ -957,8 +1061,8 @@ __device__ __forceinline__ void store8(const SumIo &io, int64_t e, const float (
     }
 }
 
-template <int SCHEME, int BITS>
-__device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const SumIo &io, const Tile &tile,
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io, const Tile &tile,
                                             int bucket, int lane, uint4v *stage)
 {
     const LaneMap map(tile, bucket, lane);
@@ -999,10 +1103,57 @@ __device__ __forceinline__ void reduce_fast(const PeerPtrs &peers, int W, const 
     }
 }
 
+// Sums of the short end of a layer, in the chunk mapping: acc[r][j] is valid for j < valid(group r).
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_tail_regs(Peers &peers, int W, const Tile &tile,
+                                                 const TailShape &shape, const LaneMap &map, float (&acc)[G][8],
+                                                 uint4v *stage, int lane)
+{
+    // lanes past the last bucket read its meta (and produce sums nobody uses)
+    const int bi = map.bi < shape.buckets ? map.bi : shape.buckets - 1;
+    reduce_chunk<SCHEME, BITS, true>(peers, W, tile.packed_off, tile.bucket0 + uint32_t(bi), map, acc, stage, lane,
+                                     shape.nvecs);
+}
+
+// Start values come in and sums go out through the staging area, element by element over the
+// elements that exist (coalesced; light on registers).
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_tail(Peers &peers, int W, const SumIo &io, const Tile &tile,
+                                            int bucket, int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const TailShape shape = TailShape::of<BITS>(tile, bucket);
+    float *staged = reinterpret_cast<float *>(stage);
+    for (int e = lane; e < kChunk; e += kWave) staged[e] = e < shape.count ? init1(io, tile.elem0 + e) : -0.0f;
+    wave_lds_fence();
+    float acc[G][8];
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const float4v *p = reinterpret_cast<const float4v *>(staged + map.group(r));
+        const float4v a = p[0], b = p[1];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            acc[r][j] = a[j];
+            acc[r][4 + j] = b[j];
+        }
+    }
+    wave_lds_fence();
+    reduce_tail_regs<SCHEME, BITS>(peers, W, tile, shape, map, acc, stage, lane);
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        float4v *p = reinterpret_cast<float4v *>(staged + map.group(r));
+        p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+        p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
+    }
+    wave_lds_fence();
+    for (int e = lane; e < shape.count; e += kWave) store1(io, tile.elem0 + e, staged[e]);
+    wave_lds_fence();
+}
+
 // Ordered sum over the peers of element j of a generic quantized tile (start = the value
 // the sum starts from).
-template <int SCHEME>
-__device__ __forceinline__ float generic_sum(const PeerPtrs &peers, int W, const Tile &tile, int bucket,
+template <int SCHEME, typename Peers>
+__device__ __forceinline__ float generic_sum(Peers &peers, int W, const Tile &tile, int bucket,
                                              uint32_t j, float start)
 {
     const int b = int(tile_bits(tile));
@@ -1035,8 +1186,8 @@ __device__ __forceinline__ float generic_sum(const PeerPtrs &peers, int W, const
 }
 
 // Any bucket size, any alignment, ragged tiles: one element per lane and pass.
-template <int SCHEME>
-__device__ void reduce_slow(const PeerPtrs &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
+template <int SCHEME, typename Peers>
+__device__ void reduce_slow(Peers &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
 {
     for (uint32_t j = lane; j < tile.count; j += kWave)
         store1(io, tile.elem0 + j, generic_sum<SCHEME>(peers, W, tile, bucket, j, init1(io, tile.elem0 + j)));
@@ -1044,8 +1195,8 @@ __device__ void reduce_slow(const PeerPtrs &peers, int W, const SumIo &io, const
 
 // Ordered sum over the peers of 8 consecutive elements of a pass-through tile (16-byte
 // aligned) and of a single element.
-template <int DT>
-__device__ __forceinline__ void copy_sum8(const PeerPtrs &peers, int W, const Tile &tile, uint32_t g,
+template <int DT, typename Peers>
+__device__ __forceinline__ void copy_sum8(Peers &peers, int W, const Tile &tile, uint32_t g,
                                           float (&acc)[8])
 {
     for_peer_blocks<8>(W, [&](int w0, auto wb) {
@@ -1063,8 +1214,8 @@ __device__ __forceinline__ void copy_sum8(const PeerPtrs &peers, int W, const Ti
     });
 }
 
-template <int DT>
-__device__ __forceinline__ float copy_sum1(const PeerPtrs &peers, int W, const Tile &tile, uint32_t j, float start)
+template <int DT, typename Peers>
+__device__ __forceinline__ float copy_sum1(Peers &peers, int W, const Tile &tile, uint32_t j, float start)
 {
     float acc = start;
     for_peer_blocks<8>(W, [&](int w0, auto wb) {
@@ -1080,8 +1231,8 @@ __device__ __forceinline__ float copy_sum1(const PeerPtrs &peers, int W, const T
 
 // Pass-through tile of the reduce kernels: plain ordered sum of the stored values; element j
 // of the tile starts from / goes to position e0 + j of io.
-template <int DT>
-__device__ void reduce_copy(const PeerPtrs &peers, int W, const SumIo &io, int64_t e0, const Tile &tile, bool fast,
+template <int DT, typename Peers>
+__device__ void reduce_copy(Peers &peers, int W, const SumIo &io, int64_t e0, const Tile &tile, bool fast,
                             int lane)
 {
     const uint32_t groups = fast ? tile.count / 8 : 0;
@@ -1095,11 +1246,19 @@ __device__ void reduce_copy(const PeerPtrs &peers, int W, const SumIo &io, int64
         store1(io, e0 + j, copy_sum1<DT>(peers, W, tile, j, init1(io, e0 + j)));
 }
 
-template <int SCHEME>
-__global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, int W, int dt, const SumIo io,
+// TAILS: the short ends of layers take the masked chunk path.  That path costs the kernel one
+// register too many for its occupancy (and fencing it in by attribute cost 9 % on one of the
+// benchmark plans), so the host asks for it only where short ends are a real share of the work;
+// elsewhere the few there are go through the generic path, overlapped with everything else.
+template <int SCHEME, bool TAILS>
+__global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_argument, int W, int dt, const SumIo io,
                                                          const Tile *__restrict__ tiles, int64_t n_tiles,
                                                          int bucket)
 {
+    // the vectorised tiles index the table with constants (it then sits in scalar registers);
+    // the other kinds index it at run time and read it from the kernarg segment
+    const PeerPtrs &peers = peers_argument;
+    KernargPeers &peers_in_memory = first_kernel_argument();
     // per-wave staging area: a chunk of binary32 results, or the packed bytes of a block of peers
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
@@ -1111,12 +1270,17 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {      // a wide tile is chunks of one bucket: kChunk / bucket == 0 below
             CGX_FOR_BITS(tile_bits(tile), (reduce_fast<SCHEME, BITS>(peers, W, io, tile, bucket, lane, stage)))
-        } else if (kind == kQuantSlow) {
-            reduce_slow<SCHEME>(peers, W, io, tile, bucket, lane);
+        } else if (TAILS && kind == kQuantTail) {
+            if constexpr (TAILS) {
+                CGX_FOR_BITS(tile_bits(tile),
+                             (reduce_tail<SCHEME, BITS>(peers_in_memory, W, io, tile, bucket, lane, stage)))
+            }
+        } else if (kind == kQuantSlow || kind == kQuantTail) {
+            reduce_slow<SCHEME>(peers_in_memory, W, io, tile, bucket, lane);
         } else if (dt == CGX_F16) {
-            reduce_copy<CGX_F16>(peers, W, io, tile.elem0, tile, kind == kCopyFast, lane);
+            reduce_copy<CGX_F16>(peers_in_memory, W, io, tile.elem0, tile, kind == kCopyFast, lane);
         } else {
-            reduce_copy<CGX_F32>(peers, W, io, tile.elem0, tile, kind == kCopyFast, lane);
+            reduce_copy<CGX_F32>(peers_in_memory, W, io, tile.elem0, tile, kind == kCopyFast, lane);
         }
     }
 }
@@ -1124,8 +1288,8 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers, in
 // ---------------------------------------------------------------- fused reduce + requantize
 
 // The sums of a chunk never leave the registers: reduce_chunk feeds quantize_chunk.
-template <int SCHEME, int BITS, bool ODD>
-__device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
+template <int SCHEME, int BITS, bool ODD, typename Peers>
+__device__ __forceinline__ void fused_fast(Peers &peers, int W, const Tile &tile, int64_t out_off,
                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                            uint8_t *__restrict__ packed_out, float *__restrict__ meta_out,
                                            int lane, uint4v *stage)
@@ -1148,8 +1312,8 @@ __device__ __forceinline__ void fused_fast(const PeerPtrs &peers, int W, const T
 // A tile that is one whole bucket of 2 or 4 chunks: the sums are formed twice, once for the
 // scale and once for the codes (they would not fit the registers, and the chunks' bytes come
 // from the caches the second time).
-template <int SCHEME, int BITS, bool ODD>
-__device__ __forceinline__ void fused_wide(const PeerPtrs &peers, int W, const Tile &tile, int64_t out_off,
+template <int SCHEME, int BITS, bool ODD, typename Peers>
+__device__ __forceinline__ void fused_wide(Peers &peers, int W, const Tile &tile, int64_t out_off,
                                            int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                            uint8_t *__restrict__ packed_out, float *__restrict__ meta_out,
                                            int lane, uint4v *stage)
@@ -1185,17 +1349,42 @@ __device__ __forceinline__ void fused_wide(const PeerPtrs &peers, int W, const T
     }
 }
 
+// The short end of a layer: masked sums feed the masked quantizer.
+template <int SCHEME, int BITS, bool ODD, typename Peers>
+__device__ __forceinline__ void fused_tail(Peers &peers, int W, const Tile &tile, int64_t out_off, int bucket,
+                                           uint32_t seed_lo, uint32_t seed_hi, uint8_t *__restrict__ packed_out,
+                                           float *__restrict__ meta_out, int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const TailShape shape = TailShape::of<BITS>(tile, bucket);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    float acc[G][8];
+    clear_sums(acc);
+    reduce_tail_regs<SCHEME, BITS>(peers, W, tile, shape, map, acc, stage, lane);
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int v = shape.valid(map.group(r));
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            if (j >= v) acc[r][j] = 0.0f;            // stale LDS bytes decoded to anything
+    }
+    quantize_tail_regs<SCHEME, BITS, ODD>(acc, shape, map, lane, tile.elem0, key,
+                                          meta_out + kMetaFloats<SCHEME> * tile.bucket0, packed_out + out_off, stage);
+}
+
 // tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
 // output (binary32 pass-through layers); the two tables list the same tiles in the same order.
 // WIDE: the call's bucket is longer than a chunk (see quantize_kernel's MAP).
 template <int SCHEME, bool WIDE, bool ODD>
-__global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int W, int dt,
+__global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers_argument, int W, int dt,
                                                         const Tile *__restrict__ tiles_in,
                                                         const Tile *__restrict__ tiles_out, int64_t n_tiles,
                                                         int bucket, uint32_t seed_lo, uint32_t seed_hi,
                                                         uint8_t *__restrict__ packed_out,
                                                         float *__restrict__ meta_out)
 {
+    (void)peers_argument;
+    KernargPeers &peers = first_kernel_argument();
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     const int lane = int(threadIdx.x) & 63;
@@ -1214,6 +1403,9 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers, int
                 CGX_FOR_BITS(tile_bits(tile), (fused_fast<SCHEME, BITS, ODD>(peers, W, tile, out_off, bucket, seed_lo,
                                                                          seed_hi, packed_out, meta_out, lane, stage)))
             }
+        } else if (kind == kQuantTail) {
+            CGX_FOR_BITS(tile_bits(tile), (fused_tail<SCHEME, BITS, ODD>(peers, W, tile, out_off, bucket, seed_lo,
+                                                                         seed_hi, packed_out, meta_out, lane, stage)))
         } else if (kind == kQuantSlow) {
             quantize_generic<SCHEME, false>(
                 [&](uint32_t j) { return generic_sum<SCHEME>(peers, W, tile, bucket, j, -0.0f); },
@@ -1298,8 +1490,8 @@ __global__ __launch_bounds__(kBlock) void sqnorm_kernel(const void *__restrict__
 
 // Squared error of a vectorised tile: the codes are decoded as in the reduce (one peer) and
 // compared with the gradient they were cut from.
-template <int SCHEME, int DT, int BITS>
-__device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, const PeerPtrs &chunk,
+template <int SCHEME, int DT, int BITS, typename Peers>
+__device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, Peers &chunk,
                                                const Tile &tile, int bucket, int lane, uint4v *stage)
 {
     const LaneMap map(tile, bucket, lane);
@@ -1326,11 +1518,13 @@ __device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, co
 }
 
 template <int SCHEME, int DT>
-__global__ __launch_bounds__(kBlock) void sqerror_kernel(const void *__restrict__ grad, const PeerPtrs chunk,
+__global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_argument, const void *__restrict__ grad,
                                                           const Tile *__restrict__ tiles,
                                                           const uint32_t *__restrict__ slots, int64_t n_tiles,
                                                           int bucket, double *__restrict__ partial)
 {
+    (void)chunk_argument;
+    KernargPeers &chunk = first_kernel_argument();
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     const int lane = int(threadIdx.x) & 63;
@@ -1342,7 +1536,7 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const void *__restrict_
         double s = 0.0;                              // pass-through tiles: no error
         if (is_vector_kind(kind)) {
             CGX_FOR_BITS(tile_bits(tile), (s = sqerror_fast<SCHEME, DT, BITS>(grad, chunk, tile, bucket, lane, stage)))
-        } else if (kind == kQuantSlow) {
+        } else if (kind == kQuantSlow || kind == kQuantTail) {
             for (uint32_t j = lane; j < tile.count; j += kWave) {
                 const double d = double(load_elem<DT>(grad, tile.elem0 + j)) -
                                  double(generic_sum<SCHEME>(chunk, 1, tile, bucket, j, -0.0f));
@@ -1449,13 +1643,16 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
 }
 
 hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+                                 bool many_tails,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
                                  const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const SumIo io{init, init_dt, out, out_dt};
-    const auto kernel = scheme == kSchemeNormSign ? reduce_kernel<kNormSign> : reduce_kernel<kMinMax>;
+    const auto kernel = scheme == kSchemeNormSign
+                            ? (many_tails ? reduce_kernel<kNormSign, true> : reduce_kernel<kNormSign, false>)
+                            : (many_tails ? reduce_kernel<kMinMax, true> : reduce_kernel<kMinMax, false>);
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles, int(bucket));
     return hipGetLastError();
 }
@@ -1514,7 +1711,7 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
             scheme == kSchemeNormSign
                 ? (dt == CGX_F16 ? sqerror_kernel<kNormSign, CGX_F16> : sqerror_kernel<kNormSign, CGX_F32>)
                 : (dt == CGX_F16 ? sqerror_kernel<kMinMax, CGX_F16> : sqerror_kernel<kMinMax, CGX_F32>);
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, chunk, tiles, slots, n_tiles, int(bucket), partial);
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, chunk, grad, tiles, slots, n_tiles, int(bucket), partial);
     }
     hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
                        static_cast<const double *>(partial), layer_first, out);

@@ -138,7 +138,10 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
                 t.packed_off = int64_t(seg + uint64_t(j) * b / 8);
                 t.bucket0 = uint32_t(bucket0 + uint64_t(j) / bucket);
                 t.count = uint32_t(len - j < step ? len - j : step);
-                t.info = uint32_t(b) | uint32_t(kQuantSlow) << 4;
+                // the short end of a layer with power-of-two buckets runs through the chunk code, masked
+                const bool tail = fast_bucket && j % kChunk == 0 && t.count < uint32_t(kChunk) &&
+                                  same_key_block(t.elem0, t.count);
+                t.info = uint32_t(b) | uint32_t(tail ? kQuantTail : kQuantSlow) << 4 | (tail ? lpb_log2 << 8 : 0u);
                 tiles.push_back(t);
             }
         }

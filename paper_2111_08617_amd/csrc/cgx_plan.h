@@ -36,7 +36,8 @@ enum TileKind : uint32_t {
     kQuantFast = 1,  // power-of-two bucket <= kChunk, whole chunks
     kCopySlow = 2,   // pass-through, element-wise (no longer produced: every copy tile is vectorised)
     kCopyFast = 3,   // pass-through, 16-byte vectors
-    kQuantWide = 4   // one whole power-of-two bucket longer than a chunk (4096, 8192)
+    kQuantWide = 4,  // one whole power-of-two bucket longer than a chunk (4096, 8192)
+    kQuantTail = 5   // power-of-two bucket <= kChunk, the last tile of a layer, shorter than a chunk
 };
 
 // Vectorised quantized tiles (everything else costs several dependent memory round trips).

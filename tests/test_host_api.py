@@ -220,7 +220,7 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
             assert kind == 3                                          # every copy tile is vectorised
             assert t["packed_off"] == seg + j * es
         else:
-            assert kind in (0, 1, 4)
+            assert kind in (0, 1, 4, 5)
             assert j % w.bucket == 0                                  # tiles start on a bucket
             assert last or t["count"] % w.bucket == 0                 # and hold whole buckets
             assert t["packed_off"] == seg + j * b // 8
@@ -229,6 +229,12 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
                 assert t["count"] % CHUNK == 0
                 assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= CHUNK
                 assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket * 64 // CHUNK))
+            if kind == 5:                                             # the short end of a layer, masked chunk
+                assert last and t["count"] < CHUNK and j % CHUNK == 0
+                assert w.bucket & (w.bucket - 1) == 0 and w.bucket <= CHUNK
+                assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket * 64 // CHUNK))
+            if kind == 0:                                             # generic: only where nothing else fits
+                assert w.bucket & (w.bucket - 1) != 0 or w.bucket > CHUNK
             if kind == 4:                                             # one whole bucket of several chunks
                 assert t["count"] == w.bucket and w.bucket in (4096, 8192)
                 assert (int(t["info"]) >> 8) & 15 == 6
