@@ -1,0 +1,372 @@
+// Device code of the dequantize-and-reduce: decoding of staged codes, the peers' loop, sums of
+// chunks, short ends, generic and pass-through tiles (shared by the reduce, fused and
+// statistics kernels).
+#pragma once
+
+#include "cgx_device.h"
+
+namespace cgx {
+namespace {
+
+// ---------------------------------------------------------------- dequantize + reduce
+
+// Levels of one group of 8 codes as floats (kNormSign: signed levels).
+template <int SCHEME, int BITS>
+__device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
+{
+    if (SCHEME == kNormSign) {
+        if (BITS == 8) {
+            const uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                f[j] = float(int32_t(int8_t(lo >> (8 * j))));
+                f[4 + j] = float(int32_t(int8_t(hi >> (8 * j))));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++)      // sign-extending field extract
+                f[j] = float(int32_t(uint32_t(v >> (j * BITS)) << (32 - BITS)) >> (32 - BITS));
+        }
+    } else if (BITS == 8) {
+        const uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            f[j] = float((lo >> (8 * j)) & 0xffu);
+            f[4 + j] = float((hi >> (8 * j)) & 0xffu);
+        }
+    } else if (BITS == 4) {
+        const uint32_t w = uint32_t(v);
+        const uint32_t even = w & 0x0f0f0f0fu, odd = (w >> 4) & 0x0f0f0f0fu;   // one code per byte
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            f[2 * j] = float((even >> (8 * j)) & 0xffu);
+            f[2 * j + 1] = float((odd >> (8 * j)) & 0xffu);
+        }
+    } else if (BITS == 2) {
+        const uint32_t w = uint32_t(v);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t t = (w >> (2 * j)) & 0x0303u;     // codes j and j + 4, one per byte
+            f[j] = float(t & 0xffu);
+            f[4 + j] = float((t >> 8) & 0xffu);
+        }
+    } else {
+        constexpr uint64_t kMask = (1u << BITS) - 1u;
+#pragma unroll
+        for (int j = 0; j < 8; j++) f[j] = float(uint32_t((v >> (j * BITS)) & kMask));
+    }
+}
+
+// Folds peers w0 .. w0+WB-1 into acc.  Each peer's share of the chunk (kChunk*BITS/8 bytes)
+// is fetched as whole 16-byte vectors, consecutive across lanes, directly into the wave's
+// LDS staging area, and read back by the lanes that own the codes.
+// TAIL: the chunk is the short end of a layer; only its first nvecs 16-byte vectors exist in the
+// packed streams (what lies behind them in LDS is stale, and so are the sums of elements past
+// the end: the caller drops them).
+template <int SCHEME, int BITS, int WB, bool TAIL, typename Peers>
+__device__ __forceinline__ void reduce_peers(Peers &peers, int w0, int64_t in_off, uint32_t g,
+                                             const int (&code_off)[G], float (&acc)[G][8], uint4v *stage,
+                                             int lane, int nvecs)
+{
+    constexpr int kBytes = kChunk * BITS / 8;        // per peer
+    constexpr int kVecs = kBytes / 16;
+    constexpr int kPerLane = (kVecs + kWave - 1) / kWave;
+    float2 m[WB];
+#pragma unroll
+    for (int i = 0; i < WB; i++) {
+        const uint4v *in = reinterpret_cast<const uint4v *>(peers.packed[w0 + i] + in_off);
+#pragma unroll
+        for (int k = 0; k < kPerLane; k++) {
+            const int v = lane + k * kWave;
+            if (TAIL ? v < nvecs : (kVecs % kWave == 0 || v < kVecs)) load_to_lds16(in + v, stage + i * kVecs + k * kWave);
+        }
+        m[i] = load_meta<SCHEME>(peers.meta[w0 + i], g);
+    }
+    wait_vector_memory();
+    wave_lds_fence();
+    const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage);
+#pragma unroll
+    for (int i = 0; i < WB; i++) {
+#pragma unroll
+        for (int r = 0; r < G; r++) {
+            float f[8];
+            codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes + i * kBytes, code_off[r]), f);
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[r][j] = __fadd_rn(acc[r][j], decode<SCHEME>(f[j], m[i]));
+        }
+        // keep the scheduler from hoisting every peer's LDS reads to the top (registers)
+        if (i % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+    wave_lds_fence();
+}
+
+// Sum over the W peers of one chunk's dequantized values, added to acc in peer order.
+template <int SCHEME, int BITS, bool TAIL = false, typename Peers>
+__device__ __forceinline__ void reduce_chunk(Peers &peers, int W, int64_t in_off, uint32_t g,
+                                             const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane,
+                                             int nvecs = 0)
+{
+    // peers staged together: 8 if their packed bytes fit the staging area (one chunk of sums,
+    // kChunk * 4 bytes), else 4; the odd widths take 4 (their two or three dwords per group
+    // and peer are all in flight together: at 8 peers the 3-bit path alone raised the fused
+    // kernel from 106 to 125 registers, which cost every other width up to 50 % there)
+    constexpr int kBytes = kChunk * BITS / 8;
+    constexpr bool kOddWidth = kStagedOverRead<BITS> != 0;
+    constexpr int kWide = (kOddWidth || 8 * kBytes > kChunk * 4) ? 4 : 8;
+    static_assert(kWide * kBytes + kStagedOverRead<BITS> <= kChunk * 4, "staging area too small");
+    int code_off[G];
+#pragma unroll
+    for (int r = 0; r < G; r++) code_off[r] = (map.group(r) >> 3) * BITS;
+    for_peer_blocks<kWide>(W, [&](int w0, auto wb) {
+        reduce_peers<SCHEME, BITS, decltype(wb)::value, TAIL>(peers, w0, in_off, g, code_off, acc, stage, lane, nvecs);
+    });
+}
+
+// -0 is the identity of binary32 addition for every addend, signed zeros included, so
+// the first peer's value enters the sum unchanged.
+__device__ __forceinline__ void clear_sums(float (&acc)[G][8])
+{
+#pragma unroll
+    for (int r = 0; r < G; r++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[r][j] = -0.0f;
+}
+
+// What a reduction starts from and where it goes: element e of the tile's buffer is
+// init[e] (binary32 or binary16; init == nullptr: nothing) and is written to out[e]
+// (binary32, or binary16 rounded to nearest even).
+struct SumIo {
+    const void *init;
+    int init_dt;
+    void *out;
+    int out_dt;
+};
+
+__device__ __forceinline__ void init8(const SumIo &io, int64_t e, float (&acc)[8])
+{
+    if (!io.init) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] = -0.0f;
+    } else if (io.init_dt == CGX_F16) {
+        load8<CGX_F16>(io.init, e, acc);
+    } else {
+        load8<CGX_F32>(io.init, e, acc);
+    }
+}
+
+__device__ __forceinline__ float init1(const SumIo &io, int64_t e)
+{
+    if (!io.init) return -0.0f;
+    return io.init_dt == CGX_F16 ? load_elem<CGX_F16>(io.init, e) : load_elem<CGX_F32>(io.init, e);
+}
+
+__device__ __forceinline__ void store1(const SumIo &io, int64_t e, float v)
+{
+    if (io.out_dt == CGX_F16)
+        reinterpret_cast<_Float16 *>(io.out)[e] = _Float16(v);
+    else
+        reinterpret_cast<float *>(io.out)[e] = v;
+}
+
+// 8 consecutive results to a 16-byte aligned position.
+__device__ __forceinline__ void store8(const SumIo &io, int64_t e, const float (&acc)[8])
+{
+    if (io.out_dt == CGX_F16) {
+        half8v h;
+#pragma unroll
+        for (int j = 0; j < 8; j++) h[j] = _Float16(acc[j]);
+        *reinterpret_cast<half8u *>(reinterpret_cast<_Float16 *>(io.out) + e) = h;
+    } else {
+        float4u *p = reinterpret_cast<float4u *>(reinterpret_cast<float *>(io.out) + e);
+        p[0] = float4v{acc[0], acc[1], acc[2], acc[3]};
+        p[1] = float4v{acc[4], acc[5], acc[6], acc[7]};
+    }
+}
+
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io, const Tile &tile,
+                                            int bucket, int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const int chunks = int(tile.count / kChunk);
+    const int buckets_per_chunk = kChunk / bucket;
+    for (int c = 0; c < chunks; c++) {
+        const int64_t first = tile.elem0 + int64_t(c) * kChunk;
+        float acc[G][8];
+#pragma unroll
+        for (int r = 0; r < G; r++) init8(io, first + map.group(r), acc[r]);
+        reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                                   tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
+        // the results leave through LDS as well, so that every store instruction writes 1 KB of
+        // consecutive addresses
+        if (io.out_dt == CGX_F16) {
+#pragma unroll
+            for (int r = 0; r < G; r++) {
+                half8v h;
+#pragma unroll
+                for (int j = 0; j < 8; j++) h[j] = _Float16(acc[r][j]);
+                reinterpret_cast<half8v *>(stage)[map.group(r) >> 3] = h;
+            }
+            wave_lds_fence();
+            flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<_Float16 *>(io.out) + first),
+                                    kChunk / 8, lane);
+        } else {
+#pragma unroll
+            for (int r = 0; r < G; r++) {
+                float4v *p = reinterpret_cast<float4v *>(stage) + (map.group(r) >> 2);
+                p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+                p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
+            }
+            wave_lds_fence();
+            flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<float *>(io.out) + first),
+                                    kChunk / 4, lane);
+        }
+        wave_lds_fence();
+    }
+}
+
+// Sums of the short end of a layer, in the chunk mapping: acc[r][j] is valid for j < valid(group r).
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_tail_regs(Peers &peers, int W, const Tile &tile,
+                                                 const TailShape &shape, const LaneMap &map, float (&acc)[G][8],
+                                                 uint4v *stage, int lane)
+{
+    // lanes past the last bucket read its meta (and produce sums nobody uses)
+    const int bi = map.bi < shape.buckets ? map.bi : shape.buckets - 1;
+    reduce_chunk<SCHEME, BITS, true>(peers, W, tile.packed_off, tile.bucket0 + uint32_t(bi), map, acc, stage, lane,
+                                     shape.nvecs);
+}
+
+// Start values come in and sums go out through the staging area, element by element over the
+// elements that exist (coalesced; light on registers).
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_tail(Peers &peers, int W, const SumIo &io, const Tile &tile,
+                                            int bucket, int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const TailShape shape = TailShape::of<BITS>(tile, bucket);
+    float *staged = reinterpret_cast<float *>(stage);
+    for (int e = lane; e < kChunk; e += kWave) staged[e] = e < shape.count ? init1(io, tile.elem0 + e) : -0.0f;
+    wave_lds_fence();
+    float acc[G][8];
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const float4v *p = reinterpret_cast<const float4v *>(staged + map.group(r));
+        const float4v a = p[0], b = p[1];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            acc[r][j] = a[j];
+            acc[r][4 + j] = b[j];
+        }
+    }
+    wave_lds_fence();
+    reduce_tail_regs<SCHEME, BITS>(peers, W, tile, shape, map, acc, stage, lane);
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        float4v *p = reinterpret_cast<float4v *>(staged + map.group(r));
+        p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+        p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
+    }
+    wave_lds_fence();
+    for (int e = lane; e < shape.count; e += kWave) store1(io, tile.elem0 + e, staged[e]);
+    wave_lds_fence();
+}
+
+// Ordered sum over the peers of element j of a generic quantized tile (start = the value
+// the sum starts from).
+template <int SCHEME, typename Peers>
+__device__ __forceinline__ float generic_sum(Peers &peers, int W, const Tile &tile, int bucket,
+                                             uint32_t j, float start)
+{
+    const int b = int(tile_bits(tile));
+    const uint32_t mask = (1u << b) - 1u;
+    const uint32_t g = tile.bucket0 + j / uint32_t(bucket);
+    const uint64_t bit = uint64_t(j) * b;
+    const int64_t at = tile.packed_off + int64_t(bit >> 3);
+    const uint32_t shift = uint32_t(bit & 7);
+    const bool two = shift + b > 8;                  // a code spans at most two bytes
+    float acc = start;
+    for_peer_blocks<8>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+        uint32_t lo[WB], hi[WB];
+        float2 m[WB];
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            const uint8_t *p = peers.packed[w0 + i] + at;
+            lo[i] = p[0];
+            hi[i] = two ? p[1] : 0u;
+            m[i] = load_meta<SCHEME>(peers.meta[w0 + i], g);
+        }
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            const uint32_t code = ((lo[i] | (hi[i] << 8)) >> shift) & mask;
+            const float level = SCHEME == kNormSign ? float(int32_t(code << (32 - b)) >> (32 - b)) : float(code);
+            acc = __fadd_rn(acc, decode<SCHEME>(level, m[i]));
+        }
+    });
+    return acc;
+}
+
+// Any bucket size, any alignment, ragged tiles: one element per lane and pass.
+template <int SCHEME, typename Peers>
+__device__ void reduce_slow(Peers &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
+{
+    for (uint32_t j = lane; j < tile.count; j += kWave)
+        store1(io, tile.elem0 + j, generic_sum<SCHEME>(peers, W, tile, bucket, j, init1(io, tile.elem0 + j)));
+}
+
+// Ordered sum over the peers of 8 consecutive elements of a pass-through tile (16-byte
+// aligned) and of a single element.
+template <int DT, typename Peers>
+__device__ __forceinline__ void copy_sum8(Peers &peers, int W, const Tile &tile, uint32_t g,
+                                          float (&acc)[8])
+{
+    for_peer_blocks<8>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+        Raw8<DT> raw[WB];
+#pragma unroll
+        for (int i = 0; i < WB; i++) raw[i].load(peers.packed[w0 + i] + tile.packed_off, int64_t(g) * 8);
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            float x[8];
+            raw[i].widen(x);
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[j] = __fadd_rn(acc[j], x[j]);
+        }
+    });
+}
+
+template <int DT, typename Peers>
+__device__ __forceinline__ float copy_sum1(Peers &peers, int W, const Tile &tile, uint32_t j, float start)
+{
+    float acc = start;
+    for_peer_blocks<8>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+        float x[WB];
+#pragma unroll
+        for (int i = 0; i < WB; i++) x[i] = load_elem<DT>(peers.packed[w0 + i] + tile.packed_off, j);
+#pragma unroll
+        for (int i = 0; i < WB; i++) acc = __fadd_rn(acc, x[i]);
+    });
+    return acc;
+}
+
+// Pass-through tile of the reduce kernels: plain ordered sum of the stored values; element j
+// of the tile starts from / goes to position e0 + j of io.
+template <int DT, typename Peers>
+__device__ void reduce_copy(Peers &peers, int W, const SumIo &io, int64_t e0, const Tile &tile, bool fast,
+                            int lane)
+{
+    const uint32_t groups = fast ? tile.count / 8 : 0;
+    for (uint32_t g = lane; g < groups; g += kWave) {
+        float acc[8];
+        init8(io, e0 + int64_t(g) * 8, acc);
+        copy_sum8<DT>(peers, W, tile, g, acc);
+        store8(io, e0 + int64_t(g) * 8, acc);
+    }
+    for (uint32_t j = groups * 8 + lane; j < tile.count; j += kWave)
+        store1(io, e0 + j, copy_sum1<DT>(peers, W, tile, j, init1(io, e0 + j)));
+}
+
+}  // namespace
+}  // namespace cgx

@@ -1,0 +1,72 @@
+// cgx_quantize / cgx_requantize / cgx_qsgd_quantize: the quantize kernel and its launcher.
+#include "cgx_device_quantize.h"
+
+namespace cgx {
+namespace {
+
+// ODD: some vectorised tile of the plan starts on an odd element index (see encode_group).
+template <int SCHEME, int DT, int MAP, bool ODD>
+__global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
+                                                           const Tile *__restrict__ tiles, int64_t n_tiles,
+                                                           int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                                           uint8_t *__restrict__ packed,
+                                                           float *__restrict__ meta)
+{
+    // per-wave staging area for a chunk's packed codes (at most kChunk bytes, at 8 bits)
+    __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 16];
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    uint4v *stage = stage_all[wave];
+    const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+        const Tile tile = tiles[t];
+        const uint32_t kind = tile_kind(tile);
+        if (is_vector_kind(kind)) {
+            if constexpr (MAP == kMapRows) {
+                CGX_FOR_BITS(tile_bits(tile), (quantize_fast_rows<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
+                                                                                      seed_lo, seed_hi, lane, stage)))
+            } else if constexpr (MAP == kMapWide) {
+                CGX_FOR_BITS(tile_bits(tile), (quantize_wide<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
+                                                                                 seed_lo, seed_hi, lane, stage)))
+            } else {
+                CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
+                                                                                 seed_lo, seed_hi, lane, stage)))
+            }
+        } else if (kind == kQuantTail) {
+            CGX_FOR_BITS(tile_bits(tile), (quantize_tail<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
+                                                                                  seed_lo, seed_hi, lane, stage)))
+        } else if (kind == kQuantSlow) {
+            quantize_generic<SCHEME, true>([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
+                                           packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo,
+                                           seed_hi, lane);
+        } else {
+            copy_tile<DT>(grad, packed, tile, kind == kCopyFast, lane);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
+                           int32_t bucket, uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
+                           hipStream_t stream)
+{
+    if (n_tiles == 0) return hipSuccess;
+    const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
+    const uint32_t seed_lo = uint32_t(seed), seed_hi = uint32_t(seed >> 32);
+    using Kernel = void (*)(const void *, const Tile *, int64_t, int, uint32_t, uint32_t, uint8_t *, float *);
+#define CGX_QUANTIZE_MAPS(S, D, O) \
+    {quantize_kernel<S, D, kMapBuckets, O>, quantize_kernel<S, D, kMapRows, O>, quantize_kernel<S, D, kMapWide, O>}
+    static const Kernel table[2][2][2][3] = {
+        {{CGX_QUANTIZE_MAPS(kMinMax, CGX_F32, false), CGX_QUANTIZE_MAPS(kMinMax, CGX_F16, false)},
+         {CGX_QUANTIZE_MAPS(kNormSign, CGX_F32, false), CGX_QUANTIZE_MAPS(kNormSign, CGX_F16, false)}},
+        {{CGX_QUANTIZE_MAPS(kMinMax, CGX_F32, true), CGX_QUANTIZE_MAPS(kMinMax, CGX_F16, true)},
+         {CGX_QUANTIZE_MAPS(kNormSign, CGX_F32, true), CGX_QUANTIZE_MAPS(kNormSign, CGX_F16, true)}}};
+#undef CGX_QUANTIZE_MAPS
+    const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket)];
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket), seed_lo, seed_hi,
+                       static_cast<uint8_t *>(packed), static_cast<float *>(meta));
+    return hipGetLastError();
+}
+
+}  // namespace cgx

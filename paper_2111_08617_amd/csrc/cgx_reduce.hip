@@ -1,0 +1,63 @@
+// cgx_dequant_reduce and its relatives: the reduce kernel and its launcher.
+#include "cgx_device_reduce.h"
+
+namespace cgx {
+namespace {
+
+// TAILS: the short ends of layers take the masked chunk path.  That path costs the kernel one
+// register too many for its occupancy (and fencing it in by attribute cost 9 % on one of the
+// benchmark plans), so the host asks for it only where short ends are a real share of the work;
+// elsewhere the few there are go through the generic path, overlapped with everything else.
+template <int SCHEME, bool TAILS>
+__global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_argument, int W, int dt, const SumIo io,
+                                                         const Tile *__restrict__ tiles, int64_t n_tiles,
+                                                         int bucket)
+{
+    // the vectorised tiles index the table with constants (it then sits in scalar registers);
+    // the other kinds index it at run time and read it from the kernarg segment
+    const PeerPtrs &peers = peers_argument;
+    KernargPeers &peers_in_memory = first_kernel_argument();
+    // per-wave staging area: a chunk of binary32 results, or the packed bytes of a block of peers
+    __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    uint4v *stage = stage_all[wave];
+    const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+        const Tile tile = tiles[t];
+        const uint32_t kind = tile_kind(tile);
+        if (is_vector_kind(kind)) {      // a wide tile is chunks of one bucket: kChunk / bucket == 0 below
+            CGX_FOR_BITS(tile_bits(tile), (reduce_fast<SCHEME, BITS>(peers, W, io, tile, bucket, lane, stage)))
+        } else if (TAILS && kind == kQuantTail) {
+            if constexpr (TAILS) {
+                CGX_FOR_BITS(tile_bits(tile),
+                             (reduce_tail<SCHEME, BITS>(peers_in_memory, W, io, tile, bucket, lane, stage)))
+            }
+        } else if (kind == kQuantSlow || kind == kQuantTail) {
+            reduce_slow<SCHEME>(peers_in_memory, W, io, tile, bucket, lane);
+        } else if (dt == CGX_F16) {
+            reduce_copy<CGX_F16>(peers_in_memory, W, io, tile.elem0, tile, kind == kCopyFast, lane);
+        } else {
+            reduce_copy<CGX_F32>(peers_in_memory, W, io, tile.elem0, tile, kind == kCopyFast, lane);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+                                 bool many_tails,
+                                 int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
+                                 const LaunchConfig &cfg, hipStream_t stream)
+{
+    if (n_tiles == 0) return hipSuccess;
+    const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
+    const SumIo io{init, init_dt, out, out_dt};
+    const auto kernel = scheme == kSchemeNormSign
+                            ? (many_tails ? reduce_kernel<kNormSign, true> : reduce_kernel<kNormSign, false>)
+                            : (many_tails ? reduce_kernel<kMinMax, true> : reduce_kernel<kMinMax, false>);
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles, int(bucket));
+    return hipGetLastError();
+}
+
+}  // namespace cgx

@@ -1,0 +1,247 @@
+// Per-layer statistics of the adaptive scheme and the streaming probe: kernels and launchers.
+#include "cgx_device_reduce.h"
+
+namespace cgx {
+namespace {
+
+// ---------------------------------------------------------------- per-layer statistics
+//
+// Squared l2 norms per layer (of a buffer, or of the compression error x - value(code)) for
+// the layer-wise adaptive scheme (paper Sec. "Layer-wise Adaptive Quantization").  Two
+// launches: one wave per tile leaves a binary64 partial sum in partial[slot of the tile]; then
+// one wave per layer adds the layer's partials.  No atomics, so a result does not depend on
+// the order in which waves finish.  Squares of binary32 values and differences of two
+// binary32 values are exact in binary64; only the additions round.
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+__device__ __forceinline__ double square(float x)
+{
+    const double d = double(x);
+    return d * d;
+}
+
+// Sum of squares of a run of elements of the buffer (tile of a pass-through plan).
+template <int DT>
+__device__ __forceinline__ double sqnorm_tile(const void *__restrict__ buf, const Tile &tile, bool fast, int lane)
+{
+    double s = 0.0;
+    const uint32_t groups = fast ? tile.count / 8 : 0;
+    for (uint32_t g0 = 0; g0 < groups; g0 += 4 * kWave) {
+        Raw8<DT> raw[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t g = g0 + u * kWave + lane;
+            raw[u].load(buf, tile.elem0 + int64_t(g < groups ? g : g0) * 8);    // clamped; masked below
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            float x[8];
+            raw[u].widen(x);
+            if (g0 + u * kWave + lane < groups) {
+#pragma unroll
+                for (int j = 0; j < 8; j++) s += square(x[j]);
+            }
+        }
+    }
+    for (uint32_t j = groups * 8 + lane; j < tile.count; j += kWave) s += square(load_elem<DT>(buf, tile.elem0 + j));
+    return s;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void sqnorm_kernel(const void *__restrict__ buf,
+                                                         const Tile *__restrict__ tiles,
+                                                         const uint32_t *__restrict__ slots, int64_t n_tiles,
+                                                         double *__restrict__ partial)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+        const Tile tile = tiles[t];
+        const double s = wave_sum(sqnorm_tile<DT>(buf, tile, tile_kind(tile) == kCopyFast, lane));
+        if (lane == 0) partial[slots[t]] = s;
+    }
+}
+
+// Squared error of a vectorised tile: the codes are decoded as in the reduce (one peer) and
+// compared with the gradient they were cut from.
+template <int SCHEME, int DT, int BITS, typename Peers>
+__device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, Peers &chunk,
+                                               const Tile &tile, int bucket, int lane, uint4v *stage)
+{
+    const LaneMap map(tile, bucket, lane);
+    const int chunks = int(tile.count / kChunk);
+    const int buckets_per_chunk = kChunk / bucket;
+    double s = 0.0;
+    for (int c = 0; c < chunks; c++) {
+        const int64_t first = tile.elem0 + int64_t(c) * kChunk;
+        float x[G][8], v[G][8];
+#pragma unroll
+        for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
+        clear_sums(v);
+        reduce_chunk<SCHEME, BITS>(chunk, 1, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
+                                   tile.bucket0 + c * buckets_per_chunk + map.bi, map, v, stage, lane);
+#pragma unroll
+        for (int r = 0; r < G; r++)
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const double d = double(x[r][j]) - double(v[r][j]);
+                s += d * d;
+            }
+    }
+    return s;
+}
+
+template <int SCHEME, int DT>
+__global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_argument, const void *__restrict__ grad,
+                                                          const Tile *__restrict__ tiles,
+                                                          const uint32_t *__restrict__ slots, int64_t n_tiles,
+                                                          int bucket, double *__restrict__ partial)
+{
+    (void)chunk_argument;
+    KernargPeers &chunk = first_kernel_argument();
+    __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    uint4v *stage = stage_all[wave];
+    const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+        const Tile tile = tiles[t];
+        const uint32_t kind = tile_kind(tile);
+        double s = 0.0;                              // pass-through tiles: no error
+        if (is_vector_kind(kind)) {
+            CGX_FOR_BITS(tile_bits(tile), (s = sqerror_fast<SCHEME, DT, BITS>(grad, chunk, tile, bucket, lane, stage)))
+        } else if (kind == kQuantSlow || kind == kQuantTail) {
+            for (uint32_t j = lane; j < tile.count; j += kWave) {
+                const double d = double(load_elem<DT>(grad, tile.elem0 + j)) -
+                                 double(generic_sum<SCHEME>(chunk, 1, tile, bucket, j, -0.0f));
+                s += d * d;
+            }
+        }
+        s = wave_sum(s);
+        if (lane == 0) partial[slots[t]] = s;
+    }
+}
+
+// out[l] = sum of the partials of layer l, numbers layer_first[l] .. layer_first[l + 1] - 1.
+// One block per layer: the largest layers own tens of thousands of partials, so the loads are
+// spread over 16 waves and issued four at a time; the order of the additions is fixed.
+constexpr int kSumBlock = 1024;
+
+__global__ __launch_bounds__(kSumBlock) void layer_sum_kernel(const double *__restrict__ partial,
+                                                               const int64_t *__restrict__ layer_first,
+                                                               double *__restrict__ out)
+{
+    __shared__ double wave_part[kSumBlock / kWave];
+    const int64_t l = blockIdx.x;
+    const int tid = int(threadIdx.x), lane = tid & 63, wave = tid >> 6;
+    const int64_t a = layer_first[l], b = layer_first[l + 1];
+    double s = 0.0;
+    for (int64_t i0 = a; i0 < b; i0 += 4 * kSumBlock) {
+        double v[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int64_t i = i0 + u * kSumBlock + tid;
+            v[u] = i < b ? partial[i] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) s += v[u];
+    }
+    s = wave_sum(s);
+    if (lane == 0) wave_part[wave] = s;
+    __syncthreads();
+    if (wave == 0) {
+        const double t = wave_sum(lane < kSumBlock / kWave ? wave_part[lane] : 0.0);
+        if (lane == 0) out[l] = t;
+    }
+}
+
+// ---------------------------------------------------------------- streaming probe
+
+// Measurement aid: moves read_bytes in and write_bytes out with the access style of the
+// kernels above (one wave per slice, lane-contiguous non-temporal 16-byte vectors) and no
+// arithmetic to speak of.  Its rate is what the memory system gives a kernel with that
+// read:write mix at that size.
+__global__ __launch_bounds__(kBlock) void stream_probe_kernel(const uint4v *__restrict__ src, int64_t read_vecs,
+                                                               uint4v *__restrict__ dst, int64_t write_vecs,
+                                                               int64_t waves)
+{
+    const int64_t wave = int64_t(blockIdx.x) * kWavesPerBlock + (int(threadIdx.x) >> 6);
+    const int lane = int(threadIdx.x) & 63;
+    if (wave >= waves) return;
+    const int64_t r0 = read_vecs * wave / waves, r1 = read_vecs * (wave + 1) / waves;
+    const int64_t w0 = write_vecs * wave / waves, w1 = write_vecs * (wave + 1) / waves;
+    uint4v acc = {0u, 0u, 0u, 0u};
+    for (int64_t v = r0 + lane; v < r1; v += 8 * kWave) {
+        uint4v x[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const int64_t i = v + u * kWave;
+            x[u] = i < r1 ? stream_load(src + i) : uint4v{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc += x[u];
+    }
+    for (int64_t v = w0 + lane; v < w1; v += kWave) stream_store(dst + v, acc + uint32_t(v));
+}
+
+}  // namespace
+
+hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
+                                const int64_t *layer_first, int32_t L, double *partial, double *out,
+                                const LaunchConfig &cfg, hipStream_t stream)
+{
+    if (L == 0) return hipSuccess;
+    const dim3 block(kBlock);
+    if (n_tiles > 0) {
+        const dim3 grid(grid_for(n_tiles, cfg));
+        const auto kernel = dt == CGX_F16 ? sqnorm_kernel<CGX_F16> : sqnorm_kernel<CGX_F32>;
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, buf, tiles, slots, n_tiles, partial);
+    }
+    hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
+                       static_cast<const double *>(partial), layer_first, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const void *packed, const void *meta,
+                                 const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
+                                 const int64_t *layer_first, int32_t L, int32_t bucket, double *partial,
+                                 double *out, const LaunchConfig &cfg, hipStream_t stream)
+{
+    if (L == 0) return hipSuccess;
+    const dim3 block(kBlock);
+    if (n_tiles > 0) {
+        const dim3 grid(grid_for(n_tiles, cfg));
+        PeerPtrs chunk{};
+        chunk.packed[0] = static_cast<const uint8_t *>(packed);
+        chunk.meta[0] = static_cast<const float *>(meta);
+        const auto kernel =
+            scheme == kSchemeNormSign
+                ? (dt == CGX_F16 ? sqerror_kernel<kNormSign, CGX_F16> : sqerror_kernel<kNormSign, CGX_F32>)
+                : (dt == CGX_F16 ? sqerror_kernel<kMinMax, CGX_F16> : sqerror_kernel<kMinMax, CGX_F32>);
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, chunk, grad, tiles, slots, n_tiles, int(bucket), partial);
+    }
+    hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
+                       static_cast<const double *>(partial), layer_first, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, hipStream_t stream)
+{
+    const int64_t read_vecs = int64_t(read_bytes / 16), write_vecs = int64_t(write_bytes / 16);
+    const int64_t larger = read_vecs > write_vecs ? read_vecs : write_vecs;
+    const int64_t waves = (larger + 511) / 512;                 // 8 KB of the larger side per wave
+    if (waves == 0) return hipSuccess;
+    const dim3 grid(unsigned((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(kBlock);
+    hipLaunchKernelGGL(stream_probe_kernel, grid, block, 0, stream, static_cast<const uint4v *>(src), read_vecs,
+                       static_cast<uint4v *>(dst), write_vecs, waves);
+    return hipGetLastError();
+}
+
+}  // namespace cgx
