@@ -10,8 +10,10 @@
  *   layer_offsets[L] = n; empty layers are allowed and skipped) and
  *   bits_per_layer[0..L-1] (host, uint8: 0 = pass-through, 1..8 = quantize to
  *   that many bits).  `bucket` is the bucket size in elements: a multiple of 32
- *   in [32, 8192].  Buckets restart at every layer's first element; a layer's
- *   last bucket may be short.  (Paper Sec. 4.1: fused buffers keep the layer
+ *   in [32, 8192] (powers of two take the vectorised kernels paths; the others
+ *   a generic, several times slower one).  Buckets restart at every layer's
+ *   first element; a layer's last bucket may be short.  Layers may start at any
+ *   element (only the buffers' base addresses must be aligned, see Memory).  (Paper Sec. 4.1: fused buffers keep the layer
  *   offsets, compression is per layer, small layers travel uncompressed;
  *   Sec. 4.3: buckets with per-bucket scaling meta-data.)
  *
@@ -31,9 +33,9 @@
  *   (built on first use, which may synchronise; later calls with the same plan
  *   only queue kernels): at most 64 of them, the least recently used one being
  *   dropped (which waits for the device) when a 65th plan arrives; cgx_shutdown()
- *   frees them all.  No call synchronises
- *   the stream.  `stream` is a hipStream_t passed as void* (NULL = the default
- *   stream).
+ *   frees them all.  No call synchronises the stream.  `stream` is a
+ *   hipStream_t passed as void* (NULL = the default stream).  Once a plan's
+ *   table exists, the calls only queue kernels and can be captured in a graph.
  *
  *   Errors.  Every function returns CGX_OK or a negative cgx_status.  Argument
  *   errors are found on the host before anything is queued; nothing is written
