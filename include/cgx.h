@@ -275,8 +275,11 @@ int cgx_assign_bits_linear(int32_t L, const int64_t *layer_offsets, const double
  * 4 = vectorised quantize of one whole bucket of 4096 or 8192 elements, 5 = the short end
  * of a layer (less than a chunk of 2048 elements) with power-of-two buckets.
  * Every element of every non-empty layer lies in exactly one tile and tiles never
- * cross layers (paper Sec. 4.1).  At most `capacity` records are written;
- * *n_tiles receives the full count.  Pure host computation.
+ * cross layers (paper Sec. 4.1).  This is the table of one chunk per vectorised
+ * tile that every call but one walks: cgx_quantize on a binary16 gradient of 2^24
+ * elements or more joins 2 or 4 consecutive chunks of a layer into one tile (same
+ * bytes out; a wave's set-up is spread over more input).  At most `capacity` records
+ * are written; *n_tiles receives the full count.  Pure host computation.
  */
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                    int32_t bucket, cgx_dtype dt, void *tiles_out /* host */, int64_t capacity,

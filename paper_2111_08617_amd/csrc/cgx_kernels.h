@@ -21,7 +21,7 @@ struct PeerPtrs {
 
 // Tunables (set once from the environment at first use; see cgx_api.cpp).
 struct LaunchConfig {
-    int chunks_per_tile = 1;   // fast-tile length in chunks of kChunk elements
+    int chunks_per_tile = 0;   // fast-tile length in chunks of kChunk elements; 0: chosen per call
     int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
 };
 

@@ -305,6 +305,19 @@ def test_gpt2_medium_config_full_size(torch, oracle):
     share_cycle(torch, oracle, w, rank=5, what="gpt2_medium")
 
 
+@pytest.mark.parametrize("bucket", [64, 128, 1024, 4096])
+def test_binary16_buffers_that_take_tiles_of_two_chunks(torch, oracle, bucket):
+    """cgx_quantize joins chunks into longer tiles on binary16 gradients of 2^24 elements or
+    more: layers of an odd number of chunks, with short ends, an odd start, a pass-through
+    layer and all widths in one buffer give the same bytes as the oracle; the reduce and the
+    fused step of the same plan (tiles of one chunk) agree too."""
+    shapes = [(2048 * 3001 + 77,), (1,), (2048 * 2000,), (999,), (2048 * 1501 + 1024,), (2048 * 1700 + 5,)]
+    bits = np.array([4, 0, 3, 0, 2, 8], np.uint8)
+    w = wl.Workload("f16long", shapes, bits, bucket, wl.F16, 2, 11, wl._normal, np.array([1.0, 1.0, 0.01, 1.0, 3.0, 1e-3]))
+    assert w.n >= 1 << 24
+    full_cycle(torch, oracle, w, W=2, what="f16long")
+
+
 def test_decoder_1p3b_config_full_size(torch, oracle):
     """292 tensors, 1.316G elements, Laplace values with outliers, bits in {2,4,8}, bucket 1024:
     quantize the full buffer (the launch bench.py times); reduce over W = 8 and requantize on
