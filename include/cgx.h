@@ -10,12 +10,13 @@
  *   layer_offsets[L] = n; empty layers are allowed and skipped) and
  *   bits_per_layer[0..L-1] (host, uint8: 0 = pass-through, 1..8 = quantize to
  *   that many bits).  `bucket` is the bucket size in elements: a multiple of 32
- *   in [32, 8192] (powers of two take the vectorised kernels paths; the others
+ *   in [32, 8192] (powers of two take the vectorised kernel paths; the others
  *   a generic, several times slower one).  Buckets restart at every layer's
  *   first element; a layer's last bucket may be short.  Layers may start at any
- *   element (only the buffers' base addresses must be aligned, see Memory).  (Paper Sec. 4.1: fused buffers keep the layer
- *   offsets, compression is per layer, small layers travel uncompressed;
- *   Sec. 4.3: buckets with per-bucket scaling meta-data.)
+ *   element (only the buffers' base addresses must be aligned, see Memory).
+ *   (Paper Sec. 4.1: fused buffers keep the layer offsets, compression is per
+ *   layer, small layers travel uncompressed; Sec. 4.3: buckets with per-bucket
+ *   scaling meta-data.)
  *
  *   Packed stream.  For each non-empty layer, in order, one segment padded with
  *   zero bytes to a multiple of 16 bytes:
@@ -31,9 +32,10 @@
  *   Pointers marked "host" are read during the call and may be reused on
  *   return.  The library keeps a small device-resident table per distinct plan
  *   (built on first use, which may synchronise; later calls with the same plan
- *   only queue kernels): at most 64 of them, the least recently used one being
- *   dropped (which waits for the device) when a 65th plan arrives; cgx_shutdown()
- *   frees them all.  No call synchronises the stream.  `stream` is a
+ *   only queue kernels; cgx_quantize on binary16 gradients of 2^24 elements or
+ *   more keeps a table of its own beside the one the other calls share): at
+ *   most 64 of them, the least recently used one being dropped (which waits for
+ *   the device) when a 65th arrives; cgx_shutdown() frees them all.  No call synchronises the stream.  `stream` is a
  *   hipStream_t passed as void* (NULL = the default stream).  Once a plan's
  *   table exists, the calls only queue kernels and can be captured in a graph.
  *
