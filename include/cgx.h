@@ -33,7 +33,8 @@
  *   return.  The library keeps a small device-resident table per distinct plan
  *   (built on first use, which may synchronise; later calls with the same plan
  *   only queue kernels; cgx_quantize on binary16 gradients of 2^24 elements or
- *   more keeps a table of its own beside the one the other calls share): at
+ *   more, and the fused call on 2^27 or more, keep tables of their own beside
+ *   the one the other calls share): at
  *   most 64 of them, the least recently used one being dropped (which waits for
  *   the device) when a 65th arrives; cgx_shutdown() frees them all.  No call synchronises the stream.  `stream` is a
  *   hipStream_t passed as void* (NULL = the default stream).  Once a plan's
@@ -278,9 +279,10 @@ int cgx_assign_bits_linear(int32_t L, const int64_t *layer_offsets, const double
  * of a layer (less than a chunk of 2048 elements) with power-of-two buckets.
  * Every element of every non-empty layer lies in exactly one tile and tiles never
  * cross layers (paper Sec. 4.1).  This is the table of one chunk per vectorised
- * tile that every call but one walks: cgx_quantize on a binary16 gradient of 2^24
- * elements or more joins 2 or 4 consecutive chunks of a layer into one tile (same
- * bytes out; a wave's set-up is spread over more input).  At most `capacity` records
+ * tile that most calls walk: cgx_quantize on a binary16 gradient of 2^24 elements
+ * or more, and the fused reduce + requantize on 2^27 elements or more, join 2 or 4
+ * consecutive chunks of a layer into one tile (same bytes out; a wave's set-up is
+ * spread over more input).  At most `capacity` records
  * are written; *n_tiles receives the full count.  Pure host computation.
  */
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,

@@ -85,16 +85,21 @@ const cgx::LaunchConfig &launch_config()
     return cfg;
 }
 
-// Chunks per vectorised tile.  One everywhere (a wave per chunk keeps the most loads in
-// flight), except where cgx_quantize reads binary16: a chunk is then only 4 KB of input and
-// the per-wave set-up shows, so on buffers that fill the chip several times over a wave
-// takes 2 chunks, 4 on large ones (measured: 12 % faster at 354 M elements).
-int tile_length(bool quantize_call, int dt, int64_t n)
+// Chunks per vectorised tile.  One keeps the most loads in flight and wins wherever a wave's
+// chunk is 8 KB of input.  Two cases differ on buffers that fill the chip many times over
+// (measured; shorter buffers lose to the coarser tail of the launch):
+//  - cgx_quantize on binary16: a chunk is only 4 KB of input and the per-wave set-up shows, so
+//    a wave takes 2 chunks, 4 on large buffers (12 % faster at 354 M elements);
+//  - the fused reduce + requantize, which is bound by arithmetic: 2 chunks (3-6 % faster at
+//    164-268 M elements for every width).
+enum CallKind { kQuantizeCall, kFusedCall, kOtherCall };
+int tile_length(CallKind call, int dt, int64_t n)
 {
     const int forced = launch_config().chunks_per_tile;
     if (forced > 0) return forced;
-    if (!quantize_call || dt != CGX_F16 || n < (int64_t(1) << 24)) return 1;
-    return n < (int64_t(1) << 27) ? 2 : 4;
+    if (call == kQuantizeCall && dt == CGX_F16 && n >= (int64_t(1) << 24)) return n < (int64_t(1) << 27) ? 2 : 4;
+    if (call == kFusedCall && n >= (int64_t(1) << 27)) return 2;
+    return 1;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -178,7 +183,7 @@ int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int6
     if (!grad || !packed || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
     if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
     PlanRef plan;
-    rc = get_plan(L, off, bits, bucket, dt, tile_length(true, dt, n), &plan);
+    rc = get_plan(L, off, bits, bucket, dt, tile_length(kQuantizeCall, dt, n), &plan);
     if (rc != CGX_OK) return rc;
     const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles, bucket,
                                               seed, packed, meta,
@@ -203,7 +208,7 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
     }
     if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
     PlanRef plan;
-    rc = get_plan(L, off, bits, bucket, dt, tile_length(false, dt, n), &plan);
+    rc = get_plan(L, off, bits, bucket, dt, tile_length(kOtherCall, dt, n), &plan);
     if (rc != CGX_OK) return rc;
     // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
     // a later launch starts from the binary32 result of the one before (W <= kPeersPerLaunch
@@ -242,9 +247,9 @@ int fused_impl(int scheme, const void *const *packed, const void *const *meta, i
     }
     if (misaligned(packed_out) || misaligned(meta_out)) return CGX_ERR_ALIGN;
     PlanRef in, out;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, dt, tile_length(false, dt, n), &in);
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, dt, tile_length(kFusedCall, dt, n), &in);
     if (rc != CGX_OK) return rc;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, tile_length(false, dt, n), &out);
+    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, tile_length(kFusedCall, dt, n), &out);
     if (rc != CGX_OK) return rc;
     if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
     cgx::PeerPtrs peers{};
@@ -273,7 +278,7 @@ int stats_tiles(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, i
     const int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
     if (rc != CGX_OK) return rc;
     std::vector<Tile> tiles;
-    cgx::build_tiles(L, off, bits, bucket, dt, tile_length(false, dt, n), tiles);
+    cgx::build_tiles(L, off, bits, bucket, dt, tile_length(kOtherCall, dt, n), tiles);
     *n_tiles = int64_t(tiles.size());
     return CGX_OK;
 }
@@ -291,7 +296,7 @@ int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *
         (reinterpret_cast<uintptr_t>(sqerr) & 7u))
         return CGX_ERR_ALIGN;
     PlanRef plan;
-    rc = get_plan(L, off, bits, bucket, dt, tile_length(false, dt, n), &plan);
+    rc = get_plan(L, off, bits, bucket, dt, tile_length(kOtherCall, dt, n), &plan);
     if (rc != CGX_OK) return rc;
     if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
     const hipError_t e = cgx::launch_layer_sqerrors(scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots,
@@ -424,7 +429,7 @@ int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *laye
     if (!sqnorm || (n > 0 && (!buf || !workspace))) return CGX_ERR_NULL;
     if (misaligned(buf) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(sqnorm) & 7u)) return CGX_ERR_ALIGN;
     PlanRef plan;
-    rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), tile_length(false, int(dt), n), &plan);
+    rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), tile_length(kOtherCall, int(dt), n), &plan);
     if (rc != CGX_OK) return rc;
     if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
     const hipError_t e = cgx::launch_layer_sqnorms(buf, int(dt), plan->d_tiles, plan->d_slots, plan->n_tiles,
@@ -456,7 +461,7 @@ int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uin
     if (rc != CGX_OK) return rc;
     if (!n_tiles || (capacity > 0 && !tiles_out)) return CGX_ERR_NULL;
     std::vector<Tile> tiles;
-    cgx::build_tiles(L, layer_offsets, bits_per_layer, bucket, int(dt), tile_length(false, int(dt), n), tiles);
+    cgx::build_tiles(L, layer_offsets, bits_per_layer, bucket, int(dt), tile_length(kOtherCall, int(dt), n), tiles);
     *n_tiles = int64_t(tiles.size());
     const int64_t k = capacity < *n_tiles ? capacity : *n_tiles;
     if (k > 0) std::memcpy(tiles_out, tiles.data(), size_t(k) * sizeof(Tile));

@@ -407,7 +407,8 @@ def test_non_finite_inputs_do_not_disturb_other_buckets(torch, oracle):
 
 
 def test_result_does_not_depend_on_launch_geometry(torch, oracle):
-    """Counter-based draws: tiles of several chunks and a small persistent grid give the same bytes."""
+    """Counter-based draws: tiles of several chunks and a small persistent grid give the same bytes
+    (quantize, reduce and the fused reduce + requantize)."""
     import hashlib
     import os
     import subprocess
@@ -422,7 +423,9 @@ def test_result_does_not_depend_on_launch_geometry(torch, oracle):
         "p = torch.zeros(pb, dtype=torch.uint8, device='cuda'); m = torch.zeros(mb // 4, device='cuda')\n"
         "cgx.cgx_quantize(torch.from_numpy(w.gradient()).cuda(), plan, 77, p, m); torch.cuda.synchronize()\n"
         "s = torch.zeros(w.n, device='cuda'); cgx.cgx_dequant_reduce([p, p], [m, m], plan, s); torch.cuda.synchronize()\n"
-        "print(hashlib.sha256(p.cpu().numpy().tobytes() + m.cpu().numpy().tobytes() + s.cpu().numpy().tobytes()).hexdigest())\n"
+        "fp = torch.zeros(pb, dtype=torch.uint8, device='cuda'); fm = torch.zeros(mb // 4, device='cuda')\n"
+        "cgx.cgx_dequant_reduce_requantize([p, p], [m, m], plan, 78, fp, fm); torch.cuda.synchronize()\n"
+        "print(hashlib.sha256(b''.join(t.cpu().numpy().tobytes() for t in (p, m, s, fp, fm))).hexdigest())\n"
     ) % root
     digests = set()
     for env in ({}, {"CGX_CHUNKS_PER_TILE": "3"}, {"CGX_CHUNKS_PER_TILE": "8", "CGX_MAX_BLOCKS": "5"}):
