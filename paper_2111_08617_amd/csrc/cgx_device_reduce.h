@@ -10,11 +10,56 @@ namespace {
 
 // ---------------------------------------------------------------- dequantize + reduce
 
-// Levels of one group of 8 codes as floats (kNormSign: signed levels).
+// Keeps a value opaque to the optimiser at no cost.  The byte-wise decoders below put one code
+// into every byte of a register and convert the bytes with v_cvt_f32_ubyte0..3; seeing through
+// the mask, the compiler would instead extract every code with a v_bfe_u32 of its own and
+// convert byte 0 (two instructions of the slow issue class per code instead of one).
+__device__ __forceinline__ uint32_t opaque(uint32_t v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+
+// The four bytes of t as floats.
+__device__ __forceinline__ void bytes_to_float(uint32_t t, float &b0, float &b1, float &b2, float &b3)
+{
+    b0 = float(t & 0xffu);
+    b1 = float((t >> 8) & 0xffu);
+    b2 = float((t >> 16) & 0xffu);
+    b3 = float(t >> 24);
+}
+
+// Levels of one group of 8 codes as floats (kNormSign: signed levels).  Of the signed widths
+// only 4 bits takes the byte-wise form: with 2 and 8 bits as well the reduce kernel needs 129
+// to 131 registers, one wave per SIMD less.
 template <int SCHEME, int BITS>
 __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
 {
-    if (SCHEME == kNormSign) {
+    constexpr bool kSigned = SCHEME == kNormSign;
+    if (BITS == 8 && !kSigned) {
+        bytes_to_float(uint32_t(v), f[0], f[1], f[2], f[3]);
+        bytes_to_float(uint32_t(v >> 32), f[4], f[5], f[6], f[7]);
+    } else if (BITS == 4) {
+        // one code per byte: even codes in one register, odd ones in another.  kSigned: a code is
+        // a two's complement nibble; with its sign bit flipped it reads level + 8 in 1..15
+        constexpr uint32_t kFlip = kSigned ? 0x88888888u : 0u;
+        const uint32_t w = uint32_t(v) ^ kFlip;
+        const uint32_t even = opaque(w & 0x0f0f0f0fu), odd = opaque((w >> 4) & 0x0f0f0f0fu);
+        bytes_to_float(even, f[0], f[2], f[4], f[6]);
+        bytes_to_float(odd, f[1], f[3], f[5], f[7]);
+        if (kSigned) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) f[j] -= 8.0f;
+        }
+    } else if (BITS == 2 && !kSigned) {
+        const uint32_t w = uint32_t(v);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t t = opaque((w >> (2 * j)) & 0x0303u);     // codes j and j + 4, one per byte
+            f[j] = float(t & 0xffu);
+            f[4 + j] = float((t >> 8) & 0xffu);
+        }
+    } else if (kSigned) {
         if (BITS == 8) {
             const uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
 #pragma unroll
@@ -26,29 +71,6 @@ __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
 #pragma unroll
             for (int j = 0; j < 8; j++)      // sign-extending field extract
                 f[j] = float(int32_t(uint32_t(v >> (j * BITS)) << (32 - BITS)) >> (32 - BITS));
-        }
-    } else if (BITS == 8) {
-        const uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            f[j] = float((lo >> (8 * j)) & 0xffu);
-            f[4 + j] = float((hi >> (8 * j)) & 0xffu);
-        }
-    } else if (BITS == 4) {
-        const uint32_t w = uint32_t(v);
-        const uint32_t even = w & 0x0f0f0f0fu, odd = (w >> 4) & 0x0f0f0f0fu;   // one code per byte
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            f[2 * j] = float((even >> (8 * j)) & 0xffu);
-            f[2 * j + 1] = float((odd >> (8 * j)) & 0xffu);
-        }
-    } else if (BITS == 2) {
-        const uint32_t w = uint32_t(v);
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const uint32_t t = (w >> (2 * j)) & 0x0303u;     // codes j and j + 4, one per byte
-            f[j] = float(t & 0xffu);
-            f[4 + j] = float((t >> 8) & 0xffu);
         }
     } else {
         constexpr uint64_t kMask = (1u << BITS) - 1u;
