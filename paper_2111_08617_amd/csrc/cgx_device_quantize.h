@@ -361,7 +361,7 @@ __device__ __forceinline__ void quantize_generic(Value value, uint8_t *__restric
 
 // Pass-through tile of the quantize kernel: verbatim copy, then the layer's zero padding.
 template <int DT>
-__device__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ packed, const Tile &tile,
+__device__ __forceinline__ void copy_tile(const void *__restrict__ grad, uint8_t *__restrict__ packed, const Tile &tile,
                           bool fast, int lane)
 {
     constexpr int S = DT == CGX_F16 ? 2 : 4;

@@ -331,7 +331,7 @@ __device__ __forceinline__ float generic_sum(Peers &peers, int W, const Tile &ti
 
 // Any bucket size, any alignment, ragged tiles: one element per lane and pass.
 template <int SCHEME, typename Peers>
-__device__ void reduce_slow(Peers &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
+__device__ __forceinline__ void reduce_slow(Peers &peers, int W, const SumIo &io, const Tile &tile, int bucket, int lane)
 {
     for (uint32_t j = lane; j < tile.count; j += kWave)
         store1(io, tile.elem0 + j, generic_sum<SCHEME>(peers, W, tile, bucket, j, init1(io, tile.elem0 + j)));
@@ -376,7 +376,7 @@ __device__ __forceinline__ float copy_sum1(Peers &peers, int W, const Tile &tile
 // Pass-through tile of the reduce kernels: plain ordered sum of the stored values; element j
 // of the tile starts from / goes to position e0 + j of io.
 template <int DT, typename Peers>
-__device__ void reduce_copy(Peers &peers, int W, const SumIo &io, int64_t e0, const Tile &tile, bool fast,
+__device__ __forceinline__ void reduce_copy(Peers &peers, int W, const SumIo &io, int64_t e0, const Tile &tile, bool fast,
                             int lane)
 {
     const uint32_t groups = fast ? tile.count / 8 : 0;

@@ -20,10 +20,15 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_arg
     // per-wave staging area: a chunk of binary32 results, or the packed bytes of a block of peers
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-    const int lane = int(threadIdx.x) & 63;
+    int lane_of_wave = int(threadIdx.x) & 63;
     uint4v *stage = stage_all[wave];
     const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
     for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+        // the lane index is made opaque once per tile: otherwise everything that depends on the
+        // lane alone (offsets, masks, of every bit width's path) is hoisted out of this loop and
+        // stays in registers across all of it
+        asm volatile("" : "+v"(lane_of_wave));
+        const int lane = lane_of_wave;
         const Tile tile = tiles[t];
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {      // a wide tile is chunks of one bucket: kChunk / bucket == 0 below
