@@ -4,10 +4,11 @@
 namespace cgx {
 namespace {
 
-// TAILS: the short ends of layers take the masked chunk path.  That path costs the kernel one
-// register too many for its occupancy (and fencing it in by attribute cost 9 % on one of the
-// benchmark plans), so the host asks for it only where short ends are a real share of the work;
-// elsewhere the few there are go through the generic path, overlapped with everything else.
+// TAILS: the short ends of layers take the masked chunk path.  The kernel with that path is
+// about 1 % slower on plans that hardly use it (and, when it was added, needed one register
+// more than the kernel's occupancy allows), and up to 6 % faster where a few dozen layers end
+// inside a few thousand tiles, so the host asks for it where short ends are at least 1/512 of
+// the tiles; elsewhere the few there are go through the generic path, overlapped with the rest.
 template <int SCHEME, bool TAILS>
 __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_argument, int W, int dt, const SumIo io,
                                                          const Tile *__restrict__ tiles, int64_t n_tiles,
