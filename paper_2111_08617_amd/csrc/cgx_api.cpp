@@ -27,7 +27,7 @@ struct CachedPlan {
     cgx::PlanShape shape;
     int64_t n_tiles = 0;
     bool odd_tiles = false;     // some vectorised quantized tile starts on an odd element index
-    bool many_tails = false;    // short ends of layers are at least 1/512 of the tiles, and at least 16
+    bool many_tails = false;    // the reduce kernel with the masked path for short ends of layers pays (see get_plan)
     Tile *d_tiles = nullptr;
     // per-layer numbering of the tiles (for the statistics): slot of every tile, first slot of every layer
     uint32_t *d_slots = nullptr;
@@ -143,7 +143,9 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
             plan->odd_tiles = true;
     int64_t tails = 0;
     for (const Tile &t : tiles) tails += cgx::tile_kind(t) == cgx::kQuantTail;
-    plan->many_tails = tails >= 16 && tails * 512 >= plan->n_tiles;
+    // One short end that goes through the generic path takes tens of microseconds (dependent
+    // round trips, bucket by bucket): hidden in a long launch, most of a short one.
+    plan->many_tails = tails > 0 && (plan->n_tiles < 16384 || tails * 512 >= plan->n_tiles);
     if (!upload(&plan->d_tiles, tiles) || !upload(&plan->d_slots, slots) ||
         !upload(&plan->d_layer_first, layer_first)) {
         free_plan(*plan);
