@@ -143,8 +143,8 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
             plan->odd_tiles = true;
     int64_t tails = 0;
     for (const Tile &t : tiles) tails += cgx::tile_kind(t) == cgx::kQuantTail;
-    // One short end that goes through the generic path takes tens of microseconds (dependent
-    // round trips, bucket by bucket): hidden in a long launch, most of a short one.
+    // One short end that goes through the generic path is a chain of dependent round trips,
+    // bucket after bucket: hidden in a long launch, it outlasts the rest of a short one.
     plan->many_tails = tails > 0 && (plan->n_tiles < 16384 || tails * 512 >= plan->n_tiles);
     if (!upload(&plan->d_tiles, tiles) || !upload(&plan->d_slots, slots) ||
         !upload(&plan->d_layer_first, layer_first)) {

@@ -7,8 +7,8 @@ namespace {
 // TAILS: the short ends of layers take the masked chunk path.  The kernel with that path is
 // about 1 % slower on plans that hardly use it (and, when it was added, needed one register
 // more than the kernel's occupancy allows).  Without it a short end goes through the generic
-// path, which takes tens of microseconds for one tile: hidden behind the rest of a long launch,
-// but most of a short one (6 % of a 25 us launch with a single short end).  The host asks for
+// path, a chain of dependent round trips for one tile: hidden behind the rest of a long launch,
+// it outlasts a short one (6 % of a 25 us launch with a single short end).  The host asks for
 // it when there is a short end and the plan has fewer than 16384 tiles, or when short ends are
 // at least 1/512 of the tiles.
 template <int SCHEME, bool TAILS>
