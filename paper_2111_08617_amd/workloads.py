@@ -159,6 +159,34 @@ class Workload:
         return out
 
 
+def random_plan(seed: int) -> Workload:
+    """A seeded random plan: layer lengths from nothing to a few chunks (whole chunks, whole
+    buckets, odd lengths, empty layers), any width per layer, any bucket size, either
+    storage type, 1 to 9 peers, per-tensor scales over five decades."""
+    rng = np.random.default_rng(1000 + seed)
+    bucket = int(rng.choice([32, 64, 96, 128, 256, 512, 1024, 2048, 4096, 8192]))
+    L = int(rng.integers(1, 14))
+    sizes = []
+    for _ in range(L):
+        kind = rng.integers(0, 6)
+        if kind == 0:
+            sizes.append(int(rng.integers(0, 40)))
+        elif kind == 1:
+            sizes.append(2048 * int(rng.integers(1, 7)))
+        elif kind == 2:
+            sizes.append(bucket * int(rng.integers(1, 9)))
+        elif kind == 3:
+            sizes.append(2048 * int(rng.integers(1, 5)) + int(rng.integers(1, 2048)))
+        else:
+            sizes.append(int(rng.integers(1, 30000)))
+    bits = rng.integers(0, 9, L).astype(np.uint8)
+    dt = F16 if rng.integers(0, 2) else F32
+    scales = 10.0 ** rng.uniform(-4, 1, L)
+    draw = [_normal, _student_t3, _sparse_normal, _laplace_outliers][int(rng.integers(0, 4))]
+    return Workload(f"random{seed}", [(int(t),) for t in sizes], bits, bucket, dt, int(rng.integers(1, 10)), seed, draw,
+                    scales)
+
+
 def _log_uniform_scales(seed: int, L: int, lo: float, hi: float) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0x5ca1e5])))
     return np.exp(rng.uniform(np.log(lo), np.log(hi), L))

@@ -96,6 +96,22 @@ def test_sqerrors_on_edge_case_plans(torch, oracle, bucket, dt, qsgd):
     assert_close(gpu_sqerrors(torch, g, p, m, w.offsets, w.bits, bucket, dt, qsgd), ref, f"tiny_mixed B={bucket}")
 
 
+@pytest.mark.parametrize("seed", range(0, 24, 2))
+def test_statistics_of_random_plans(torch, oracle, seed):
+    """Seeded random plans: squared norms, and squared errors of both quantizers."""
+    w = wl.random_plan(seed)
+    if w.n == 0:
+        pytest.skip("empty plan (covered by the edge cases)")
+    g = w.gradient()
+    assert_close(gpu_sqnorms(torch, g, w.offsets, w.dt), oracle.layer_sqnorms(g, w.offsets, w.dt), f"random plan {seed}")
+    for qsgd in (False, True):
+        bits = np.where(w.bits == 1, 2, w.bits).astype(np.uint8) if qsgd else w.bits
+        p, m = (oracle.qsgd_quantize if qsgd else oracle.quantize)(g, w.offsets, bits, w.bucket, 5, w.dt)
+        ref = oracle.layer_sqerrors(g, p, m, w.offsets, bits, w.bucket, w.dt, scheme=int(qsgd))
+        assert_close(gpu_sqerrors(torch, g, p, m, w.offsets, bits, w.bucket, w.dt, qsgd), ref,
+                     f"random plan {seed} (bucket {w.bucket}, bits {bits.tolist()}, {'norm-sign' if qsgd else 'min/max'})")
+
+
 @pytest.mark.parametrize("qsgd", [False, True], ids=["minmax", "normsign"])
 @pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
 @pytest.mark.parametrize("bucket", [64, 512, 2048, 4096])

@@ -318,6 +318,15 @@ def test_binary16_buffers_that_take_tiles_of_two_chunks(torch, oracle, bucket):
     full_cycle(torch, oracle, w, W=2, what="f16long")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_plans(torch, oracle, seed):
+    """Seeded random plans through the whole cycle (quantize, reduce, requantize, fused)."""
+    w = wl.random_plan(seed)
+    if w.n == 0:
+        pytest.skip("empty plan (covered by the edge cases)")
+    full_cycle(torch, oracle, w, W=w.W, what=f"random plan {seed} (bucket {w.bucket}, bits {w.bits.tolist()})")
+
+
 def test_decoder_1p3b_config_full_size(torch, oracle):
     """292 tensors, 1.316G elements, Laplace values with outliers, bits in {2,4,8}, bucket 1024:
     quantize the full buffer (the launch bench.py times); reduce over W = 8 and requantize on

@@ -111,6 +111,15 @@ def full_cycle(torch, oracle, w, W, what=""):
         assert_same_chunk(fp, fm, op, om, f"{what} fused reduce+requantize")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_plans(torch, oracle, seed):
+    """Seeded random plans (1-bit layers widened to 2 bits) through the whole cycle."""
+    w = no_one_bit(wl.random_plan(seed))
+    if w.n == 0:
+        pytest.skip("empty plan (covered by the edge cases)")
+    full_cycle(torch, oracle, w, W=w.W, what=f"random plan {seed} (bucket {w.bucket}, bits {w.bits.tolist()})")
+
+
 @pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
 @pytest.mark.parametrize("bucket", [32, 96, 128, 512, 4096, 8192])
 def test_edge_case_plan(torch, oracle, bucket, dt):
