@@ -113,7 +113,7 @@ def main():
     alg = {"quantize": q_alg, "dequant_reduce": r_algs["dequant_reduce"], "requantize": r_algs["requantize"]}
 
     traffic = q_alg + alg["dequant_reduce"] + alg["requantize"]
-    R = args.rotate if args.rotate > 0 else max(2, min(8, int(np.ceil(1.0e9 / traffic))))
+    R = args.rotate if args.rotate > 0 else max(2, min(8, int(np.ceil(2.5e9 / traffic))))
 
     # ---- inputs, resident in HBM before timing
     t0 = time.time()
