@@ -66,6 +66,11 @@ def _load():
         lib.oracle_layer_sqerrors.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p] + plan + \
             [c.c_int32, c.c_void_p]
         lib.oracle_unpack_codes.argtypes = [c.c_void_p] + plan + [c.c_int32, c.c_void_p]
+        layered = [c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_layered_sizes.argtypes = layered + [c.c_int32, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64)]
+        lib.oracle_layered_quantize.argtypes = [c.c_void_p] + layered + [c.c_uint64, c.c_int32, c.c_void_p, c.c_void_p]
+        lib.oracle_layered_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
+            [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         _lib = lib
     return _lib
 
@@ -205,6 +210,60 @@ def unpack_codes(packed, offsets, bits, bucket: int, dt: int = F32):
     codes = np.zeros(n, dtype=np.uint8)
     _check(_load().oracle_unpack_codes(_ptr(p), n, L, _ptr(off), _ptr(bt), bucket, dt, _ptr(codes)), "unpack_codes")
     return codes
+
+
+# ---- a bucket size per layer
+
+def _layer_buckets(buckets, L):
+    bk = np.ascontiguousarray(buckets, dtype=np.int32)
+    if bk.ndim != 1 or bk.size != L:
+        raise ValueError("one bucket size per layer")
+    return bk
+
+
+def layered_sizes(offsets, bits, buckets, dt: int = F32):
+    """(packed_bytes, meta_bytes) of a plan whose layer l has bucket size buckets[l]."""
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    pb, mb = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(_load().oracle_layered_sizes(n, L, _ptr(off), _ptr(bt), _ptr(bk), dt, ctypes.byref(pb), ctypes.byref(mb)),
+           "layered_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def layered_quantize(grad, offsets, bits, buckets, seed: int, dt: int = F32):
+    """quantize() with a bucket size per layer."""
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    g = _grad(grad, n, dt)
+    pb, mb = layered_sizes(off, bt, bk, dt)
+    packed = np.zeros(pb, dtype=np.uint8)
+    meta = np.zeros((mb // 8, 2), dtype=np.float32)
+    _check(_load().oracle_layered_quantize(_ptr(g), n, L, _ptr(off), _ptr(bt), _ptr(bk), seed & (2**64 - 1), dt,
+                                           _ptr(packed), _ptr(meta)), "layered_quantize")
+    return packed, meta
+
+
+def layered_dequant_reduce(packed_list, meta_list, offsets, bits, buckets, dt: int = F32):
+    """dequant_reduce() with a bucket size per layer; returns sum32, sum64 and abs64."""
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    W = len(packed_list)
+    if W < 1 or len(meta_list) != W:
+        raise ValueError("need W >= 1 packed chunks and as many meta arrays")
+    pb, mb = layered_sizes(off, bt, bk, dt)
+    pk = [np.ascontiguousarray(p, dtype=np.uint8) for p in packed_list]
+    mt = [np.ascontiguousarray(m, dtype=np.float32) for m in meta_list]
+    for p, m in zip(pk, mt):
+        if p.size != pb or m.size * 4 != mb:
+            raise ValueError("chunk sizes do not match the plan")
+    pp = (ctypes.c_void_p * W)(*[p.ctypes.data for p in pk])
+    mp = (ctypes.c_void_p * W)(*[m.ctypes.data for m in mt])
+    out = {"sum32": np.zeros(n, dtype=np.float32), "sum64": np.zeros(n, dtype=np.float64),
+           "abs64": np.zeros(n, dtype=np.float64)}
+    _check(_load().oracle_layered_dequant_reduce(pp, mp, W, n, L, _ptr(off), _ptr(bt), _ptr(bk), dt, _ptr(out["sum32"]),
+                                                 _ptr(out["sum64"]), _ptr(out["abs64"])), "layered_dequant_reduce")
+    return out
 
 
 # ---- the norm-and-sign form (see the second half of cgx_oracle.c)

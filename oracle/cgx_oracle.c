@@ -168,6 +168,23 @@ static int check_plan(int64_t n, int32_t L, const int64_t *off, const uint8_t *b
     return ORACLE_OK;
 }
 
+/*
+ * A bucket size per layer (CGX paper Sec. 4.1: compression parameters, the bucket size among
+ * them, are per layer; the adaptive scheme maps bit-widths and bucket sizes to layers):
+ * layer_buckets == NULL means `bucket` for every layer.
+ */
+static int check_layer_buckets(int32_t L, const int32_t *layer_buckets)
+{
+    if (!layer_buckets) return ORACLE_OK;
+    for (int32_t l = 0; l < L; l++)
+        if (layer_buckets[l] < 32 || layer_buckets[l] > 8192 || layer_buckets[l] % 32) return ORACLE_ERR_ARG;
+    return ORACLE_OK;
+}
+static int32_t bucket_of(int32_t l, int32_t bucket, const int32_t *layer_buckets)
+{
+    return layer_buckets ? layer_buckets[l] : bucket;
+}
+
 /* Bytes of layer l's segment in the packed stream and its bucket count. */
 static void layer_extent(int64_t len, int b, int32_t bucket, int dt,
                          uint64_t *seg_bytes, uint64_t *n_buckets)
@@ -182,21 +199,36 @@ static void layer_extent(int64_t len, int b, int32_t bucket, int dt,
     }
 }
 
-int oracle_sizes(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
-                 int32_t bucket, int32_t dt, uint64_t *packed_bytes, uint64_t *meta_bytes)
+static int sizes_impl(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
+                      const int32_t *layer_buckets, int32_t dt, uint64_t *packed_bytes, uint64_t *meta_bytes)
 {
-    int rc = check_plan(n, L, off, bits, bucket, dt);
+    int rc = check_plan(n, L, off, bits, layer_buckets ? 32 : bucket, dt);
+    if (rc) return rc;
+    rc = check_layer_buckets(L, layer_buckets);
     if (rc) return rc;
     uint64_t pb = 0, nb = 0;
     for (int32_t l = 0; l < L; l++) {
         uint64_t s, k;
-        layer_extent(off[l + 1] - off[l], bits[l], bucket, dt, &s, &k);
+        layer_extent(off[l + 1] - off[l], bits[l], bucket_of(l, bucket, layer_buckets), dt, &s, &k);
         pb += s;
         nb += k;
     }
     if (packed_bytes) *packed_bytes = pb;
     if (meta_bytes) *meta_bytes = 8 * nb;
     return ORACLE_OK;
+}
+
+int oracle_sizes(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                 int32_t bucket, int32_t dt, uint64_t *packed_bytes, uint64_t *meta_bytes)
+{
+    return sizes_impl(n, L, off, bits, bucket, NULL, dt, packed_bytes, meta_bytes);
+}
+
+int oracle_layered_sizes(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                         const int32_t *layer_buckets, int32_t dt, uint64_t *packed_bytes, uint64_t *meta_bytes)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return sizes_impl(n, L, off, bits, 32, layer_buckets, dt, packed_bytes, meta_bytes);
 }
 
 /* ---- quantize ------------------------------------------------------------ */
@@ -263,15 +295,19 @@ static uint32_t get_bits(const uint8_t *stream, uint64_t bitpos, int b)
  * tests use that to enumerate the rounding rule exhaustively.
  */
 static int quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off,
-                         const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
+                         const uint8_t *bits, int32_t uniform_bucket, const int32_t *layer_buckets,
+                         uint64_t seed, int32_t dt,
                          const uint16_t *draws, uint64_t index_base, uint8_t *packed, float *meta)
 {
-    int rc = check_plan(n, L, off, bits, bucket, dt);
+    int rc = check_plan(n, L, off, bits, layer_buckets ? 32 : uniform_bucket, dt);
+    if (rc) return rc;
+    rc = check_layer_buckets(L, layer_buckets);
     if (rc) return rc;
     uint64_t seg_start = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         int64_t first = off[l], len = off[l + 1] - off[l];
         int b = bits[l];
+        const int32_t bucket = bucket_of(l, uniform_bucket, layer_buckets);
         uint64_t seg_bytes, n_buckets;
         layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
         if (len == 0) continue;
@@ -308,7 +344,7 @@ int oracle_quantize(const void *grad, int64_t n, int32_t L, const int64_t *off,
                     const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
                     uint8_t *packed, float *meta)
 {
-    return quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, 0, packed, meta);
+    return quantize_impl(grad, n, L, off, bits, bucket, NULL, seed, dt, NULL, 0, packed, meta);
 }
 
 /*
@@ -321,7 +357,16 @@ int oracle_quantize_window(const void *grad, int64_t n, int32_t L, const int64_t
                            const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
                            uint64_t index_base, uint8_t *packed, float *meta)
 {
-    return quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, index_base, packed, meta);
+    return quantize_impl(grad, n, L, off, bits, bucket, NULL, seed, dt, NULL, index_base, packed, meta);
+}
+
+/* Every layer with its own bucket size (see check_layer_buckets). */
+int oracle_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *off,
+                            const uint8_t *bits, const int32_t *layer_buckets, uint64_t seed, int32_t dt,
+                            uint8_t *packed, float *meta)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return quantize_impl(grad, n, L, off, bits, 32, layer_buckets, seed, dt, NULL, 0, packed, meta);
 }
 
 int oracle_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int64_t *off,
@@ -329,7 +374,7 @@ int oracle_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int
                                const uint16_t *draws, uint8_t *packed, float *meta)
 {
     if (!draws) return ORACLE_ERR_ARG;
-    return quantize_impl(grad, n, L, off, bits, bucket, 0, dt, draws, 0, packed, meta);
+    return quantize_impl(grad, n, L, off, bits, bucket, NULL, 0, dt, draws, 0, packed, meta);
 }
 
 /* ---- dequantize and reduce ---------------------------------------------- */
@@ -344,12 +389,14 @@ int oracle_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int
  *   abs64[i]: binary64 sum of the absolute values of the terms, the scale of the tolerance.
  * Any of the three outputs may be NULL.
  */
-int oracle_dequant_reduce_add(const void *local, int32_t local_dt, const uint8_t *const *packed,
-                              const float *const *meta, int32_t W, int64_t n, int32_t L, const int64_t *off,
-                              const uint8_t *bits, int32_t bucket, int32_t dt, float *sum32, double *sum64,
-                              double *abs64)
+static int reduce_impl(const void *local, int32_t local_dt, const uint8_t *const *packed,
+                       const float *const *meta, int32_t W, int64_t n, int32_t L, const int64_t *off,
+                       const uint8_t *bits, int32_t uniform_bucket, const int32_t *layer_buckets, int32_t dt,
+                       float *sum32, double *sum64, double *abs64)
 {
-    int rc = check_plan(n, L, off, bits, bucket, dt);
+    int rc = check_plan(n, L, off, bits, layer_buckets ? 32 : uniform_bucket, dt);
+    if (rc) return rc;
+    rc = check_layer_buckets(L, layer_buckets);
     if (rc) return rc;
     if (W < 1 || !packed || !meta) return ORACLE_ERR_ARG;
     if (local && local_dt != DT_F32 && local_dt != DT_F16) return ORACLE_ERR_ARG;
@@ -357,6 +404,7 @@ int oracle_dequant_reduce_add(const void *local, int32_t local_dt, const uint8_t
     for (int32_t l = 0; l < L; l++) {
         int64_t first = off[l], len = off[l + 1] - off[l];
         int b = bits[l];
+        const int32_t bucket = bucket_of(l, uniform_bucket, layer_buckets);
         uint64_t seg_bytes, n_buckets;
         layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
         if (len == 0) continue;
@@ -398,6 +446,23 @@ int oracle_dequant_reduce_add(const void *local, int32_t local_dt, const uint8_t
         bucket0 += n_buckets;
     }
     return ORACLE_OK;
+}
+
+int oracle_dequant_reduce_add(const void *local, int32_t local_dt, const uint8_t *const *packed,
+                              const float *const *meta, int32_t W, int64_t n, int32_t L, const int64_t *off,
+                              const uint8_t *bits, int32_t bucket, int32_t dt, float *sum32, double *sum64,
+                              double *abs64)
+{
+    return reduce_impl(local, local_dt, packed, meta, W, n, L, off, bits, bucket, NULL, dt, sum32, sum64, abs64);
+}
+
+int oracle_layered_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W,
+                                  int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                                  const int32_t *layer_buckets, int32_t dt, float *sum32, double *sum64,
+                                  double *abs64)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return reduce_impl(NULL, DT_F32, packed, meta, W, n, L, off, bits, 32, layer_buckets, dt, sum32, sum64, abs64);
 }
 
 int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W,
