@@ -167,6 +167,36 @@ int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *
                                   uint64_t seed, void *packed_out, void *meta_out, void *stream);
 
 /*
+ * The same calls with a bucket size per layer (paper Sec. 4.1: compression parameters are
+ * per layer, the bucket size among them; Sec. "Layer-wise Adaptive Quantization": bit-widths
+ * and bucket sizes are mapped to the layers).  buckets_per_layer[0..L-1] (host, int32) gives
+ * every layer its own bucket size, each a multiple of 32 in [32, 8192] (CGX_ERR_BUCKET
+ * otherwise; the entries of pass-through and empty layers are checked but not used).
+ * Layout, meta numbering (buckets in layer order), draws, sums and errors are those of the
+ * calls above; with all entries equal the results are byte for byte those of the call with
+ * that one size.  The kernels take one bucket size per launch, so a call queues one launch
+ * per distinct size among the quantized layers (each over those layers' tiles only) and keeps
+ * one device table per size.
+ */
+int cgx_layered_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                      const int32_t *buckets_per_layer /* host [L] */, cgx_dtype dt, size_t *packed_bytes,
+                      size_t *meta_bytes);
+int cgx_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                         const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
+                         cgx_dtype dt, void *packed, void *meta, void *stream);
+int cgx_layered_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                               int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                               const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream);
+int cgx_layered_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
+                           const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
+                           void *packed, void *meta, void *stream);
+int cgx_layered_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W,
+                                          int64_t n, int32_t L, const int64_t *layer_offsets,
+                                          const uint8_t *bits_per_layer, const int32_t *buckets_per_layer,
+                                          cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
+                                          void *stream);
+
+/*
  * The norm-and-sign form of the quantizer, Q_s as printed in paper Sec. 2.2
  * (Q_s(v_i) = ||v|| sign(v_i) q(|v_i| / ||v||, s)), applied per bucket (Sec. 4.3)
  * with per-layer widths (Sec. 4.1).  Same plan, layout of the packed stream,

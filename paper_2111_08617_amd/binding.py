@@ -25,7 +25,8 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_dequant_reduce_requantize", "cgx_qsgd_sizes", "cgx_qsgd_quantize", "cgx_qsgd_dequant_reduce",
            "cgx_qsgd_dequant_reduce_requantize", "cgx_layer_stats_workspace", "cgx_layer_sqnorms",
            "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
-           "cgx_plan_tiles", "cgx_stream_probe",
+           "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
+           "cgx_layered_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -59,6 +60,15 @@ def lib() -> ctypes.CDLL:
             [c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_dequantize.argtypes = [c.c_void_p, c.c_void_p] + plan + [c.c_int, c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + plan + \
+            [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        layered = [c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_layered_sizes.argtypes = layered + [c.c_int, c.POINTER(c.c_size_t), c.POINTER(c.c_size_t)]
+        L.cgx_layered_quantize.argtypes = [c.c_void_p] + layered + [c.c_uint64, c.c_int, c.c_void_p, c.c_void_p,
+                                                                     c.c_void_p]
+        L.cgx_layered_requantize.argtypes = [c.c_void_p] + layered + [c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_layered_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
+            [c.c_int, c.c_void_p, c.c_void_p]
+        L.cgx_layered_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
             [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
         L.cgx_qsgd_sizes.argtypes = L.cgx_sizes.argtypes
         L.cgx_qsgd_quantize.argtypes = L.cgx_quantize.argtypes
@@ -106,6 +116,24 @@ class Plan:
     @property
     def args(self):
         return (self.n, self.L, self.offsets.ctypes.data, self.bits.ctypes.data, self.bucket)
+
+
+class LayeredPlan:
+    """A plan with a bucket size per layer (the cgx_layered_* calls)."""
+
+    def __init__(self, layer_offsets, bits_per_layer, buckets_per_layer, dt: int = F32):
+        self.offsets = np.ascontiguousarray(layer_offsets, dtype=np.int64)
+        self.bits = np.ascontiguousarray(bits_per_layer, dtype=np.uint8)
+        self.buckets = np.ascontiguousarray(buckets_per_layer, dtype=np.int32)
+        if self.offsets.ndim != 1 or self.offsets.size != self.bits.size + 1 or self.buckets.shape != self.bits.shape:
+            raise ValueError("one bits and one bucket entry per layer, one more layer offset")
+        self.dt = int(dt)
+        self.n = int(self.offsets[-1])
+        self.L = int(self.bits.size)
+
+    @property
+    def args(self):
+        return (self.n, self.L, self.offsets.ctypes.data, self.bits.ctypes.data, self.buckets.ctypes.data)
 
 
 def _check(status: int, where: str) -> None:
@@ -199,6 +227,41 @@ def _peer_arrays(packed: Sequence, meta: Sequence):
     pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
     mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
     return W, pp, mp
+
+
+def cgx_layered_sizes(plan: LayeredPlan) -> Tuple[int, int]:
+    """(packed_bytes, meta_bytes) of a plan with a bucket size per layer."""
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().cgx_layered_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_layered_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def cgx_layered_quantize(grad, plan: LayeredPlan, seed: int, packed, meta, stream=None) -> None:
+    """As cgx_quantize, every layer with its own bucket size."""
+    _check(lib().cgx_layered_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
+                                      meta.data_ptr(), _stream(stream)), "cgx_layered_quantize")
+
+
+def cgx_layered_requantize(total, plan: LayeredPlan, seed: int, packed, meta, stream=None) -> None:
+    """As cgx_requantize, every layer with its own bucket size."""
+    _check(lib().cgx_layered_requantize(total.data_ptr(), *plan.args, seed & (2**64 - 1), packed.data_ptr(),
+                                        meta.data_ptr(), _stream(stream)), "cgx_layered_requantize")
+
+
+def cgx_layered_dequant_reduce(packed: Sequence, meta: Sequence, plan: LayeredPlan, total, stream=None) -> None:
+    """As cgx_dequant_reduce, every layer with its own bucket size."""
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_layered_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
+           "cgx_layered_dequant_reduce")
+
+
+def cgx_layered_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: LayeredPlan, seed: int, packed_out,
+                                          meta_out, stream=None) -> None:
+    """As cgx_dequant_reduce_requantize, every layer with its own bucket size."""
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_layered_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
+                                                       packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
+           "cgx_layered_dequant_reduce_requantize")
 
 
 def cgx_qsgd_sizes(plan: Plan) -> Tuple[int, int]:

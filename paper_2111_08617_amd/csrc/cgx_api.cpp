@@ -23,6 +23,8 @@ struct CachedPlan {
     int chunks_per_tile = 0;
     std::vector<int64_t> off;
     std::vector<uint8_t> bits;
+    std::vector<int32_t> layer_buckets;   // empty: `bucket` for every layer; else the table holds the
+    bool with_copies = true;              // layers of size `bucket` (and the pass-through ones if with_copies)
     // content
     cgx::PlanShape shape;
     int64_t n_tiles = 0;
@@ -104,9 +106,35 @@ int tile_length(CallKind call, int dt, int64_t n)
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Bucket sizes of a call: one for all layers, or one per layer (per_layer != nullptr).
+struct Buckets {
+    int32_t uniform;
+    const int32_t *per_layer;
+};
+
+// One launch per distinct bucket size (the kernels take one size per launch); the first one
+// also carries the pass-through layers.
+struct Launch {
+    int32_t bucket;
+    bool with_copies;
+};
+std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off, const uint8_t *bits)
+{
+    if (!b.per_layer) return {{b.uniform, true}};
+    std::vector<int32_t> sizes;
+    for (int32_t l = 0; l < L; l++)
+        if (bits[l] != 0 && off[l + 1] > off[l]) sizes.push_back(b.per_layer[l]);
+    std::sort(sizes.begin(), sizes.end());
+    sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
+    if (sizes.empty()) sizes.push_back(32);         // pass-through layers only
+    std::vector<Launch> out;
+    for (size_t i = 0; i < sizes.size(); i++) out.push_back({sizes[i], i == 0});
+    return out;
+}
+
 // Finds or builds the device-resident tile table of a (valid) plan.
 int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunks_per_tile,
-             PlanRef *out)
+             PlanRef *out, const int32_t *layer_buckets = nullptr, bool with_copies = true)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     int device = 0;
@@ -114,6 +142,9 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     for (const auto &p : g_plans) {
         if (p->device == device && p->bucket == bucket && p->dt == dt &&
             p->chunks_per_tile == chunks_per_tile && p->bits.size() == size_t(L) &&
+            p->with_copies == with_copies && p->layer_buckets.size() == (layer_buckets ? size_t(L) : 0) &&
+            (!layer_buckets || L == 0 ||
+             std::memcmp(p->layer_buckets.data(), layer_buckets, sizeof(int32_t) * size_t(L)) == 0) &&
             std::memcmp(p->bits.data(), bits, size_t(L)) == 0 &&
             std::memcmp(p->off.data(), off, sizeof(int64_t) * (size_t(L) + 1)) == 0) {
             p->last_use = ++g_clock;
@@ -131,11 +162,14 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     plan->chunks_per_tile = chunks_per_tile;
     plan->off.assign(off, off + L + 1);
     plan->bits.assign(bits, bits + L);
-    plan->shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    if (layer_buckets) plan->layer_buckets.assign(layer_buckets, layer_buckets + L);
+    plan->with_copies = with_copies;
+    plan->shape = cgx::plan_shape(L, off, bits, bucket, dt, layer_buckets);
     std::vector<Tile> tiles;
     std::vector<uint32_t> slots;
     std::vector<int64_t> layer_first;
-    cgx::build_tiles(L, off, bits, bucket, dt, chunks_per_tile, tiles, &slots, &layer_first);
+    cgx::build_tiles(L, off, bits, bucket, dt, chunks_per_tile, tiles, &slots, &layer_first, layer_buckets,
+                     with_copies);
     if (tiles.size() > size_t(0xffffffffu)) return CGX_ERR_SIZE;
     plan->n_tiles = int64_t(tiles.size());
     for (const Tile &t : tiles)
@@ -165,10 +199,15 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
 
 // Plan check of an entry point: the common rules, and for the norm-and-sign quantizer no
 // 1-bit layers (a sign bit alone carries no level).
-int check_plan(int scheme, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt)
+int check_plan(int scheme, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, const Buckets &buckets,
+               int dt)
 {
-    const int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
+    int rc = cgx::validate_plan(n, L, off, bits, buckets.per_layer ? 32 : buckets.uniform, dt);
     if (rc != CGX_OK) return rc;
+    if (buckets.per_layer) {
+        rc = cgx::validate_layer_buckets(L, buckets.per_layer);
+        if (rc != CGX_OK) return rc;
+    }
     if (scheme == cgx::kSchemeNormSign)
         for (int32_t l = 0; l < L; l++)
             if (bits[l] == 1) return CGX_ERR_BITS;
@@ -176,94 +215,106 @@ int check_plan(int scheme, int64_t n, int32_t L, const int64_t *off, const uint8
 }
 
 int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
-                  int32_t bucket, uint64_t seed, int dt, void *packed, void *meta, void *stream)
+                  const Buckets &buckets, uint64_t seed, int dt, void *packed, void *meta, void *stream)
 {
-    int rc = check_plan(scheme, n, L, off, bits, bucket, dt);
+    int rc = check_plan(scheme, n, L, off, bits, buckets, dt);
     if (rc != CGX_OK) return rc;
     if (n == 0) return CGX_OK;
-    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, buckets.uniform, dt, buckets.per_layer);
     if (!grad || !packed || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
     if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
-    PlanRef plan;
-    rc = get_plan(L, off, bits, bucket, dt, tile_length(kQuantizeCall, dt, n), &plan);
-    if (rc != CGX_OK) return rc;
-    const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles, bucket,
-                                              seed, packed, meta,
-                                              launch_config(), static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+    for (const Launch &launch : launches_of(buckets, L, off, bits)) {
+        PlanRef plan;
+        rc = get_plan(L, off, bits, launch.bucket, dt, tile_length(kQuantizeCall, dt, n), &plan, buckets.per_layer,
+                      launch.with_copies);
+        if (rc != CGX_OK) return rc;
+        const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles,
+                                                  launch.bucket, seed, packed, meta, launch_config(),
+                                                  static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return CGX_ERR_HIP;
+    }
+    return CGX_OK;
 }
 
 // Shared body of the dequantize / reduce entry points: out = [local +] deq_0 + ... + deq_{W-1}.
 int reduce_impl(int scheme, const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
-                const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, const void *local, int local_dt,
-                bool want_local, void *out, int out_dt, void *stream)
+                const int64_t *off, const uint8_t *bits, const Buckets &buckets, int dt, const void *local,
+                int local_dt, bool want_local, void *out, int out_dt, void *stream)
 {
-    int rc = check_plan(scheme, n, L, off, bits, bucket, dt);
+    int rc = check_plan(scheme, n, L, off, bits, buckets, dt);
     if (rc != CGX_OK) return rc;
     if (W < 1 || W > CGX_MAX_PEERS) return CGX_ERR_PEERS;
     if (n == 0) return CGX_OK;
-    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, buckets.uniform, dt, buckets.per_layer);
     if (!packed || !meta || !out || (want_local && !local)) return CGX_ERR_NULL;
     for (int w = 0; w < W; w++) {
         if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
-    PlanRef plan;
-    rc = get_plan(L, off, bits, bucket, dt, tile_length(kOtherCall, dt, n), &plan);
-    if (rc != CGX_OK) return rc;
-    // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
-    // a later launch starts from the binary32 result of the one before (W <= kPeersPerLaunch
-    // whenever the output is not binary32: only cgx_dequantize asks for that, with W = 1)
-    for (int w0 = 0; w0 < W; w0 += cgx::kPeersPerLaunch) {
-        const int k = W - w0 < cgx::kPeersPerLaunch ? W - w0 : cgx::kPeersPerLaunch;
-        cgx::PeerPtrs peers{};
-        for (int i = 0; i < k; i++) {
-            peers.packed[i] = static_cast<const uint8_t *>(packed[w0 + i]);
-            peers.meta[i] = static_cast<const float *>(meta[w0 + i]);
+    for (const Launch &launch : launches_of(buckets, L, off, bits)) {
+        PlanRef plan;
+        rc = get_plan(L, off, bits, launch.bucket, dt, tile_length(kOtherCall, dt, n), &plan, buckets.per_layer,
+                      launch.with_copies);
+        if (rc != CGX_OK) return rc;
+        // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
+        // a later launch starts from the binary32 result of the one before (W <= kPeersPerLaunch
+        // whenever the output is not binary32: only cgx_dequantize asks for that, with W = 1)
+        for (int w0 = 0; w0 < W; w0 += cgx::kPeersPerLaunch) {
+            const int k = W - w0 < cgx::kPeersPerLaunch ? W - w0 : cgx::kPeersPerLaunch;
+            cgx::PeerPtrs peers{};
+            for (int i = 0; i < k; i++) {
+                peers.packed[i] = static_cast<const uint8_t *>(packed[w0 + i]);
+                peers.meta[i] = static_cast<const float *>(meta[w0 + i]);
+            }
+            const void *init = w0 == 0 ? local : out;
+            const int init_dt = w0 == 0 ? local_dt : CGX_F32;
+            const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
+                                                            plan->many_tails, launch.bucket, init, init_dt, out,
+                                                            out_dt, launch_config(),
+                                                            static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return CGX_ERR_HIP;
         }
-        const void *init = w0 == 0 ? local : out;
-        const int init_dt = w0 == 0 ? local_dt : CGX_F32;
-        const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
-                                                        plan->many_tails, bucket, init,
-                                                        init_dt, out, out_dt, launch_config(),
-                                                        static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return CGX_ERR_HIP;
     }
     return CGX_OK;
 }
 
 int fused_impl(int scheme, const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
-               const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, int dt, uint64_t seed,
-               void *packed_out, void *meta_out, void *stream)
+               const int64_t *layer_offsets, const uint8_t *bits_per_layer, const Buckets &buckets, int dt,
+               uint64_t seed, void *packed_out, void *meta_out, void *stream)
 {
-    int rc = check_plan(scheme, n, L, layer_offsets, bits_per_layer, bucket, dt);
+    int rc = check_plan(scheme, n, L, layer_offsets, bits_per_layer, buckets, dt);
     if (rc != CGX_OK) return rc;
     if (W < 1 || W > CGX_MAX_FUSED_PEERS) return CGX_ERR_PEERS;
     if (n == 0) return CGX_OK;
-    const cgx::PlanShape shape = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, dt);
+    const cgx::PlanShape shape =
+        cgx::plan_shape(L, layer_offsets, bits_per_layer, buckets.uniform, dt, buckets.per_layer);
     if (!packed || !meta || !packed_out || (shape.meta_bytes && !meta_out)) return CGX_ERR_NULL;
     for (int w = 0; w < W; w++) {
         if (!packed[w] || (shape.meta_bytes && !meta[w])) return CGX_ERR_NULL;
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(packed_out) || misaligned(meta_out)) return CGX_ERR_ALIGN;
-    PlanRef in, out;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, dt, tile_length(kFusedCall, dt, n), &in);
-    if (rc != CGX_OK) return rc;
-    rc = get_plan(L, layer_offsets, bits_per_layer, bucket, CGX_F32, tile_length(kFusedCall, dt, n), &out);
-    if (rc != CGX_OK) return rc;
-    if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
     cgx::PeerPtrs peers{};
     for (int i = 0; i < W; i++) {
         peers.packed[i] = static_cast<const uint8_t *>(packed[i]);
         peers.meta[i] = static_cast<const float *>(meta[i]);
     }
-    const hipError_t e = cgx::launch_dequant_reduce_requantize(scheme, peers, W, dt, in->d_tiles, out->d_tiles,
-                                                               in->n_tiles, in->odd_tiles, bucket, seed, packed_out,
-                                                               meta_out,
-                                                               launch_config(), static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+    for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer)) {
+        PlanRef in, out;
+        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, dt, tile_length(kFusedCall, dt, n), &in,
+                      buckets.per_layer, launch.with_copies);
+        if (rc != CGX_OK) return rc;
+        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, CGX_F32, tile_length(kFusedCall, dt, n), &out,
+                      buckets.per_layer, launch.with_copies);
+        if (rc != CGX_OK) return rc;
+        if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
+        const hipError_t e = cgx::launch_dequant_reduce_requantize(
+            scheme, peers, W, dt, in->d_tiles, out->d_tiles, in->n_tiles, in->odd_tiles, launch.bucket, seed,
+            packed_out, meta_out, launch_config(), static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return CGX_ERR_HIP;
+    }
+    return CGX_OK;
 }
 
 // Number of tiles (= doubles of workspace) of the plan the statistics walk; bits == nullptr:
@@ -289,7 +340,7 @@ int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *
                   const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, double *sqerr, void *workspace,
                   size_t workspace_bytes, void *stream)
 {
-    int rc = check_plan(scheme, n, L, off, bits, bucket, dt);
+    int rc = check_plan(scheme, n, L, off, bits, Buckets{bucket, nullptr}, dt);
     if (rc != CGX_OK) return rc;
     if (L == 0) return CGX_OK;
     const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
@@ -327,21 +378,21 @@ int cgx_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_of
                  const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt, void *packed,
                  void *meta, void *stream)
 {
-    return quantize_impl(cgx::kSchemeMinMax, grad, n, L, layer_offsets, bits_per_layer, bucket, seed, int(dt), packed, meta, stream);
+    return quantize_impl(cgx::kSchemeMinMax, grad, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, seed, int(dt), packed, meta, stream);
 }
 
 int cgx_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
                    const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, void *packed, void *meta,
                    void *stream)
 {
-    return quantize_impl(cgx::kSchemeMinMax, sum, n, L, layer_offsets, bits_per_layer, bucket, seed, CGX_F32, packed, meta, stream);
+    return quantize_impl(cgx::kSchemeMinMax, sum, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, seed, CGX_F32, packed, meta, stream);
 }
 
 int cgx_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
                        const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
                        float *sum, void *stream)
 {
-    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32,
+    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt), nullptr, CGX_F32,
                        false, sum, CGX_F32, stream);
 }
 
@@ -351,7 +402,7 @@ int cgx_dequant_reduce_add(const void *local, cgx_dtype local_dt, const void *co
                            cgx_dtype dt, float *sum, void *stream)
 {
     if (local_dt != CGX_F32 && local_dt != CGX_F16) return CGX_ERR_DTYPE;
-    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), local, int(local_dt),
+    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt), local, int(local_dt),
                        true, sum, CGX_F32, stream);
 }
 
@@ -361,7 +412,7 @@ int cgx_dequantize(const void *packed, const void *meta, int64_t n, int32_t L, c
 {
     if (out_dt != CGX_F32 && out_dt != CGX_F16) return CGX_ERR_DTYPE;
     const void *const p[1] = {packed}, *const m[1] = {meta};
-    return reduce_impl(cgx::kSchemeMinMax, p, m, 1, n, L, layer_offsets, bits_per_layer, bucket, int(dt), nullptr, CGX_F32, false, out,
+    return reduce_impl(cgx::kSchemeMinMax, p, m, 1, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt), nullptr, CGX_F32, false, out,
                        int(out_dt), stream);
 }
 
@@ -370,14 +421,64 @@ int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *
                                   int32_t bucket, cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
                                   void *stream)
 {
-    return fused_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt), seed,
+    return fused_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt), seed,
                       packed_out, meta_out, stream);
+}
+
+int cgx_layered_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                      const int32_t *buckets_per_layer, cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes)
+{
+    const int rc = check_plan(cgx::kSchemeMinMax, n, L, layer_offsets, bits_per_layer, Buckets{32, buckets_per_layer},
+                              int(dt));
+    if (rc != CGX_OK) return rc;
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    const cgx::PlanShape s = cgx::plan_shape(L, layer_offsets, bits_per_layer, 32, int(dt), buckets_per_layer);
+    if (packed_bytes) *packed_bytes = s.packed_bytes;
+    if (meta_bytes) *meta_bytes = s.meta_bytes;
+    return CGX_OK;
+}
+
+int cgx_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                         const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
+                         cgx_dtype dt, void *packed, void *meta, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return quantize_impl(cgx::kSchemeMinMax, grad, n, L, layer_offsets, bits_per_layer, Buckets{32, buckets_per_layer},
+                         seed, int(dt), packed, meta, stream);
+}
+
+int cgx_layered_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
+                           const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
+                           void *packed, void *meta, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return quantize_impl(cgx::kSchemeMinMax, sum, n, L, layer_offsets, bits_per_layer, Buckets{32, buckets_per_layer},
+                         seed, CGX_F32, packed, meta, stream);
+}
+
+int cgx_layered_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n, int32_t L,
+                               const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                               const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer,
+                       Buckets{32, buckets_per_layer}, int(dt), nullptr, CGX_F32, false, sum, CGX_F32, stream);
+}
+
+int cgx_layered_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                                          int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                          const int32_t *buckets_per_layer, cgx_dtype dt, uint64_t seed,
+                                          void *packed_out, void *meta_out, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return fused_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer,
+                      Buckets{32, buckets_per_layer}, int(dt), seed, packed_out, meta_out, stream);
 }
 
 int cgx_qsgd_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                    int32_t bucket, cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes)
 {
-    const int rc = check_plan(cgx::kSchemeNormSign, n, L, layer_offsets, bits_per_layer, bucket, int(dt));
+    const int rc = check_plan(cgx::kSchemeNormSign, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt));
     if (rc != CGX_OK) return rc;
     const cgx::PlanShape s = cgx::plan_shape(L, layer_offsets, bits_per_layer, bucket, int(dt));
     if (packed_bytes) *packed_bytes = s.packed_bytes;
@@ -389,7 +490,7 @@ int cgx_qsgd_quantize(const void *grad, int64_t n, int32_t L, const int64_t *lay
                       const uint8_t *bits_per_layer, int32_t bucket, uint64_t seed, cgx_dtype dt, void *packed,
                       void *meta, void *stream)
 {
-    return quantize_impl(cgx::kSchemeNormSign, grad, n, L, layer_offsets, bits_per_layer, bucket, seed, int(dt),
+    return quantize_impl(cgx::kSchemeNormSign, grad, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, seed, int(dt),
                          packed, meta, stream);
 }
 
@@ -397,7 +498,7 @@ int cgx_qsgd_dequant_reduce(const void *const *packed, const void *const *meta, 
                             const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
                             cgx_dtype dt, float *sum, void *stream)
 {
-    return reduce_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt),
+    return reduce_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt),
                        nullptr, CGX_F32, false, sum, CGX_F32, stream);
 }
 
@@ -406,7 +507,7 @@ int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *co
                                        int32_t bucket, cgx_dtype dt, uint64_t seed, void *packed_out,
                                        void *meta_out, void *stream)
 {
-    return fused_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer, bucket, int(dt),
+    return fused_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer, Buckets{bucket, nullptr}, int(dt),
                       seed, packed_out, meta_out, stream);
 }
 

@@ -26,6 +26,14 @@ int validate_plan(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
     return CGX_OK;
 }
 
+int validate_layer_buckets(int32_t L, const int32_t *layer_buckets)
+{
+    if (L > 0 && !layer_buckets) return CGX_ERR_NULL;
+    for (int32_t l = 0; l < L; l++)
+        if (layer_buckets[l] < 32 || layer_buckets[l] > 8192 || layer_buckets[l] % 32) return CGX_ERR_BUCKET;
+    return CGX_OK;
+}
+
 // Payload bytes (before padding) and buckets of one layer.
 static inline void layer_extent(int64_t len, int b, int32_t bucket, int dt, uint64_t &payload, uint64_t &buckets)
 {
@@ -38,14 +46,15 @@ static inline void layer_extent(int64_t len, int b, int32_t bucket, int dt, uint
     }
 }
 
-PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt)
+PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+                     const int32_t *layer_buckets)
 {
     PlanShape s;
     for (int32_t l = 0; l < L; l++) {
         int64_t len = off[l + 1] - off[l];
         if (len == 0) continue;
         uint64_t payload, buckets;
-        layer_extent(len, bits[l], bucket, dt, payload, buckets);
+        layer_extent(len, bits[l], layer_buckets ? layer_buckets[l] : bucket, dt, payload, buckets);
         s.packed_bytes += round_up16(payload);
         s.n_buckets += buckets;
     }
@@ -65,7 +74,7 @@ static inline bool same_key_block(int64_t e0, int64_t count)
 
 void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
                  int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots,
-                 std::vector<int64_t> *layer_first)
+                 std::vector<int64_t> *layer_first, const int32_t *layer_buckets, bool with_copies)
 {
     tiles.clear();
     if (layer_first) layer_first->assign(size_t(L) + 1, 0);
@@ -82,7 +91,13 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
         if (len == 0) continue;
         const int b = bits[l];
         uint64_t payload, buckets;
-        layer_extent(len, b, bucket, dt, payload, buckets);
+        const int32_t own_bucket = layer_buckets ? layer_buckets[l] : bucket;
+        layer_extent(len, b, own_bucket, dt, payload, buckets);
+        if (b == 0 ? !with_copies : own_bucket != bucket) {      // another launch's layer: only its extent counts
+            seg += round_up16(payload);
+            bucket0 += buckets;
+            continue;
+        }
         const uint32_t pad = uint32_t(round_up16(payload) - payload);
         // vector accesses on the gradient side are element-aligned, so a layer may start anywhere
         const bool aligned = true;

@@ -65,17 +65,26 @@ struct PlanShape {
 
 // Returns CGX_OK or the status code of the first violated rule.
 int validate_plan(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt);
+// The same rule for a bucket size per layer (every entry, also those of pass-through layers).
+int validate_layer_buckets(int32_t L, const int32_t *layer_buckets);
 
-// Sizes only (layout rules of cgx.h).  The plan must be valid.
-PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt);
+// Sizes only (layout rules of cgx.h).  The plan must be valid.  layer_buckets, if not null,
+// gives every layer its own bucket size and `bucket` is ignored.
+PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+                     const int32_t *layer_buckets = nullptr);
 
 // Tile table.  `chunks_per_tile` bounds the length of fast tiles.
 // With `slots` and `layer_first` (both or neither): numbering the tiles layer by layer and,
 // inside a layer, by first element, tile t of the table has number slots[t], and layer l owns
 // the numbers layer_first[l] .. layer_first[l + 1] - 1 (the per-layer statistics keep one
 // partial sum per tile and add them up in that order).
+// With layer_buckets (a bucket size per layer) the table holds the tiles of the layers whose
+// bucket size is `bucket` only, at their places in the whole plan's streams: the kernels take
+// one bucket size per launch, so such a plan runs as one launch per distinct size.  The
+// pass-through layers belong to the launch with with_copies set.
 void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
                  int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots = nullptr,
-                 std::vector<int64_t> *layer_first = nullptr);
+                 std::vector<int64_t> *layer_first = nullptr, const int32_t *layer_buckets = nullptr,
+                 bool with_copies = true);
 
 }  // namespace cgx

@@ -1,0 +1,109 @@
+"""Parity of the cgx_layered_* calls (a bucket size per layer) with the CPU oracle.
+
+Same bar as the single-size calls: packed stream and meta bit-exact, sums bit-exact against the
+oracle's ordered binary32 sum and within 1e-6 * sum |deq| of its binary64 sum.  Inputs of the
+reduce come from the oracle's quantizer.
+"""
+import numpy as np
+import pytest
+
+from paper_2111_08617_amd import binding as cgx
+from paper_2111_08617_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BUCKETS = [32, 64, 96, 128, 256, 512, 1024, 2048, 4096, 8192]
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    cgx.lib()
+    return t
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_quantize(torch, grad, plan, seed, requant=False):
+    pb, mb = cgx.cgx_layered_sizes(cgx.LayeredPlan(plan.offsets, plan.bits, plan.buckets, wl.F32 if requant else plan.dt))
+    packed = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    meta = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+    g = grad if isinstance(grad, torch.Tensor) else dev(torch, grad)
+    if requant:
+        cgx.cgx_layered_requantize(g, plan, seed, packed, meta)
+    else:
+        cgx.cgx_layered_quantize(g, plan, seed, packed, meta)
+    torch.cuda.synchronize()
+    p, m = packed.cpu().numpy(), meta.cpu().numpy()
+    assert (p[pb:] == 0xA5).all() and (m[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+    return p[:pb], m[:mb // 4].reshape(-1, 2)
+
+
+def same_chunk(gp, gm, op, om, what):
+    assert gm.tobytes() == om.tobytes(), f"{what}: meta differs"
+    assert np.array_equal(gp, op), f"{what}: packed differs in {int((gp != op).sum())} bytes"
+
+
+def cycle(torch, oracle, w, buckets, what):
+    plan = cgx.LayeredPlan(w.offsets, w.bits, buckets, w.dt)
+    chunks, metas = [], []
+    for peer in range(w.W):
+        g = w.gradient(peer)
+        op, om = oracle.layered_quantize(g, w.offsets, w.bits, buckets, w.quant_seed(peer), w.dt)
+        if peer < 2:
+            gp, gm = gpu_quantize(torch, g, plan, w.quant_seed(peer))
+            same_chunk(gp, gm, op, om, f"{what} quantize peer {peer}")
+        chunks.append(op)
+        metas.append(om)
+    ref = oracle.layered_dequant_reduce(chunks, metas, w.offsets, w.bits, buckets, w.dt)
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m.reshape(-1)) if m.size else torch.zeros(4, device="cuda") for m in metas]
+    total = torch.full((w.n + 16,), 123.0, dtype=torch.float32, device="cuda")
+    cgx.cgx_layered_dequant_reduce(dp, dm, plan, total)
+    torch.cuda.synchronize()
+    got = total.cpu().numpy()
+    assert (got[w.n:] == 123.0).all(), "wrote past the end of the sum"
+    got = got[:w.n]
+    assert np.array_equal(got.view(np.uint32), ref["sum32"].view(np.uint32)), f"{what}: sums differ"
+    assert (np.abs(got.astype(np.float64) - ref["sum64"]) <= 1e-6 * ref["abs64"] + 1e-45).all(), what
+    rp, rm = gpu_quantize(torch, total[:w.n], plan, 99, requant=True)
+    op, om = oracle.layered_quantize(got, w.offsets, w.bits, buckets, 99, wl.F32)
+    same_chunk(rp, rm, op, om, f"{what} requantize")
+    if w.W <= cgx.MAX_FUSED_PEERS:
+        pb, mb = cgx.cgx_layered_sizes(cgx.LayeredPlan(w.offsets, w.bits, buckets, wl.F32))
+        fp = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        fm = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+        cgx.cgx_layered_dequant_reduce_requantize(dp, dm, plan, 99, fp, fm)
+        torch.cuda.synchronize()
+        p, m = fp.cpu().numpy(), fm.cpu().numpy()
+        assert (p[pb:] == 0xA5).all() and (m[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+        op, om = oracle.layered_quantize(ref["sum32"], w.offsets, w.bits, buckets, 99, wl.F32)
+        same_chunk(p[:pb], m[:mb // 4].reshape(-1, 2), op, om, f"{what} fused reduce+requantize")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_plans_with_a_bucket_size_per_layer(torch, oracle, seed):
+    w = wl.random_plan(seed)
+    if w.n == 0:
+        pytest.skip("empty plan")
+    buckets = np.random.default_rng(seed).choice(BUCKETS, w.L).astype(np.int32)
+    cycle(torch, oracle, w, buckets, f"random plan {seed} (buckets {buckets.tolist()}, bits {w.bits.tolist()})")
+
+
+def test_equal_sizes_give_the_single_size_bytes(torch, oracle):
+    w = wl.tiny_mixed(seed=5, dt=wl.F32, bucket=256)
+    g = w.gradient()
+    gp, gm = gpu_quantize(torch, g, cgx.LayeredPlan(w.offsets, w.bits, np.full(w.L, 256, np.int32), w.dt), 21)
+    op, om = oracle.quantize(g, w.offsets, w.bits, 256, 21, w.dt)
+    same_chunk(gp, gm, op, om, "equal sizes")
+
+
+def test_resnet50_with_bucket_sizes_by_layer_size(torch, oracle):
+    """The ResNet-50 plan at full size: small layers 128, medium 512, large 2048 (three launches)."""
+    w = wl.resnet50()
+    sizes = np.diff(w.offsets)
+    buckets = np.where(sizes < 100_000, 128, np.where(sizes < 1_000_000, 512, 2048)).astype(np.int32)
+    cycle(torch, oracle, w, buckets, "resnet50 layered")

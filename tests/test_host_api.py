@@ -264,3 +264,43 @@ def test_tiles_do_not_straddle_a_generator_key_block(lib):
     assert ((lo == hi) | (kind == 0)).all()
     assert tiles["count"].astype(np.int64).sum() == n
     assert old == os.environ.get("CGX_CHUNKS_PER_TILE")
+
+
+def test_layered_sizes_and_argument_checks(lib, oracle):
+    """A bucket size per layer (paper Sec. 4.1: per-layer compression parameters): sizes follow the
+    oracle's layout, bad sizes and missing arrays are refused before anything is queued."""
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        L = int(rng.integers(1, 10))
+        sizes = rng.choice([0, 1, 31, 96, 1000, 2048, 4097, 9000], L)
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        bits = rng.integers(0, 9, L).astype(np.uint8)
+        buckets = rng.choice([32, 64, 96, 128, 512, 1024, 4096, 8192], L).astype(np.int32)
+        for dt in (wl.F32, wl.F16):
+            assert cgx.cgx_layered_sizes(cgx.LayeredPlan(off, bits, buckets, dt)) == \
+                oracle.layered_sizes(off, bits, buckets, dt)
+        same = np.full(L, 512, np.int32)
+        assert cgx.cgx_layered_sizes(cgx.LayeredPlan(off, bits, same)) == cgx.cgx_sizes(cgx.Plan(off, bits, 512))
+    off = np.array([0, 100, 300], np.int64)
+    bits = np.array([4, 0], np.uint8)
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    for bad in ([16, 32], [32, 100], [8224, 32], [32, 0]):      # also the entry of the pass-through layer
+        bk = np.array(bad, np.int32)
+        assert lib.cgx_layered_sizes(300, 2, off.ctypes.data, bits.ctypes.data, bk.ctypes.data, 0,
+                                     ctypes.byref(pb), ctypes.byref(mb)) == -5
+        assert lib.cgx_layered_quantize(16, 300, 2, off.ctypes.data, bits.ctypes.data, bk.ctypes.data, 1, 0, 16, 16,
+                                        None) == -5
+    ok = np.array([64, 32], np.int32)
+    assert lib.cgx_layered_sizes(300, 2, off.ctypes.data, bits.ctypes.data, None, 0, ctypes.byref(pb),
+                                 ctypes.byref(mb)) == -1
+    assert lib.cgx_layered_quantize(None, 300, 2, off.ctypes.data, bits.ctypes.data, ok.ctypes.data, 1, 0, 16, 16,
+                                    None) == -1
+    assert lib.cgx_layered_quantize(24, 300, 2, off.ctypes.data, bits.ctypes.data, ok.ctypes.data, 1, 0, 16, 16,
+                                    None) == -9
+    ptrs = (ctypes.c_void_p * 1)(16)
+    assert lib.cgx_layered_dequant_reduce(ptrs, ptrs, 0, 300, 2, off.ctypes.data, bits.ctypes.data, ok.ctypes.data, 0,
+                                          16, None) == -6
+    assert lib.cgx_layered_dequant_reduce_requantize(ptrs, ptrs, 17, 300, 2, off.ctypes.data, bits.ctypes.data,
+                                                     ok.ctypes.data, 0, 1, 16, 16, None) == -6
+    assert lib.cgx_layered_requantize(16, 299, 2, off.ctypes.data, bits.ctypes.data, ok.ctypes.data, 1, 16, 16,
+                                      None) == -2
