@@ -120,3 +120,29 @@ def linear_bits(sizes, norms, bits_in, candidates):
     for r, l in enumerate(order):
         out[l] = cands[(r * k) // M]
     return np.array(out, np.uint8)
+
+
+def buckets_from_bits(bits, width_candidates, bucket_candidates):
+    """Bucket size per layer from the widths an assigner chose.
+
+    The section maps bit-widths and bucket sizes to the layers linearly over the same order of
+    layers; it prints no rule for the bucket sizes.  Reading used: the position of a layer's
+    width among the ascending width candidates decides, linearly, its position among the
+    DESCENDING bucket candidates, so the layers that get the fewest bits also get the longest
+    buckets (both choices compress more): width number i of k takes bucket number
+    round_half_up(i * (kb - 1) / (k - 1)) of kb (k = 1: the longest bucket).  Layers with width
+    0 (uncompressed) take the longest bucket, which nothing uses.
+    """
+    widths = sorted(int(c) for c in width_candidates)
+    sizes = sorted((int(c) for c in bucket_candidates), reverse=True)
+    k, kb = len(widths), len(sizes)
+    out = []
+    for b in bits:
+        b = int(b)
+        if b == 0:
+            out.append(sizes[0])
+            continue
+        i = widths.index(b)               # an assigned width is one of the candidates
+        j = 0 if k == 1 else (2 * i * (kb - 1) + (k - 1)) // (2 * (k - 1))
+        out.append(sizes[j])
+    return np.array(out, np.int32)

@@ -167,3 +167,27 @@ def test_linear_heuristic_sorts_by_norm_over_size():
     assert sorted(np.bincount(b)[[2, 3, 4, 8]]) == [10, 10, 10, 10]
     r = t / s
     assert all(b[i] <= b[j] for i in range(40) for j in range(40) if r[i] < r[j])
+
+
+def test_bucket_sizes_follow_the_widths_linearly():
+    """Sec. "Layer-wise Adaptive Quantization": bit-widths and bucket sizes are mapped to the layers
+    linearly; fewest bits go with the longest buckets.  Hand-worked cases of the interpolation."""
+    from oracle import adaptive as A
+    # as many sizes as widths: a one-to-one, order-reversing map
+    assert A.buckets_from_bits([2, 3, 4, 8], [8, 4, 3, 2], [128, 512, 1024, 2048]).tolist() == [2048, 1024, 512, 128]
+    # 4 widths over 3 sizes: positions 0, 1, 2, 3 -> 0, 2/3, 4/3, 2 -> rounded 0, 1, 1, 2
+    assert A.buckets_from_bits([2, 3, 4, 8], [2, 3, 4, 8], [2048, 512, 128]).tolist() == [2048, 512, 512, 128]
+    # 2 widths over 5 sizes take the two ends
+    assert A.buckets_from_bits([2, 8, 2], [2, 8], [64, 128, 256, 512, 1024]).tolist() == [1024, 64, 1024]
+    # half-way positions round up: 3 widths over 2 sizes -> 0, 1/2, 1 -> 0, 1, 1
+    assert A.buckets_from_bits([1, 4, 8], [1, 4, 8], [1024, 128]).tolist() == [1024, 128, 128]
+    # one width: the longest bucket; uncompressed layers get a valid size too
+    assert A.buckets_from_bits([4, 0, 4], [4], [128, 512]).tolist() == [512, 512, 512]
+    # monotone: more bits never means a longer bucket
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        widths = sorted(rng.choice(np.arange(1, 9), int(rng.integers(1, 8)), replace=False).tolist())
+        sizes = rng.choice([32, 64, 128, 256, 512, 1024, 2048, 4096], int(rng.integers(1, 8)), replace=False).tolist()
+        got = A.buckets_from_bits(widths, widths, sizes)
+        assert all(a >= b for a, b in zip(got[:-1], got[1:]))
+        assert got[0] == max(sizes) and (len(widths) == 1 or got[-1] == min(sizes))
