@@ -299,6 +299,23 @@ int cgx_assign_bits_linear(int32_t L, const int64_t *layer_offsets, const double
                            const uint8_t *bits_in, const uint8_t *candidates, int32_t k, uint8_t *bits_out);
 
 /*
+ * Bucket sizes to go with assigned widths (same section: bit-widths and bucket sizes are mapped
+ * to the layers linearly; no rule is printed for the sizes).  The position of a layer's width
+ * among the ascending width candidates decides, linearly, its position among the DESCENDING
+ * bucket candidates, so the layers with the fewest bits also get the longest buckets: width
+ * number i of k takes bucket number round_half_up(i * (kb - 1) / (k - 1)) of kb (k = 1: the
+ * longest).  Layers with width 0 get the longest size (unused, but valid for cgx_layered_*).
+ * buckets_out is a valid buckets_per_layer for the cgx_layered_* calls.  Host only.
+ * Errors: CGX_ERR_NULL, CGX_ERR_SIZE (L < 0, k or kb outside 1..64), CGX_ERR_BITS (a candidate
+ * outside 1..8, or a width that is neither 0 nor a candidate), CGX_ERR_BUCKET (a bucket
+ * candidate that is not a multiple of 32 in [32, 8192]).
+ */
+int cgx_assign_buckets_from_bits(int32_t L, const uint8_t *bits_per_layer /* host [L] */,
+                                 const uint8_t *width_candidates /* host [k] */, int32_t k,
+                                 const int32_t *bucket_candidates /* host [kb] */, int32_t kb,
+                                 int32_t *buckets_out /* host [L] */);
+
+/*
  * Diagnostic: the table of wavefront work items ("tiles") the kernels walk for
  * a plan, written to host memory as 32-byte records
  *   { int64 first_element; int64 packed_byte_offset; uint32 first_bucket;

@@ -25,7 +25,7 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_dequant_reduce_requantize", "cgx_qsgd_sizes", "cgx_qsgd_quantize", "cgx_qsgd_dequant_reduce",
            "cgx_qsgd_dequant_reduce_requantize", "cgx_layer_stats_workspace", "cgx_layer_sqnorms",
            "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
-           "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
+           "cgx_assign_buckets_from_bits", "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
            "cgx_layered_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
                                              c.c_int32, c.c_void_p]
         L.cgx_assign_bits_linear.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
                                              c.c_void_p]
+        L.cgx_assign_buckets_from_bits.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
+                                                   c.c_void_p]
         L.cgx_stream_probe.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_status_string.restype = c.c_char_p
@@ -341,6 +343,18 @@ def cgx_assign_bits_linear(layer_offsets, layer_norms, bits_in, candidates) -> n
     off, norms, bits, cand, out = _assign_inputs(layer_offsets, layer_norms, bits_in, candidates)
     _check(lib().cgx_assign_bits_linear(bits.size, off.ctypes.data, norms.ctypes.data, bits.ctypes.data,
                                         cand.ctypes.data, cand.size, out.ctypes.data), "cgx_assign_bits_linear")
+    return out
+
+
+def cgx_assign_buckets_from_bits(bits_per_layer, width_candidates, bucket_candidates) -> np.ndarray:
+    """buckets_per_layer (int32) to go with widths chosen by an assigner: fewest bits, longest buckets."""
+    bits = np.ascontiguousarray(bits_per_layer, dtype=np.uint8)
+    widths = np.ascontiguousarray(width_candidates, dtype=np.uint8)
+    sizes = np.ascontiguousarray(bucket_candidates, dtype=np.int32)
+    out = np.zeros(bits.size, dtype=np.int32)
+    _check(lib().cgx_assign_buckets_from_bits(bits.size, bits.ctypes.data, widths.ctypes.data, widths.size,
+                                              sizes.ctypes.data, sizes.size, out.ctypes.data),
+           "cgx_assign_buckets_from_bits")
     return out
 
 

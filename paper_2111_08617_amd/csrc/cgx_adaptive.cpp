@@ -166,4 +166,30 @@ int cgx_assign_bits_linear(int32_t L, const int64_t *layer_offsets, const double
     return CGX_OK;
 }
 
+int cgx_assign_buckets_from_bits(int32_t L, const uint8_t *bits_per_layer, const uint8_t *width_candidates, int32_t k,
+                                 const int32_t *bucket_candidates, int32_t kb, int32_t *buckets_out)
+{
+    if (L < 0 || k < 1 || k > 64 || kb < 1 || kb > 64) return CGX_ERR_SIZE;
+    if (!width_candidates || !bucket_candidates || (L > 0 && (!bits_per_layer || !buckets_out))) return CGX_ERR_NULL;
+    std::vector<uint8_t> widths(width_candidates, width_candidates + k);
+    std::vector<int32_t> sizes(bucket_candidates, bucket_candidates + kb);
+    for (uint8_t w : widths)
+        if (w < 1 || w > 8) return CGX_ERR_BITS;
+    for (int32_t b : sizes)
+        if (b < 32 || b > 8192 || b % 32) return CGX_ERR_BUCKET;
+    std::sort(widths.begin(), widths.end());
+    std::sort(sizes.begin(), sizes.end(), [](int32_t a, int32_t b) { return a > b; });       // longest first
+    for (int32_t l = 0; l < L; l++) {
+        if (bits_per_layer[l] == 0) {
+            buckets_out[l] = sizes[0];
+            continue;
+        }
+        const auto at = std::find(widths.begin(), widths.end(), bits_per_layer[l]);
+        if (at == widths.end()) return CGX_ERR_BITS;        // not one of the candidates
+        const int64_t i = at - widths.begin();
+        buckets_out[l] = sizes[size_t(k == 1 ? 0 : (2 * i * (kb - 1) + (k - 1)) / (2 * (k - 1)))];
+    }
+    return CGX_OK;
+}
+
 }  // extern "C"

@@ -107,3 +107,29 @@ def test_resnet50_with_bucket_sizes_by_layer_size(torch, oracle):
     sizes = np.diff(w.offsets)
     buckets = np.where(sizes < 100_000, 128, np.where(sizes < 1_000_000, 512, 2048)).astype(np.int32)
     cycle(torch, oracle, w, buckets, "resnet50 layered")
+
+
+def test_adaptive_round_with_widths_and_bucket_sizes(torch, oracle):
+    """One round of the layer-wise scheme ending in a layered plan: norms of an accumulated gradient
+    on the device -> k-means widths -> bucket sizes from the widths -> the layered cycle."""
+    from oracle import adaptive
+    w = wl.bert_base()
+    L = 40                                                       # embeddings + 2 blocks
+    off = (w.offsets[:L + 1] - w.offsets[0]).astype(np.int64)
+    n = int(off[-1])
+    acc = sum(w.gradient(p, 0, n) for p in range(3))
+    bits_in = np.where(w.bits[:L] == 0, 0, 4).astype(np.uint8)
+    plan0 = cgx.Plan(off, np.zeros(L, np.uint8), 32, w.dt)
+    ws = torch.empty(max(cgx.cgx_layer_stats_workspace(plan0, for_sqnorms=True), 16), dtype=torch.uint8, device="cuda")
+    sq = torch.zeros(L, dtype=torch.float64, device="cuda")
+    cgx.cgx_layer_sqnorms(dev(torch, acc), plan0, sq, ws)
+    torch.cuda.synchronize()
+    norms = np.sqrt(sq.cpu().numpy())
+    bits = cgx.cgx_assign_bits_kmeans(off, norms, bits_in, [2, 3, 4])
+    buckets = cgx.cgx_assign_buckets_from_bits(bits, [2, 3, 4], [128, 512, 2048])
+    sizes = np.diff(off)
+    assert bits.tolist() == adaptive.kmeans_bits(sizes, norms, bits_in, [2, 3, 4]).tolist()
+    assert buckets.tolist() == adaptive.buckets_from_bits(bits, [2, 3, 4], [128, 512, 2048]).tolist()
+    assert len(set(buckets[bits != 0].tolist())) > 1, "the round should mix bucket sizes"
+    sub = wl.Workload("bert_head", [tuple(s) for s in w.shapes[:L]], bits, 512, w.dt, 3, w.seed, w.draw, w.scales[:L])
+    cycle(torch, oracle, sub, buckets, "adaptive round, layered")

@@ -136,3 +136,32 @@ def test_statistics_workspace_and_argument_errors(lib):
     assert lib.cgx_layer_sqerrors(buf, buf, None, w.n, w.L, o, b, w.bucket, w.dt, buf, buf, 1 << 20, None) == -1
     assert lib.cgx_layer_sqerrors(buf, buf, buf, w.n, w.L, o, b, w.bucket, w.dt, None, buf, 1 << 20, None) == -1
     assert lib.cgx_layer_sqerrors(buf, buf + 8, buf, w.n, w.L, o, b, w.bucket, w.dt, buf, buf, 1 << 20, None) == -9
+
+
+def test_bucket_sizes_from_widths_equal_the_oracle_and_check_their_arguments(lib):
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        widths = rng.choice(np.arange(1, 9), int(rng.integers(1, 9)), replace=False).astype(np.uint8)
+        sizes = rng.choice(np.arange(1, 257) * 32, int(rng.integers(1, 12)), replace=False).astype(np.int32)
+        bits = rng.choice(np.concatenate([[0], widths]), int(rng.integers(0, 40))).astype(np.uint8)
+        got = cgx.cgx_assign_buckets_from_bits(bits, widths, sizes)
+        assert got.tolist() == adaptive.buckets_from_bits(bits, widths, sizes).tolist()
+    c = ctypes
+    bits = np.array([2, 0, 4], np.uint8)
+    widths = np.array([2, 4], np.uint8)
+    sizes = np.array([128, 1024], np.int32)
+    out = np.zeros(3, np.int32)
+
+    def call(L=3, b=bits, w=widths, k=2, s=sizes, kb=2, o=out):
+        return lib.cgx_assign_buckets_from_bits(L, b.ctypes.data if b is not None else None,
+                                                w.ctypes.data if w is not None else None, k,
+                                                s.ctypes.data if s is not None else None, kb,
+                                                o.ctypes.data if o is not None else None)
+
+    assert call() == 0 and out.tolist() == [1024, 1024, 128]
+    assert call(L=-1) == -2 and call(k=0) == -2 and call(kb=65) == -2
+    assert call(b=None) == -1 and call(w=None) == -1 and call(s=None) == -1 and call(o=None) == -1
+    assert call(w=np.array([2, 9], np.uint8)) == -4
+    assert call(b=np.array([2, 3, 4], np.uint8)) == -4          # 3 is not a candidate
+    assert call(s=np.array([128, 100], np.int32)) == -5
+    assert call(L=0, b=None, o=None) == 0
