@@ -174,9 +174,9 @@ int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *
  * otherwise; the entries of pass-through and empty layers are checked but not used).
  * Layout, meta numbering (buckets in layer order), draws, sums and errors are those of the
  * calls above; with all entries equal the results are byte for byte those of the call with
- * that one size.  The kernels take one bucket size per launch, so a call queues one launch
- * per distinct size among the quantized layers (each over those layers' tiles only) and keeps
- * one device table per size.
+ * that one size.  A call queues one launch for each of the three size classes in use among its
+ * quantized layers (32-64, 96-2048, above 2048: each class has its own kernel instantiation)
+ * and keeps one device table per class.
  */
 int cgx_layered_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                       const int32_t *buckets_per_layer /* host [L] */, cgx_dtype dt, size_t *packed_bytes,

@@ -112,8 +112,9 @@ struct Buckets {
     const int32_t *per_layer;
 };
 
-// One launch per distinct bucket size (the kernels take one size per launch); the first one
-// also carries the pass-through layers.
+// One launch per lane mapping in use (a launch runs one kernel instantiation; the bucket size
+// itself travels in the tile descriptors), named by the smallest bucket size of that mapping;
+// the first launch also carries the pass-through layers.
 struct Launch {
     int32_t bucket;
     bool with_copies;
@@ -121,14 +122,16 @@ struct Launch {
 std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off, const uint8_t *bits)
 {
     if (!b.per_layer) return {{b.uniform, true}};
-    std::vector<int32_t> sizes;
+    int32_t smallest[3] = {0, 0, 0};
     for (int32_t l = 0; l < L; l++)
-        if (bits[l] != 0 && off[l + 1] > off[l]) sizes.push_back(b.per_layer[l]);
-    std::sort(sizes.begin(), sizes.end());
-    sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
-    if (sizes.empty()) sizes.push_back(32);         // pass-through layers only
+        if (bits[l] != 0 && off[l + 1] > off[l]) {
+            int32_t &s = smallest[cgx::mapping_of(b.per_layer[l])];
+            if (s == 0 || b.per_layer[l] < s) s = b.per_layer[l];
+        }
     std::vector<Launch> out;
-    for (size_t i = 0; i < sizes.size(); i++) out.push_back({sizes[i], i == 0});
+    for (int32_t s : smallest)
+        if (s != 0) out.push_back({s, out.empty()});
+    if (out.empty()) out.push_back({32, true});         // pass-through layers only
     return out;
 }
 

@@ -464,14 +464,6 @@ struct TailShape {
     default: { constexpr int BITS = 8; CALL; } break; \
     }
 
-// MAP: how the vectorised tiles of the plan are laid over the lanes, fixed by the call's bucket
-// size: kMapBuckets for 128..2048 (bucket-major), kMapRows for 32 and 64 (row by row; needs more
-// registers, so a kernel of its own keeps the others' occupancy), kMapWide for 4096 and 8192
-// (a tile is one bucket of several chunks).
-enum LaneMapping { kMapBuckets = 0, kMapRows = 1, kMapWide = 2 };
-
-inline int mapping_of(int bucket) { return bucket <= 64 ? kMapRows : bucket > kChunk ? kMapWide : kMapBuckets; }
-
 inline unsigned grid_for(int64_t n_tiles, const LaunchConfig &cfg)
 {
     int64_t blocks = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;

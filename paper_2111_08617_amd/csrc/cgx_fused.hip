@@ -99,7 +99,7 @@ template <int SCHEME, bool WIDE, bool ODD>
 __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers_argument, int W, int dt,
                                                         const Tile *__restrict__ tiles_in,
                                                         const Tile *__restrict__ tiles_out, int64_t n_tiles,
-                                                        int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                                        uint32_t seed_lo, uint32_t seed_hi,
                                                         uint8_t *__restrict__ packed_out,
                                                         float *__restrict__ meta_out)
 {
@@ -117,6 +117,7 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers_argu
         asm volatile("" : "+v"(lane_of_wave));
         const int lane = lane_of_wave;
         const Tile tile = tiles_in[t];
+        const int bucket = tile_bucket(tile);       // per tile: a launch may mix sizes of one lane mapping
         const int64_t out_off = tiles_out[t].packed_off;
         const uint32_t out_pad = tiles_out[t].pad;
         const uint32_t kind = tile_kind(tile);
@@ -158,7 +159,7 @@ hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, i
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const bool wide = mapping_of(bucket) == kMapWide;
-    using Kernel = void (*)(const PeerPtrs, int, int, const Tile *, const Tile *, int64_t, int, uint32_t, uint32_t,
+    using Kernel = void (*)(const PeerPtrs, int, int, const Tile *, const Tile *, int64_t, uint32_t, uint32_t,
                             uint8_t *, float *);
     static const Kernel table[2][2][2] = {
         {{fused_kernel<kMinMax, false, false>, fused_kernel<kMinMax, true, false>},
@@ -166,7 +167,7 @@ hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, i
         {{fused_kernel<kMinMax, false, true>, fused_kernel<kMinMax, true, true>},
          {fused_kernel<kNormSign, false, true>, fused_kernel<kNormSign, true, true>}}};
     const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][wide];
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles, int(bucket),
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles,
                        uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
                        static_cast<float *>(meta_out));
     return hipGetLastError();

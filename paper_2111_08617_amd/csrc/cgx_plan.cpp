@@ -80,10 +80,7 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     if (layer_first) layer_first->assign(size_t(L) + 1, 0);
     if (chunks_per_tile < 1) chunks_per_tile = 1;
     const int S = elem_size(dt);
-    const bool fast_bucket = is_pow2(bucket) && bucket <= kChunk;
-    const bool wide_bucket = is_pow2(bucket) && bucket > kChunk;       // a bucket is 2 or 4 chunks
-    // 64 lanes x kGroups groups x 8 elements = kChunk, so a bucket spans bucket / (8 * kGroups) lanes
-    const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(bucket / (8 * kGroups))) : 0u;
+    const int launch_mapping = mapping_of(bucket);
     uint64_t seg = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         const int64_t first = off[l], len = off[l + 1] - off[l];
@@ -93,11 +90,16 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
         uint64_t payload, buckets;
         const int32_t own_bucket = layer_buckets ? layer_buckets[l] : bucket;
         layer_extent(len, b, own_bucket, dt, payload, buckets);
-        if (b == 0 ? !with_copies : own_bucket != bucket) {      // another launch's layer: only its extent counts
-            seg += round_up16(payload);
+        if (b == 0 ? !with_copies : mapping_of(own_bucket) != launch_mapping) {
+            seg += round_up16(payload);                           // another launch's layer: only its extent counts
             bucket0 += buckets;
             continue;
         }
+        const bool fast_bucket = is_pow2(own_bucket) && own_bucket <= kChunk;
+        const bool wide_bucket = is_pow2(own_bucket) && own_bucket > kChunk;       // a bucket is 2 or 4 chunks
+        // 64 lanes x kGroups groups x 8 elements = kChunk, so a bucket spans bucket / (8 * kGroups) lanes
+        const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(own_bucket / (8 * kGroups))) : 0u;
+        const uint32_t size_bits = uint32_t(own_bucket / 32) << 12;
         const uint32_t pad = uint32_t(round_up16(payload) - payload);
         // vector accesses on the gradient side are element-aligned, so a layer may start anywhere
         const bool aligned = true;
@@ -122,41 +124,41 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
                     Tile t{};
                     t.elem0 = first + c * kChunk;
                     t.packed_off = int64_t(seg + uint64_t(c) * kChunk * b / 8);
-                    t.bucket0 = uint32_t(bucket0 + uint64_t(c) * kChunk / bucket);
+                    t.bucket0 = uint32_t(bucket0 + uint64_t(c) * kChunk / own_bucket);
                     t.count = uint32_t(k * kChunk);
                     const bool fast = same_key_block(t.elem0, t.count);
-                    t.info = uint32_t(b) | uint32_t(fast ? kQuantFast : kQuantSlow) << 4 | lpb_log2 << 8;
+                    t.info = uint32_t(b) | uint32_t(fast ? kQuantFast : kQuantSlow) << 4 | lpb_log2 << 8 | size_bits;
                     tiles.push_back(t);
                     c += k;
                 }
                 j = full_chunks * kChunk;
             } else if (wide_bucket && aligned) {
                 // one tile per whole bucket: its scale needs all of it (lanes-per-bucket field: the whole wave)
-                const int64_t full = len / bucket;
+                const int64_t full = len / own_bucket;
                 for (int64_t k = 0; k < full; k++) {
                     Tile t{};
-                    t.elem0 = first + k * bucket;
-                    t.packed_off = int64_t(seg + uint64_t(k) * bucket * b / 8);
+                    t.elem0 = first + k * own_bucket;
+                    t.packed_off = int64_t(seg + uint64_t(k) * own_bucket * b / 8);
                     t.bucket0 = uint32_t(bucket0 + uint64_t(k));
-                    t.count = uint32_t(bucket);
+                    t.count = uint32_t(own_bucket);
                     const bool fast = same_key_block(t.elem0, t.count);
-                    t.info = uint32_t(b) | uint32_t(fast ? kQuantWide : kQuantSlow) << 4 | 6u << 8;
+                    t.info = uint32_t(b) | uint32_t(fast ? kQuantWide : kQuantSlow) << 4 | 6u << 8 | size_bits;
                     tiles.push_back(t);
                 }
-                j = full * bucket;
+                j = full * own_bucket;
             }
             // what is left (or the whole layer): whole buckets, about a chunk per tile
-            const int64_t step = bucket >= kChunk ? bucket : int64_t(kChunk / bucket) * bucket;
+            const int64_t step = own_bucket >= kChunk ? own_bucket : int64_t(kChunk / own_bucket) * own_bucket;
             for (; j < len; j += step) {
                 Tile t{};
                 t.elem0 = first + j;
                 t.packed_off = int64_t(seg + uint64_t(j) * b / 8);
-                t.bucket0 = uint32_t(bucket0 + uint64_t(j) / bucket);
+                t.bucket0 = uint32_t(bucket0 + uint64_t(j) / own_bucket);
                 t.count = uint32_t(len - j < step ? len - j : step);
                 // the short end of a layer with power-of-two buckets runs through the chunk code, masked
                 const bool tail = fast_bucket && j % kChunk == 0 && t.count < uint32_t(kChunk) &&
                                   same_key_block(t.elem0, t.count);
-                t.info = uint32_t(b) | uint32_t(tail ? kQuantTail : kQuantSlow) << 4 | (tail ? lpb_log2 << 8 : 0u);
+                t.info = uint32_t(b) | uint32_t(tail ? kQuantTail : kQuantSlow) << 4 | (tail ? lpb_log2 << 8 : 0u) | size_bits;
                 tiles.push_back(t);
             }
         }

@@ -48,7 +48,7 @@ struct Tile {               // 32 bytes, read by the kernels with scalar loads
     int64_t packed_off;     // byte offset of the tile's payload in the packed stream
     uint32_t bucket0;       // index of the tile's first bucket in the meta array
     uint32_t count;         // elements in the tile
-    uint32_t info;          // bits [0:3] bit width, [4:7] TileKind, [8:11] log2(lanes per bucket)
+    uint32_t info;          // bits [0:3] bit width, [4:7] TileKind, [8:11] log2(lanes per bucket), [12:20] bucket / 32
     uint32_t pad;           // zero bytes to append after the payload (last tile of a layer)
 };
 static_assert(sizeof(Tile) == 32, "tile layout is shared with the kernels");
@@ -56,6 +56,16 @@ static_assert(sizeof(Tile) == 32, "tile layout is shared with the kernels");
 CGX_HOST_DEVICE inline uint32_t tile_bits(const Tile &t) { return t.info & 15u; }
 CGX_HOST_DEVICE inline uint32_t tile_kind(const Tile &t) { return (t.info >> 4) & 15u; }
 CGX_HOST_DEVICE inline uint32_t tile_lpb_log2(const Tile &t) { return (t.info >> 8) & 15u; }
+// Bucket size of a quantized tile (0 for pass-through tiles): info bits [12:20] hold bucket / 32.
+CGX_HOST_DEVICE inline int tile_bucket(const Tile &t) { return int((t.info >> 12) & 0x1ffu) * 32; }
+
+// How the vectorised tiles of a bucket size are laid over the lanes, which fixes the kernel
+// instantiation of a launch: kMapBuckets for 96..2048 (bucket-major), kMapRows for 32 and 64
+// (row by row; needs more registers, so a kernel of its own keeps the others' occupancy),
+// kMapWide above 2048 (a tile is one bucket of several chunks).  One launch serves every
+// bucket size of one class.
+enum LaneMapping { kMapBuckets = 0, kMapRows = 1, kMapWide = 2 };
+inline int mapping_of(int bucket) { return bucket <= 64 ? kMapRows : bucket > 64 * 8 * CGX_GROUPS ? kMapWide : kMapBuckets; }
 
 struct PlanShape {
     size_t packed_bytes = 0;
@@ -79,9 +89,10 @@ PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t
 // the numbers layer_first[l] .. layer_first[l + 1] - 1 (the per-layer statistics keep one
 // partial sum per tile and add them up in that order).
 // With layer_buckets (a bucket size per layer) the table holds the tiles of the layers whose
-// bucket size is `bucket` only, at their places in the whole plan's streams: the kernels take
-// one bucket size per launch, so such a plan runs as one launch per distinct size.  The
-// pass-through layers belong to the launch with with_copies set.
+// bucket size has the lane mapping of `bucket` (mapping_of) only, at their places in the whole
+// plan's streams: a launch runs one kernel instantiation, so such a plan takes one launch per
+// mapping in use (at most three).  The pass-through layers belong to the launch with
+// with_copies set.
 void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
                  int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots = nullptr,
                  std::vector<int64_t> *layer_first = nullptr, const int32_t *layer_buckets = nullptr,

@@ -8,7 +8,7 @@ namespace {
 template <int SCHEME, int DT, int MAP, bool ODD>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
                                                            const Tile *__restrict__ tiles, int64_t n_tiles,
-                                                           int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                                           uint32_t seed_lo, uint32_t seed_hi,
                                                            uint8_t *__restrict__ packed,
                                                            float *__restrict__ meta)
 {
@@ -25,6 +25,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
         asm volatile("" : "+v"(lane_of_wave));
         const int lane = lane_of_wave;
         const Tile tile = tiles[t];
+        const int bucket = tile_bucket(tile);       // per tile: a launch may mix sizes of one lane mapping
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {
             if constexpr (MAP == kMapRows) {
@@ -59,7 +60,7 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const uint32_t seed_lo = uint32_t(seed), seed_hi = uint32_t(seed >> 32);
-    using Kernel = void (*)(const void *, const Tile *, int64_t, int, uint32_t, uint32_t, uint8_t *, float *);
+    using Kernel = void (*)(const void *, const Tile *, int64_t, uint32_t, uint32_t, uint8_t *, float *);
 #define CGX_QUANTIZE_MAPS(S, D, O) \
     {quantize_kernel<S, D, kMapBuckets, O>, quantize_kernel<S, D, kMapRows, O>, quantize_kernel<S, D, kMapWide, O>}
     static const Kernel table[2][2][2][3] = {
@@ -69,7 +70,7 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
          {CGX_QUANTIZE_MAPS(kNormSign, CGX_F32, true), CGX_QUANTIZE_MAPS(kNormSign, CGX_F16, true)}}};
 #undef CGX_QUANTIZE_MAPS
     const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket)];
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, int(bucket), seed_lo, seed_hi,
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, seed_lo, seed_hi,
                        static_cast<uint8_t *>(packed), static_cast<float *>(meta));
     return hipGetLastError();
 }

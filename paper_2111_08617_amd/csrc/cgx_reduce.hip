@@ -13,8 +13,7 @@ namespace {
 // at least 1/512 of the tiles.
 template <int SCHEME, bool TAILS>
 __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_argument, int W, int dt, const SumIo io,
-                                                         const Tile *__restrict__ tiles, int64_t n_tiles,
-                                                         int bucket)
+                                                         const Tile *__restrict__ tiles, int64_t n_tiles)
 {
     // the vectorised tiles index the table with constants (it then sits in scalar registers);
     // the other kinds index it at run time and read it from the kernarg segment
@@ -33,6 +32,7 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_arg
         asm volatile("" : "+v"(lane_of_wave));
         const int lane = lane_of_wave;
         const Tile tile = tiles[t];
+        const int bucket = tile_bucket(tile);       // per tile: a launch may mix sizes of one lane mapping
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {      // a wide tile is chunks of one bucket: kChunk / bucket == 0 below
             CGX_FOR_BITS(tile_bits(tile), (reduce_fast<SCHEME, BITS>(peers, W, io, tile, bucket, lane, stage)))
@@ -64,7 +64,8 @@ hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int d
     const auto kernel = scheme == kSchemeNormSign
                             ? (many_tails ? reduce_kernel<kNormSign, true> : reduce_kernel<kNormSign, false>)
                             : (many_tails ? reduce_kernel<kMinMax, true> : reduce_kernel<kMinMax, false>);
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles, int(bucket));
+    (void)bucket;
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles);
     return hipGetLastError();
 }
 

@@ -102,7 +102,7 @@ template <int SCHEME, int DT>
 __global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_argument, const void *__restrict__ grad,
                                                           const Tile *__restrict__ tiles,
                                                           const uint32_t *__restrict__ slots, int64_t n_tiles,
-                                                          int bucket, double *__restrict__ partial)
+                                                          double *__restrict__ partial)
 {
     (void)chunk_argument;
     KernargPeers &chunk = first_kernel_argument();
@@ -113,6 +113,7 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_ar
     const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
     for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
         const Tile tile = tiles[t];
+        const int bucket = tile_bucket(tile);
         const uint32_t kind = tile_kind(tile);
         double s = 0.0;                              // pass-through tiles: no error
         if (is_vector_kind(kind)) {
@@ -225,7 +226,8 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
             scheme == kSchemeNormSign
                 ? (dt == CGX_F16 ? sqerror_kernel<kNormSign, CGX_F16> : sqerror_kernel<kNormSign, CGX_F32>)
                 : (dt == CGX_F16 ? sqerror_kernel<kMinMax, CGX_F16> : sqerror_kernel<kMinMax, CGX_F32>);
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, chunk, grad, tiles, slots, n_tiles, int(bucket), partial);
+        (void)bucket;
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, chunk, grad, tiles, slots, n_tiles, partial);
     }
     hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
                        static_cast<const double *>(partial), layer_first, out);
