@@ -320,7 +320,8 @@ int cgx_assign_buckets_from_bits(int32_t L, const uint8_t *bits_per_layer /* hos
  * a plan, written to host memory as 32-byte records
  *   { int64 first_element; int64 packed_byte_offset; uint32 first_bucket;
  *     uint32 elements; uint32 info; uint32 pad_bytes }
- * with info = bits | kind << 4 | log2(lanes per bucket) << 8 and kind 0 = generic
+ * with info = bits | kind << 4 | log2(lanes per bucket) << 8 | (bucket / 32) << 12 (the last
+ * two fields are 0 where they do not apply) and kind 0 = generic
  * quantize, 1 = vectorised quantize, 2 = element-wise copy, 3 = vectorised copy,
  * 4 = vectorised quantize of one whole bucket of 4096 or 8192 elements, 5 = the short end
  * of a layer (less than a chunk of 2048 elements) with power-of-two buckets.

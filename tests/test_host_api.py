@@ -304,3 +304,14 @@ def test_layered_sizes_and_argument_checks(lib, oracle):
                                                      ok.ctypes.data, 0, 1, 16, 16, None) == -6
     assert lib.cgx_layered_requantize(16, 299, 2, off.ctypes.data, bits.ctypes.data, ok.ctypes.data, 1, 16, 16,
                                       None) == -2
+
+
+def test_tiles_carry_their_bucket_size(lib):
+    """Quantized tiles name their bucket size (info bits 12..20 = bucket / 32); pass-through tiles carry 0."""
+    for bucket in (32, 96, 512, 2048, 8192):
+        w = wl.tiny_mixed(seed=1, dt=wl.F32, bucket=bucket)
+        tiles = cgx.cgx_plan_tiles(cgx.Plan(w.offsets, w.bits, bucket, w.dt))
+        kind = (tiles["info"] >> 4) & 15
+        size = ((tiles["info"] >> 12) & 0x1ff) * 32
+        quantized = (kind != 2) & (kind != 3)
+        assert (size[quantized] == bucket).all() and (size[~quantized] == 0).all()
