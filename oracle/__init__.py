@@ -71,6 +71,7 @@ def _load():
         lib.oracle_layered_quantize.argtypes = [c.c_void_p] + layered + [c.c_uint64, c.c_int32, c.c_void_p, c.c_void_p]
         lib.oracle_layered_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_layered_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + layered + [c.c_int32, c.c_void_p]
         _lib = lib
     return _lib
 
@@ -263,6 +264,22 @@ def layered_dequant_reduce(packed_list, meta_list, offsets, bits, buckets, dt: i
            "abs64": np.zeros(n, dtype=np.float64)}
     _check(_load().oracle_layered_dequant_reduce(pp, mp, W, n, L, _ptr(off), _ptr(bt), _ptr(bk), dt, _ptr(out["sum32"]),
                                                  _ptr(out["sum64"]), _ptr(out["abs64"])), "layered_dequant_reduce")
+    return out
+
+
+def layered_layer_sqerrors(grad, packed, meta, offsets, bits, buckets, dt: int = F32):
+    """layer_sqerrors() for a chunk written with a bucket size per layer (min/max form)."""
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    g = _grad(grad, n, dt)
+    pk = np.ascontiguousarray(packed, dtype=np.uint8)
+    mt = np.ascontiguousarray(meta, dtype=np.float32).reshape(-1)
+    pb, mb = layered_sizes(off, bt, bk, dt)
+    if pk.size != pb or mt.size * 4 != mb:
+        raise ValueError("chunk sizes do not match the plan")
+    out = np.zeros(L, dtype=np.float64)
+    _check(_load().oracle_layered_layer_sqerrors(_ptr(g), _ptr(pk), _ptr(mt), n, L, _ptr(off), _ptr(bt), _ptr(bk), dt,
+                                                 _ptr(out)), "layered_layer_sqerrors")
     return out
 
 

@@ -678,11 +678,13 @@ int oracle_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *o
 /* out[l] = sum over the layer of (x_i - value of its code)^2, the value being the binary32 one
  * the dequantizer returns; 0 for pass-through layers.  scheme 0: min/max form (meta {unit, mn}),
  * scheme 1: norm-and-sign form (meta unit). */
-int oracle_layer_sqerrors(int32_t scheme, const void *grad, const uint8_t *packed, const float *meta, int64_t n,
-                          int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int32_t dt,
-                          double *out)
+static int sqerrors_impl(int32_t scheme, const void *grad, const uint8_t *packed, const float *meta, int64_t n,
+                         int32_t L, const int64_t *off, const uint8_t *bits, int32_t uniform_bucket,
+                         const int32_t *layer_buckets, int32_t dt, double *out)
 {
-    int rc = check_plan(n, L, off, bits, bucket, dt);
+    int rc = check_plan(n, L, off, bits, layer_buckets ? 32 : uniform_bucket, dt);
+    if (rc) return rc;
+    rc = check_layer_buckets(L, layer_buckets);
     if (rc) return rc;
     if ((scheme != 0 && scheme != 1) || (scheme == 1 && check_qsgd_bits(L, bits))) return ORACLE_ERR_ARG;
     if (L > 0 && !out) return ORACLE_ERR_ARG;
@@ -690,6 +692,7 @@ int oracle_layer_sqerrors(int32_t scheme, const void *grad, const uint8_t *packe
     for (int32_t l = 0; l < L; l++) {
         int64_t first = off[l], len = off[l + 1] - off[l];
         int b = bits[l];
+        const int32_t bucket = bucket_of(l, uniform_bucket, layer_buckets);
         uint64_t seg_bytes, n_buckets;
         layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
         long double acc = 0.0L;
@@ -714,4 +717,20 @@ int oracle_layer_sqerrors(int32_t scheme, const void *grad, const uint8_t *packe
         bucket0 += n_buckets;
     }
     return ORACLE_OK;
+}
+
+int oracle_layer_sqerrors(int32_t scheme, const void *grad, const uint8_t *packed, const float *meta, int64_t n,
+                          int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int32_t dt,
+                          double *out)
+{
+    return sqerrors_impl(scheme, grad, packed, meta, n, L, off, bits, bucket, NULL, dt, out);
+}
+
+/* The same for a chunk written with a bucket size per layer (min/max form). */
+int oracle_layered_layer_sqerrors(const void *grad, const uint8_t *packed, const float *meta, int64_t n, int32_t L,
+                                  const int64_t *off, const uint8_t *bits, const int32_t *layer_buckets,
+                                  int32_t dt, double *out)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return sqerrors_impl(0, grad, packed, meta, n, L, off, bits, 32, layer_buckets, dt, out);
 }

@@ -85,3 +85,26 @@ def test_equal_sizes_give_the_single_size_result_and_bad_sizes_are_rejected(orac
     for bad in (0, 16, 100, 8224):
         with pytest.raises(ValueError):
             oracle.layered_sizes(off, bits, np.full(bits.size, bad, np.int32))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_squared_errors_are_those_of_the_layers_alone(oracle, seed):
+    """Per-layer squared compression errors of a layered chunk: each layer's value is what the
+    single-size function gives for that layer alone (same codes, same meta, its bucket size)."""
+    off, bits, buckets, rng = plan(200 + seed)
+    n = int(off[-1])
+    g = rng.standard_normal(n).astype(np.float32)
+    packed, meta = oracle.layered_quantize(g, off, bits, buckets, 9)
+    got = oracle.layered_layer_sqerrors(g, packed, meta, off, bits, buckets)
+    pos = mpos = 0
+    for l in range(bits.size):
+        a, b = int(off[l]), int(off[l + 1])
+        if a == b:
+            assert got[l] == 0
+            continue
+        pb, mb = oracle.sizes([0, b - a], [bits[l]], int(buckets[l]))
+        ref = oracle.layer_sqerrors(g[a:b], packed[pos:pos + pb], meta.reshape(-1)[mpos:mpos + mb // 4],
+                                    [0, b - a], [bits[l]], int(buckets[l]))
+        assert got[l] == ref[0], f"layer {l}"
+        pos += pb
+        mpos += mb // 4
