@@ -195,6 +195,13 @@ int cgx_layered_dequant_reduce_requantize(const void *const *packed, const void 
                                           const uint8_t *bits_per_layer, const int32_t *buckets_per_layer,
                                           cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
                                           void *stream);
+/* cgx_layer_sqerrors and its workspace size for a chunk written by cgx_layered_quantize. */
+int cgx_layered_stats_workspace(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                const int32_t *buckets_per_layer, cgx_dtype dt, size_t *bytes);
+int cgx_layered_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                               const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                               const int32_t *buckets_per_layer, cgx_dtype dt, double *sqerr, void *workspace,
+                               size_t workspace_bytes, void *stream);
 
 /*
  * The norm-and-sign form of the quantizer, Q_s as printed in paper Sec. 2.2

@@ -26,7 +26,8 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_qsgd_dequant_reduce_requantize", "cgx_layer_stats_workspace", "cgx_layer_sqnorms",
            "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
            "cgx_assign_buckets_from_bits", "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
-           "cgx_layered_dequant_reduce_requantize", "cgx_plan_tiles", "cgx_stream_probe",
+           "cgx_layered_dequant_reduce_requantize", "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors",
+           "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -70,6 +71,9 @@ def lib() -> ctypes.CDLL:
             [c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_layered_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
             [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_layered_stats_workspace.argtypes = layered + [c.c_int, c.POINTER(c.c_size_t)]
+        L.cgx_layered_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + layered + \
+            [c.c_int, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
         L.cgx_qsgd_sizes.argtypes = L.cgx_sizes.argtypes
         L.cgx_qsgd_quantize.argtypes = L.cgx_quantize.argtypes
         L.cgx_qsgd_dequant_reduce.argtypes = L.cgx_dequant_reduce.argtypes
@@ -264,6 +268,21 @@ def cgx_layered_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan
     _check(lib().cgx_layered_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
                                                        packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
            "cgx_layered_dequant_reduce_requantize")
+
+
+def cgx_layered_stats_workspace(plan: LayeredPlan) -> int:
+    """Bytes of device workspace cgx_layered_layer_sqerrors needs for this plan."""
+    nbytes = ctypes.c_size_t()
+    _check(lib().cgx_layered_stats_workspace(*plan.args, plan.dt, ctypes.byref(nbytes)), "cgx_layered_stats_workspace")
+    return int(nbytes.value)
+
+
+def cgx_layered_layer_sqerrors(grad, packed, meta, plan: LayeredPlan, sqerr, workspace, stream=None) -> None:
+    """sqerr (device float64[L]) = per-layer squared l2 norm of grad - dequantize(packed, meta)."""
+    _check(lib().cgx_layered_layer_sqerrors(grad.data_ptr(), packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt,
+                                            sqerr.data_ptr(), workspace.data_ptr(),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "cgx_layered_layer_sqerrors")
 
 
 def cgx_qsgd_sizes(plan: Plan) -> Tuple[int, int]:

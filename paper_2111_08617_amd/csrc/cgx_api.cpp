@@ -28,6 +28,7 @@ struct CachedPlan {
     // content
     cgx::PlanShape shape;
     int64_t n_tiles = 0;
+    int64_t plan_tiles = 0;     // tiles of the whole plan: n_tiles, or the sum over the launches of a layered plan
     bool odd_tiles = false;     // some vectorised quantized tile starts on an odd element index
     bool many_tails = false;    // the reduce kernel with the masked path for short ends of layers pays (see get_plan)
     Tile *d_tiles = nullptr;
@@ -175,6 +176,29 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
                      with_copies);
     if (tiles.size() > size_t(0xffffffffu)) return CGX_ERR_SIZE;
     plan->n_tiles = int64_t(tiles.size());
+    plan->plan_tiles = plan->n_tiles;
+    if (layer_buckets) {
+        // The per-layer statistics number the tiles of the WHOLE plan layer by layer; this table
+        // holds one launch's share of them, so its tiles take their numbers in that common order.
+        std::vector<int64_t> common(size_t(L) + 1, 0);
+        for (const Launch &other : launches_of(Buckets{bucket, layer_buckets}, L, off, bits)) {
+            std::vector<Tile> their_tiles;
+            std::vector<uint32_t> their_slots;
+            std::vector<int64_t> their_first;
+            cgx::build_tiles(L, off, bits, other.bucket, dt, chunks_per_tile, their_tiles, &their_slots, &their_first,
+                             layer_buckets, other.with_copies);
+            for (int32_t l = 0; l < L; l++) common[size_t(l) + 1] += their_first[size_t(l) + 1] - their_first[size_t(l)];
+        }
+        for (int32_t l = 0; l < L; l++) common[size_t(l) + 1] += common[size_t(l)];
+        if (common[size_t(L)] > int64_t(0xffffffffu)) return CGX_ERR_SIZE;
+        for (uint32_t &slot : slots) {
+            const size_t l = size_t(std::upper_bound(layer_first.begin(), layer_first.end(), int64_t(slot)) -
+                                    layer_first.begin()) - 1;
+            slot = uint32_t(common[l] + (int64_t(slot) - layer_first[l]));
+        }
+        layer_first = common;
+        plan->plan_tiles = common[size_t(L)];
+    }
     for (const Tile &t : tiles)
         if ((cgx::is_vector_kind(cgx::tile_kind(t)) || cgx::tile_kind(t) == cgx::kQuantTail) && (t.elem0 & 1))
             plan->odd_tiles = true;
@@ -340,26 +364,32 @@ int stats_tiles(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, i
 }
 
 int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
-                  const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, double *sqerr, void *workspace,
-                  size_t workspace_bytes, void *stream)
+                  const int64_t *off, const uint8_t *bits, const Buckets &buckets, int dt, double *sqerr,
+                  void *workspace, size_t workspace_bytes, void *stream)
 {
-    int rc = check_plan(scheme, n, L, off, bits, Buckets{bucket, nullptr}, dt);
+    int rc = check_plan(scheme, n, L, off, bits, buckets, dt);
     if (rc != CGX_OK) return rc;
     if (L == 0) return CGX_OK;
-    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, bucket, dt);
+    const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, buckets.uniform, dt, buckets.per_layer);
     if (!sqerr || (n > 0 && (!grad || !packed || !workspace)) || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
     if (misaligned(grad) || misaligned(packed) || misaligned(meta) || misaligned(workspace) ||
         (reinterpret_cast<uintptr_t>(sqerr) & 7u))
         return CGX_ERR_ALIGN;
-    PlanRef plan;
-    rc = get_plan(L, off, bits, bucket, dt, tile_length(kOtherCall, dt, n), &plan);
-    if (rc != CGX_OK) return rc;
-    if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
-    const hipError_t e = cgx::launch_layer_sqerrors(scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots,
-                                                    plan->n_tiles, plan->d_layer_first, L, bucket,
-                                                    static_cast<double *>(workspace), sqerr, launch_config(),
-                                                    static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+    // every launch leaves its tiles' partial sums in the workspace; the last one adds them up layer by layer
+    const std::vector<Launch> launches = launches_of(buckets, L, off, bits);
+    for (size_t i = 0; i < launches.size(); i++) {
+        PlanRef plan;
+        rc = get_plan(L, off, bits, launches[i].bucket, dt, tile_length(kOtherCall, dt, n), &plan, buckets.per_layer,
+                      launches[i].with_copies);
+        if (rc != CGX_OK) return rc;
+        if (workspace_bytes < size_t(plan->plan_tiles) * sizeof(double)) return CGX_ERR_SIZE;
+        const hipError_t e = cgx::launch_layer_sqerrors(
+            scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots, plan->n_tiles, plan->d_layer_first, L,
+            static_cast<double *>(workspace), sqerr, launch_config(), static_cast<hipStream_t>(stream),
+            i + 1 == launches.size());
+        if (e != hipSuccess) return CGX_ERR_HIP;
+    }
+    return CGX_OK;
 }
 
 }  // namespace
@@ -478,6 +508,34 @@ int cgx_layered_dequant_reduce_requantize(const void *const *packed, const void 
                       Buckets{32, buckets_per_layer}, int(dt), seed, packed_out, meta_out, stream);
 }
 
+int cgx_layered_stats_workspace(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                const int32_t *buckets_per_layer, cgx_dtype dt, size_t *bytes)
+{
+    if (!bytes || (L > 0 && !buckets_per_layer)) return CGX_ERR_NULL;
+    const Buckets buckets{32, buckets_per_layer};
+    const int rc = check_plan(cgx::kSchemeMinMax, n, L, layer_offsets, bits_per_layer, buckets, int(dt));
+    if (rc != CGX_OK) return rc;
+    size_t tiles_of_plan = 0;
+    for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer)) {
+        std::vector<Tile> tiles;
+        cgx::build_tiles(L, layer_offsets, bits_per_layer, launch.bucket, int(dt), tile_length(kOtherCall, int(dt), n),
+                         tiles, nullptr, nullptr, buckets_per_layer, launch.with_copies);
+        tiles_of_plan += tiles.size();
+    }
+    *bytes = tiles_of_plan * sizeof(double);
+    return CGX_OK;
+}
+
+int cgx_layered_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
+                               const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                               const int32_t *buckets_per_layer, cgx_dtype dt, double *sqerr, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return sqerrors_impl(cgx::kSchemeMinMax, grad, packed, meta, n, L, layer_offsets, bits_per_layer,
+                         Buckets{32, buckets_per_layer}, int(dt), sqerr, workspace, workspace_bytes, stream);
+}
+
 int cgx_qsgd_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                    int32_t bucket, cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes)
 {
@@ -548,16 +606,16 @@ int cgx_layer_sqerrors(const void *grad, const void *packed, const void *meta, i
                        const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
                        double *sqerr, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return sqerrors_impl(cgx::kSchemeMinMax, grad, packed, meta, n, L, layer_offsets, bits_per_layer, bucket, int(dt),
-                         sqerr, workspace, workspace_bytes, stream);
+    return sqerrors_impl(cgx::kSchemeMinMax, grad, packed, meta, n, L, layer_offsets, bits_per_layer,
+                         Buckets{bucket, nullptr}, int(dt), sqerr, workspace, workspace_bytes, stream);
 }
 
 int cgx_qsgd_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
                             const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
                             cgx_dtype dt, double *sqerr, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return sqerrors_impl(cgx::kSchemeNormSign, grad, packed, meta, n, L, layer_offsets, bits_per_layer, bucket,
-                         int(dt), sqerr, workspace, workspace_bytes, stream);
+    return sqerrors_impl(cgx::kSchemeNormSign, grad, packed, meta, n, L, layer_offsets, bits_per_layer,
+                         Buckets{bucket, nullptr}, int(dt), sqerr, workspace, workspace_bytes, stream);
 }
 
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,

@@ -57,8 +57,10 @@ hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, cons
                                 const LaunchConfig &cfg, hipStream_t stream);
 hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const void *packed, const void *meta,
                                  const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
-                                 const int64_t *layer_first, int32_t L, int32_t bucket, double *partial,
-                                 double *out, const LaunchConfig &cfg, hipStream_t stream);
+                                 const int64_t *layer_first, int32_t L, double *partial,
+                                 double *out, const LaunchConfig &cfg, hipStream_t stream, bool sum_layers = true);
+// (sum_layers = false: only the tiles' partial sums are written; a plan served by several tile
+// tables adds them up after the last one)
 
 // Measurement aid: streams read_bytes in and write_bytes out (multiples of 16) with the access
 // style of the kernels and no arithmetic; see cgx_stream_probe in cgx.h.

@@ -212,8 +212,8 @@ hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, cons
 
 hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const void *packed, const void *meta,
                                  const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
-                                 const int64_t *layer_first, int32_t L, int32_t bucket, double *partial,
-                                 double *out, const LaunchConfig &cfg, hipStream_t stream)
+                                 const int64_t *layer_first, int32_t L, double *partial,
+                                 double *out, const LaunchConfig &cfg, hipStream_t stream, bool sum_layers)
 {
     if (L == 0) return hipSuccess;
     const dim3 block(kBlock);
@@ -226,11 +226,11 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
             scheme == kSchemeNormSign
                 ? (dt == CGX_F16 ? sqerror_kernel<kNormSign, CGX_F16> : sqerror_kernel<kNormSign, CGX_F32>)
                 : (dt == CGX_F16 ? sqerror_kernel<kMinMax, CGX_F16> : sqerror_kernel<kMinMax, CGX_F32>);
-        (void)bucket;
         hipLaunchKernelGGL(kernel, grid, block, 0, stream, chunk, grad, tiles, slots, n_tiles, partial);
     }
-    hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
-                       static_cast<const double *>(partial), layer_first, out);
+    if (sum_layers)
+        hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
+                           static_cast<const double *>(partial), layer_first, out);
     return hipGetLastError();
 }
 

@@ -133,3 +133,40 @@ def test_adaptive_round_with_widths_and_bucket_sizes(torch, oracle):
     assert len(set(buckets[bits != 0].tolist())) > 1, "the round should mix bucket sizes"
     sub = wl.Workload("bert_head", [tuple(s) for s in w.shapes[:L]], bits, 512, w.dt, 3, w.seed, w.draw, w.scales[:L])
     cycle(torch, oracle, sub, buckets, "adaptive round, layered")
+
+
+def gpu_layered_sqerrors(torch, grad, packed, meta, plan):
+    need = cgx.cgx_layered_stats_workspace(plan)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    out = torch.full((plan.L + 2,), -1.0, dtype=torch.float64, device="cuda")
+    m = dev(torch, meta.reshape(-1)) if meta.size else torch.zeros(4, device="cuda")
+    cgx.cgx_layered_layer_sqerrors(dev(torch, grad), dev(torch, packed), m, plan, out, ws)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    assert (res[plan.L:] == -1.0).all(), "wrote past the L outputs"
+    return res[:plan.L], need
+
+
+@pytest.mark.parametrize("seed", range(0, 24, 2))
+def test_squared_errors_of_layered_chunks(torch, oracle, seed):
+    """Per-layer squared compression errors of chunks with a bucket size per layer: within
+    1e-12 relative of the oracle (binary64 sums in a fixed order), zeros exactly."""
+    w = wl.random_plan(seed)
+    if w.n == 0:
+        pytest.skip("empty plan")
+    buckets = np.random.default_rng(100 + seed).choice(BUCKETS, w.L).astype(np.int32)
+    plan = cgx.LayeredPlan(w.offsets, w.bits, buckets, w.dt)
+    g = w.gradient()
+    p, m = oracle.layered_quantize(g, w.offsets, w.bits, buckets, 4, w.dt)
+    ref = oracle.layered_layer_sqerrors(g, p, m, w.offsets, w.bits, buckets, w.dt)
+    got, need = gpu_layered_sqerrors(torch, g, p, m, plan)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - ref) <= 1e-12 * ref).all(), f"layers {np.nonzero(np.abs(got - ref) > 1e-12 * ref)[0][:5]}"
+    assert (got[ref == 0] == 0).all()
+    if need >= 16:                      # (an empty tensor has a null pointer: another error)
+        small = torch.empty(need - 8, dtype=torch.uint8, device="cuda")
+        out = torch.zeros(plan.L, dtype=torch.float64, device="cuda")
+        mm = dev(torch, m.reshape(-1)) if m.size else torch.zeros(4, device="cuda")
+        with pytest.raises(cgx.CgxError) as e:
+            cgx.cgx_layered_layer_sqerrors(dev(torch, g), dev(torch, p), mm, plan, out, small)
+        assert e.value.status == -2
