@@ -71,6 +71,8 @@ def _load():
         lib.oracle_layered_quantize.argtypes = [c.c_void_p] + layered + [c.c_uint64, c.c_int32, c.c_void_p, c.c_void_p]
         lib.oracle_layered_dequant_reduce.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_layered_dequant_reduce_add.argtypes = [c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_int32] + \
+            layered + [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_layered_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + layered + [c.c_int32, c.c_void_p]
         _lib = lib
     return _lib
@@ -245,8 +247,9 @@ def layered_quantize(grad, offsets, bits, buckets, seed: int, dt: int = F32):
     return packed, meta
 
 
-def layered_dequant_reduce(packed_list, meta_list, offsets, bits, buckets, dt: int = F32):
-    """dequant_reduce() with a bucket size per layer; returns sum32, sum64 and abs64."""
+def layered_dequant_reduce(packed_list, meta_list, offsets, bits, buckets, dt: int = F32, local=None):
+    """dequant_reduce() with a bucket size per layer; returns sum32, sum64 and abs64.  `local`
+    (float32 or float16 array of n elements) is the rank's own uncompressed term, added first."""
     off, bt, n, L = _plan(offsets, bits)
     bk = _layer_buckets(buckets, L)
     W = len(packed_list)
@@ -262,8 +265,15 @@ def layered_dequant_reduce(packed_list, meta_list, offsets, bits, buckets, dt: i
     mp = (ctypes.c_void_p * W)(*[m.ctypes.data for m in mt])
     out = {"sum32": np.zeros(n, dtype=np.float32), "sum64": np.zeros(n, dtype=np.float64),
            "abs64": np.zeros(n, dtype=np.float64)}
-    _check(_load().oracle_layered_dequant_reduce(pp, mp, W, n, L, _ptr(off), _ptr(bt), _ptr(bk), dt, _ptr(out["sum32"]),
-                                                 _ptr(out["sum64"]), _ptr(out["abs64"])), "layered_dequant_reduce")
+    loc, loc_dt = None, F32
+    if local is not None:
+        loc = np.ascontiguousarray(local)
+        if loc.dtype not in (np.float32, np.float16) or loc.size != n:
+            raise ValueError("local must be float32 or float16 with n elements")
+        loc_dt = F16 if loc.dtype == np.float16 else F32
+    _check(_load().oracle_layered_dequant_reduce_add(_ptr(loc), loc_dt, pp, mp, W, n, L, _ptr(off), _ptr(bt), _ptr(bk),
+                                                     dt, _ptr(out["sum32"]), _ptr(out["sum64"]), _ptr(out["abs64"])),
+           "layered_dequant_reduce")
     return out
 
 

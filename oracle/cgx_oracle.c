@@ -465,6 +465,16 @@ int oracle_layered_dequant_reduce(const uint8_t *const *packed, const float *con
     return reduce_impl(NULL, DT_F32, packed, meta, W, n, L, off, bits, 32, layer_buckets, dt, sum32, sum64, abs64);
 }
 
+int oracle_layered_dequant_reduce_add(const void *local, int32_t local_dt, const uint8_t *const *packed,
+                                      const float *const *meta, int32_t W, int64_t n, int32_t L,
+                                      const int64_t *off, const uint8_t *bits, const int32_t *layer_buckets,
+                                      int32_t dt, float *sum32, double *sum64, double *abs64)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return reduce_impl(local, local_dt, packed, meta, W, n, L, off, bits, 32, layer_buckets, dt, sum32, sum64,
+                       abs64);
+}
+
 int oracle_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W,
                           int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
                           int32_t bucket, int32_t dt, float *sum32, double *sum64, double *abs64)

@@ -108,3 +108,25 @@ def test_squared_errors_are_those_of_the_layers_alone(oracle, seed):
         assert got[l] == ref[0], f"layer {l}"
         pos += pb
         mpos += mb // 4
+
+
+def test_local_addend_comes_first_in_the_layered_reduce(oracle):
+    """With a local term the layered reduce is the single-size one layer by layer as well, and with
+    W = 1 and no local term it is plain dequantization of the chunk."""
+    off, bits, buckets, rng = plan(301)
+    n = int(off[-1])
+    chunks = [oracle.layered_quantize(rng.standard_normal(n).astype(np.float32), off, bits, buckets, 5 + w) for w in range(2)]
+    local = rng.standard_normal(n).astype(np.float16)
+    got = oracle.layered_dequant_reduce([c[0] for c in chunks], [c[1] for c in chunks], off, bits, buckets, local=local)
+    pos = mpos = 0
+    for l in range(bits.size):
+        a, b = int(off[l]), int(off[l + 1])
+        if a == b:
+            continue
+        pb, mb = oracle.sizes([0, b - a], [bits[l]], int(buckets[l]))
+        ref = oracle.dequant_reduce([c[0][pos:pos + pb] for c in chunks],
+                                    [c[1].reshape(-1)[mpos:mpos + mb // 4] for c in chunks],
+                                    [0, b - a], [bits[l]], int(buckets[l]), local=local[a:b])
+        assert np.array_equal(got["sum32"][a:b], ref["sum32"]) and np.array_equal(got["sum64"][a:b], ref["sum64"])
+        pos += pb
+        mpos += mb // 4
