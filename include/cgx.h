@@ -167,7 +167,7 @@ int cgx_dequant_reduce_requantize(const void *const *packed, const void *const *
                                   uint64_t seed, void *packed_out, void *meta_out, void *stream);
 
 /*
- * The same calls with a bucket size per layer (paper Sec. 4.1: compression parameters are
+ * The calls above with a bucket size per layer (paper Sec. 4.1: compression parameters are
  * per layer, the bucket size among them; Sec. "Layer-wise Adaptive Quantization": bit-widths
  * and bucket sizes are mapped to the layers).  buckets_per_layer[0..L-1] (host, int32) gives
  * every layer its own bucket size, each a multiple of 32 in [32, 8192] (CGX_ERR_BUCKET
@@ -187,6 +187,14 @@ int cgx_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *
 int cgx_layered_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
                                int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                                const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream);
+int cgx_layered_dequant_reduce_add(const void *local, cgx_dtype local_dt, const void *const *packed,
+                                   const void *const *meta, int32_t W, int64_t n, int32_t L,
+                                   const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                   const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream);
+int cgx_layered_dequantize(const void *packed, const void *meta, int64_t n, int32_t L,
+                           const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                           const int32_t *buckets_per_layer, cgx_dtype dt, cgx_dtype out_dt, void *out,
+                           void *stream);
 int cgx_layered_requantize(const float *sum, int64_t n, int32_t L, const int64_t *layer_offsets,
                            const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
                            void *packed, void *meta, void *stream);

@@ -26,7 +26,8 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_qsgd_dequant_reduce_requantize", "cgx_layer_stats_workspace", "cgx_layer_sqnorms",
            "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
            "cgx_assign_buckets_from_bits", "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
-           "cgx_layered_dequant_reduce_requantize", "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors",
+           "cgx_layered_dequant_reduce_requantize", "cgx_layered_dequant_reduce_add", "cgx_layered_dequantize",
+           "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors",
            "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
@@ -71,6 +72,9 @@ def lib() -> ctypes.CDLL:
             [c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_layered_dequant_reduce_requantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int32] + layered + \
             [c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.cgx_layered_dequant_reduce_add.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_void_p, c.c_int32] + layered + \
+            [c.c_int, c.c_void_p, c.c_void_p]
+        L.cgx_layered_dequantize.argtypes = [c.c_void_p, c.c_void_p] + layered + [c.c_int, c.c_int, c.c_void_p, c.c_void_p]
         L.cgx_layered_stats_workspace.argtypes = layered + [c.c_int, c.POINTER(c.c_size_t)]
         L.cgx_layered_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + layered + \
             [c.c_int, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -268,6 +272,20 @@ def cgx_layered_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan
     _check(lib().cgx_layered_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
                                                        packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
            "cgx_layered_dequant_reduce_requantize")
+
+
+def cgx_layered_dequant_reduce_add(local, local_dt: int, packed: Sequence, meta: Sequence, plan: LayeredPlan, total,
+                                   stream=None) -> None:
+    """As cgx_dequant_reduce_add, every layer with its own bucket size."""
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_layered_dequant_reduce_add(local.data_ptr(), local_dt, pp, mp, W, *plan.args, plan.dt,
+                                                total.data_ptr(), _stream(stream)), "cgx_layered_dequant_reduce_add")
+
+
+def cgx_layered_dequantize(packed, meta, plan: LayeredPlan, out_dt: int, out, stream=None) -> None:
+    """As cgx_dequantize, every layer with its own bucket size."""
+    _check(lib().cgx_layered_dequantize(packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt, out_dt,
+                                        out.data_ptr(), _stream(stream)), "cgx_layered_dequantize")
 
 
 def cgx_layered_stats_workspace(plan: LayeredPlan) -> int:

@@ -498,6 +498,28 @@ int cgx_layered_dequant_reduce(const void *const *packed, const void *const *met
                        Buckets{32, buckets_per_layer}, int(dt), nullptr, CGX_F32, false, sum, CGX_F32, stream);
 }
 
+int cgx_layered_dequant_reduce_add(const void *local, cgx_dtype local_dt, const void *const *packed,
+                                   const void *const *meta, int32_t W, int64_t n, int32_t L,
+                                   const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                   const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    if (local_dt != CGX_F32 && local_dt != CGX_F16) return CGX_ERR_DTYPE;
+    return reduce_impl(cgx::kSchemeMinMax, packed, meta, W, n, L, layer_offsets, bits_per_layer,
+                       Buckets{32, buckets_per_layer}, int(dt), local, int(local_dt), true, sum, CGX_F32, stream);
+}
+
+int cgx_layered_dequantize(const void *packed, const void *meta, int64_t n, int32_t L, const int64_t *layer_offsets,
+                           const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, cgx_dtype dt,
+                           cgx_dtype out_dt, void *out, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    if (out_dt != CGX_F32 && out_dt != CGX_F16) return CGX_ERR_DTYPE;
+    const void *const p[1] = {packed}, *const m[1] = {meta};
+    return reduce_impl(cgx::kSchemeMinMax, p, m, 1, n, L, layer_offsets, bits_per_layer, Buckets{32, buckets_per_layer},
+                       int(dt), nullptr, CGX_F32, false, out, int(out_dt), stream);
+}
+
 int cgx_layered_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
                                           int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                                           const int32_t *buckets_per_layer, cgx_dtype dt, uint64_t seed,

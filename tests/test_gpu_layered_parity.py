@@ -170,3 +170,37 @@ def test_squared_errors_of_layered_chunks(torch, oracle, seed):
         with pytest.raises(cgx.CgxError) as e:
             cgx.cgx_layered_layer_sqerrors(dev(torch, g), dev(torch, p), mm, plan, out, small)
         assert e.value.status == -2
+
+
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+def test_layered_dequantize_and_local_addend(torch, oracle, dt):
+    """cgx_layered_dequantize into binary32 / binary16 and cgx_layered_dequant_reduce_add with a
+    binary32 / binary16 local term, on a plan that mixes all three size classes."""
+    sizes = [2048 * 3, 100, 2048 + 700, 8, 8192 + 4096, 33, 2048 * 2, 640]
+    bits = np.array([4, 0, 3, 0, 8, 2, 1, 5], np.uint8)
+    buckets = np.array([128, 32, 64, 512, 4096, 96, 2048, 32], np.int32)
+    w = wl.Workload("mix", [(s,) for s in sizes], bits, 128, dt, 4, 321, wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    plan = cgx.LayeredPlan(w.offsets, w.bits, buckets, w.dt)
+    chunks, metas = zip(*[oracle.layered_quantize(w.gradient(p), w.offsets, w.bits, buckets, 50 + p, w.dt) for p in range(20)])
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m.reshape(-1)) for m in metas]
+    one = oracle.layered_dequant_reduce([chunks[0]], [metas[0]], w.offsets, w.bits, buckets, w.dt)["sum32"]
+    for out_dt, tdt in ((wl.F32, torch.float32), (wl.F16, torch.float16)):
+        out = torch.full((w.n + 16,), 9.0, dtype=tdt, device="cuda")
+        cgx.cgx_layered_dequantize(dp[0], dm[0], plan, out_dt, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert (got[w.n:] == 9.0).all()
+        want = one if out_dt == wl.F32 else oracle.float_to_half(one).view(np.float16)
+        assert got[:w.n].tobytes() == want.tobytes(), f"dequantize to {'f16' if out_dt else 'f32'}"
+    for W in (3, 20):
+        for local in (w.gradient(99).astype(np.float32), w.gradient(99).astype(np.float16)):
+            total = torch.full((w.n + 16,), 9.0, dtype=torch.float32, device="cuda")
+            cgx.cgx_layered_dequant_reduce_add(dev(torch, local), wl.F16 if local.dtype == np.float16 else wl.F32,
+                                               dp[:W], dm[:W], plan, total)
+            torch.cuda.synchronize()
+            got = total.cpu().numpy()
+            assert (got[w.n:] == 9.0).all()
+            ref = oracle.layered_dequant_reduce(list(chunks[:W]), list(metas[:W]), w.offsets, w.bits, buckets, w.dt,
+                                                local=local)
+            assert np.array_equal(got[:w.n].view(np.uint32), ref["sum32"].view(np.uint32)), f"W={W} {local.dtype}"
