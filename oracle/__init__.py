@@ -73,6 +73,11 @@ def _load():
             [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
         lib.oracle_layered_dequant_reduce_add.argtypes = [c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_int32] + \
             layered + [c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        lib.oracle_qsgd_quantize_window.argtypes = [c.c_void_p] + plan + [c.c_uint64, c.c_int32, c.c_uint64, c.c_void_p,
+                                                                          c.c_void_p]
+        lib.oracle_qsgd_layered_sizes.argtypes = lib.oracle_layered_sizes.argtypes
+        lib.oracle_qsgd_layered_quantize.argtypes = lib.oracle_layered_quantize.argtypes
+        lib.oracle_qsgd_layered_dequant_reduce.argtypes = lib.oracle_layered_dequant_reduce.argtypes
         lib.oracle_layered_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + layered + [c.c_int32, c.c_void_p]
         _lib = lib
     return _lib
@@ -303,8 +308,9 @@ def qsgd_sizes(offsets, bits, bucket: int, dt: int = F32):
     return int(pb.value), int(mb.value)
 
 
-def qsgd_quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=None):
-    """Returns (packed uint8[packed_bytes], meta float32[n_buckets] = unit)."""
+def qsgd_quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, draws=None, index_base: int = 0):
+    """Returns (packed uint8[packed_bytes], meta float32[n_buckets] = unit).
+    index_base: position of grad[0] in the whole buffer when grad is a window of it."""
     off, bt, n, L = _plan(offsets, bits)
     g = _grad(grad, n, dt)
     pb, mb = qsgd_sizes(off, bt, bucket, dt)
@@ -312,8 +318,8 @@ def qsgd_quantize(grad, offsets, bits, bucket: int, seed: int, dt: int = F32, dr
     meta = np.zeros(mb // 4, dtype=np.float32)
     lib = _load()
     if draws is None:
-        rc = lib.oracle_qsgd_quantize(_ptr(g), n, L, _ptr(off), _ptr(bt), bucket, seed & (2**64 - 1), dt,
-                                      _ptr(packed), _ptr(meta))
+        rc = lib.oracle_qsgd_quantize_window(_ptr(g), n, L, _ptr(off), _ptr(bt), bucket, seed & (2**64 - 1), dt,
+                                             index_base, _ptr(packed), _ptr(meta))
     else:
         d = np.ascontiguousarray(draws, dtype=np.uint16)
         if d.size != n:
@@ -374,4 +380,49 @@ def layer_sqerrors(grad, packed, meta, offsets, bits, bucket: int, dt: int = F32
     out = np.zeros(L, dtype=np.float64)
     _check(_load().oracle_layer_sqerrors(scheme, _ptr(g), _ptr(pk), _ptr(mt), n, L, _ptr(off), _ptr(bt), bucket, dt,
                                          _ptr(out)), "layer_sqerrors")
+    return out
+
+
+# ---- the norm-and-sign form with a bucket size per layer
+
+def qsgd_layered_sizes(offsets, bits, buckets, dt: int = F32):
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    pb, mb = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(_load().oracle_qsgd_layered_sizes(n, L, _ptr(off), _ptr(bt), _ptr(bk), dt, ctypes.byref(pb),
+                                             ctypes.byref(mb)), "qsgd_layered_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def qsgd_layered_quantize(grad, offsets, bits, buckets, seed: int, dt: int = F32):
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    g = _grad(grad, n, dt)
+    pb, mb = qsgd_layered_sizes(off, bt, bk, dt)
+    packed = np.zeros(pb, dtype=np.uint8)
+    meta = np.zeros(mb // 4, dtype=np.float32)
+    _check(_load().oracle_qsgd_layered_quantize(_ptr(g), n, L, _ptr(off), _ptr(bt), _ptr(bk), seed & (2**64 - 1), dt,
+                                                _ptr(packed), _ptr(meta)), "qsgd_layered_quantize")
+    return packed, meta
+
+
+def qsgd_layered_dequant_reduce(packed_list, meta_list, offsets, bits, buckets, dt: int = F32):
+    off, bt, n, L = _plan(offsets, bits)
+    bk = _layer_buckets(buckets, L)
+    W = len(packed_list)
+    if W < 1 or len(meta_list) != W:
+        raise ValueError("need W >= 1 packed chunks and as many meta arrays")
+    pb, mb = qsgd_layered_sizes(off, bt, bk, dt)
+    pk = [np.ascontiguousarray(p, dtype=np.uint8) for p in packed_list]
+    mt = [np.ascontiguousarray(m, dtype=np.float32) for m in meta_list]
+    for p, m in zip(pk, mt):
+        if p.size != pb or m.size * 4 != mb:
+            raise ValueError("chunk sizes do not match the plan")
+    pp = (ctypes.c_void_p * W)(*[p.ctypes.data for p in pk])
+    mp = (ctypes.c_void_p * W)(*[m.ctypes.data for m in mt])
+    out = {"sum32": np.zeros(n, dtype=np.float32), "sum64": np.zeros(n, dtype=np.float64),
+           "abs64": np.zeros(n, dtype=np.float64)}
+    _check(_load().oracle_qsgd_layered_dequant_reduce(pp, mp, W, n, L, _ptr(off), _ptr(bt), _ptr(bk), dt,
+                                                      _ptr(out["sum32"]), _ptr(out["sum64"]), _ptr(out["abs64"])),
+           "qsgd_layered_dequant_reduce")
     return out

@@ -537,17 +537,33 @@ int oracle_qsgd_sizes(int64_t n, int32_t L, const int64_t *off, const uint8_t *b
     return ORACLE_OK;
 }
 
-static int qsgd_quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off,
-                              const uint8_t *bits, int32_t bucket, uint64_t seed, int32_t dt,
-                              const uint16_t *draws, uint8_t *packed, float *meta)
+int oracle_qsgd_layered_sizes(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                              const int32_t *layer_buckets, int32_t dt, uint64_t *packed_bytes,
+                              uint64_t *meta_bytes)
 {
-    int rc = check_plan(n, L, off, bits, bucket, dt);
+    uint64_t mb = 0;
+    int rc = oracle_layered_sizes(n, L, off, bits, layer_buckets, dt, packed_bytes, &mb);
+    if (rc) return rc;
+    if (check_qsgd_bits(L, bits)) return ORACLE_ERR_ARG;
+    if (meta_bytes) *meta_bytes = mb / 2;
+    return ORACLE_OK;
+}
+
+static int qsgd_quantize_impl(const void *grad, int64_t n, int32_t L, const int64_t *off,
+                              const uint8_t *bits, int32_t uniform_bucket, const int32_t *layer_buckets,
+                              uint64_t seed, int32_t dt, const uint16_t *draws, uint64_t index_base,
+                              uint8_t *packed, float *meta)
+{
+    int rc = check_plan(n, L, off, bits, layer_buckets ? 32 : uniform_bucket, dt);
+    if (rc) return rc;
+    rc = check_layer_buckets(L, layer_buckets);
     if (rc) return rc;
     if (check_qsgd_bits(L, bits)) return ORACLE_ERR_ARG;
     uint64_t seg_start = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         int64_t first = off[l], len = off[l + 1] - off[l];
         int b = bits[l];
+        const int32_t bucket = bucket_of(l, uniform_bucket, layer_buckets);
         uint64_t seg_bytes, n_buckets;
         layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
         if (len == 0) continue;
@@ -575,7 +591,7 @@ static int qsgd_quantize_impl(const void *grad, int64_t n, int32_t L, const int6
                 meta[bucket0 + k] = unit;
                 for (int64_t j = j0; j < j0 + count; j++) {
                     uint64_t i = (uint64_t)(first + j);
-                    uint32_t u16 = draws ? draws[i] : oracle_u16(seed, i);
+                    uint32_t u16 = draws ? draws[i] : oracle_u16(seed, index_base + i);
                     float x = load_elem(grad, first + j, dt);
                     float S = fabsf(x) * inv16;
                     uint64_t T;
@@ -599,7 +615,23 @@ static int qsgd_quantize_impl(const void *grad, int64_t n, int32_t L, const int6
 int oracle_qsgd_quantize(const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
                          int32_t bucket, uint64_t seed, int32_t dt, uint8_t *packed, float *meta)
 {
-    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, seed, dt, NULL, packed, meta);
+    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, NULL, seed, dt, NULL, 0, packed, meta);
+}
+
+/* A window of a larger buffer (see oracle_quantize_window), and a bucket size per layer. */
+int oracle_qsgd_quantize_window(const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                                int32_t bucket, uint64_t seed, int32_t dt, uint64_t index_base, uint8_t *packed,
+                                float *meta)
+{
+    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, NULL, seed, dt, NULL, index_base, packed, meta);
+}
+
+int oracle_qsgd_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                                 const int32_t *layer_buckets, uint64_t seed, int32_t dt, uint8_t *packed,
+                                 float *meta)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return qsgd_quantize_impl(grad, n, L, off, bits, 32, layer_buckets, seed, dt, NULL, 0, packed, meta);
 }
 
 int oracle_qsgd_quantize_with_draws(const void *grad, int64_t n, int32_t L, const int64_t *off,
@@ -607,21 +639,24 @@ int oracle_qsgd_quantize_with_draws(const void *grad, int64_t n, int32_t L, cons
                                     uint8_t *packed, float *meta)
 {
     if (!draws) return ORACLE_ERR_ARG;
-    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, 0, dt, draws, packed, meta);
+    return qsgd_quantize_impl(grad, n, L, off, bits, bucket, NULL, 0, dt, draws, 0, packed, meta);
 }
 
 /* Sum over the W peers of the decoded values; outputs as in oracle_dequant_reduce. */
-int oracle_qsgd_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W, int64_t n,
-                               int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int32_t dt,
-                               float *sum32, double *sum64, double *abs64)
+static int qsgd_reduce_impl(const uint8_t *const *packed, const float *const *meta, int32_t W, int64_t n,
+                            int32_t L, const int64_t *off, const uint8_t *bits, int32_t uniform_bucket,
+                            const int32_t *layer_buckets, int32_t dt, float *sum32, double *sum64, double *abs64)
 {
-    int rc = check_plan(n, L, off, bits, bucket, dt);
+    int rc = check_plan(n, L, off, bits, layer_buckets ? 32 : uniform_bucket, dt);
+    if (rc) return rc;
+    rc = check_layer_buckets(L, layer_buckets);
     if (rc) return rc;
     if (check_qsgd_bits(L, bits) || W < 1 || !packed || !meta) return ORACLE_ERR_ARG;
     uint64_t seg_start = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         int64_t first = off[l], len = off[l + 1] - off[l];
         int b = bits[l];
+        const int32_t bucket = bucket_of(l, uniform_bucket, layer_buckets);
         uint64_t seg_bytes, n_buckets;
         layer_extent(len, b, bucket, dt, &seg_bytes, &n_buckets);
         if (len == 0) continue;
@@ -656,6 +691,22 @@ int oracle_qsgd_dequant_reduce(const uint8_t *const *packed, const float *const 
         bucket0 += n_buckets;
     }
     return ORACLE_OK;
+}
+
+int oracle_qsgd_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W, int64_t n,
+                               int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int32_t dt,
+                               float *sum32, double *sum64, double *abs64)
+{
+    return qsgd_reduce_impl(packed, meta, W, n, L, off, bits, bucket, NULL, dt, sum32, sum64, abs64);
+}
+
+int oracle_qsgd_layered_dequant_reduce(const uint8_t *const *packed, const float *const *meta, int32_t W,
+                                       int64_t n, int32_t L, const int64_t *off, const uint8_t *bits,
+                                       const int32_t *layer_buckets, int32_t dt, float *sum32, double *sum64,
+                                       double *abs64)
+{
+    if (L > 0 && !layer_buckets) return ORACLE_ERR_ARG;
+    return qsgd_reduce_impl(packed, meta, W, n, L, off, bits, 32, layer_buckets, dt, sum32, sum64, abs64);
 }
 
 /* ======================================================================== *

@@ -130,3 +130,52 @@ def test_local_addend_comes_first_in_the_layered_reduce(oracle):
         assert np.array_equal(got["sum32"][a:b], ref["sum32"]) and np.array_equal(got["sum64"][a:b], ref["sum64"])
         pos += pb
         mpos += mb // 4
+
+
+def qsgd_plan(seed):
+    off, bits, buckets, rng = plan(seed)
+    return off, np.where(bits == 1, 2, bits).astype(np.uint8), buckets, rng
+
+
+@pytest.mark.parametrize("dt", [F32, F16])
+@pytest.mark.parametrize("seed", range(6))
+def test_norm_and_sign_form_layer_by_layer(oracle, seed, dt):
+    """The norm-and-sign quantizer with a bucket size per layer: every layer is the single-size
+    quantizer on its window, and the reduce is the single-size reduce of the layers' pieces."""
+    off, bits, buckets, rng = qsgd_plan(400 + seed)
+    n = int(off[-1])
+    W = 2
+    grads = [(rng.standard_normal(n) * 2).astype(np.float16 if dt == F16 else np.float32) for _ in range(W)]
+    chunks = [oracle.qsgd_layered_quantize(g, off, bits, buckets, 7 + w, dt) for w, g in enumerate(grads)]
+    assert (chunks[0][0].size, chunks[0][1].size * 4) == oracle.qsgd_layered_sizes(off, bits, buckets, dt)
+    got = oracle.qsgd_layered_dequant_reduce([c[0] for c in chunks], [c[1] for c in chunks], off, bits, buckets, dt)
+    pos = mpos = 0
+    for l in range(bits.size):
+        a, b = int(off[l]), int(off[l + 1])
+        if a == b:
+            continue
+        pieces = []
+        for w in range(W):
+            pl, ml = oracle.qsgd_quantize(grads[w][a:b], [0, b - a], [bits[l]], int(buckets[l]), 7 + w, dt, index_base=a)
+            assert np.array_equal(chunks[w][0][pos:pos + pl.size], pl), f"layer {l} peer {w}"
+            assert np.array_equal(chunks[w][1][mpos:mpos + ml.size].view(np.uint32), ml.view(np.uint32)), f"layer {l}"
+            pieces.append((pl, ml))
+        ref = oracle.qsgd_dequant_reduce([p for p, _ in pieces], [m for _, m in pieces], [0, b - a], [bits[l]],
+                                         int(buckets[l]), dt)
+        for key in ("sum32", "sum64", "abs64"):
+            assert np.array_equal(got[key][a:b], ref[key]), f"layer {l} {key}"
+        pos += pieces[0][0].size
+        mpos += pieces[0][1].size
+    assert pos == chunks[0][0].size and mpos == chunks[0][1].size
+
+
+def test_norm_and_sign_window_equals_the_slice_of_the_whole(oracle):
+    """The window form of the norm-and-sign quantizer (used by the pin above): a window of a
+    single-layer buffer that starts on a bucket boundary gives the slice of the whole chunk."""
+    rng = np.random.default_rng(9)
+    n, bucket, b = 4096, 256, 5
+    g = rng.standard_normal(n).astype(np.float32)
+    p, m = oracle.qsgd_quantize(g, [0, n], [b], bucket, 13)
+    a = 1024
+    pw, mw = oracle.qsgd_quantize(g[a:], [0, n - a], [b], bucket, 13, index_base=a)
+    assert np.array_equal(pw, p[a * b // 8:]) and np.array_equal(mw.view(np.uint32), m[a // bucket:].view(np.uint32))
