@@ -246,6 +246,22 @@ int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *co
                                        const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
                                        uint64_t seed, void *packed_out, void *meta_out, void *stream);
 
+/* The norm-and-sign calls with a bucket size per layer (see the cgx_layered_* calls above). */
+int cgx_qsgd_layered_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                           const int32_t *buckets_per_layer, cgx_dtype dt, size_t *packed_bytes,
+                           size_t *meta_bytes);
+int cgx_qsgd_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                              const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
+                              cgx_dtype dt, void *packed, void *meta, void *stream);
+int cgx_qsgd_layered_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                                    int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                    const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream);
+int cgx_qsgd_layered_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W,
+                                               int64_t n, int32_t L, const int64_t *layer_offsets,
+                                               const uint8_t *bits_per_layer, const int32_t *buckets_per_layer,
+                                               cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
+                                               void *stream);
+
 /*
  * Per-layer statistics for the layer-wise adaptive scheme (paper Sec. "Layer-wise
  * Adaptive Quantization").  Sums are binary64; squares of binary32 values and

@@ -27,7 +27,8 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
            "cgx_assign_buckets_from_bits", "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
            "cgx_layered_dequant_reduce_requantize", "cgx_layered_dequant_reduce_add", "cgx_layered_dequantize",
-           "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors",
+           "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors", "cgx_qsgd_layered_sizes",
+           "cgx_qsgd_layered_quantize", "cgx_qsgd_layered_dequant_reduce", "cgx_qsgd_layered_dequant_reduce_requantize",
            "cgx_plan_tiles", "cgx_stream_probe",
            "cgx_status_string", "cgx_shutdown")
 
@@ -78,6 +79,10 @@ def lib() -> ctypes.CDLL:
         L.cgx_layered_stats_workspace.argtypes = layered + [c.c_int, c.POINTER(c.c_size_t)]
         L.cgx_layered_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + layered + \
             [c.c_int, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.cgx_qsgd_layered_sizes.argtypes = L.cgx_layered_sizes.argtypes
+        L.cgx_qsgd_layered_quantize.argtypes = L.cgx_layered_quantize.argtypes
+        L.cgx_qsgd_layered_dequant_reduce.argtypes = L.cgx_layered_dequant_reduce.argtypes
+        L.cgx_qsgd_layered_dequant_reduce_requantize.argtypes = L.cgx_layered_dequant_reduce_requantize.argtypes
         L.cgx_qsgd_sizes.argtypes = L.cgx_sizes.argtypes
         L.cgx_qsgd_quantize.argtypes = L.cgx_quantize.argtypes
         L.cgx_qsgd_dequant_reduce.argtypes = L.cgx_dequant_reduce.argtypes
@@ -301,6 +306,32 @@ def cgx_layered_layer_sqerrors(grad, packed, meta, plan: LayeredPlan, sqerr, wor
                                             sqerr.data_ptr(), workspace.data_ptr(),
                                             workspace.numel() * workspace.element_size(), _stream(stream)),
            "cgx_layered_layer_sqerrors")
+
+
+def cgx_qsgd_layered_sizes(plan: LayeredPlan) -> Tuple[int, int]:
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().cgx_qsgd_layered_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_qsgd_layered_sizes")
+    return int(pb.value), int(mb.value)
+
+
+def cgx_qsgd_layered_quantize(grad, plan: LayeredPlan, seed: int, packed, meta, stream=None) -> None:
+    _check(lib().cgx_qsgd_layered_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
+                                           meta.data_ptr(), _stream(stream)), "cgx_qsgd_layered_quantize")
+
+
+def cgx_qsgd_layered_dequant_reduce(packed: Sequence, meta: Sequence, plan: LayeredPlan, total, stream=None) -> None:
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_qsgd_layered_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
+           "cgx_qsgd_layered_dequant_reduce")
+
+
+def cgx_qsgd_layered_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: LayeredPlan, seed: int,
+                                               packed_out, meta_out, stream=None) -> None:
+    W, pp, mp = _peer_arrays(packed, meta)
+    _check(lib().cgx_qsgd_layered_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
+                                                            packed_out.data_ptr(), meta_out.data_ptr(),
+                                                            _stream(stream)),
+           "cgx_qsgd_layered_dequant_reduce_requantize")
 
 
 def cgx_qsgd_sizes(plan: Plan) -> Tuple[int, int]:

@@ -594,6 +594,48 @@ int cgx_qsgd_dequant_reduce_requantize(const void *const *packed, const void *co
                       seed, packed_out, meta_out, stream);
 }
 
+int cgx_qsgd_layered_sizes(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                           const int32_t *buckets_per_layer, cgx_dtype dt, size_t *packed_bytes, size_t *meta_bytes)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    const int rc = check_plan(cgx::kSchemeNormSign, n, L, layer_offsets, bits_per_layer, Buckets{32, buckets_per_layer},
+                              int(dt));
+    if (rc != CGX_OK) return rc;
+    const cgx::PlanShape s = cgx::plan_shape(L, layer_offsets, bits_per_layer, 32, int(dt), buckets_per_layer);
+    if (packed_bytes) *packed_bytes = s.packed_bytes;
+    if (meta_bytes) *meta_bytes = s.meta_bytes / 2;
+    return CGX_OK;
+}
+
+int cgx_qsgd_layered_quantize(const void *grad, int64_t n, int32_t L, const int64_t *layer_offsets,
+                              const uint8_t *bits_per_layer, const int32_t *buckets_per_layer, uint64_t seed,
+                              cgx_dtype dt, void *packed, void *meta, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return quantize_impl(cgx::kSchemeNormSign, grad, n, L, layer_offsets, bits_per_layer,
+                         Buckets{32, buckets_per_layer}, seed, int(dt), packed, meta, stream);
+}
+
+int cgx_qsgd_layered_dequant_reduce(const void *const *packed, const void *const *meta, int32_t W, int64_t n,
+                                    int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                                    const int32_t *buckets_per_layer, cgx_dtype dt, float *sum, void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return reduce_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer,
+                       Buckets{32, buckets_per_layer}, int(dt), nullptr, CGX_F32, false, sum, CGX_F32, stream);
+}
+
+int cgx_qsgd_layered_dequant_reduce_requantize(const void *const *packed, const void *const *meta, int32_t W,
+                                               int64_t n, int32_t L, const int64_t *layer_offsets,
+                                               const uint8_t *bits_per_layer, const int32_t *buckets_per_layer,
+                                               cgx_dtype dt, uint64_t seed, void *packed_out, void *meta_out,
+                                               void *stream)
+{
+    if (L > 0 && !buckets_per_layer) return CGX_ERR_NULL;
+    return fused_impl(cgx::kSchemeNormSign, packed, meta, W, n, L, layer_offsets, bits_per_layer,
+                      Buckets{32, buckets_per_layer}, int(dt), seed, packed_out, meta_out, stream);
+}
+
 int cgx_layer_stats_workspace(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                               int32_t bucket, cgx_dtype dt, size_t *bytes)
 {

@@ -204,3 +204,62 @@ def test_layered_dequantize_and_local_addend(torch, oracle, dt):
             ref = oracle.layered_dequant_reduce(list(chunks[:W]), list(metas[:W]), w.offsets, w.bits, buckets, w.dt,
                                                 local=local)
             assert np.array_equal(got[:w.n].view(np.uint32), ref["sum32"].view(np.uint32)), f"W={W} {local.dtype}"
+
+
+def qsgd_cycle(torch, oracle, w, buckets, what):
+    """The norm-and-sign calls with a bucket size per layer: quantize, reduce, requantize, fused."""
+    plan = cgx.LayeredPlan(w.offsets, w.bits, buckets, w.dt)
+    out_plan = cgx.LayeredPlan(w.offsets, w.bits, buckets, wl.F32)
+
+    def quantize(grad, p, seed):
+        pb, mb = cgx.cgx_qsgd_layered_sizes(p)
+        packed = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        meta = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+        cgx.cgx_qsgd_layered_quantize(grad if isinstance(grad, torch.Tensor) else dev(torch, grad), p, seed, packed, meta)
+        torch.cuda.synchronize()
+        a, b = packed.cpu().numpy(), meta.cpu().numpy()
+        assert (a[pb:] == 0xA5).all() and (b[mb // 4:] == -7.0).all(), "wrote past the reported sizes"
+        return a[:pb], b[:mb // 4]
+
+    chunks, metas = [], []
+    for peer in range(w.W):
+        g = w.gradient(peer)
+        op, om = oracle.qsgd_layered_quantize(g, w.offsets, w.bits, buckets, w.quant_seed(peer), w.dt)
+        if peer < 2:
+            gp, gm = quantize(g, plan, w.quant_seed(peer))
+            same_chunk(gp, gm, op, om, f"{what} quantize peer {peer}")
+        chunks.append(op)
+        metas.append(om)
+    ref = oracle.qsgd_layered_dequant_reduce(chunks, metas, w.offsets, w.bits, buckets, w.dt)
+    dp = [dev(torch, c) for c in chunks]
+    dm = [dev(torch, m) if m.size else torch.zeros(4, device="cuda") for m in metas]
+    total = torch.full((w.n + 16,), 123.0, dtype=torch.float32, device="cuda")
+    cgx.cgx_qsgd_layered_dequant_reduce(dp, dm, plan, total)
+    torch.cuda.synchronize()
+    got = total.cpu().numpy()
+    assert (got[w.n:] == 123.0).all()
+    got = got[:w.n]
+    assert np.array_equal(got.view(np.uint32), ref["sum32"].view(np.uint32)), f"{what}: sums differ"
+    rp, rm = quantize(total[:w.n], out_plan, 99)
+    op, om = oracle.qsgd_layered_quantize(got, w.offsets, w.bits, buckets, 99, wl.F32)
+    same_chunk(rp, rm, op, om, f"{what} requantize")
+    if w.W <= cgx.MAX_FUSED_PEERS:
+        pb, mb = cgx.cgx_qsgd_layered_sizes(out_plan)
+        fp = torch.full((pb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        fm = torch.full((mb // 4 + 16,), -7.0, dtype=torch.float32, device="cuda")
+        cgx.cgx_qsgd_layered_dequant_reduce_requantize(dp, dm, plan, 99, fp, fm)
+        torch.cuda.synchronize()
+        a, b = fp.cpu().numpy(), fm.cpu().numpy()
+        assert (a[pb:] == 0xA5).all() and (b[mb // 4:] == -7.0).all()
+        op, om = oracle.qsgd_layered_quantize(ref["sum32"], w.offsets, w.bits, buckets, 99, wl.F32)
+        same_chunk(a[:pb], b[:mb // 4], op, om, f"{what} fused reduce+requantize")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_norm_and_sign_random_plans_with_a_bucket_size_per_layer(torch, oracle, seed):
+    w = wl.random_plan(seed)
+    if w.n == 0:
+        pytest.skip("empty plan")
+    w.bits = np.where(w.bits == 1, 2, w.bits).astype(np.uint8)
+    buckets = np.random.default_rng(50 + seed).choice(BUCKETS, w.L).astype(np.int32)
+    qsgd_cycle(torch, oracle, w, buckets, f"norm-sign random plan {seed} (buckets {buckets.tolist()}, bits {w.bits.tolist()})")

@@ -315,3 +315,24 @@ def test_tiles_carry_their_bucket_size(lib):
         size = ((tiles["info"] >> 12) & 0x1ff) * 32
         quantized = (kind != 2) & (kind != 3)
         assert (size[quantized] == bucket).all() and (size[~quantized] == 0).all()
+
+
+def test_norm_and_sign_layered_sizes_and_checks(lib, oracle):
+    rng = np.random.default_rng(4)
+    for _ in range(10):
+        L = int(rng.integers(1, 10))
+        off = np.concatenate([[0], np.cumsum(rng.choice([0, 1, 31, 96, 1000, 2048, 4097], L))]).astype(np.int64)
+        bits = rng.choice([0, 2, 3, 4, 8], L).astype(np.uint8)
+        buckets = rng.choice([32, 64, 96, 128, 512, 1024, 4096, 8192], L).astype(np.int32)
+        assert cgx.cgx_qsgd_layered_sizes(cgx.LayeredPlan(off, bits, buckets)) == oracle.qsgd_layered_sizes(off, bits, buckets)
+    off = np.array([0, 100, 300], np.int64)
+    one_bit = np.array([1, 4], np.uint8)
+    ok = np.array([64, 32], np.int32)
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.cgx_qsgd_layered_sizes(300, 2, off.ctypes.data, one_bit.ctypes.data, ok.ctypes.data, 0, ctypes.byref(pb),
+                                      ctypes.byref(mb)) == -4
+    bits = np.array([2, 4], np.uint8)
+    assert lib.cgx_qsgd_layered_quantize(16, 300, 2, off.ctypes.data, bits.ctypes.data, None, 1, 0, 16, 16, None) == -1
+    bad = np.array([64, 48], np.int32)
+    assert lib.cgx_qsgd_layered_quantize(16, 300, 2, off.ctypes.data, bits.ctypes.data, bad.ctypes.data, 1, 0, 16, 16,
+                                         None) == -5
