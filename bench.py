@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--step-only", action="store_true",
                     help="time the step alone: no fused / norm-and-sign / statistics / probe legs (for counter "
                          "runs, where every dispatch is slow)")
+    ap.add_argument("--with-fused", action="store_true",
+                    help="with --step-only: run the fused leg (quantize + dequant_reduce_requantize) as well")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB three times: "
                          "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its known size gives the factor "
@@ -217,7 +219,7 @@ def main():
                                           rq_out[r][1])
 
     fused = None
-    if W <= cgx.MAX_FUSED_PEERS and not args.step_only:
+    if W <= cgx.MAX_FUSED_PEERS and (not args.step_only or args.with_fused):
         for i in range(args.warmup):
             fused_step(i)
         fe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
