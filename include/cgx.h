@@ -65,7 +65,8 @@ typedef enum {
     CGX_ERR_PEERS = -6,    /* W outside [1, CGX_MAX_PEERS] */
     CGX_ERR_DTYPE = -7,    /* unknown storage type */
     CGX_ERR_HIP = -8,      /* the HIP runtime reported an error */
-    CGX_ERR_ALIGN = -9     /* a device pointer is not 16-byte aligned */
+    CGX_ERR_ALIGN = -9,    /* a device pointer is not 16-byte aligned */
+    CGX_ERR_CAPACITY = -10 /* the plan is larger than a no-allocation entry point's fixed tables */
 } cgx_status;
 
 typedef enum {
@@ -295,6 +296,26 @@ int cgx_qsgd_layer_sqerrors(const void *grad, const void *packed, const void *me
                             const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket,
                             cgx_dtype dt, double *sqerr, void *workspace, size_t workspace_bytes,
                             void *stream);
+
+/*
+ * cgx_layer_sqnorms for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result, bit for bit, as
+ * cgx_layer_sqnorms; no workspace argument: the tile table, its numbering and the partial sums
+ * live in a fixed array of 11.1 MB inside the library's device
+ * code, one copy per GPU, held until the process ends.  The call allocates nothing on the
+ * device (no hipMalloc, no hipFree, no table cache) and copies nothing from host memory on the
+ * stream: the layer table travels in kernel arguments, ceil((L + 1) / 192) small launches
+ * ahead of the three that compute.
+ * Limits: L <= CGX_NOALLOC_MAX_LAYERS, and at most CGX_NOALLOC_MAX_TILES work items (a layer of
+ * len elements takes ceil(len / 8192) of them); beyond either the call returns
+ * CGX_ERR_CAPACITY and queues nothing.  The other errors are those of cgx_layer_sqnorms.
+ * Every call on a GPU uses that GPU's one array: calls on different streams of one GPU, or
+ * from different threads, must not overlap (calls queued on one stream are ordered and safe).
+ */
+#define CGX_NOALLOC_MAX_LAYERS 4096
+#define CGX_NOALLOC_MAX_TILES 262144
+int cgx_layer_sqnorms_noalloc(const void *buf, int64_t n, int32_t L, const int64_t *layer_offsets, cgx_dtype dt,
+                              double *sqnorm, void *stream);
 
 /*
  * Bit-width assigners of the layer-wise adaptive scheme (same section; host only, no

@@ -24,7 +24,7 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_requantize",
            "cgx_dequant_reduce_requantize", "cgx_qsgd_sizes", "cgx_qsgd_quantize", "cgx_qsgd_dequant_reduce",
            "cgx_qsgd_dequant_reduce_requantize", "cgx_layer_stats_workspace", "cgx_layer_sqnorms",
-           "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
+           "cgx_layer_sqnorms_noalloc", "cgx_layer_sqerrors", "cgx_qsgd_layer_sqerrors", "cgx_assign_bits_kmeans", "cgx_assign_bits_linear",
            "cgx_assign_buckets_from_bits", "cgx_layered_sizes", "cgx_layered_quantize", "cgx_layered_dequant_reduce", "cgx_layered_requantize",
            "cgx_layered_dequant_reduce_requantize", "cgx_layered_dequant_reduce_add", "cgx_layered_dequantize",
            "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors", "cgx_qsgd_layered_sizes",
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.cgx_layer_stats_workspace.argtypes = plan + [c.c_int, c.POINTER(c.c_size_t)]
         L.cgx_layer_sqnorms.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p, c.c_int, c.c_void_p, c.c_void_p,
                                         c.c_size_t, c.c_void_p]
+        L.cgx_layer_sqnorms_noalloc.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p, c.c_int, c.c_void_p,
+                                                c.c_void_p]
         L.cgx_layer_sqerrors.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p] + plan + \
             [c.c_int, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
         L.cgx_qsgd_layer_sqerrors.argtypes = L.cgx_layer_sqerrors.argtypes
@@ -377,6 +379,15 @@ def cgx_layer_sqnorms(buf, plan: Plan, sqnorm, workspace, stream=None) -> None:
     _check(lib().cgx_layer_sqnorms(buf.data_ptr(), plan.n, plan.L, plan.offsets.ctypes.data, plan.dt,
                                    sqnorm.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                    _stream(stream)), "cgx_layer_sqnorms")
+
+
+NOALLOC_MAX_LAYERS, NOALLOC_MAX_TILES = 4096, 262144
+
+
+def cgx_layer_sqnorms_noalloc(buf, plan: Plan, sqnorm, stream=None) -> None:
+    """cgx_layer_sqnorms without workspace and without device allocations (fixed tables inside the library)."""
+    _check(lib().cgx_layer_sqnorms_noalloc(buf.data_ptr(), plan.n, plan.L, plan.offsets.ctypes.data, plan.dt,
+                                           sqnorm.data_ptr(), _stream(stream)), "cgx_layer_sqnorms_noalloc")
 
 
 def cgx_layer_sqerrors(grad, packed, meta, plan: Plan, sqerr, workspace, stream=None, qsgd: bool = False) -> None:

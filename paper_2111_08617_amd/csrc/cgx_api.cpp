@@ -666,6 +666,33 @@ int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *laye
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
 }
 
+int cgx_layer_sqnorms_noalloc(const void *buf, int64_t n, int32_t L, const int64_t *layer_offsets, cgx_dtype dt,
+                              double *sqnorm, void *stream)
+{
+    // the checks of validate_plan that concern the layer table (this call has no widths), without
+    // the heap: nothing here allocates
+    if (n < 0 || L < 0) return CGX_ERR_SIZE;
+    if (L > 0 && !layer_offsets) return CGX_ERR_NULL;
+    if (dt != CGX_F32 && dt != CGX_F16) return CGX_ERR_DTYPE;
+    if (L == 0) return n == 0 ? CGX_OK : CGX_ERR_SIZE;
+    if (layer_offsets[0] != 0) return CGX_ERR_OFFSETS;
+    for (int32_t l = 0; l < L; l++)
+        if (layer_offsets[l + 1] < layer_offsets[l]) return CGX_ERR_OFFSETS;
+    if (layer_offsets[L] != n || n / 32 > int64_t(0xfffffff0u)) return CGX_ERR_SIZE;
+    if (L > CGX_NOALLOC_MAX_LAYERS) return CGX_ERR_CAPACITY;
+    // number of each layer's first work item: runs of kCopyTile elements, layer by layer
+    static thread_local int64_t first[CGX_NOALLOC_MAX_LAYERS + 1];
+    first[0] = 0;
+    for (int32_t l = 0; l < L; l++)
+        first[l + 1] = first[l] + (layer_offsets[l + 1] - layer_offsets[l] + cgx::kCopyTile - 1) / cgx::kCopyTile;
+    if (first[L] > CGX_NOALLOC_MAX_TILES) return CGX_ERR_CAPACITY;
+    if (!sqnorm || (n > 0 && !buf)) return CGX_ERR_NULL;
+    if (misaligned(buf) || (reinterpret_cast<uintptr_t>(sqnorm) & 7u)) return CGX_ERR_ALIGN;
+    const hipError_t e = cgx::launch_layer_sqnorms_noalloc(buf, int(dt), layer_offsets, first, L, sqnorm,
+                                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
 int cgx_layer_sqerrors(const void *grad, const void *packed, const void *meta, int64_t n, int32_t L,
                        const int64_t *layer_offsets, const uint8_t *bits_per_layer, int32_t bucket, cgx_dtype dt,
                        double *sqerr, void *workspace, size_t workspace_bytes, void *stream)
@@ -718,6 +745,8 @@ const char *cgx_status_string(int status)
     case CGX_ERR_DTYPE: return "unknown storage type";
     case CGX_ERR_HIP: return "the HIP runtime reported an error";
     case CGX_ERR_ALIGN: return "device pointers must be 16-byte aligned";
+    case CGX_ERR_CAPACITY: return "the plan exceeds the fixed tables of a no-allocation entry point "
+                                  "(CGX_NOALLOC_MAX_LAYERS layers, CGX_NOALLOC_MAX_TILES work items)";
     default: return "unknown status";
     }
 }

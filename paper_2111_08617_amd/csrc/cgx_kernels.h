@@ -1,4 +1,5 @@
-// Launchers of the gfx950 kernels (implemented in cgx_kernels.hip).
+// Launchers of the gfx950 kernels (implemented in cgx_quantize.hip, cgx_reduce.hip, cgx_fused.hip
+// and cgx_stats.hip).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -61,6 +62,13 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
                                  double *out, const LaunchConfig &cfg, hipStream_t stream, bool sum_layers = true);
 // (sum_layers = false: only the tiles' partial sums are written; a plan served by several tile
 // tables adds them up after the last one)
+
+// launch_layer_sqnorms with every table and the partial sums in a fixed device array of the
+// library: no allocation, nothing copied from host memory on the stream.  off / first: host
+// arrays [L + 1], layer offsets and the number of each layer's first tile (runs of kCopyTile
+// elements); L <= CGX_NOALLOC_MAX_LAYERS and first[L] <= CGX_NOALLOC_MAX_TILES (caller-checked).
+hipError_t launch_layer_sqnorms_noalloc(const void *buf, int dt, const int64_t *off, const int64_t *first, int32_t L,
+                                        double *out, hipStream_t stream);
 
 // Measurement aid: streams read_bytes in and write_bytes out (multiples of 16) with the access
 // style of the kernels and no arithmetic; see cgx_stream_probe in cgx.h.

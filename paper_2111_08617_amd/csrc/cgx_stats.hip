@@ -1,5 +1,34 @@
 // Per-layer statistics of the adaptive scheme and the streaming probe: kernels and launchers.
+#include <mutex>
+
 #include "cgx_device_reduce.h"
+
+// Layout of the device array behind cgx_layer_sqnorms_noalloc (see the kernels further down):
+// the layer table, the tile table with its numbering, and one partial sum per tile.
+namespace cgx {
+namespace {
+constexpr int kStaticLayers = CGX_NOALLOC_MAX_LAYERS;
+constexpr int64_t kStaticTiles = CGX_NOALLOC_MAX_TILES;
+
+constexpr size_t round256(size_t v) { return (v + 255) & ~size_t(255); }
+
+struct StaticLayout {                        // offsets into the array, each a multiple of 256 bytes
+    static constexpr size_t kTable = (size_t(kStaticLayers) + 1) * sizeof(int64_t);
+    static constexpr size_t off = 0;                                                  // int64 [L + 1]
+    static constexpr size_t first = off + round256(kTable);                              // int64 [L + 1]
+    static constexpr size_t partial = first + round256(kTable);                          // double [tiles]
+    static constexpr size_t slots = partial + round256(size_t(kStaticTiles) * sizeof(double));     // uint32 [tiles]
+    static constexpr size_t tiles = slots + round256(size_t(kStaticTiles) * sizeof(uint32_t));     // Tile [tiles]
+    static constexpr size_t bytes = tiles + round256(size_t(kStaticTiles) * sizeof(Tile));
+};
+
+}  // namespace
+}  // namespace cgx
+
+// One copy per device, held from the load of the library's code until the process ends.  Host
+// code never uses this name as an address: it asks the runtime for the array's device address
+// (static_scratch below) and passes that to the kernels.
+static __device__ __align__(256) unsigned char scratch[cgx::StaticLayout::bytes];
 
 namespace cgx {
 namespace {
@@ -163,6 +192,80 @@ __global__ __launch_bounds__(kSumBlock) void layer_sum_kernel(const double *__re
     }
 }
 
+// ---------------------------------------------------------------- statistics without allocations
+//
+// cgx_layer_sqnorms_noalloc: the tile table, its numbering and the partial sums live in a
+// file-scope device array instead of library-allocated tables and a caller workspace, for callers
+// that cannot allocate.  The layer table reaches the device through kernel arguments (a few
+// hundred entries per launch), so that the call copies nothing from host memory on the stream;
+// a kernel expands it into the same tile table the allocating call builds on the host, and the
+// two statistics kernels above do the rest.
+
+// A slice of the layer table as a kernel argument: layer offsets and first tile numbers.
+constexpr int kSliceEntries = 192;
+struct TableSlice {
+    int64_t off[kSliceEntries];
+    int64_t first[kSliceEntries];
+};
+
+// Entries [at, at + count) of both tables, from the kernel's arguments (the slice is the first
+// parameter: read where the dispatch put it, indexed by the thread).
+__global__ __launch_bounds__(kSliceEntries) void table_slice_kernel(const TableSlice slice_argument, int count, int at,
+                                                                      int64_t *__restrict__ off,
+                                                                      int64_t *__restrict__ first)
+{
+    (void)slice_argument;
+    const __attribute__((address_space(4))) TableSlice &slice =
+        *(const __attribute__((address_space(4))) TableSlice *)__builtin_amdgcn_kernarg_segment_ptr();
+    const int i = int(threadIdx.x);
+    if (i < count) {
+        off[at + i] = slice.off[i];
+        first[at + i] = slice.first[i];
+    }
+}
+
+// The tiles of an all-pass-through plan, layer by layer (one block per layer): runs of kCopyTile
+// elements, numbered in table order -- what build_tiles gives for such a plan.
+__global__ __launch_bounds__(kBlock) void expand_tiles_kernel(const int64_t *__restrict__ off,
+                                                               const int64_t *__restrict__ first,
+                                                               Tile *__restrict__ tiles, uint32_t *__restrict__ slots)
+{
+    const int64_t l = blockIdx.x;
+    const int64_t e0 = off[l], len = off[l + 1] - e0, a = first[l], b = first[l + 1];
+    for (int64_t t = a + int(threadIdx.x); t < b; t += kBlock) {
+        const int64_t j = (t - a) * kCopyTile;
+        Tile tile{};
+        tile.elem0 = e0 + j;
+        tile.count = uint32_t(len - j < kCopyTile ? len - j : kCopyTile);
+        tile.info = uint32_t(kCopyFast) << 4;
+        tiles[t] = tile;
+        slots[t] = uint32_t(t);
+    }
+}
+
+// Device address of this device's copy of the array (looked up once per device).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(unsigned char **ptr)
+{
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<unsigned char *>(p);
+    }
+    *ptr = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 // ---------------------------------------------------------------- streaming probe
 
 // Measurement aid: moves read_bytes in and write_bytes out with the access style of the
@@ -207,6 +310,40 @@ hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, cons
     }
     hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
                        static_cast<const double *>(partial), layer_first, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_layer_sqnorms_noalloc(const void *buf, int dt, const int64_t *off, const int64_t *first, int32_t L,
+                                        double *out, hipStream_t stream)
+{
+    if (L == 0) return hipSuccess;
+    unsigned char *base = nullptr;
+    const hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return e;
+    int64_t *d_off = reinterpret_cast<int64_t *>(base + StaticLayout::off);
+    int64_t *d_first = reinterpret_cast<int64_t *>(base + StaticLayout::first);
+    double *d_partial = reinterpret_cast<double *>(base + StaticLayout::partial);
+    uint32_t *d_slots = reinterpret_cast<uint32_t *>(base + StaticLayout::slots);
+    Tile *d_tiles = reinterpret_cast<Tile *>(base + StaticLayout::tiles);
+    for (int at = 0; at <= L; at += kSliceEntries) {
+        TableSlice slice{};
+        const int count = L + 1 - at < kSliceEntries ? L + 1 - at : kSliceEntries;
+        for (int i = 0; i < count; i++) {
+            slice.off[i] = off[at + i];
+            slice.first[i] = first[at + i];
+        }
+        hipLaunchKernelGGL(table_slice_kernel, dim3(1), dim3(kSliceEntries), 0, stream, slice, count, at, d_off, d_first);
+    }
+    const int64_t n_tiles = first[L];
+    if (n_tiles > 0) {
+        hipLaunchKernelGGL(expand_tiles_kernel, dim3(unsigned(L)), dim3(kBlock), 0, stream,
+                           static_cast<const int64_t *>(d_off), static_cast<const int64_t *>(d_first), d_tiles, d_slots);
+        const auto kernel = dt == CGX_F16 ? sqnorm_kernel<CGX_F16> : sqnorm_kernel<CGX_F32>;
+        hipLaunchKernelGGL(kernel, dim3(grid_for(n_tiles, LaunchConfig{})), dim3(kBlock), 0, stream, buf,
+                           static_cast<const Tile *>(d_tiles), static_cast<const uint32_t *>(d_slots), n_tiles, d_partial);
+    }
+    hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
+                       static_cast<const double *>(d_partial), static_cast<const int64_t *>(d_first), out);
     return hipGetLastError();
 }
 

@@ -37,8 +37,8 @@ def test_library_exports_every_declared_symbol(lib):
 
 
 def test_status_strings(lib):
-    seen = {cgx.status_string(s) for s in range(0, -10, -1)}
-    assert len(seen) == 10 and "unknown status" not in seen
+    seen = {cgx.status_string(s) for s in range(0, -11, -1)}
+    assert len(seen) == 11 and "unknown status" not in seen
     assert cgx.status_string(-99) == "unknown status"
 
 
@@ -133,6 +133,36 @@ def test_argument_errors_are_found_on_the_host(lib):
     z = np.zeros(1, np.int64)
     assert lib.cgx_quantize(None, 0, 0, z.ctypes.data, None, 128, 0, 0, None, None, None) == 0
     assert lib.cgx_dequant_reduce(ptrs, ptrs, 2, 0, 0, z.ctypes.data, None, 128, 0, None, None) == 0
+
+
+def test_no_allocation_entry_point_checks_its_arguments_and_limits(lib):
+    """cgx_layer_sqnorms_noalloc: the errors of cgx_layer_sqnorms, and CGX_ERR_CAPACITY beyond its fixed tables;
+    all found on the host before anything is queued."""
+    fn = lib.cgx_layer_sqnorms_noalloc
+    buf = 0x1000                                                      # never dereferenced
+    off = np.array([0, 100, 300], np.int64)
+    o = off.ctypes.data
+    assert fn(buf, -1, 2, o, 0, buf, None) == -2
+    assert fn(buf, 301, 2, o, 0, buf, None) == -2
+    assert fn(buf, 300, 2, None, 0, buf, None) == -1
+    assert fn(buf, 300, 2, o, 2, buf, None) == -7
+    assert fn(buf, 300, 2, np.array([1, 100, 300], np.int64).ctypes.data, 0, buf, None) == -3
+    assert fn(buf, 300, 2, np.array([0, 400, 300], np.int64).ctypes.data, 0, buf, None) == -3
+    assert fn(None, 300, 2, o, 0, buf, None) == -1
+    assert fn(buf, 300, 2, o, 0, None, None) == -1
+    assert fn(buf + 4, 300, 2, o, 0, buf, None) == -9
+    assert fn(buf, 300, 2, o, 0, buf + 4, None) == -9
+    assert fn(None, 0, 0, o, 0, None, None) == 0                      # no layers: nothing to do
+    # one layer too many
+    many = np.arange(cgx.NOALLOC_MAX_LAYERS + 2, dtype=np.int64)
+    assert fn(buf, int(many[-1]), many.size - 1, many.ctypes.data, 0, buf, None) == -10
+    # one work item too many: a work item is a run of 8192 elements of one layer
+    big = np.array([0, 8192 * cgx.NOALLOC_MAX_TILES, 8192 * cgx.NOALLOC_MAX_TILES + 1], np.int64)
+    assert fn(buf, int(big[-1]), 2, big.ctypes.data, 0, buf, None) == -10
+    assert "no-allocation" in cgx.status_string(-10)
+    header = open(os.path.join(ROOT, "include", "cgx.h")).read()
+    assert "#define CGX_NOALLOC_MAX_LAYERS %d\n" % cgx.NOALLOC_MAX_LAYERS in header
+    assert "#define CGX_NOALLOC_MAX_TILES %d\n" % cgx.NOALLOC_MAX_TILES in header
 
 
 def test_norm_and_sign_entry_points_check_their_arguments(lib, oracle):
