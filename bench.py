@@ -4,6 +4,10 @@
 A step is one pass of the whole path over one synthetic batch: cgx_quantize of
 a fused gradient buffer, cgx_dequant_reduce over W compressed chunks, and
 cgx_requantize of the sum.  Inputs are resident in HBM before the timed region.
+
+The headline workload is the 1.3 B-parameter decoder (the larger of the two
+target configurations); the 25.6 M-parameter ResNet-50 plan is measured in the
+same run and reported as a second block of the same JSON line.
 Prints ONE JSON line (see --help for the knobs).
 """
 import argparse
@@ -17,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+NAMES = ["quantize", "dequant_reduce", "requantize"]
 
 
 def algorithmic_bytes(tiles, bucket, elem_bytes, W, meta_per_bucket=8):
@@ -33,6 +38,8 @@ def algorithmic_bytes(tiles, bucket, elem_bytes, W, meta_per_bucket=8):
     n = int(count.sum())
     packed_meta = int(payload + meta_per_bucket * buckets)
     return {
+        "n": n,
+        "packed_meta": packed_meta,
         "quantize": n * elem_bytes + packed_meta,
         "dequant_reduce": W * packed_meta + 4 * n,
         "requantize": 4 * n + int(np.where(q, (count * bits + 7) // 8, count * 4).sum() + meta_per_bucket * buckets),
@@ -54,50 +61,28 @@ def read_traffic(workload, kernel):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser(description=__doc__)
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="resnet50",
-                    choices=["single_1m", "resnet50", "bert_base", "gpt2_medium", "decoder_1p3b"])
-    ap.add_argument("--rotate", type=int, default=0,
-                    help="distinct buffer sets cycled through so that launches do not re-hit the 256 MB "
-                         "memory-side cache (0 = enough for 1 GB of traffic)")
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
-    ap.add_argument("--spin-up-ms", type=float, default=50.0,
-                    help="untimed steps run for this long before the warmup steps, so that the clocks have "
-                         "settled whatever --warmup is (the first ~10 ms of activity run slower)")
-    ap.add_argument("--step-only", action="store_true",
-                    help="time the step alone: no fused / norm-and-sign / statistics / probe legs (for counter "
-                         "runs, where every dispatch is slow)")
-    ap.add_argument("--with-fused", action="store_true",
-                    help="with --step-only: run the fused leg (quantize + dequant_reduce_requantize) as well")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB three times: "
-                         "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its known size gives the factor "
-                         "that scales the counters to bytes")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the W peers of the reduce step are W compressed "
-                 "chunks resident in HBM); run with --gpus 1")
+def rate(nbytes, ms):
+    """{ms, algorithmic bytes, GB/s, fraction of the HBM peak} of one launch."""
+    return {"ms": round(ms, 5), "algorithmic_bytes": int(nbytes),
+            "algorithmic_GBps": round(nbytes / ms / 1e6, 1),
+            "hbm_frac": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
 
+
+def measure(name, args, extras=True):
+    """Times the step of one workload and its kernels; returns (result dict, workload, host gradient)."""
     import numpy as np
     import torch
 
     from paper_2111_08617_amd import binding as cgx
     from paper_2111_08617_amd import workloads as wl
 
-    assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    cgx.lib()
     dev = torch.device("cuda:0")
-    w = wl.WORKLOADS[args.workload]()
+    w = wl.WORKLOADS[name]()
     W = w.W
     S = 2 if w.dt == wl.F16 else 4
-    tdtype = torch.float16 if w.dt == wl.F16 else torch.float32
 
     # the reduce step runs on one rank's share when the buffer is large (1/W of it), else on the full buffer
-    on_share = args.workload in ("gpt2_medium", "decoder_1p3b", "bert_base")
+    on_share = name in ("gpt2_medium", "decoder_1p3b", "bert_base")
     if on_share:
         first, r_off, r_bits = wl.share_subplan(w.offsets, w.bits, w.bucket, W, W // 2)
     else:
@@ -113,6 +98,7 @@ def main():
     q_alg = algorithmic_bytes(cgx.cgx_plan_tiles(q_plan), w.bucket, S, W)["quantize"]
     r_algs = algorithmic_bytes(cgx.cgx_plan_tiles(r_plan), w.bucket, S, W)
     alg = {"quantize": q_alg, "dequant_reduce": r_algs["dequant_reduce"], "requantize": r_algs["requantize"]}
+    chunk_bytes = r_algs["packed_meta"]                       # one peer's packed stream + meta of the share
 
     traffic = q_alg + alg["dequant_reduce"] + alg["requantize"]
     R = args.rotate if args.rotate > 0 else max(2, min(8, int(np.ceil(2.5e9 / traffic))))
@@ -134,6 +120,7 @@ def main():
             ps.append(packed)
             ms.append(meta)
         chunk_sets.append((ps, ms))
+    locals32 = [share_grads[0].float().clone() for _ in range(R)] if extras else None
     del share_grads
     q_out = [(torch.empty(q_pb, dtype=torch.uint8, device=dev),
               torch.empty(max(q_mb // 4, 4), dtype=torch.float32, device=dev)) for _ in range(R)]
@@ -142,8 +129,6 @@ def main():
                torch.empty(max(rq_mb // 4, 4), dtype=torch.float32, device=dev)) for _ in range(R)]
     torch.cuda.synchronize()
     setup_s = time.time() - t0
-
-    names = ["quantize", "dequant_reduce", "requantize"]
 
     def step(i, ev=None, only=None):
         """One step; ev: four events recorded around the three calls (only = j: just the two around call j).
@@ -161,8 +146,8 @@ def main():
         if ev and only in (None, 2):
             ev[3].record()
 
-    def new_events(k):
-        return [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(k)]
+    def new_events(k, per=4):
+        return [[torch.cuda.Event(enable_timing=True) for _ in range(per)] for _ in range(k)]
 
     def all_ms(evs, j):
         return np.array([e[j].elapsed_time(e[j + 1]) for e in evs])
@@ -187,7 +172,7 @@ def main():
     if args.warmup > 0:
         dom = int(np.argmax([mean_ms(warm_events[args.warmup // 2:], j) for j in range(3)]))
     else:
-        dom = int(np.argmax([alg[k] for k in names]))
+        dom = int(np.argmax([alg[k] for k in NAMES]))
 
     # timed region: exactly `steps` steps; the dominant kernel is bracketed by two events on every
     # `stride`-th step (about 25 samples), nothing else sits between the launches
@@ -211,18 +196,58 @@ def main():
         step(i, all_events[i])
     torch.cuda.synchronize()
 
-    # the same rank's work with the fused entry point: quantize + dequant_reduce_requantize
-    def fused_step(i):
-        r = i % R
-        cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1])
-        cgx.cgx_dequant_reduce_requantize(chunk_sets[r][0], chunk_sets[r][1], r_plan, 29 + i, rq_out[r][0],
-                                          rq_out[r][1])
+    def timed(fn, reps=None):
+        """Mean event time of fn(i) over some launches (outside the timed region)."""
+        for i in range(max(args.warmup // 2, 2)):
+            fn(i)
+        reps = reps or max(args.steps // 2, 5)
+        evs = new_events(reps, 2)
+        torch.cuda.synchronize()
+        for i in range(reps):
+            evs[i][0].record()
+            fn(i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
+    # the same step with the quantize (own buffer) and the reduce + requantize (received chunks) on two
+    # streams of equal priority: the two are independent in a scatter-reduce, so one's tail fills
+    # with the other's head
+    overlapped = None
+    if extras:
+        s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def overlapped_step(i):
+            r = i % R
+            cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1], stream=s_a)
+            cgx.cgx_dequant_reduce(chunk_sets[r][0], chunk_sets[r][1], r_plan, sums[r], stream=s_b)
+            cgx.cgx_requantize(sums[r], rq_plan, 29 + i, rq_out[r][0], rq_out[r][1], stream=s_b)
+
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            overlapped_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            overlapped_step(i)
+        torch.cuda.synchronize()
+        ov_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        overlapped = {"step": "cgx_quantize on one stream, cgx_dequant_reduce + cgx_requantize on another",
+                      "ms_per_step": round(ov_ms, 5),
+                      "value": round((w.n * S + 8 * m) / (ov_ms * 1e6), 1)}
+
+    # the same rank's work with the fused entry point: quantize + dequant_reduce_requantize
     fused = None
-    if W <= cgx.MAX_FUSED_PEERS and (not args.step_only or args.with_fused):
+    if W <= cgx.MAX_FUSED_PEERS and (extras or args.with_fused):
+        def fused_step(i):
+            r = i % R
+            cgx.cgx_quantize(grads[r], q_plan, 17 + i, q_out[r][0], q_out[r][1])
+            cgx.cgx_dequant_reduce_requantize(chunk_sets[r][0], chunk_sets[r][1], r_plan, 29 + i, rq_out[r][0],
+                                              rq_out[r][1])
+
         for i in range(args.warmup):
             fused_step(i)
-        fe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        fe = new_events(args.steps, 2)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -236,21 +261,37 @@ def main():
         fused_wall = (time.perf_counter() - t0) * 1e3 / args.steps
         fused_kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in fe]))
         fused_alg = alg["dequant_reduce"] - 4 * m + (alg["requantize"] - 4 * m)
-        fused = {
-            "step": "cgx_quantize(full buffer) + cgx_dequant_reduce_requantize(W chunks)",
-            "ms_per_step": round(fused_wall, 5),
-            "dequant_reduce_requantize": {
-                "ms": round(fused_kernel_ms, 5),
-                "algorithmic_bytes": int(fused_alg),
-                "algorithmic_GBps": round(fused_alg / fused_kernel_ms / 1e6, 1),
-                "hbm_frac": round(fused_alg / fused_kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
-                "raw_gradient_GBps": round(4 * m / fused_kernel_ms / 1e6, 1),
-            },
-        }
+        fused = {"step": "cgx_quantize(full buffer) + cgx_dequant_reduce_requantize(W chunks)",
+                 "ms_per_step": round(fused_wall, 5),
+                 "dequant_reduce_requantize": dict(rate(fused_alg, fused_kernel_ms),
+                                                   raw_gradient_GBps=round(4 * m / fused_kernel_ms / 1e6, 1))}
 
-    # the same step with the norm-and-sign form of the quantizer (Sec. 2.2, Q_s), timed per kernel
+    # the remaining calls of a rank's scatter-reduce / all-gather: decompression of a gathered chunk into the
+    # storage type, and the reduce with the rank's own contribution still uncompressed
+    next_rows = None
+    if extras:
+        out32 = sums
+        out16 = [torch.empty(m, dtype=torch.float16, device=dev) for _ in range(min(R, 2))]
+        deq32 = timed(lambda i: cgx.cgx_dequantize(chunk_sets[i % R][0][0], chunk_sets[i % R][1][0], r_plan, wl.F32,
+                                                   out32[i % R]))
+        deq16 = timed(lambda i: cgx.cgx_dequantize(chunk_sets[i % R][0][0], chunk_sets[i % R][1][0], r_plan, wl.F16,
+                                                   out16[i % len(out16)]))
+        add = timed(lambda i: cgx.cgx_dequant_reduce_add(locals32[i % R], wl.F32, chunk_sets[i % R][0][:W - 1],
+                                                         chunk_sets[i % R][1][:W - 1], r_plan, sums[i % R]))
+        next_rows = {
+            "dequantize_to_f32": dict(rate(chunk_bytes + 4 * m, deq32), W=1),
+            "dequantize_to_f16": dict(rate(chunk_bytes + 2 * m, deq16), W=1),
+            "dequant_reduce_add": dict(rate((W - 1) * chunk_bytes + 4 * m + 4 * m, add), W=W - 1,
+                                       local="binary32, uncompressed"),
+            "bytes": "dequantize: packed + meta of one chunk + S_out per element; reduce_add: (W-1) chunks + the "
+                     "local binary32 term + the binary32 sum",
+        }
+        del out16
+    del locals32
+
+    # the same step with the norm-and-sign form of the quantizer (Sec. 2.3, Q_s), timed per kernel
     norm_sign = None
-    if not (w.bits == 1).any() and not args.step_only:
+    if extras and not (w.bits == 1).any():
         ns_meta = lambda mb: torch.empty(max(mb // 8, 4), dtype=torch.float32, device=dev)
         ns_chunks = []
         share = [torch.from_numpy(w.gradient(p, first, first + m, threads=16)).to(dev) for p in range(W)]
@@ -283,7 +324,7 @@ def main():
 
         for i in range(args.warmup):
             ns_step(i)
-        ne = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        ne = new_events(args.steps)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -295,30 +336,14 @@ def main():
         ns_alg.update(dequant_reduce=ns_r["dequant_reduce"], requantize=ns_r["requantize"])
         norm_sign = {"step": "cgx_qsgd_quantize + cgx_qsgd_dequant_reduce + cgx_qsgd_quantize(sum)",
                      "ms_per_step": round(ns_wall, 5)}
-        for j, k in enumerate(["quantize", "dequant_reduce", "requantize"]):
-            ms = float(np.mean([ne[i][j].elapsed_time(ne[i][j + 1]) for i in range(args.steps)]))
-            norm_sign[k] = {"ms": round(ms, 5), "algorithmic_bytes": int(ns_alg[k]),
-                            "algorithmic_GBps": round(ns_alg[k] / ms / 1e6, 1),
-                            "hbm_frac": round(ns_alg[k] / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+        for j, k in enumerate(NAMES):
+            norm_sign[k] = rate(ns_alg[k], mean_ms(ne, j))
         del ns_chunks
 
     # per-layer statistics of the adaptive scheme: squared norms of the full buffer, squared
     # compression error of the full buffer's chunk (read-only kernels: bytes in / time)
-    def timed(fn):
-        for i in range(max(args.warmup // 2, 2)):
-            fn(i)
-        reps = max(args.steps // 2, 5)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
-        torch.cuda.synchronize()
-        for i in range(reps):
-            evs[i][0].record()
-            fn(i)
-            evs[i][1].record()
-        torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
-
     layer_stats = None
-    if not args.step_only:
+    if extras:
         ws_bytes = max(cgx.cgx_layer_stats_workspace(q_plan), cgx.cgx_layer_stats_workspace(q_plan, for_sqnorms=True), 16)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         stat_out = torch.empty(w.L, dtype=torch.float64, device=dev)
@@ -326,16 +351,8 @@ def main():
             cgx.cgx_quantize(grads[r], q_plan, 17 + r, q_out[r][0], q_out[r][1])
         sqn_ms = timed(lambda i: cgx.cgx_layer_sqnorms(grads[i % R], q_plan, stat_out, ws))
         sqe_ms = timed(lambda i: cgx.cgx_layer_sqerrors(grads[i % R], q_out[i % R][0], q_out[i % R][1], q_plan, stat_out, ws))
-        sqn_bytes, sqe_bytes = w.n * S, alg["quantize"]
-        layer_stats = {
-            "sqnorms": {"ms": round(sqn_ms, 5), "algorithmic_bytes": int(sqn_bytes),
-                        "algorithmic_GBps": round(sqn_bytes / sqn_ms / 1e6, 1),
-                        "hbm_frac": round(sqn_bytes / sqn_ms / 1e6 / HBM_PEAK_GBPS, 4)},
-            "sqerrors": {"ms": round(sqe_ms, 5), "algorithmic_bytes": int(sqe_bytes),
-                         "algorithmic_GBps": round(sqe_bytes / sqe_ms / 1e6, 1),
-                         "hbm_frac": round(sqe_bytes / sqe_ms / 1e6 / HBM_PEAK_GBPS, 4)},
-            "note": "each figure covers the tile kernel and the per-layer sum kernel (two launches)",
-        }
+        layer_stats = {"sqnorms": rate(w.n * S, sqn_ms), "sqerrors": rate(alg["quantize"], sqe_ms),
+                       "note": "each figure covers the tile kernel and the per-layer sum kernel (two launches)"}
         del ws
 
     # what the memory system gives a plain streaming kernel with each call's read:write mix at its size
@@ -343,48 +360,24 @@ def main():
         rb, wb = read_bytes // 16 * 16, write_bytes // 16 * 16
         srcs = [torch.empty(rb, dtype=torch.uint8, device=dev) for _ in range(R)]
         dsts = [torch.empty(max(wb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
-        for i in range(max(args.warmup // 2, 2)):
-            cgx.cgx_stream_probe(srcs[i % R], rb, dsts[i % R], wb)
-        reps = max(args.steps // 2, 5)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
-        torch.cuda.synchronize()
-        for i in range(reps):
-            evs[i][0].record()
-            cgx.cgx_stream_probe(srcs[i % R], rb, dsts[i % R], wb)
-            evs[i][1].record()
-        torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        return timed(lambda i: cgx.cgx_stream_probe(srcs[i % R], rb, dsts[i % R], wb))
 
     probe = None
-    if not args.step_only:
+    if extras:
         probe = {
             "quantize": probe_ms(w.n * S, alg["quantize"] - w.n * S),
             "dequant_reduce": probe_ms(alg["dequant_reduce"] - 4 * m, 4 * m),
             "requantize": probe_ms(4 * m, alg["requantize"] - 4 * m),
         }
 
-    if args.calibration_copy:
-        # an elementwise kernel that reads 1 GiB and writes 1 GiB (grid unlike any cgx launch)
-        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1.0, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
-
-    kern_ms = {k: mean_ms(all_events, j) for j, k in enumerate(names)}
+    kern_ms = {k: mean_ms(all_events, j) for j, k in enumerate(NAMES)}
     raw_bytes = {"quantize": w.n * S, "dequant_reduce": 4 * m, "requantize": 4 * m}
     kernels = {}
-    for k in names:
-        kernels[k] = {
-            "ms": round(kern_ms[k], 5),
-            "ms_median": round(float(np.median(all_ms(all_events, names.index(k)))), 5),
-            "ms_min": round(float(np.min(all_ms(all_events, names.index(k)))), 5),
-            "raw_gradient_GBps": round(raw_bytes[k] / kern_ms[k] / 1e6, 1),
-            "algorithmic_bytes": int(alg[k]),
-            "algorithmic_GBps": round(alg[k] / kern_ms[k] / 1e6, 1),
-            "hbm_frac": round(alg[k] / kern_ms[k] / 1e6 / HBM_PEAK_GBPS, 4),
-        }
+    for k in NAMES:
+        ms_k = all_ms(all_events, NAMES.index(k))
+        kernels[k] = dict(rate(alg[k], kern_ms[k]), ms_median=round(float(np.median(ms_k)), 5),
+                          ms_min=round(float(np.min(ms_k)), 5),
+                          raw_gradient_GBps=round(raw_bytes[k] / kern_ms[k] / 1e6, 1))
         if k == "dequant_reduce":
             # the W chunks stand for W gradients of the share: can exceed the HBM peak, not a roofline figure
             kernels[k]["represented_gradient_GBps"] = round(4 * W * m / kern_ms[k] / 1e6, 1)
@@ -392,24 +385,14 @@ def main():
             kernels[k].update(stream_probe_ms=round(probe[k], 5),
                               stream_probe_GBps=round(alg[k] // 16 * 16 / probe[k] / 1e6, 1),
                               frac_of_stream_probe=round(probe[k] / kern_ms[k], 4))
-    dominant = names[dom]
+    dominant = NAMES[dom]
     achieved = alg[dominant] / dominant_ms / 1e6
-    traffic = read_traffic(w.name, dominant)
     value = sum(raw_bytes.values()) / (ms_per_step * 1e6)
 
     result = {
-        "metric": "GB/s of fp32 gradient quantized and dequant-reduced (W=8); % of HBM peak",
         "value": round(value, 1),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
         "dtype": "f16" if w.dt == wl.F16 else "f32",
-        "data": "synthetic",
         "config": {
             "workload": w.name,
             "description": w.description,
@@ -420,7 +403,7 @@ def main():
             "bucket": w.bucket,
             "step": "cgx_quantize(full buffer) + cgx_dequant_reduce(W chunks) + cgx_requantize(sum)",
             "value_definition": "raw gradient bytes entering quantize + leaving dequant_reduce + entering "
-                                "requantize, per second of step wall time",
+                                "requantize, per second of step wall time (the three calls on one stream)",
             "buffer_sets_rotated": R,
             "spin_up_steps_before_warmup": spin_steps,
         },
@@ -433,65 +416,152 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": traffic,
+            "traffic": read_traffic(w.name, dominant),
+            "traffic_source": "stored: profiles/hbm_traffic_%s.txt, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs "
+                              "of this command (not measured in this run)" % w.name,
             "launch_ms": round(dominant_ms, 5),
             "timing": "HIP events around %d of the %d launches of the timed region (every %d-th step)"
                       % (len(events[::stride]), args.steps, stride),
         },
+        "two_streams": overlapped,
         "fused": fused,
+        "next_rows": next_rows,
         "norm_sign": norm_sign,
         "layer_stats": layer_stats,
         "setup_s": round(setup_s, 1),
     }
+    return result, w, host_grad
 
-    if not args.no_cpu_baseline:
-        import oracle
-        cores = oracle.get_max_threads()
-        # bounded sample: whole step for small workloads, else the first tensors up to ~64M elements
-        cap = 64_000_000
-        L_s = int(np.searchsorted(w.offsets, cap, side="right")) - 1 if w.n > cap else w.L
-        L_s = max(L_s, 1)
-        off_s, bits_s = w.offsets[:L_s + 1], w.bits[:L_s]
-        n_s = int(off_s[-1])
-        g_s = host_grad[:n_s]
-        cpu_bytes = n_s * S + 4 * n_s + 4 * n_s
 
-        def oracle_step():
-            t0 = time.perf_counter()
-            cp, cm = oracle.quantize(g_s, off_s, bits_s, w.bucket, 17, w.dt)
-            t1 = time.perf_counter()
-            s32 = oracle.dequant_reduce([cp] * W, [cm] * W, off_s, bits_s, w.bucket, w.dt, want=("sum32",))["sum32"]
-            t2 = time.perf_counter()
-            oracle.quantize(s32, off_s, bits_s, w.bucket, 29, wl.F32)
-            t3 = time.perf_counter()
-            return np.array([t1 - t0, t2 - t1, t3 - t2])
+def cpu_baseline(w, host_grad):
+    """The oracle, as it stands, on a bounded sample of the workload: one whole step."""
+    import numpy as np
 
-        # all threads: repeated until about 3 s have passed (at least twice), mean of the repeats
-        runs = [oracle_step()]
-        while len(runs) < 2 or (sum(r.sum() for r in runs) < 3.0 and len(runs) < 20):
-            runs.append(oracle_step())
-        t_all = np.mean(runs, axis=0)
-        # one thread, once
-        single = None
-        if n_s <= 128_000_000:
-            oracle.set_threads(1)
-            t_one = oracle_step()
-            oracle.set_threads(cores)
-            single = {"value": round(cpu_bytes / t_one.sum() / 1e9, 3), "unit": "GB/s", "cores": 1,
-                      "seconds": [round(float(t), 3) for t in t_one]}
-        result["cpu_baseline"] = {
-            "value": round(cpu_bytes / t_all.sum() / 1e9, 3),
-            "unit": "GB/s",
-            "cores": cores,
-            "kind": "oracle",
-            "sample": "one step (quantize + dequant_reduce W=%d + requantize) on the first %d tensors / %d "
-                      "elements of %s, OpenMP over buckets, mean of %d repeats" % (W, L_s, n_s, w.name, len(runs)),
-            "seconds": {"quantize": round(float(t_all[0]), 3), "dequant_reduce": round(float(t_all[1]), 3),
-                        "requantize": round(float(t_all[2]), 3)},
-            "single_thread": single,
-        }
-    else:
-        result["cpu_baseline"] = None
+    import oracle
+    from paper_2111_08617_amd import workloads as wl
+
+    W = w.W
+    S = 2 if w.dt == wl.F16 else 4
+    cores = oracle.get_max_threads()
+    # bounded sample: whole step for small workloads, else the first tensors up to ~64M elements
+    cap = 64_000_000
+    L_s = int(np.searchsorted(w.offsets, cap, side="right")) - 1 if w.n > cap else w.L
+    L_s = max(L_s, 1)
+    off_s, bits_s = w.offsets[:L_s + 1], w.bits[:L_s]
+    n_s = int(off_s[-1])
+    g_s = host_grad[:n_s]
+    cpu_bytes = n_s * S + 4 * n_s + 4 * n_s
+
+    def oracle_step():
+        t0 = time.perf_counter()
+        cp, cm = oracle.quantize(g_s, off_s, bits_s, w.bucket, 17, w.dt)
+        t1 = time.perf_counter()
+        s32 = oracle.dequant_reduce([cp] * W, [cm] * W, off_s, bits_s, w.bucket, w.dt, want=("sum32",))["sum32"]
+        t2 = time.perf_counter()
+        oracle.quantize(s32, off_s, bits_s, w.bucket, 29, wl.F32)
+        t3 = time.perf_counter()
+        return np.array([t1 - t0, t2 - t1, t3 - t2])
+
+    # all threads: repeated until about 3 s have passed (at least twice), mean of the repeats
+    runs = [oracle_step()]
+    while len(runs) < 2 or (sum(r.sum() for r in runs) < 3.0 and len(runs) < 20):
+        runs.append(oracle_step())
+    t_all = np.mean(runs, axis=0)
+    # one thread, once
+    single = None
+    if n_s <= 128_000_000:
+        oracle.set_threads(1)
+        t_one = oracle_step()
+        oracle.set_threads(cores)
+        single = {"value": round(cpu_bytes / t_one.sum() / 1e9, 3), "unit": "GB/s", "cores": 1,
+                  "seconds": [round(float(t), 3) for t in t_one]}
+    return {
+        "value": round(cpu_bytes / t_all.sum() / 1e9, 3),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": "one step (quantize + dequant_reduce W=%d + requantize) on the first %d tensors / %d "
+                  "elements of %s, OpenMP over buckets, mean of %d repeats" % (W, L_s, n_s, w.name, len(runs)),
+        "seconds": {"quantize": round(float(t_all[0]), 3), "dequant_reduce": round(float(t_all[1]), 3),
+                    "requantize": round(float(t_all[2]), 3)},
+        "single_thread": single,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="decoder_1p3b",
+                    choices=["single_1m", "resnet50", "bert_base", "gpt2_medium", "decoder_1p3b"],
+                    help="the headline workload")
+    ap.add_argument("--also", default="resnet50",
+                    help="a second workload measured in the same run and reported as a block of its own "
+                         "('none': only the headline workload)")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="distinct buffer sets cycled through so that launches do not re-hit the 256 MB "
+                         "memory-side cache (0 = enough for 2.5 GB of traffic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--spin-up-ms", type=float, default=50.0,
+                    help="untimed steps run for this long before the warmup steps, so that the clocks have "
+                         "settled whatever --warmup is (the first ~10 ms of activity run slower)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="time the step alone: no two-stream / fused / other entry points / norm-and-sign / "
+                         "statistics / probe legs and no second workload (for counter runs, where every dispatch "
+                         "is slow)")
+    ap.add_argument("--with-fused", action="store_true",
+                    help="with --step-only: run the fused leg (quantize + dequant_reduce_requantize) as well")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB three times: "
+                         "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its known size gives the factor "
+                         "that scales the counters to bytes")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the W peers of the reduce step are W compressed "
+                 "chunks resident in HBM); run with --gpus 1")
+
+    import torch
+
+    from paper_2111_08617_amd import binding as cgx
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    cgx.lib()
+
+    head, w, host_grad = measure(args.workload, args, extras=not args.step_only)
+    result = {
+        "metric": "GB/s of fp32 gradient quantized and dequant-reduced (W=8); % of HBM peak",
+        "value": head.pop("value"),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head.pop("ms_per_step"),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": head.pop("dtype"),
+        "data": "synthetic",
+    }
+    result.update(head)
+
+    if args.calibration_copy:
+        # an elementwise kernel that reads 1 GiB and writes 1 GiB (grid unlike any cgx launch)
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    result["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w, host_grad)
+    del host_grad
+
+    if args.also != "none" and args.also != args.workload and not args.step_only:
+        torch.cuda.empty_cache()
+        second, _, _ = measure(args.also, args, extras=True)
+        second["unit"] = "GB/s"
+        result[args.also] = second
 
     print(json.dumps(result))
 
