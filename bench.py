@@ -488,6 +488,95 @@ def cpu_baseline(w, host_grad):
     }
 
 
+CEILING_CASES = [
+    # name, bytes read, bytes written: the read:write mixes and sizes of the calls of the two target workloads,
+    # and pure reads / writes / copies of the same sizes
+    ("quantize resnet50 (8:1, 115 MB)", 102_228_128, 13_167_184),
+    ("dequant_reduce resnet50 (1:1, 208 MB)", 105_337_472, 102_228_128),
+    ("quantize decoder_1p3b (6:1, 6.1 GB)", 5_262_893_056, 844_533_008),
+    ("dequant_reduce decoder_1p3b share (5:4, 1.5 GB)", 811_545_472, 657_858_560),
+    ("requantize decoder_1p3b share (6:1, 0.76 GB)", 657_858_560, 101_443_184),
+    ("read only, 115 MB", 115_343_360, 0),
+    ("read only, 1.5 GB", 1_500_000_256, 0),
+    ("read only, 6 GB", 6_000_000_000, 0),
+    ("write only, 115 MB", 0, 115_343_360),
+    ("write only, 1.5 GB", 0, 1_500_000_256),
+    ("copy 1:1, 1.5 GB", 750_000_128, 750_000_128),
+    ("copy 1:1, 6 GB", 3_000_000_000, 3_000_000_000),
+]
+
+
+def ceilings(args):
+    """What a kernel that only moves bytes sustains, by launch shape and cache policy: a staged sweep of
+    cgx_stream_probe_shaped per (size, read:write mix).  Stage 1: every load x store policy at the kernels' own
+    shape; stage 2: slice size x block size x die-contiguous numbering for the best three policy pairs; stage 3:
+    persistent grids for the best shape.  Event-timed, median of `reps` launches over rotated buffers."""
+    import numpy as np
+    import torch
+
+    from paper_2111_08617_amd import binding as cgx
+
+    dev = torch.device("cuda:0")
+    reps = max(args.steps // 2, 7)
+    out = {"mode": "ceilings", "peak_GBps": HBM_PEAK_GBPS, "reps": reps, "cases": []}
+    pick = [c for c in CEILING_CASES if args.ceilings_case in c[0]]
+    for name, rb, wb in pick:
+        rb, wb = rb // 16 * 16, wb // 16 * 16
+        R = max(2, min(8, int(np.ceil(2.5e9 / (rb + wb)))))
+        srcs = [torch.zeros(max(rb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
+        dsts = [torch.empty(max(wb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
+        tried = {}
+
+        def run(slice_bytes=8192, block=256, loads="nt", stores="nt", xcd=False, max_blocks=0):
+            key = (slice_bytes, block, loads, stores, xcd, max_blocks)
+            if key in tried:
+                return tried[key]
+            call = lambda i: cgx.cgx_stream_probe_shaped(srcs[i % R], rb, dsts[i % R], wb, slice_bytes, block, loads,
+                                                         stores, xcd, max_blocks)
+            for i in range(2):
+                call(i)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+            torch.cuda.synchronize()
+            for i in range(reps):
+                evs[i][0].record()
+                call(i)
+                evs[i][1].record()
+            torch.cuda.synchronize()
+            ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
+            tried[key] = ms
+            return ms
+
+        base = run()
+        for loads in cgx.LOAD_POLICIES if rb else ("nt",):
+            for stores in cgx.STORE_POLICIES if wb else ("nt",):
+                run(loads=loads, stores=stores)
+        best_pol = sorted({(k[2], k[3]): v for k, v in tried.items()}.items(), key=lambda kv: kv[1])[:3]
+        for (loads, stores), _ in best_pol:
+            for slice_bytes in (2048, 4096, 8192, 16384, 32768, 65536):
+                for block in (64, 256, 1024):
+                    for xcd in (False, True):
+                        run(slice_bytes, block, loads, stores, xcd)
+        best = min(tried, key=tried.get)
+        for max_blocks in (256, 512, 1024, 2048, 4096, 8192):
+            for slice_bytes in (8192, 65536, 1 << 20):
+                run(slice_bytes, best[1], best[2], best[3], best[4], max_blocks)
+        best = min(tried, key=tried.get)
+        rows = [{"slice_bytes": k[0], "block_threads": k[1], "loads": k[2], "stores": k[3], "die_contiguous": k[4],
+                 "max_blocks": k[5], "ms": round(v, 5), "GBps": round((rb + wb) / v / 1e6, 1),
+                 "hbm_frac": round((rb + wb) / v / 1e6 / HBM_PEAK_GBPS, 4)} for k, v in sorted(tried.items(), key=lambda kv: kv[1])]
+        out["cases"].append({"case": name, "read_bytes": rb, "write_bytes": wb, "buffer_sets_rotated": R,
+                             "kernels_own_shape": {"ms": round(base, 5),
+                                                   "hbm_frac": round((rb + wb) / base / 1e6 / HBM_PEAK_GBPS, 4)},
+                             "best": rows[0], "configs_tried": len(rows), "top": rows[:12],
+                             "policies_at_own_shape": [r for r in rows if (r["slice_bytes"], r["block_threads"],
+                                                                             r["die_contiguous"], r["max_blocks"]) ==
+                                                       (8192, 256, False, 0)],
+                             "all": rows if args.ceilings_all else None})
+        del srcs, dsts
+        torch.cuda.empty_cache()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__)
     ap.add_argument("--gpus", type=int, default=1)
@@ -516,6 +605,11 @@ def main():
                     help="also run a plain elementwise kernel that reads 1 GiB and writes 1 GiB three times: "
                          "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its known size gives the factor "
                          "that scales the counters to bytes")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the step: sweep the arithmetic-free streaming probe over launch shapes and cache "
+                         "policies at the sizes and read:write mixes of the calls (what the memory system allows)")
+    ap.add_argument("--ceilings-case", default="", help="with --ceilings: only the cases whose name contains this")
+    ap.add_argument("--ceilings-all", action="store_true", help="with --ceilings: list every configuration tried")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the W peers of the reduce step are W compressed "
@@ -527,6 +621,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     cgx.lib()
+    if args.ceilings:
+        ceilings(args)
+        return
 
     head, w, host_grad = measure(args.workload, args, extras=not args.step_only)
     result = {

@@ -367,38 +367,6 @@ int cgx_assign_buckets_from_bits(int32_t L, const uint8_t *bits_per_layer /* hos
                                  const int32_t *bucket_candidates /* host [kb] */, int32_t kb,
                                  int32_t *buckets_out /* host [L] */);
 
-/*
- * Diagnostic: the table of wavefront work items ("tiles") the kernels walk for
- * a plan, written to host memory as 32-byte records
- *   { int64 first_element; int64 packed_byte_offset; uint32 first_bucket;
- *     uint32 elements; uint32 info; uint32 pad_bytes }
- * with info = bits | kind << 4 | log2(lanes per bucket) << 8 | (bucket / 32) << 12 (the last
- * two fields are 0 where they do not apply) and kind 0 = generic
- * quantize, 1 = vectorised quantize, 2 = element-wise copy, 3 = vectorised copy,
- * 4 = vectorised quantize of one whole bucket of 4096 or 8192 elements, 5 = the short end
- * of a layer (less than a chunk of 2048 elements) with power-of-two buckets.
- * Every element of every non-empty layer lies in exactly one tile and tiles never
- * cross layers (paper Sec. 4.1).  This is the table of one chunk per vectorised
- * tile that most calls walk: cgx_quantize on a binary16 gradient of 2^24 elements
- * or more, and the fused reduce + requantize on 2^27 elements or more, join 2 or 4
- * consecutive chunks of a layer into one tile (same bytes out; a wave's set-up is
- * spread over more input).  At most `capacity` records
- * are written; *n_tiles receives the full count.  Pure host computation.
- */
-int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
-                   int32_t bucket, cgx_dtype dt, void *tiles_out /* host */, int64_t capacity,
-                   int64_t *n_tiles);
-
-/*
- * Measurement aid, not part of the method: one launch that reads read_bytes from src and
- * writes write_bytes to dst (both device, 16-byte aligned, sizes multiples of 16) with the
- * kernels' access style (one wavefront per 8 KB slice, non-temporal 16-byte vectors,
- * lane-contiguous) and no arithmetic.  Its rate is what the memory system gives a kernel with
- * that read:write mix at that size; the benchmark reports it next to each kernel.  What is
- * written to dst is unspecified.
- */
-int cgx_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream);
-
 /* Human-readable name of a status code (static storage). */
 const char *cgx_status_string(int status);
 

@@ -29,7 +29,7 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_layered_dequant_reduce_requantize", "cgx_layered_dequant_reduce_add", "cgx_layered_dequantize",
            "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors", "cgx_qsgd_layered_sizes",
            "cgx_qsgd_layered_quantize", "cgx_qsgd_layered_dequant_reduce", "cgx_qsgd_layered_dequant_reduce_requantize",
-           "cgx_plan_tiles", "cgx_stream_probe",
+           "cgx_plan_tiles", "cgx_plan_tiles_chunk", "cgx_stream_probe", "cgx_stream_probe_shaped",
            "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
@@ -102,7 +102,9 @@ def lib() -> ctypes.CDLL:
         L.cgx_assign_buckets_from_bits.argtypes = [c.c_int32, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
                                                    c.c_void_p]
         L.cgx_stream_probe.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.cgx_stream_probe_shaped.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
+        L.cgx_plan_tiles_chunk.argtypes = plan + [c.c_int, c.c_int32, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_status_string.restype = c.c_char_p
         L.cgx_status_string.argtypes = [c.c_int]
         L.cgx_shutdown.argtypes = []
@@ -172,13 +174,14 @@ def cgx_sizes(plan: Plan) -> Tuple[int, int]:
     return int(pb.value), int(mb.value)
 
 
-def cgx_plan_tiles(plan: Plan) -> np.ndarray:
-    """The tile table of a plan as a structured numpy array (host only)."""
+def cgx_plan_tiles(plan: Plan, chunk: int = 2048) -> np.ndarray:
+    """The tile table of a plan, for kernels with chunks of `chunk` elements (1024 or 2048), as a
+    structured numpy array (host only)."""
     count = ctypes.c_int64()
-    _check(lib().cgx_plan_tiles(*plan.args, plan.dt, None, 0, ctypes.byref(count)), "cgx_plan_tiles")
+    _check(lib().cgx_plan_tiles_chunk(*plan.args, plan.dt, chunk, None, 0, ctypes.byref(count)), "cgx_plan_tiles_chunk")
     tiles = np.zeros(count.value, dtype=TILE_DTYPE)
-    _check(lib().cgx_plan_tiles(*plan.args, plan.dt, tiles.ctypes.data, count.value, ctypes.byref(count)),
-           "cgx_plan_tiles")
+    _check(lib().cgx_plan_tiles_chunk(*plan.args, plan.dt, chunk, tiles.ctypes.data, count.value, ctypes.byref(count)),
+           "cgx_plan_tiles_chunk")
     return tiles
 
 
@@ -441,6 +444,22 @@ def cgx_stream_probe(src, read_bytes: int, dst, write_bytes: int, stream=None) -
     """Measurement aid: one launch reading read_bytes from src and writing write_bytes to dst."""
     _check(lib().cgx_stream_probe(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes, _stream(stream)),
            "cgx_stream_probe")
+
+
+LOAD_POLICIES = ("plain", "nt", "sc1", "sc0 sc1")
+STORE_POLICIES = ("plain", "nt", "sc0 sc1", "sc0 sc1 nt", "sc1")
+
+
+def cgx_stream_probe_shaped(src, read_bytes: int, dst, write_bytes: int, slice_bytes: int = 8192,
+                            block_threads: int = 256, loads: str = "nt", stores: str = "nt",
+                            xcd_contiguous: bool = False, max_blocks: int = 0, paired_loads: bool = False,
+                            alu_ops_per_pass: int = 0, lds_bytes_per_block: int = 0, stream=None) -> None:
+    """The probe with its launch shape and cache policies chosen by the caller (see cgx_diag.h)."""
+    shape = (ctypes.c_int32 * 9)(slice_bytes, block_threads, LOAD_POLICIES.index(loads), STORE_POLICIES.index(stores),
+                                 int(xcd_contiguous), max_blocks, int(paired_loads), alu_ops_per_pass,
+                                 lds_bytes_per_block)
+    _check(lib().cgx_stream_probe_shaped(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes, shape,
+                                         _stream(stream)), "cgx_stream_probe_shaped")
 
 
 def cgx_shutdown() -> None:

@@ -9,8 +9,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcgx.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["cgx_plan.cpp", "cgx_api.cpp", "cgx_adaptive.cpp", "cgx_quantize.hip", "cgx_reduce.hip", "cgx_fused.hip",
-           "cgx_stats.hip"]
+# (source, object name, extra flags): the quantize kernel is built for chunks of 1024 and of 2048 elements
+SOURCES = [("cgx_plan.cpp", "cgx_plan", []), ("cgx_api.cpp", "cgx_api", []), ("cgx_adaptive.cpp", "cgx_adaptive", []),
+           ("cgx_quantize.hip", "cgx_quantize_g2", ["-DCGX_GROUPS=2"]),
+           ("cgx_quantize.hip", "cgx_quantize_g4", ["-DCGX_GROUPS=4"]),
+           ("cgx_reduce.hip", "cgx_reduce", []), ("cgx_fused.hip", "cgx_fused", []), ("cgx_stats.hip", "cgx_stats", []),
+           ("cgx_probe.hip", "cgx_probe", [])]
 
 # -ffp-contract=off: the code decision is binary32 without fused operations.
 # packed-fp32 instructions stay disabled for this target.
@@ -24,9 +28,10 @@ def build(verbose: bool = False, extra=(), jobs: int = 8) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
 
-    def compile_one(src):
-        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    def compile_one(item):
+        src, name, flags = item
+        obj = os.path.join(OBJ, name + ".o")
+        cmd = [hipcc, *FLAGS, *flags, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         subprocess.run(cmd, check=True, cwd=CSRC)

@@ -8,6 +8,7 @@
 #include <mutex>
 #include <vector>
 
+#include "../../include/cgx_diag.h"
 #include "cgx_kernels.h"
 #include "cgx_plan.h"
 
@@ -20,6 +21,7 @@ struct CachedPlan {
     int device = 0;
     int32_t bucket = 0;
     int dt = 0;
+    int chunk = 0;              // elements per chunk of the kernels that walk this table
     int chunks_per_tile = 0;
     std::vector<int64_t> off;
     std::vector<uint8_t> bits;
@@ -30,6 +32,7 @@ struct CachedPlan {
     int64_t n_tiles = 0;
     int64_t plan_tiles = 0;     // tiles of the whole plan: n_tiles, or the sum over the launches of a layered plan
     bool odd_tiles = false;     // some vectorised quantized tile starts on an odd element index
+    bool aligned_tiles = true;  // every vectorised quantized tile starts on a 16-byte boundary of the buffer
     bool many_tails = false;    // the reduce kernel with the masked path for short ends of layers pays (see get_plan)
     Tile *d_tiles = nullptr;
     // per-layer numbering of the tiles (for the statistics): slot of every tile, first slot of every layer
@@ -83,6 +86,8 @@ const cgx::LaunchConfig &launch_config()
         cgx::LaunchConfig c;
         c.chunks_per_tile = env_int("CGX_CHUNKS_PER_TILE", 0);
         c.max_blocks = env_int("CGX_MAX_BLOCKS", c.max_blocks);
+        c.via_lds = env_int("CGX_VIA_LDS", c.via_lds);
+        c.quantize_groups = env_int("CGX_QUANTIZE_GROUPS", 0) == 2 ? 2 : env_int("CGX_QUANTIZE_GROUPS", 0) == 4 ? 4 : 0;
         return c;
     }();
     return cfg;
@@ -96,6 +101,19 @@ const cgx::LaunchConfig &launch_config()
 //  - the fused reduce + requantize, which is bound by arithmetic: 2 chunks (3-6 % faster at
 //    164-268 M elements for every width).
 enum CallKind { kQuantizeCall, kFusedCall, kOtherCall };
+
+// Elements per chunk of the kernel a call runs.  The quantizer of binary32 input takes chunks of 1024
+// elements (4 KB per wave and pass: measured, a streaming kernel sustains about a tenth more with 4 KB
+// per wave than with 8 KB, and the quantizer follows it: 0.74 -> 0.78 of the HBM peak on 1.3 G
+// elements); on binary16 a chunk of 2048 elements is 4 KB already.  The reduce, fused and statistics
+// kernels take 2048 (a peer's codes of a chunk then fill a whole load instruction at 4 bits).
+int chunk_length(CallKind call, int dt)
+{
+    const int forced = launch_config().quantize_groups;
+    if (call == kQuantizeCall) return cgx::chunk_of(forced > 0 ? forced : dt == CGX_F32 ? 2 : 4);
+    return cgx::kDefaultChunk;
+}
+
 int tile_length(CallKind call, int dt, int64_t n)
 {
     const int forced = launch_config().chunks_per_tile;
@@ -120,13 +138,13 @@ struct Launch {
     int32_t bucket;
     bool with_copies;
 };
-std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off, const uint8_t *bits)
+std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off, const uint8_t *bits, int chunk)
 {
     if (!b.per_layer) return {{b.uniform, true}};
     int32_t smallest[3] = {0, 0, 0};
     for (int32_t l = 0; l < L; l++)
         if (bits[l] != 0 && off[l + 1] > off[l]) {
-            int32_t &s = smallest[cgx::mapping_of(b.per_layer[l])];
+            int32_t &s = smallest[cgx::mapping_of(b.per_layer[l], chunk)];
             if (s == 0 || b.per_layer[l] < s) s = b.per_layer[l];
         }
     std::vector<Launch> out;
@@ -137,15 +155,15 @@ std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off,
 }
 
 // Finds or builds the device-resident tile table of a (valid) plan.
-int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunks_per_tile,
-             PlanRef *out, const int32_t *layer_buckets = nullptr, bool with_copies = true)
+int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunk,
+             int chunks_per_tile, PlanRef *out, const int32_t *layer_buckets = nullptr, bool with_copies = true)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return CGX_ERR_HIP;
     for (const auto &p : g_plans) {
         if (p->device == device && p->bucket == bucket && p->dt == dt &&
-            p->chunks_per_tile == chunks_per_tile && p->bits.size() == size_t(L) &&
+            p->chunk == chunk && p->chunks_per_tile == chunks_per_tile && p->bits.size() == size_t(L) &&
             p->with_copies == with_copies && p->layer_buckets.size() == (layer_buckets ? size_t(L) : 0) &&
             (!layer_buckets || L == 0 ||
              std::memcmp(p->layer_buckets.data(), layer_buckets, sizeof(int32_t) * size_t(L)) == 0) &&
@@ -163,6 +181,7 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     plan->device = device;
     plan->bucket = bucket;
     plan->dt = dt;
+    plan->chunk = chunk;
     plan->chunks_per_tile = chunks_per_tile;
     plan->off.assign(off, off + L + 1);
     plan->bits.assign(bits, bits + L);
@@ -172,7 +191,7 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     std::vector<Tile> tiles;
     std::vector<uint32_t> slots;
     std::vector<int64_t> layer_first;
-    cgx::build_tiles(L, off, bits, bucket, dt, chunks_per_tile, tiles, &slots, &layer_first, layer_buckets,
+    cgx::build_tiles(L, off, bits, bucket, dt, chunk, chunks_per_tile, tiles, &slots, &layer_first, layer_buckets,
                      with_copies);
     if (tiles.size() > size_t(0xffffffffu)) return CGX_ERR_SIZE;
     plan->n_tiles = int64_t(tiles.size());
@@ -181,11 +200,11 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
         // The per-layer statistics number the tiles of the WHOLE plan layer by layer; this table
         // holds one launch's share of them, so its tiles take their numbers in that common order.
         std::vector<int64_t> common(size_t(L) + 1, 0);
-        for (const Launch &other : launches_of(Buckets{bucket, layer_buckets}, L, off, bits)) {
+        for (const Launch &other : launches_of(Buckets{bucket, layer_buckets}, L, off, bits, chunk)) {
             std::vector<Tile> their_tiles;
             std::vector<uint32_t> their_slots;
             std::vector<int64_t> their_first;
-            cgx::build_tiles(L, off, bits, other.bucket, dt, chunks_per_tile, their_tiles, &their_slots, &their_first,
+            cgx::build_tiles(L, off, bits, other.bucket, dt, chunk, chunks_per_tile, their_tiles, &their_slots, &their_first,
                              layer_buckets, other.with_copies);
             for (int32_t l = 0; l < L; l++) common[size_t(l) + 1] += their_first[size_t(l) + 1] - their_first[size_t(l)];
         }
@@ -202,6 +221,9 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     for (const Tile &t : tiles)
         if ((cgx::is_vector_kind(cgx::tile_kind(t)) || cgx::tile_kind(t) == cgx::kQuantTail) && (t.elem0 & 1))
             plan->odd_tiles = true;
+    for (const Tile &t : tiles)
+        if (cgx::is_vector_kind(cgx::tile_kind(t)) && (t.elem0 * (dt == CGX_F16 ? 2 : 4)) % 16 != 0)
+            plan->aligned_tiles = false;
     int64_t tails = 0;
     for (const Tile &t : tiles) tails += cgx::tile_kind(t) == cgx::kQuantTail;
     // One short end that goes through the generic path is a chain of dependent round trips,
@@ -250,13 +272,15 @@ int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int6
     const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, buckets.uniform, dt, buckets.per_layer);
     if (!grad || !packed || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
     if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
-    for (const Launch &launch : launches_of(buckets, L, off, bits)) {
+    const int chunk = chunk_length(kQuantizeCall, dt);
+    const auto launch_quantize = chunk == cgx::chunk_of(2) ? cgx::launch_quantize_g2 : cgx::launch_quantize_g4;
+    for (const Launch &launch : launches_of(buckets, L, off, bits, chunk)) {
         PlanRef plan;
-        rc = get_plan(L, off, bits, launch.bucket, dt, tile_length(kQuantizeCall, dt, n), &plan, buckets.per_layer,
-                      launch.with_copies);
+        rc = get_plan(L, off, bits, launch.bucket, dt, chunk, tile_length(kQuantizeCall, dt, n), &plan,
+                      buckets.per_layer, launch.with_copies);
         if (rc != CGX_OK) return rc;
-        const hipError_t e = cgx::launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles,
-                                                  launch.bucket, seed, packed, meta, launch_config(),
+        const hipError_t e = launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles,
+                                                  plan->aligned_tiles, launch.bucket, seed, packed, meta, launch_config(),
                                                   static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return CGX_ERR_HIP;
     }
@@ -279,10 +303,10 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
-    for (const Launch &launch : launches_of(buckets, L, off, bits)) {
+    for (const Launch &launch : launches_of(buckets, L, off, bits, cgx::kDefaultChunk)) {
         PlanRef plan;
-        rc = get_plan(L, off, bits, launch.bucket, dt, tile_length(kOtherCall, dt, n), &plan, buckets.per_layer,
-                      launch.with_copies);
+        rc = get_plan(L, off, bits, launch.bucket, dt, cgx::kDefaultChunk, tile_length(kOtherCall, dt, n), &plan,
+                      buckets.per_layer, launch.with_copies);
         if (rc != CGX_OK) return rc;
         // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
         // a later launch starts from the binary32 result of the one before (W <= kPeersPerLaunch
@@ -327,13 +351,13 @@ int fused_impl(int scheme, const void *const *packed, const void *const *meta, i
         peers.packed[i] = static_cast<const uint8_t *>(packed[i]);
         peers.meta[i] = static_cast<const float *>(meta[i]);
     }
-    for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer)) {
+    for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer, cgx::kDefaultChunk)) {
         PlanRef in, out;
-        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, dt, tile_length(kFusedCall, dt, n), &in,
-                      buckets.per_layer, launch.with_copies);
+        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, dt, cgx::kDefaultChunk,
+                      tile_length(kFusedCall, dt, n), &in, buckets.per_layer, launch.with_copies);
         if (rc != CGX_OK) return rc;
-        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, CGX_F32, tile_length(kFusedCall, dt, n), &out,
-                      buckets.per_layer, launch.with_copies);
+        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, CGX_F32, cgx::kDefaultChunk,
+                      tile_length(kFusedCall, dt, n), &out, buckets.per_layer, launch.with_copies);
         if (rc != CGX_OK) return rc;
         if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
         const hipError_t e = cgx::launch_dequant_reduce_requantize(
@@ -358,7 +382,7 @@ int stats_tiles(int64_t n, int32_t L, const int64_t *off, const uint8_t *bits, i
     const int rc = cgx::validate_plan(n, L, off, bits, bucket, dt);
     if (rc != CGX_OK) return rc;
     std::vector<Tile> tiles;
-    cgx::build_tiles(L, off, bits, bucket, dt, tile_length(kOtherCall, dt, n), tiles);
+    cgx::build_tiles(L, off, bits, bucket, dt, cgx::kDefaultChunk, tile_length(kOtherCall, dt, n), tiles);
     *n_tiles = int64_t(tiles.size());
     return CGX_OK;
 }
@@ -376,11 +400,11 @@ int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *
         (reinterpret_cast<uintptr_t>(sqerr) & 7u))
         return CGX_ERR_ALIGN;
     // every launch leaves its tiles' partial sums in the workspace; the last one adds them up layer by layer
-    const std::vector<Launch> launches = launches_of(buckets, L, off, bits);
+    const std::vector<Launch> launches = launches_of(buckets, L, off, bits, cgx::kDefaultChunk);
     for (size_t i = 0; i < launches.size(); i++) {
         PlanRef plan;
-        rc = get_plan(L, off, bits, launches[i].bucket, dt, tile_length(kOtherCall, dt, n), &plan, buckets.per_layer,
-                      launches[i].with_copies);
+        rc = get_plan(L, off, bits, launches[i].bucket, dt, cgx::kDefaultChunk, tile_length(kOtherCall, dt, n), &plan,
+                      buckets.per_layer, launches[i].with_copies);
         if (rc != CGX_OK) return rc;
         if (workspace_bytes < size_t(plan->plan_tiles) * sizeof(double)) return CGX_ERR_SIZE;
         const hipError_t e = cgx::launch_layer_sqerrors(
@@ -538,9 +562,10 @@ int cgx_layered_stats_workspace(int64_t n, int32_t L, const int64_t *layer_offse
     const int rc = check_plan(cgx::kSchemeMinMax, n, L, layer_offsets, bits_per_layer, buckets, int(dt));
     if (rc != CGX_OK) return rc;
     size_t tiles_of_plan = 0;
-    for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer)) {
+    for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer, cgx::kDefaultChunk)) {
         std::vector<Tile> tiles;
-        cgx::build_tiles(L, layer_offsets, bits_per_layer, launch.bucket, int(dt), tile_length(kOtherCall, int(dt), n),
+        cgx::build_tiles(L, layer_offsets, bits_per_layer, launch.bucket, int(dt), cgx::kDefaultChunk,
+                         tile_length(kOtherCall, int(dt), n),
                          tiles, nullptr, nullptr, buckets_per_layer, launch.with_copies);
         tiles_of_plan += tiles.size();
     }
@@ -657,7 +682,8 @@ int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *laye
     if (!sqnorm || (n > 0 && (!buf || !workspace))) return CGX_ERR_NULL;
     if (misaligned(buf) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(sqnorm) & 7u)) return CGX_ERR_ALIGN;
     PlanRef plan;
-    rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), tile_length(kOtherCall, int(dt), n), &plan);
+    rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), cgx::kDefaultChunk, tile_length(kOtherCall, int(dt), n),
+                  &plan);
     if (rc != CGX_OK) return rc;
     if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
     const hipError_t e = cgx::launch_layer_sqnorms(buf, int(dt), plan->d_tiles, plan->d_slots, plan->n_tiles,
@@ -712,24 +738,57 @@ int cgx_qsgd_layer_sqerrors(const void *grad, const void *packed, const void *me
 int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
                    int32_t bucket, cgx_dtype dt, void *tiles_out, int64_t capacity, int64_t *n_tiles)
 {
+    return cgx_plan_tiles_chunk(n, L, layer_offsets, bits_per_layer, bucket, dt, cgx::kDefaultChunk, tiles_out, capacity,
+                                n_tiles);
+}
+
+int cgx_plan_tiles_chunk(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
+                         int32_t bucket, cgx_dtype dt, int32_t chunk_elements, void *tiles_out, int64_t capacity,
+                         int64_t *n_tiles)
+{
     const int rc = cgx::validate_plan(n, L, layer_offsets, bits_per_layer, bucket, int(dt));
     if (rc != CGX_OK) return rc;
+    if (chunk_elements != cgx::chunk_of(2) && chunk_elements != cgx::chunk_of(4)) return CGX_ERR_SIZE;
     if (!n_tiles || (capacity > 0 && !tiles_out)) return CGX_ERR_NULL;
     std::vector<Tile> tiles;
-    cgx::build_tiles(L, layer_offsets, bits_per_layer, bucket, int(dt), tile_length(kOtherCall, int(dt), n), tiles);
+    cgx::build_tiles(L, layer_offsets, bits_per_layer, bucket, int(dt), chunk_elements, 1, tiles);
     *n_tiles = int64_t(tiles.size());
     const int64_t k = capacity < *n_tiles ? capacity : *n_tiles;
     if (k > 0) std::memcpy(tiles_out, tiles.data(), size_t(k) * sizeof(Tile));
     return CGX_OK;
 }
 
-int cgx_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream)
+int cgx_stream_probe_shaped(const void *src, size_t read_bytes, void *dst, size_t write_bytes,
+                            const cgx_probe_shape *shape, void *stream)
 {
-    if ((read_bytes && !src) || (write_bytes && !dst)) return CGX_ERR_NULL;
+    if (!shape || (read_bytes && !src) || (write_bytes && !dst)) return CGX_ERR_NULL;
     if (read_bytes % 16 || write_bytes % 16) return CGX_ERR_SIZE;
     if (misaligned(src) || misaligned(dst)) return CGX_ERR_ALIGN;
-    const hipError_t e = cgx::launch_stream_probe(src, read_bytes, dst, write_bytes, static_cast<hipStream_t>(stream));
+    const int32_t s = shape->slice_bytes, t = shape->block_threads;
+    if (s < 1024 || s > (1 << 20) || (s & (s - 1)) || (t != 64 && t != 128 && t != 256 && t != 512 && t != 1024) ||
+        shape->load_policy < 0 || shape->load_policy > 3 || shape->store_policy < 0 || shape->store_policy > 4 ||
+        (shape->xcd_contiguous != 0 && shape->xcd_contiguous != 1) || shape->max_blocks < 0 ||
+        (shape->paired_loads != 0 && shape->paired_loads != 1) || shape->alu_ops_per_pass < 0 ||
+        shape->alu_ops_per_pass > 65536 || shape->lds_bytes_per_block < 0 || shape->lds_bytes_per_block > 65536)
+        return CGX_ERR_SIZE;
+    cgx::ProbeShape k;
+    k.slice_bytes = s;
+    k.block_threads = t;
+    k.load_policy = shape->load_policy;
+    k.store_policy = shape->store_policy;
+    k.xcd_contiguous = shape->xcd_contiguous;
+    k.max_blocks = shape->max_blocks;
+    k.paired_loads = shape->paired_loads;
+    k.alu_ops_per_pass = shape->alu_ops_per_pass;
+    k.lds_bytes_per_block = shape->lds_bytes_per_block;
+    const hipError_t e = cgx::launch_stream_probe(src, read_bytes, dst, write_bytes, k, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
+int cgx_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream)
+{
+    const cgx_probe_shape shape = {8192, 256, 1, 1, 0, 0, 0, 0, 0};      // the kernels' own style
+    return cgx_stream_probe_shaped(src, read_bytes, dst, write_bytes, &shape, stream);
 }
 
 const char *cgx_status_string(int status)

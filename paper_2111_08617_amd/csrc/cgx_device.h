@@ -6,9 +6,11 @@
 // (cgx_fused.hip), per-layer statistics and the streaming probe (cgx_stats.hip).
 //
 // One wavefront (64 lanes) owns one tile of the plan.  In the vectorised path a
-// wave takes a chunk of kChunk = 2048 elements per pass: each lane holds 4 groups
+// wave takes a chunk of kChunk elements per pass: each lane holds kGroups groups
 // of 8 consecutive elements, all of the same bucket (a bucket of B elements
-// spans B/32 neighbouring lanes), so
+// spans B / (8 kGroups) neighbouring lanes).  kGroups is fixed per translation unit
+// (CGX_GROUPS: 4 unless the build says otherwise, i.e. chunks of 2048 elements; the
+// binary32 quantizer is also built with 2), so
 //   - the bucket minimum / maximum is a lane-local reduction over 32 values
 //     followed by a log2(B/32)-step butterfly across lanes (DPP within a row of
 //     16 lanes, ds_swizzle across rows, a permute across the two halves);
@@ -46,6 +48,12 @@ __device__ __forceinline__ KernargPeers &first_kernel_argument()
 {
     return *(KernargPeers *)__builtin_amdgcn_kernarg_segment_ptr();
 }
+
+#ifndef CGX_GROUPS
+#define CGX_GROUPS 4
+#endif
+constexpr int kGroups = CGX_GROUPS;            // groups of 8 elements per lane and chunk
+constexpr int kChunk = chunk_of(kGroups);      // elements a wave takes per pass of the vectorised path
 
 constexpr int kWave = 64;
 #ifndef CGX_WAVES_PER_BLOCK

@@ -158,7 +158,7 @@ hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, i
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
-    const bool wide = mapping_of(bucket) == kMapWide;
+    const bool wide = mapping_of(bucket, kChunk) == kMapWide;
     using Kernel = void (*)(const PeerPtrs, int, int, const Tile *, const Tile *, int64_t, uint32_t, uint32_t,
                             uint8_t *, float *);
     static const Kernel table[2][2][2] = {

@@ -24,13 +24,24 @@ struct PeerPtrs {
 struct LaunchConfig {
     int chunks_per_tile = 0;   // fast-tile length in chunks of kChunk elements; 0: chosen per call
     int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
+    int via_lds = 1;           // quantize: fetch aligned chunks through LDS
+    int quantize_groups = 0;   // 2 or 4: chunk size of every quantize call; 0: chosen per call
 };
 
 // odd_tiles: some vectorised tile starts on an odd element index (the kernels then take the
 // variant that can draw across generator words; a property of the tile table).
-hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
-                           int32_t bucket, uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
-                           hipStream_t stream);
+// aligned_tiles: every vectorised tile starts on a 16-byte boundary of the buffer (its chunks can then be
+// fetched through LDS with whole-line loads).
+// The quantize kernel is built for chunks of 1024 elements (_g2: two groups of 8 per lane) and of 2048
+// (_g4); `tiles` must have been built for that chunk size.
+hipError_t launch_quantize_g2(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
+                              bool aligned_tiles, int32_t bucket, uint64_t seed, void *packed, void *meta,
+                              const LaunchConfig &cfg, hipStream_t stream);
+hipError_t launch_quantize_g4(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
+                              bool aligned_tiles, int32_t bucket, uint64_t seed, void *packed, void *meta,
+                              const LaunchConfig &cfg, hipStream_t stream);
+// Chunk size of every other kernel (reduce, fused, statistics).
+constexpr int kDefaultChunk = chunk_of(4);
 
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
 // term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
@@ -70,9 +81,20 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
 hipError_t launch_layer_sqnorms_noalloc(const void *buf, int dt, const int64_t *off, const int64_t *first, int32_t L,
                                         double *out, hipStream_t stream);
 
-// Measurement aid: streams read_bytes in and write_bytes out (multiples of 16) with the access
-// style of the kernels and no arithmetic; see cgx_stream_probe in cgx.h.
+// Measurement aid (cgx_diag.h): streams read_bytes in and write_bytes out (multiples of 16) with the
+// access style of the kernels and no arithmetic, in the given launch shape (checked by the caller).
+struct ProbeShape {
+    int slice_bytes = 8192;
+    int block_threads = 256;
+    int load_policy = 1;
+    int store_policy = 1;
+    int xcd_contiguous = 0;
+    int max_blocks = 0;
+    int paired_loads = 0;
+    int alu_ops_per_pass = 0;
+    int lds_bytes_per_block = 0;
+};
 hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes,
-                               hipStream_t stream);
+                               const ProbeShape &shape, hipStream_t stream);
 
 }  // namespace cgx

@@ -72,7 +72,7 @@ static inline bool same_key_block(int64_t e0, int64_t count)
     return ((uint64_t(e0) >> 1) >> 32) == ((uint64_t(e0 + count - 1) >> 1) >> 32);
 }
 
-void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunk,
                  int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots,
                  std::vector<int64_t> *layer_first, const int32_t *layer_buckets, bool with_copies)
 {
@@ -80,7 +80,8 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     if (layer_first) layer_first->assign(size_t(L) + 1, 0);
     if (chunks_per_tile < 1) chunks_per_tile = 1;
     const int S = elem_size(dt);
-    const int launch_mapping = mapping_of(bucket);
+    const int kChunk = chunk, kGroups = chunk / (64 * 8);
+    const int launch_mapping = mapping_of(bucket, chunk);
     uint64_t seg = 0, bucket0 = 0;
     for (int32_t l = 0; l < L; l++) {
         const int64_t first = off[l], len = off[l + 1] - off[l];
@@ -90,13 +91,13 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
         uint64_t payload, buckets;
         const int32_t own_bucket = layer_buckets ? layer_buckets[l] : bucket;
         layer_extent(len, b, own_bucket, dt, payload, buckets);
-        if (b == 0 ? !with_copies : mapping_of(own_bucket) != launch_mapping) {
+        if (b == 0 ? !with_copies : mapping_of(own_bucket, chunk) != launch_mapping) {
             seg += round_up16(payload);                           // another launch's layer: only its extent counts
             bucket0 += buckets;
             continue;
         }
         const bool fast_bucket = is_pow2(own_bucket) && own_bucket <= kChunk;
-        const bool wide_bucket = is_pow2(own_bucket) && own_bucket > kChunk;       // a bucket is 2 or 4 chunks
+        const bool wide_bucket = is_pow2(own_bucket) && own_bucket > kChunk;       // a bucket is 2, 4 or 8 chunks
         // 64 lanes x kGroups groups x 8 elements = kChunk, so a bucket spans bucket / (8 * kGroups) lanes
         const uint32_t lpb_log2 = fast_bucket ? uint32_t(log2i(own_bucket / (8 * kGroups))) : 0u;
         const uint32_t size_bits = uint32_t(own_bucket / 32) << 12;
@@ -110,7 +111,7 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
                 t.elem0 = first + j;
                 t.packed_off = int64_t(seg + uint64_t(j) * S);
                 t.count = uint32_t(len - j < kCopyTile ? len - j : kCopyTile);
-                t.info = uint32_t(aligned ? kCopyFast : kCopySlow) << 4;
+                t.info = uint32_t(kCopyFast) << 4;
                 tiles.push_back(t);
             }
         } else {

@@ -21,23 +21,20 @@
 
 namespace cgx {
 
-// Elements a wavefront handles per pass of the fast path: 64 lanes x kGroups
-// groups of 8 consecutive elements.  A fast tile is a whole number of chunks.
-#ifndef CGX_GROUPS
-#define CGX_GROUPS 4
-#endif
-constexpr int kGroups = CGX_GROUPS;
-constexpr int kChunk = 64 * 8 * kGroups;
+// A chunk is what a wavefront handles per pass of the vectorised path: 64 lanes x `groups` groups
+// of 8 consecutive elements.  A kernel is compiled for one chunk size (2 groups = 1024 elements or
+// 4 groups = 2048 elements) and walks a tile table built for that size: a vectorised tile is a
+// whole number of chunks.
+constexpr int chunk_of(int groups) { return 64 * 8 * groups; }
 // Elements per pass-through tile.
 constexpr int kCopyTile = 8192;
 
 enum TileKind : uint32_t {
     kQuantSlow = 0,  // any bucket size, any alignment, ragged last bucket
-    kQuantFast = 1,  // power-of-two bucket <= kChunk, whole chunks
-    kCopySlow = 2,   // pass-through, element-wise (no longer produced: every copy tile is vectorised)
+    kQuantFast = 1,  // power-of-two bucket <= chunk, whole chunks
     kCopyFast = 3,   // pass-through, 16-byte vectors
     kQuantWide = 4,  // one whole power-of-two bucket longer than a chunk (4096, 8192)
-    kQuantTail = 5   // power-of-two bucket <= kChunk, the last tile of a layer, shorter than a chunk
+    kQuantTail = 5   // power-of-two bucket <= chunk, the last tile of a layer, shorter than a chunk
 };
 
 // Vectorised quantized tiles (everything else costs several dependent memory round trips).
@@ -60,12 +57,12 @@ CGX_HOST_DEVICE inline uint32_t tile_lpb_log2(const Tile &t) { return (t.info >>
 CGX_HOST_DEVICE inline int tile_bucket(const Tile &t) { return int((t.info >> 12) & 0x1ffu) * 32; }
 
 // How the vectorised tiles of a bucket size are laid over the lanes, which fixes the kernel
-// instantiation of a launch: kMapBuckets for 96..2048 (bucket-major), kMapRows for 32 and 64
+// instantiation of a launch: kMapBuckets for 96..chunk (bucket-major), kMapRows for 32 and 64
 // (row by row; needs more registers, so a kernel of its own keeps the others' occupancy),
-// kMapWide above 2048 (a tile is one bucket of several chunks).  One launch serves every
-// bucket size of one class.
+// kMapWide above the chunk size (a tile is one bucket of several chunks).  One launch serves
+// every bucket size of one class.
 enum LaneMapping { kMapBuckets = 0, kMapRows = 1, kMapWide = 2 };
-inline int mapping_of(int bucket) { return bucket <= 64 ? kMapRows : bucket > 64 * 8 * CGX_GROUPS ? kMapWide : kMapBuckets; }
+inline int mapping_of(int bucket, int chunk) { return bucket <= 64 ? kMapRows : bucket > chunk ? kMapWide : kMapBuckets; }
 
 struct PlanShape {
     size_t packed_bytes = 0;
@@ -83,17 +80,18 @@ int validate_layer_buckets(int32_t L, const int32_t *layer_buckets);
 PlanShape plan_shape(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
                      const int32_t *layer_buckets = nullptr);
 
-// Tile table.  `chunks_per_tile` bounds the length of fast tiles.
+// Tile table for kernels with chunks of `chunk` elements.  `chunks_per_tile` bounds the length of
+// fast tiles.
 // With `slots` and `layer_first` (both or neither): numbering the tiles layer by layer and,
 // inside a layer, by first element, tile t of the table has number slots[t], and layer l owns
 // the numbers layer_first[l] .. layer_first[l + 1] - 1 (the per-layer statistics keep one
 // partial sum per tile and add them up in that order).
 // With layer_buckets (a bucket size per layer) the table holds the tiles of the layers whose
-// bucket size has the lane mapping of `bucket` (mapping_of) only, at their places in the whole
+// bucket size has the lane mapping of `bucket` (mapping_of at this chunk size) only, at their places in the whole
 // plan's streams: a launch runs one kernel instantiation, so such a plan takes one launch per
 // mapping in use (at most three).  The pass-through layers belong to the launch with
 // with_copies set.
-void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt,
+void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunk,
                  int chunks_per_tile, std::vector<Tile> &tiles, std::vector<uint32_t> *slots = nullptr,
                  std::vector<int64_t> *layer_first = nullptr, const int32_t *layer_buckets = nullptr,
                  bool with_copies = true);

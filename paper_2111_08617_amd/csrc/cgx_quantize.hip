@@ -5,15 +5,19 @@ namespace cgx {
 namespace {
 
 // ODD: some vectorised tile of the plan starts on an odd element index (see encode_group).
-template <int SCHEME, int DT, int MAP, bool ODD>
+// VIA_LDS: every vectorised tile starts on a 16-byte boundary and the bucket-major mapping reads its
+// chunks through LDS (see chunk_through_lds); never together with ODD.
+template <int SCHEME, int DT, int MAP, bool ODD, bool VIA_LDS = false>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict__ grad,
                                                            const Tile *__restrict__ tiles, int64_t n_tiles,
                                                            uint32_t seed_lo, uint32_t seed_hi,
                                                            uint8_t *__restrict__ packed,
                                                            float *__restrict__ meta)
 {
-    // per-wave staging area for a chunk's packed codes (at most kChunk bytes, at 8 bits)
-    __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 16];
+    // per-wave staging area for a chunk's packed codes (at most kChunk bytes, at 8 bits), and with
+    // VIA_LDS for the chunk as stored
+    constexpr int kStageBytes = VIA_LDS ? kChunk * (DT == CGX_F16 ? 2 : 4) : kChunk;
+    __shared__ uint4v stage_all[kWavesPerBlock][kStageBytes / 16];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     int lane_of_wave = int(threadIdx.x) & 63;
     uint4v *stage = stage_all[wave];
@@ -35,8 +39,8 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
                 CGX_FOR_BITS(tile_bits(tile), (quantize_wide<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
                                                                                  seed_lo, seed_hi, lane, stage)))
             } else {
-                CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
-                                                                                 seed_lo, seed_hi, lane, stage)))
+                CGX_FOR_BITS(tile_bits(tile), (quantize_fast<SCHEME, DT, BITS, ODD, VIA_LDS>(
+                                                  grad, packed, meta, tile, bucket, seed_lo, seed_hi, lane, stage)))
             }
         } else if (kind == kQuantTail) {
             CGX_FOR_BITS(tile_bits(tile), (quantize_tail<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
@@ -53,9 +57,12 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
 
 }  // namespace
 
-hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
-                           int32_t bucket, uint64_t seed, void *packed, void *meta, const LaunchConfig &cfg,
-                           hipStream_t stream)
+// This file is compiled once per chunk size (CGX_GROUPS = 2 and 4): launch_quantize_g2, launch_quantize_g4.
+#define CGX_CONCAT2(a, b) a##b
+#define CGX_CONCAT(a, b) CGX_CONCAT2(a, b)
+hipError_t CGX_CONCAT(launch_quantize_g, CGX_GROUPS)(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
+                           bool aligned_tiles, int32_t bucket, uint64_t seed, void *packed, void *meta,
+                           const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
@@ -69,7 +76,12 @@ hipError_t launch_quantize(int scheme, const void *grad, int dt, const Tile *til
         {{CGX_QUANTIZE_MAPS(kMinMax, CGX_F32, true), CGX_QUANTIZE_MAPS(kMinMax, CGX_F16, true)},
          {CGX_QUANTIZE_MAPS(kNormSign, CGX_F32, true), CGX_QUANTIZE_MAPS(kNormSign, CGX_F16, true)}}};
 #undef CGX_QUANTIZE_MAPS
-    const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket)];
+    static const Kernel through_lds[2][2] = {
+        {quantize_kernel<kMinMax, CGX_F32, kMapBuckets, false, true>, quantize_kernel<kMinMax, CGX_F16, kMapBuckets, false, true>},
+        {quantize_kernel<kNormSign, CGX_F32, kMapBuckets, false, true>, quantize_kernel<kNormSign, CGX_F16, kMapBuckets, false, true>}};
+    const bool via_lds = aligned_tiles && !odd_tiles && mapping_of(bucket, kChunk) == kMapBuckets && cfg.via_lds;
+    const Kernel kernel = via_lds ? through_lds[scheme == kSchemeNormSign][dt == CGX_F16]
+                                  : table[odd_tiles][scheme == kSchemeNormSign][dt == CGX_F16][mapping_of(bucket, kChunk)];
     hipLaunchKernelGGL(kernel, grid, block, 0, stream, grad, tiles, n_tiles, seed_lo, seed_hi,
                        static_cast<uint8_t *>(packed), static_cast<float *>(meta));
     return hipGetLastError();

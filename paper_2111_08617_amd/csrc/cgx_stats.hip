@@ -1,4 +1,4 @@
-// Per-layer statistics of the adaptive scheme and the streaming probe: kernels and launchers.
+// Per-layer statistics of the adaptive scheme: kernels and launchers.
 #include <mutex>
 
 #include "cgx_device_reduce.h"
@@ -266,35 +266,6 @@ hipError_t static_scratch(unsigned char **ptr)
     return hipSuccess;
 }
 
-// ---------------------------------------------------------------- streaming probe
-
-// Measurement aid: moves read_bytes in and write_bytes out with the access style of the
-// kernels above (one wave per slice, lane-contiguous non-temporal 16-byte vectors) and no
-// arithmetic to speak of.  Its rate is what the memory system gives a kernel with that
-// read:write mix at that size.
-__global__ __launch_bounds__(kBlock) void stream_probe_kernel(const uint4v *__restrict__ src, int64_t read_vecs,
-                                                               uint4v *__restrict__ dst, int64_t write_vecs,
-                                                               int64_t waves)
-{
-    const int64_t wave = int64_t(blockIdx.x) * kWavesPerBlock + (int(threadIdx.x) >> 6);
-    const int lane = int(threadIdx.x) & 63;
-    if (wave >= waves) return;
-    const int64_t r0 = read_vecs * wave / waves, r1 = read_vecs * (wave + 1) / waves;
-    const int64_t w0 = write_vecs * wave / waves, w1 = write_vecs * (wave + 1) / waves;
-    uint4v acc = {0u, 0u, 0u, 0u};
-    for (int64_t v = r0 + lane; v < r1; v += 8 * kWave) {
-        uint4v x[8];
-#pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const int64_t i = v + u * kWave;
-            x[u] = i < r1 ? stream_load(src + i) : uint4v{0u, 0u, 0u, 0u};
-        }
-#pragma unroll
-        for (int u = 0; u < 8; u++) acc += x[u];
-    }
-    for (int64_t v = w0 + lane; v < w1; v += kWave) stream_store(dst + v, acc + uint32_t(v));
-}
-
 }  // namespace
 
 hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
@@ -368,18 +339,6 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
     if (sum_layers)
         hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
                            static_cast<const double *>(partial), layer_first, out);
-    return hipGetLastError();
-}
-
-hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes, hipStream_t stream)
-{
-    const int64_t read_vecs = int64_t(read_bytes / 16), write_vecs = int64_t(write_bytes / 16);
-    const int64_t larger = read_vecs > write_vecs ? read_vecs : write_vecs;
-    const int64_t waves = (larger + 511) / 512;                 // 8 KB of the larger side per wave
-    if (waves == 0) return hipSuccess;
-    const dim3 grid(unsigned((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(kBlock);
-    hipLaunchKernelGGL(stream_probe_kernel, grid, block, 0, stream, static_cast<const uint4v *>(src), read_vecs,
-                       static_cast<uint4v *>(dst), write_vecs, waves);
     return hipGetLastError();
 }
 

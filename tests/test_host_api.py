@@ -28,7 +28,7 @@ def lib():
 
 
 def test_library_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "cgx.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("cgx.h", "cgx_diag.h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(cgx_[a-z_0-9]+)\s*\(", header))
     assert declared == set(cgx.EXPORTS)
@@ -120,6 +120,13 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.cgx_stream_probe(None, 1024, buf, 1024, None) == -1
     assert lib.cgx_stream_probe(buf, 1000, buf, 1024, None) == -2
     assert lib.cgx_stream_probe(buf + 4, 1024, buf, 1024, None) == -9
+    shaped = lambda *v: lib.cgx_stream_probe_shaped(buf, 1024, buf, 1024, (c.c_int32 * 9)(*(v + (0,) * (9 - len(v)))), None)
+    assert lib.cgx_stream_probe_shaped(buf, 1024, buf, 1024, None, None) == -1
+    for bad in ((1000, 256, 1, 1, 0, 0), (512, 256, 1, 1, 0, 0), (1 << 21, 256, 1, 1, 0, 0), (8192, 96, 1, 1, 0, 0),
+                (8192, 2048, 1, 1, 0, 0), (8192, 256, 4, 1, 0, 0), (8192, 256, 1, 5, 0, 0), (8192, 256, -1, 1, 0, 0),
+                (8192, 256, 1, 1, 2, 0), (8192, 256, 1, 1, 0, -1), (8192, 256, 1, 1, 0, 0, 2),
+                (8192, 256, 1, 1, 0, 0, 0, -1), (8192, 256, 1, 1, 0, 0, 0, 0, 65537)):
+        assert shaped(*bad) == -2
     fused = lib.cgx_dequant_reduce_requantize
     assert fused(ptrs, ptrs, 0, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
     assert fused(ptrs, ptrs, 17, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
@@ -218,10 +225,13 @@ def layer_segments(w):
     lambda: wl.Workload("wide16", [(8192 * 2 + 8,), (8192,), (100,)], np.array([4, 5, 1], np.uint8),
                         8192, wl.F16, 2, 1, wl._normal, np.ones(3)),
 ])
-def test_tiles_cover_every_layer_exactly_once(lib, make):
+@pytest.mark.parametrize("CHUNK", [2048, 1024])
+def test_tiles_cover_every_layer_exactly_once(lib, make, CHUNK):
+    """Both tile tables: chunks of 2048 elements (reduce, fused and statistics kernels, binary16 quantizer)
+    and of 1024 (binary32 quantizer)."""
     w = make()
     plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
-    tiles = cgx.cgx_plan_tiles(plan)
+    tiles = cgx.cgx_plan_tiles(plan, CHUNK)
     segs = layer_segments(w)
     es = 2 if w.dt else 4
     # generic and pass-through tiles first, then the vectorised ones; buffer order within each class
@@ -266,7 +276,7 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
             if kind == 0:                                             # generic: only where nothing else fits
                 assert w.bucket & (w.bucket - 1) != 0 or w.bucket > CHUNK
             if kind == 4:                                             # one whole bucket of several chunks
-                assert t["count"] == w.bucket and w.bucket in (4096, 8192)
+                assert t["count"] == w.bucket and w.bucket in (4096, 8192) + ((2048,) if CHUNK == 1024 else ())
                 assert (int(t["info"]) >> 8) & 15 == 6
     if w.name.startswith("wide"):
         assert (((tiles["info"] >> 4) & 15) == 4).sum() == (9 if w.name == "wide" else 3)
@@ -274,12 +284,17 @@ def test_tiles_cover_every_layer_exactly_once(lib, make):
 
 def test_large_plans_use_the_vectorised_path(lib):
     for make in (wl.resnet50, wl.decoder_1p3b):
-        w = make()
-        plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
-        tiles = cgx.cgx_plan_tiles(plan)
-        kind = (tiles["info"] >> 4) & 15
-        fast = tiles["count"][(kind == 1) | (kind == 3)].astype(np.int64).sum()
-        assert fast / w.n > 0.999
+        for chunk in (1024, 2048):
+            w = make()
+            plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+            tiles = cgx.cgx_plan_tiles(plan, chunk)
+            kind = (tiles["info"] >> 4) & 15
+            fast = tiles["count"][(kind == 1) | (kind == 3)].astype(np.int64).sum()
+            assert fast / w.n > 0.999
+    plan = cgx.Plan(np.array([0, 5000], np.int64), np.array([4], np.uint8), 128)
+    n_tiles = ctypes.c_int64()
+    assert lib.cgx_plan_tiles_chunk(*plan.args, plan.dt, 512, None, 0, ctypes.byref(n_tiles)) == -2
+    assert lib.cgx_plan_tiles_chunk(*plan.args, plan.dt, 4096, None, 0, ctypes.byref(n_tiles)) == -2
 
 
 def test_tiles_do_not_straddle_a_generator_key_block(lib):
