@@ -525,7 +525,7 @@ def ceilings(args):
         R = max(2, min(8, int(np.ceil(2.5e9 / (rb + wb)))))
         srcs = [torch.zeros(max(rb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
         dsts = [torch.empty(max(wb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
-        tried = {}
+        tried, order = {}, []
 
         def run(slice_bytes=8192, block=256, loads="nt", stores="nt", xcd=False, max_blocks=0):
             key = (slice_bytes, block, loads, stores, xcd, max_blocks)
@@ -544,6 +544,7 @@ def ceilings(args):
             torch.cuda.synchronize()
             ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
             tried[key] = ms
+            order.append(list(key))
             return ms
 
         base = run()
@@ -571,7 +572,9 @@ def ceilings(args):
                              "policies_at_own_shape": [r for r in rows if (r["slice_bytes"], r["block_threads"],
                                                                              r["die_contiguous"], r["max_blocks"]) ==
                                                        (8192, 256, False, 0)],
-                             "all": rows if args.ceilings_all else None})
+                             "all": rows if args.ceilings_all else None,
+                             # execution order, 2 + reps launches each (to match a kernel trace of this run)
+                             "order": order if args.ceilings_all else None})
         del srcs, dsts
         torch.cuda.empty_cache()
     print(json.dumps(out))

@@ -87,6 +87,7 @@ const cgx::LaunchConfig &launch_config()
         c.chunks_per_tile = env_int("CGX_CHUNKS_PER_TILE", 0);
         c.max_blocks = env_int("CGX_MAX_BLOCKS", c.max_blocks);
         c.via_lds = env_int("CGX_VIA_LDS", c.via_lds);
+        c.keep_sums_max_bytes = long(env_int("CGX_KEEP_SUMS_MB", int(c.keep_sums_max_bytes >> 20))) << 20;
         c.quantize_groups = env_int("CGX_QUANTIZE_GROUPS", 0) == 2 ? 2 : env_int("CGX_QUANTIZE_GROUPS", 0) == 4 ? 4 : 0;
         return c;
     }();
@@ -320,9 +321,14 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
             }
             const void *init = w0 == 0 ? local : out;
             const int init_dt = w0 == 0 ? local_dt : CGX_F32;
+            // a result that fits the 256 MB memory-side cache with room to spare is left there for the
+            // call that consumes it (requantize, the optimizer): measured on 102 MB of sums, the reduce
+            // runs 7 % and the requantize after it 10 % faster; on 658 MB the reader loses what the
+            // writer gains
+            const bool keep = int64_t(n) * (out_dt == CGX_F16 ? 2 : 4) <= launch_config().keep_sums_max_bytes;
             const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
                                                             plan->many_tails, launch.bucket, init, init_dt, out,
-                                                            out_dt, launch_config(),
+                                                            out_dt, keep, launch_config(),
                                                             static_cast<hipStream_t>(stream));
             if (e != hipSuccess) return CGX_ERR_HIP;
         }

@@ -343,10 +343,19 @@ __device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, in
     for (int v = lane; v < vecs; v += kWave) stream_store(dst + v, stage[v]);
 }
 
-// The same to an element-aligned destination (sums).
-__device__ __forceinline__ void flush_stage_to_elements(const uint4v *stage, uint4u2 *dst, int vecs, int lane)
+// The same to an element-aligned destination (sums).  keep: the stores are written through at
+// device scope (sc1) instead of as a non-temporal stream.  Measured: a result of about 100 MB then
+// stays in the 256 MB memory-side cache, the launch that writes it gets 7 % shorter and the one
+// that reads it next 10 %; results of several hundred MB gain 3 % in the writer and lose 7 % in the
+// reader, so the host asks for it only below a size (see reduce_impl).
+__device__ __forceinline__ void flush_stage_to_elements(const uint4v *stage, uint4u2 *dst, int vecs, int lane, bool keep)
 {
-    for (int v = lane; v < vecs; v += kWave) __builtin_nontemporal_store(stage[v], dst + v);
+    if (keep) {
+        for (int v = lane; v < vecs; v += kWave)
+            asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst + v), "v"(stage[v]) : "memory");
+    } else {
+        for (int v = lane; v < vecs; v += kWave) __builtin_nontemporal_store(stage[v], dst + v);
+    }
 }
 
 // One 16-byte vector per lane from global memory straight into LDS, without passing

@@ -162,6 +162,7 @@ struct SumIo {
     int init_dt;
     void *out;
     int out_dt;
+    int keep;          // the result is small enough to stay in the memory-side cache: see flush_stage_to_elements
 };
 
 __device__ __forceinline__ void init8(const SumIo &io, int64_t e, float (&acc)[8])
@@ -231,7 +232,7 @@ __device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io
             }
             wave_lds_fence();
             flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<_Float16 *>(io.out) + first),
-                                    kChunk / 8, lane);
+                                    kChunk / 8, lane, io.keep != 0);
         } else {
 #pragma unroll
             for (int r = 0; r < G; r++) {
@@ -241,7 +242,7 @@ __device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io
             }
             wave_lds_fence();
             flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<float *>(io.out) + first),
-                                    kChunk / 4, lane);
+                                    kChunk / 4, lane, io.keep != 0);
         }
         wave_lds_fence();
     }

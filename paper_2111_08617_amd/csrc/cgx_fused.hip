@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers_argu
                 packed_out + out_off, meta_out, tile, out_pad, bucket, seed_lo, seed_hi, lane);
         } else {
             // pass-through: the sum is written as binary32 into the output stream, then its padding
-            const SumIo io{nullptr, CGX_F32, packed_out + out_off, CGX_F32};
+            const SumIo io{nullptr, CGX_F32, packed_out + out_off, CGX_F32, 0};
             if (dt == CGX_F16)
                 reduce_copy<CGX_F16>(peers, W, io, 0, tile, kind == kCopyFast, lane);
             else

@@ -26,6 +26,7 @@ struct LaunchConfig {
     int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
     int via_lds = 1;           // quantize: fetch aligned chunks through LDS
     int quantize_groups = 0;   // 2 or 4: chunk size of every quantize call; 0: chosen per call
+    long keep_sums_max_bytes = 128l << 20;   // reduce: results up to this size are kept in the memory-side cache
 };
 
 // odd_tiles: some vectorised tile starts on an odd element index (the kernels then take the
@@ -45,12 +46,14 @@ constexpr int kDefaultChunk = chunk_of(4);
 
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
 // term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
+// keep_output: the result is written through at device scope rather than streamed (it then stays in the
+// memory-side cache if it is small enough; the caller decides by size).
 // many_tails: the short ends of layers are a real share of the plan's tiles (the kernel then
 // takes them through the masked chunk path instead of the generic one).
 hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
                                  bool many_tails,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
-                                 const LaunchConfig &cfg, hipStream_t stream);
+                                 bool keep_output, const LaunchConfig &cfg, hipStream_t stream);
 
 // packed_out / meta_out = quantize(deq_0 + ... + deq_{W-1}) without the binary32 sum ever
 // reaching memory; tiles_in describes the chunks (storage type dt), tiles_out the output
