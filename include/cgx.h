@@ -86,14 +86,18 @@ int cgx_sizes(int64_t n, int32_t L, const int64_t *layer_offsets /* host [L+1] *
               size_t *packed_bytes, size_t *meta_bytes);
 
 /*
- * Bucketed stochastic quantization of a fused buffer (paper Sec. 2.2, the
- * rounding rule q(v_i, s); Sec. 4.3, buckets; Sec. 4.1, per-layer parameters).
+ * Bucketed stochastic quantization of a fused buffer (paper Sec. 2.3, "Gradient
+ * Quantization": the rounding rule q(v_i, s); Sec. 4.3, buckets; Sec. 4.1, per-layer parameters).
  * Per bucket: mn = min, mx = max, Lv = 2^b - 1, unit = (mx - mn) / Lv,
  * inv16 = (Lv * 65536) / (mx - mn); unit = inv16 = 0 for a constant or
  * degenerate bucket; a zero minimum is stored as +0.  Per element with buffer
  * index i: T = trunc((x - mn) * inv16), code = min((T + u) >> 16, Lv), where u
  * is the 16-bit draw of a counter-based generator keyed on (seed, i).  All
- * arithmetic is binary32 without fused operations.
+ * arithmetic is binary32 without fused operations.  The rule's probability p of
+ * taking the upper level is thereby cut to 16 bits: a code goes up with
+ * probability floor(p * 65536) / 65536, never more than p and less than 2^-16
+ * below it, so the expected value of a code lies at most 2^-16 of a step (on
+ * average 2^-17) below the unbiased one; values on the grid (p = 0) stay exact.
  *   grad    device, n elements of dt
  *   packed  device, at least packed_bytes; every byte of it is written
  *   meta    device, at least meta_bytes
@@ -213,9 +217,11 @@ int cgx_layered_layer_sqerrors(const void *grad, const void *packed, const void 
                                size_t workspace_bytes, void *stream);
 
 /*
- * The norm-and-sign form of the quantizer, Q_s as printed in paper Sec. 2.2
- * (Q_s(v_i) = ||v|| sign(v_i) q(|v_i| / ||v||, s)), applied per bucket (Sec. 4.3)
- * with per-layer widths (Sec. 4.1).  Same plan, layout of the packed stream,
+ * The norm-and-sign form of the quantizer: Q_s of paper Sec. 2.3
+ * (Q_s(v_i) = ||v|| sign(v_i) q(|v_i| / ||v||, s)) applied per bucket (Sec. 4.3)
+ * with per-layer widths (Sec. 4.1) and with the bucket's LARGEST MAGNITUDE as
+ * ||v|| (the l-infinity norm: a variant of the printed form, which uses the l2
+ * norm; with it all s levels are in use).  Same plan, layout of the packed stream,
  * draws, pass-through layers, summation order and error codes as the calls
  * above; what differs:
  *   - the norm of a bucket is its largest magnitude (so that |v_i| / ||v||

@@ -7,7 +7,7 @@
  * library and the product path never routes through it.
  *
  * What it follows (CGX paper, arXiv 2111.08617):
- *   - Sec. 2.2 "Gradient Quantization", the definition of q(v_i, s): a value
+ *   - Sec. 2.3 "Gradient Quantization", the definition of q(v_i, s): a value
  *     normalised to a in [0,1] falls in the interval [l/s, (l+1)/s] and is
  *     rounded to level l+1 with probability p = a*s - l, else to level l.
  *   - Sec. 4.3 "Efficient Quantization": the vector is split into buckets,
@@ -45,7 +45,7 @@
  *     peers in ascending order in binary32 (sum32) and, separately, evaluates
  *     sum_w (mn_w + q_w * unit_w) in binary64 (sum64).
  *   - the second half of the file holds the norm-and-sign form of the same
- *     quantizer (the formula Q_s of Sec. 2.2 taken literally), with its own
+ *     quantizer (the formula Q_s of Sec. 2.3 taken literally), with its own
  *     header comment.
  *
  * Build:  gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
@@ -504,7 +504,7 @@ int oracle_unpack_codes(const uint8_t *packed, int64_t n, int32_t L, const int64
 
 /* ======================================================================== *
  * The norm-and-sign form of the quantizer, as the paper prints it
- * (Sec. 2.2: Q_s(v_i) = ||v|| * sign(v_i) * q(|v_i| / ||v||, s)), per bucket.
+ * (Sec. 2.3: Q_s(v_i) = ||v|| * sign(v_i) * q(|v_i| / ||v||, s)), per bucket.
  *
  * Readings: the norm is the maximum absolute value of the bucket (so that
  * |v_i| / ||v|| covers [0, 1] and no summation order enters the result);

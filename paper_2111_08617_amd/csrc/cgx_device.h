@@ -167,8 +167,8 @@ __device__ __forceinline__ void group_max(float &mx, int lg, int lane)
 //
 // kMinMax: affine per bucket.  A b-bit code is a level 0..2^b-1 between the bucket's minimum
 // and maximum; meta = {unit, minimum} (float2 per bucket); value = fma(level, unit, minimum).
-// kNormSign: the norm-and-sign form printed in Sec. 2.2 (Q_s), with the bucket's largest
-// magnitude as the norm.  A b-bit code (b >= 2) is sign(x) times a level 0..s,
+// kNormSign: a variant of the norm-and-sign form Q_s printed in Sec. 2.3: the norm is the bucket's
+// largest magnitude (l-infinity) where the paper prints the l2 norm.  A b-bit code (b >= 2) is sign(x) times a level 0..s,
 // s = 2^(b-1)-1, of |x| / norm, as a two's complement number (decoding, done once per peer
 // and element, is then a sign-extending conversion and a multiplication; encoding, done once
 // per element, pays the negation); meta = unit = norm / s (one float per bucket);

@@ -5,12 +5,12 @@ the quantizer's arithmetic and is the one piece shared by the GPU path's tests,
 the CPU oracle's tests and the benchmark.
 
 The paper evaluates on training runs of ResNet-50, BERT, GPT-2 and other
-models (Sec. 5, "Experimental Validation"); their gradients are replaced here
+models (Sec. 6, "Experimental Validation"); their gradients are replaced here
 by synthetic buffers that take those models' parameter shapes, fused in
 parameter order into one buffer with a layer offset table (Sec. 4.1, fused
 buffers and layer offsets).  Small one-dimensional tensors (bias,
 normalisation) are marked pass-through (bits = 0), following the layer filter
-of Sec. 4.1 and the evaluation set-up of Sec. 5.
+of Sec. 4.1 and the evaluation set-up of Sec. 6.
 """
 from __future__ import annotations
 

@@ -1,14 +1,15 @@
 """Pins of the CPU oracle against what the paper and the mathematics fix.
 
 Nothing here touches the GPU library.  Each test names the passage it pins:
-  - rounding rule: Sec. 2.2 "Gradient Quantization", definition of q(v_i, s)
+  - rounding rule: Sec. 2.3 "Communication Compression Methods", paragraph
+    "Gradient Quantization", definition of q(v_i, s)
     (level l+1 with probability p = a*s - l, else l);
   - bucketing with per-bucket meta-data: Sec. 4.3 "Efficient Quantization";
   - per-layer compression and uncompressed small layers: Sec. 4.1 "The Native
     CGX Framework";
   - dequantize first, then sum: Sec. 4 (non-associativity) and Sec. 4.1
     "Choosing a Reduction Scheme" (Scatter-Reduce-Allgather);
-  - "~8x" compression at 4 bits: Table 1 "Compression approaches".
+  - "~8x" compression at 4 bits: the table "Compression approaches" (the paper's third).
 """
 import os
 from fractions import Fraction
@@ -59,6 +60,103 @@ def test_rounding_probability_brute_force(oracle, b):
     assert (codes[:, int(x.argmin())] == 0).all()
     top = codes[:, int(x.argmax())]
     assert (top >= Lv - 1).all() and (top == Lv).sum() >= K - 4
+
+
+def to_binary32(v: Fraction) -> Fraction:
+    """v rounded to the nearest IEEE binary32 number, ties to even, in exact integer arithmetic
+    (written out here so that the pins below do not lean on any library's float32)."""
+    if v == 0:
+        return Fraction(0)
+    sign, a = (-1 if v < 0 else 1), abs(v)
+    e = a.numerator.bit_length() - a.denominator.bit_length()          # 2^(e-1) < a < 2^(e+1)
+    if Fraction(2) ** e > a:
+        e -= 1                                                          # now 2^e <= a < 2^(e+1)
+    q = max(e - 23, -149)                                               # weight of the last mantissa bit
+    scaled = a / Fraction(2) ** q
+    m = scaled.numerator // scaled.denominator
+    rest = scaled - m
+    if rest > Fraction(1, 2) or (rest == Fraction(1, 2) and m % 2 == 1):
+        m += 1
+    assert m < 2 ** 24 + 1 and e < 128
+    return sign * m * Fraction(2) ** q
+
+
+def test_binary32_rounding_helper():
+    rng = np.random.default_rng(0)
+    for v in np.concatenate([rng.standard_normal(200) * 10.0 ** rng.integers(-30, 30, 200), [1e-45, 3e-39, 2.0 ** -126]]):
+        assert to_binary32(Fraction(float(v))) == Fraction(float(np.float32(v)))
+    assert to_binary32(Fraction(2 ** 24 + 1)) == 2 ** 24 and to_binary32(Fraction(2 ** 24 + 3)) == 2 ** 24 + 4
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 8])
+def test_rounding_rule_is_exact_draw_by_draw(oracle, b):
+    """Sec. 2.3 "Gradient Quantization": level l goes up with probability p = a s - l.  The reading
+    in force resolves p to 16 bits: with T = trunc((x - mn) * inv16) in binary32 arithmetic, exactly
+    the T mod 65536 largest of the 65536 possible draws round up.  Every element, every draw:
+    code(u) = min(floor((T + u) / 65536), Lv), with T recomputed here in exact rational arithmetic
+    with an explicit round-to-nearest-even after each of the three binary32 operations and after the
+    division that gives inv16.  (Fails for a rounded instead of truncated T, for <= in place of <
+    in the carry, for a fused multiply, for one rounding left out.)"""
+    rng = np.random.default_rng(200 + b)
+    B, Lv, K = 32, (1 << b) - 1, 65536
+    x = (rng.standard_normal(B) * 10.0 ** rng.uniform(-3, 2)).astype(np.float32)
+    x[3] = x[9]
+    grad = np.tile(x, K)
+    offsets = np.arange(K + 1, dtype=np.int64) * B
+    bits = np.full(K, b, np.uint8)
+    draws = np.repeat(np.arange(K, dtype=np.uint16), B)
+    packed, meta = oracle.quantize(grad, offsets, bits, B, seed=0, draws=draws)
+    codes = oracle.unpack_codes(packed, offsets, bits, B).reshape(K, B).astype(np.int64)
+    mn, mx = Fraction(float(x.min())), Fraction(float(x.max()))
+    rng_ = to_binary32(mx - mn)
+    inv16 = to_binary32(Fraction(Lv * 65536) / rng_)
+    unit = to_binary32(rng_ / Lv)
+    assert Fraction(float(meta[0, 0])) == unit and Fraction(float(meta[0, 1])) == mn
+    u = np.arange(K, dtype=np.int64)
+    up_total = 0
+    for j in range(B):
+        S = to_binary32(to_binary32(Fraction(float(x[j])) - mn) * inv16)
+        T = S.numerator // S.denominator                                # truncation (S >= 0)
+        expect = np.minimum((T + u) >> 16, Lv)
+        assert np.array_equal(codes[:, j], expect), (j, T)
+        if (T >> 16) < Lv:
+            assert int(codes[:, j].sum()) == 65536 * (T >> 16) + (T & 0xffff)
+            up_total += T & 0xffff
+        # and the same T from numpy's binary32, step by step
+        d32 = np.float32(x[j]) - np.float32(x.min())
+        S32 = np.float32(d32) * np.float32(float(inv16))
+        assert int(S32) == T
+    assert up_total > 0
+    # the probability of going up is p truncated to 16 bits: never above p, less than 2^-16 below it
+    for j in range(B):
+        pos = (Fraction(float(x[j])) - mn) / (mx - mn) * Lv
+        mean = Fraction(int(codes[:, j].sum()), K)
+        if 0 < pos < Lv:
+            assert mean - pos <= Fraction(4 * Lv, 1 << 24)               # binary32 rounding of (x - mn) * inv16 only
+            assert pos - mean < Fraction(1, 65536) + Fraction(4 * Lv, 1 << 24)
+
+
+def test_real_draws_even_elements_take_the_low_half(oracle):
+    """With the generator in place of mock draws: element i uses the low half of the word of its pair
+    i >> 1 when i is even and the high half when it is odd (the words are taken from oracle.rng32,
+    whose stream is pinned statistically further down; what is pinned here is which half goes where,
+    and that the buffer index, not the position in the bucket or layer, selects the draw)."""
+    rng = np.random.default_rng(9)
+    B, b, n, seed = 64, 4, 64 * 5, 2 ** 40 + 17
+    x = rng.standard_normal(n).astype(np.float32)
+    offsets, bits = np.array([0, 3 * B, n], np.int64), np.array([b, b], np.uint8)
+    for base in (0, 2 ** 33 - 2 * B, 7):
+        packed, meta = oracle.quantize(x, offsets, bits, B, seed=seed, index_base=base)
+        codes = oracle.unpack_codes(packed, offsets, bits, B).astype(np.int64)
+        words = [oracle.rng32(seed, (base + i) >> 1) for i in range(n)]
+        u = np.array([(w >> 16) if (base + i) & 1 else (w & 0xffff) for i, w in enumerate(words)], np.int64)
+        assert len(set(words[::2])) > n // 2 - 2
+        for k in range(n // B):
+            xb = x[k * B:(k + 1) * B]
+            r32 = np.float32(xb.max()) - np.float32(xb.min())
+            inv16 = np.float32(15 * 65536) / r32
+            T = ((xb - xb.min()) * inv16).astype(np.int64)
+            assert np.array_equal(codes[k * B:(k + 1) * B], np.minimum((T + u[k * B:(k + 1) * B]) >> 16, 15))
 
 
 def test_unbiased_over_seeds(oracle):

@@ -1,5 +1,5 @@
 """Pins of the oracle's norm-and-sign quantizer against the paper's printed formula
-(Sec. 2.2 "Gradient Quantization": Q_s(v_i) = ||v|| sign(v_i) q(|v_i| / ||v||, s), with
+(Sec. 2.3, paragraph "Gradient Quantization": Q_s(v_i) = ||v|| sign(v_i) q(|v_i| / ||v||, s), with
 q = l/s with probability 1 - p and (l+1)/s otherwise, p = a s - l), applied per bucket
 (Sec. 4.3) with the maximum absolute value as the norm."""
 from fractions import Fraction
@@ -48,6 +48,36 @@ def test_levels_follow_the_printed_rule_exactly_enumerated(oracle, b):
     top = level[:, int(np.abs(x).argmax())]
     assert (top >= s - 1).all() and (top == s).sum() >= K - 4
     assert np.allclose(meta, float(norm) / s, rtol=1e-6)
+
+
+@pytest.mark.parametrize("b", [2, 3, 4, 8])
+def test_levels_are_exact_draw_by_draw(oracle, b):
+    """The 16-bit reading of the rule, every element and every draw: with T = trunc(|v| * inv16) and
+    inv16 = (s * 65536) / ||v|| in binary32 arithmetic (each operation rounded to nearest even, redone
+    here in exact rational arithmetic), level(u) = min(floor((T + u) / 65536), s): exactly the
+    T mod 65536 largest draws go up.  The code is the signed level as a b-bit two's complement number."""
+    from test_oracle_pins import to_binary32
+    rng = np.random.default_rng(300 + b)
+    B, s, K = 32, (1 << (b - 1)) - 1, 65536
+    x = (rng.standard_normal(B) * 10.0 ** rng.uniform(-3, 2)).astype(np.float32)
+    x[4] = -x[11]
+    grad = np.tile(x, K)
+    offsets = np.arange(K + 1, dtype=np.int64) * B
+    bits = np.full(K, b, np.uint8)
+    draws = np.repeat(np.arange(K, dtype=np.uint16), B)
+    packed, meta = oracle.qsgd_quantize(grad, offsets, bits, B, seed=0, draws=draws)
+    codes = oracle.unpack_codes(packed, offsets, bits, B).reshape(K, B).astype(np.int64)
+    norm = Fraction(float(np.abs(x).max()))
+    inv16 = to_binary32(Fraction(s * 65536) / norm)
+    assert Fraction(float(np.asarray(meta).reshape(-1)[0])) == to_binary32(norm / s)
+    u = np.arange(K, dtype=np.int64)
+    for j in range(B):
+        S = to_binary32(abs(Fraction(float(x[j]))) * inv16)
+        T = S.numerator // S.denominator
+        level = np.minimum((T + u) >> 16, s)
+        signed = -level if x[j] < 0 else level
+        assert np.array_equal(codes[:, j], signed & ((1 << b) - 1)), (j, T)
+        assert np.array_equal(signed_levels(codes[:, j], b), signed)
 
 
 def test_unbiased_and_within_one_step(oracle):
