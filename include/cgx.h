@@ -30,15 +30,30 @@
  *   Memory.  Every pointer marked "device" is device memory owned by the
  *   caller, 16-byte aligned, valid until the work queued on `stream` has run.
  *   Pointers marked "host" are read during the call and may be reused on
- *   return.  The library keeps a small device-resident table per distinct plan
- *   (built on first use, which may synchronise; later calls with the same plan
- *   only queue kernels; cgx_quantize on binary16 gradients of 2^24 elements or
- *   more, and the fused call on 2^27 or more, keep tables of their own beside
- *   the one the other calls share): at
- *   most 64 of them, the least recently used one being dropped (which waits for
- *   the device) when a 65th arrives; cgx_shutdown() frees them all.  No call synchronises the stream.  `stream` is a
- *   hipStream_t passed as void* (NULL = the default stream).  Once a plan's
- *   table exists, the calls only queue kernels and can be captured in a graph.
+ *   return.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *   stream).  No call synchronises the stream.
+ *
+ *   Plan tables and graph capture.  The library keeps a small device-resident
+ *   table per distinct plan.  It is built on the first call with that plan,
+ *   which allocates device memory and copies synchronously; later calls with the
+ *   same plan only queue kernels.  (cgx_quantize on binary32 input and
+ *   cgx_requantize, cgx_quantize on binary16 gradients of 2^24 elements or more,
+ *   and the fused call on 2^27 or more, keep tables of their own beside the one
+ *   the other calls share.)  At most 64 tables are kept: when a 65th arrives
+ *   the least recently used one is freed, which waits for the device;
+ *   cgx_shutdown() frees them all.
+ *   A call on a stream that is capturing a graph records its launches into the
+ *   graph, and those read the plan's table on every replay.  Therefore:
+ *     - the table must exist before the capture: run the same call once, not
+ *       captured, first; a captured call whose plan has no table yet returns
+ *       CGX_ERR_CAPTURE and records nothing (it neither allocates nor copies in
+ *       the middle of a capture), and the capture can go on;
+ *     - a table used by a captured call is pinned: it is never the one freed for
+ *       a new plan, so the graph stays valid however many other plans follow;
+ *       only cgx_shutdown() frees it, after which such graphs must not be
+ *       replayed;
+ *     - no first call with a new plan may run while ANOTHER thread captures in
+ *       the global capture mode (the runtime forbids allocations then).
  *
  *   Errors.  Every function returns CGX_OK or a negative cgx_status.  Argument
  *   errors are found on the host before anything is queued; nothing is written
@@ -66,7 +81,8 @@ typedef enum {
     CGX_ERR_DTYPE = -7,    /* unknown storage type */
     CGX_ERR_HIP = -8,      /* the HIP runtime reported an error */
     CGX_ERR_ALIGN = -9,    /* a device pointer is not 16-byte aligned */
-    CGX_ERR_CAPACITY = -10 /* the plan is larger than a no-allocation entry point's fixed tables */
+    CGX_ERR_CAPACITY = -10, /* the plan is larger than a no-allocation entry point's fixed tables */
+    CGX_ERR_CAPTURE = -11  /* the stream is capturing a graph and the plan's tables do not exist yet */
 } cgx_status;
 
 typedef enum {

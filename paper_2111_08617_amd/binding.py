@@ -167,11 +167,88 @@ def _stream(stream) -> int:
     return int(getattr(stream, "cuda_stream", stream))
 
 
+_TORCH_DTYPES = {F32: "float32", F16: "float16"}
+
+
+_dtype_objects = {}
+
+
+def _torch_dtype(name: str):
+    if name not in _dtype_objects:
+        import torch
+        _dtype_objects[name] = getattr(torch, name)
+    return _dtype_objects[name]
+
+
+def _device_buffer(t, what, nbytes: int, dtype: str = None) -> int:
+    """Address of a device tensor after the checks the C ABI cannot make (it sees no sizes): a contiguous
+    device tensor of the expected element type holding at least nbytes bytes.  Raises ValueError.
+    `what` names the argument in the message (a string, or a tuple of parts joined only when needed)."""
+    try:
+        ok = t.is_cuda and t.is_contiguous() and (dtype is None or t.dtype is _torch_dtype(dtype)) and \
+            t.numel() * t.element_size() >= nbytes
+    except AttributeError:
+        ok = False
+    if ok:
+        return t.data_ptr()
+    def flat(w):
+        return [str(w)] if not isinstance(w, tuple) else [x for part in w for x in flat(part)]
+    what = what if isinstance(what, str) else ": ".join([flat(what)[0], " ".join(flat(what)[1:])])
+    if not hasattr(t, "data_ptr") or not hasattr(t, "is_cuda"):
+        raise ValueError(f"{what}: a device tensor is needed, got {type(t).__name__}")
+    if not t.is_cuda:
+        raise ValueError(f"{what}: the tensor lives on {t.device}, the kernels need device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: the tensor is not contiguous")
+    if dtype is not None and t.dtype is not _torch_dtype(dtype):
+        raise ValueError(f"{what}: element type {t.dtype}, expected torch.{dtype}")
+    raise ValueError(f"{what}: {t.numel() * t.element_size()} bytes, the call needs {nbytes}")
+
+
+def _elements(t, what, n: int, dt: int) -> int:
+    """A buffer of n elements of storage type dt."""
+    return _device_buffer(t, what, n * (2 if dt == F16 else 4), _TORCH_DTYPES[dt])
+
+
+def _chunk(packed, meta, what, packed_bytes: int, meta_bytes: int):
+    """One compressed chunk: the packed stream (any element type) and its float32 meta."""
+    if meta_bytes:
+        m = _device_buffer(meta, (what, "meta"), meta_bytes, "float32")
+    else:
+        m = _device_buffer(meta, (what, "meta"), 0) if meta is not None else 0
+    return _device_buffer(packed, (what, "packed"), packed_bytes), m
+
+
+def _peers(packed: Sequence, meta: Sequence, what: str, packed_bytes: int, meta_bytes: int):
+    W = len(packed)
+    if len(meta) != W:
+        raise ValueError("as many meta tensors as packed tensors")
+    pp, mp = (ctypes.c_void_p * max(W, 1))(), (ctypes.c_void_p * max(W, 1))()
+    for w in range(W):
+        pp[w], mp[w] = _chunk(packed[w], meta[w], (what, "chunk", w), packed_bytes, meta_bytes)
+    return W, pp, mp
+
+
+def _sizes_of(plan, qsgd: bool = False, dt: int = None) -> Tuple[int, int]:
+    """(packed_bytes, meta_bytes) of a Plan or LayeredPlan, for either quantizer, optionally at another storage type."""
+    dt = plan.dt if dt is None else dt
+    cache = plan.__dict__.setdefault("_sizes", {})           # a plan's arrays are not changed after construction
+    if (qsgd, dt) in cache:
+        return cache[(qsgd, dt)]
+    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
+    if isinstance(plan, LayeredPlan):
+        fn, name = (lib().cgx_qsgd_layered_sizes, "cgx_qsgd_layered_sizes") if qsgd else \
+            (lib().cgx_layered_sizes, "cgx_layered_sizes")
+    else:
+        fn, name = (lib().cgx_qsgd_sizes, "cgx_qsgd_sizes") if qsgd else (lib().cgx_sizes, "cgx_sizes")
+    _check(fn(*plan.args, dt, ctypes.byref(pb), ctypes.byref(mb)), name)
+    cache[(qsgd, dt)] = (int(pb.value), int(mb.value))
+    return cache[(qsgd, dt)]
+
+
 def cgx_sizes(plan: Plan) -> Tuple[int, int]:
     """(packed_bytes, meta_bytes) of a plan."""
-    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().cgx_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_sizes")
-    return int(pb.value), int(mb.value)
+    return _sizes_of(plan)
 
 
 def cgx_plan_tiles(plan: Plan, chunk: int = 2048) -> np.ndarray:
@@ -185,117 +262,115 @@ def cgx_plan_tiles(plan: Plan, chunk: int = 2048) -> np.ndarray:
     return tiles
 
 
+_M64 = 2**64 - 1
+
+
+def _quantize(name: str, qsgd: bool, grad, plan, seed: int, packed, meta, stream, requantize: bool = False) -> None:
+    in_dt = F32 if requantize else plan.dt
+    pb, mb = _sizes_of(plan, qsgd, in_dt)
+    g = _elements(grad, (name, "input"), plan.n, in_dt)
+    p, m = _chunk(packed, meta, (name, "output"), pb, mb)
+    dt_arg = () if requantize else (plan.dt,)
+    _check(getattr(lib(), name)(g, *plan.args, seed & _M64, *dt_arg, p, m, _stream(stream)), name)
+
+
+def _reduce(name: str, qsgd: bool, packed, meta, plan, total, stream, local=None, local_dt: int = None) -> None:
+    pb, mb = _sizes_of(plan, qsgd)
+    W, pp, mp = _peers(packed, meta, name, pb, mb)
+    out = _elements(total, (name, "sum"), plan.n, F32)
+    head = () if local is None else (_elements(local, (name, "local"), plan.n, local_dt), local_dt)
+    _check(getattr(lib(), name)(*head, pp, mp, W, *plan.args, plan.dt, out, _stream(stream)), name)
+
+
+def _fused(name: str, qsgd: bool, packed, meta, plan, seed: int, packed_out, meta_out, stream) -> None:
+    pb, mb = _sizes_of(plan, qsgd)
+    ob, omb = _sizes_of(plan, qsgd, F32)
+    W, pp, mp = _peers(packed, meta, name, pb, mb)
+    po, mo = _chunk(packed_out, meta_out, (name, "output"), ob, omb)
+    _check(getattr(lib(), name)(pp, mp, W, *plan.args, plan.dt, seed & _M64, po, mo, _stream(stream)), name)
+
+
+def _dequantize(name: str, packed, meta, plan, out_dt: int, out, stream) -> None:
+    if out_dt not in (F32, F16):
+        raise ValueError(f"{name}: out_dt must be F32 or F16")
+    pb, mb = _sizes_of(plan)
+    p, m = _chunk(packed, meta, (name, "input"), pb, mb)
+    o = _elements(out, (name, "output"), plan.n, out_dt)
+    _check(getattr(lib(), name)(p, m, *plan.args, plan.dt, out_dt, o, _stream(stream)), name)
+
+
 def cgx_quantize(grad, plan: Plan, seed: int, packed, meta, stream=None) -> None:
     """grad: device tensor of n elements (float32 or float16 per plan.dt);
-    packed: device uint8 tensor of >= packed_bytes; meta: device float32 tensor of >= meta_bytes/4."""
-    _check(lib().cgx_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
-                              meta.data_ptr(), _stream(stream)), "cgx_quantize")
+    packed: device tensor of >= packed_bytes; meta: device float32 tensor of >= meta_bytes/4 elements."""
+    _quantize("cgx_quantize", False, grad, plan, seed, packed, meta, stream)
 
 
 def cgx_requantize(total, plan: Plan, seed: int, packed, meta, stream=None) -> None:
-    """total: device float32 tensor of n elements (the reduced chunk)."""
-    _check(lib().cgx_requantize(total.data_ptr(), *plan.args, seed & (2**64 - 1), packed.data_ptr(),
-                                meta.data_ptr(), _stream(stream)), "cgx_requantize")
+    """total: device float32 tensor of n elements (the reduced chunk); outputs sized for dt = F32."""
+    _quantize("cgx_requantize", False, total, plan, seed, packed, meta, stream, requantize=True)
 
 
 def cgx_dequant_reduce(packed: Sequence, meta: Sequence, plan: Plan, total, stream=None) -> None:
     """packed / meta: W device tensors each; total: device float32 tensor of n elements (output)."""
-    W = len(packed)
-    if len(meta) != W:
-        raise ValueError("as many meta tensors as packed tensors")
-    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
-    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
-    _check(lib().cgx_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
-           "cgx_dequant_reduce")
+    _reduce("cgx_dequant_reduce", False, packed, meta, plan, total, stream)
 
 
 def cgx_dequant_reduce_add(local, local_dt: int, packed: Sequence, meta: Sequence, plan: Plan, total, stream=None) -> None:
     """total = local + sum of the W dequantized chunks; local: device tensor of n elements (float32 / float16)."""
-    W = len(packed)
-    if len(meta) != W:
-        raise ValueError("as many meta tensors as packed tensors")
-    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
-    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
-    _check(lib().cgx_dequant_reduce_add(local.data_ptr(), local_dt, pp, mp, W, *plan.args, plan.dt, total.data_ptr(),
-                                        _stream(stream)), "cgx_dequant_reduce_add")
+    if local_dt not in (F32, F16):
+        raise ValueError("cgx_dequant_reduce_add: local_dt must be F32 or F16")
+    _reduce("cgx_dequant_reduce_add", False, packed, meta, plan, total, stream, local, local_dt)
 
 
 def cgx_dequantize(packed, meta, plan: Plan, out_dt: int, out, stream=None) -> None:
     """out: device tensor of n elements of out_dt (float32 or float16) receiving the decompressed chunk."""
-    _check(lib().cgx_dequantize(packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt, out_dt, out.data_ptr(),
-                                _stream(stream)), "cgx_dequantize")
+    _dequantize("cgx_dequantize", packed, meta, plan, out_dt, out, stream)
 
 
 def cgx_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, seed: int, packed_out, meta_out,
                                   stream=None) -> None:
     """packed / meta: W <= 16 device tensors each (chunks of `plan`); packed_out / meta_out: device
     tensors sized by cgx_sizes of the same plan with dt = F32."""
-    W = len(packed)
-    if len(meta) != W:
-        raise ValueError("as many meta tensors as packed tensors")
-    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
-    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
-    _check(lib().cgx_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
-                                               packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
-           "cgx_dequant_reduce_requantize")
-
-
-def _peer_arrays(packed: Sequence, meta: Sequence):
-    W = len(packed)
-    if len(meta) != W:
-        raise ValueError("as many meta tensors as packed tensors")
-    pp = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
-    mp = (ctypes.c_void_p * max(W, 1))(*[m.data_ptr() for m in meta])
-    return W, pp, mp
+    _fused("cgx_dequant_reduce_requantize", False, packed, meta, plan, seed, packed_out, meta_out, stream)
 
 
 def cgx_layered_sizes(plan: LayeredPlan) -> Tuple[int, int]:
     """(packed_bytes, meta_bytes) of a plan with a bucket size per layer."""
-    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().cgx_layered_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_layered_sizes")
-    return int(pb.value), int(mb.value)
+    return _sizes_of(plan)
 
 
 def cgx_layered_quantize(grad, plan: LayeredPlan, seed: int, packed, meta, stream=None) -> None:
     """As cgx_quantize, every layer with its own bucket size."""
-    _check(lib().cgx_layered_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
-                                      meta.data_ptr(), _stream(stream)), "cgx_layered_quantize")
+    _quantize("cgx_layered_quantize", False, grad, plan, seed, packed, meta, stream)
 
 
 def cgx_layered_requantize(total, plan: LayeredPlan, seed: int, packed, meta, stream=None) -> None:
     """As cgx_requantize, every layer with its own bucket size."""
-    _check(lib().cgx_layered_requantize(total.data_ptr(), *plan.args, seed & (2**64 - 1), packed.data_ptr(),
-                                        meta.data_ptr(), _stream(stream)), "cgx_layered_requantize")
+    _quantize("cgx_layered_requantize", False, total, plan, seed, packed, meta, stream, requantize=True)
 
 
 def cgx_layered_dequant_reduce(packed: Sequence, meta: Sequence, plan: LayeredPlan, total, stream=None) -> None:
     """As cgx_dequant_reduce, every layer with its own bucket size."""
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_layered_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
-           "cgx_layered_dequant_reduce")
+    _reduce("cgx_layered_dequant_reduce", False, packed, meta, plan, total, stream)
 
 
 def cgx_layered_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: LayeredPlan, seed: int, packed_out,
                                           meta_out, stream=None) -> None:
     """As cgx_dequant_reduce_requantize, every layer with its own bucket size."""
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_layered_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
-                                                       packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
-           "cgx_layered_dequant_reduce_requantize")
+    _fused("cgx_layered_dequant_reduce_requantize", False, packed, meta, plan, seed, packed_out, meta_out, stream)
 
 
 def cgx_layered_dequant_reduce_add(local, local_dt: int, packed: Sequence, meta: Sequence, plan: LayeredPlan, total,
                                    stream=None) -> None:
     """As cgx_dequant_reduce_add, every layer with its own bucket size."""
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_layered_dequant_reduce_add(local.data_ptr(), local_dt, pp, mp, W, *plan.args, plan.dt,
-                                                total.data_ptr(), _stream(stream)), "cgx_layered_dequant_reduce_add")
+    if local_dt not in (F32, F16):
+        raise ValueError("cgx_layered_dequant_reduce_add: local_dt must be F32 or F16")
+    _reduce("cgx_layered_dequant_reduce_add", False, packed, meta, plan, total, stream, local, local_dt)
 
 
 def cgx_layered_dequantize(packed, meta, plan: LayeredPlan, out_dt: int, out, stream=None) -> None:
     """As cgx_dequantize, every layer with its own bucket size."""
-    _check(lib().cgx_layered_dequantize(packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt, out_dt,
-                                        out.data_ptr(), _stream(stream)), "cgx_layered_dequantize")
+    _dequantize("cgx_layered_dequantize", packed, meta, plan, out_dt, out, stream)
 
 
 def cgx_layered_stats_workspace(plan: LayeredPlan) -> int:
@@ -305,67 +380,57 @@ def cgx_layered_stats_workspace(plan: LayeredPlan) -> int:
     return int(nbytes.value)
 
 
+def _sqerrors(name: str, qsgd: bool, grad, packed, meta, plan, sqerr, workspace, stream) -> None:
+    pb, mb = _sizes_of(plan, qsgd)
+    g = _elements(grad, f"{name}: grad", plan.n, plan.dt)
+    p, m = _chunk(packed, meta, f"{name}: chunk", pb, mb)
+    out = _device_buffer(sqerr, f"{name}: sqerr", 8 * plan.L, "float64")
+    ws = _device_buffer(workspace, f"{name}: workspace", 0)        # its size travels with the call: the library checks it
+    _check(getattr(lib(), name)(g, p, m, *plan.args, plan.dt, out, ws, workspace.numel() * workspace.element_size(),
+                                _stream(stream)), name)
+
+
 def cgx_layered_layer_sqerrors(grad, packed, meta, plan: LayeredPlan, sqerr, workspace, stream=None) -> None:
     """sqerr (device float64[L]) = per-layer squared l2 norm of grad - dequantize(packed, meta)."""
-    _check(lib().cgx_layered_layer_sqerrors(grad.data_ptr(), packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt,
-                                            sqerr.data_ptr(), workspace.data_ptr(),
-                                            workspace.numel() * workspace.element_size(), _stream(stream)),
-           "cgx_layered_layer_sqerrors")
+    _sqerrors("cgx_layered_layer_sqerrors", False, grad, packed, meta, plan, sqerr, workspace, stream)
 
 
 def cgx_qsgd_layered_sizes(plan: LayeredPlan) -> Tuple[int, int]:
-    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().cgx_qsgd_layered_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_qsgd_layered_sizes")
-    return int(pb.value), int(mb.value)
+    return _sizes_of(plan, qsgd=True)
 
 
 def cgx_qsgd_layered_quantize(grad, plan: LayeredPlan, seed: int, packed, meta, stream=None) -> None:
-    _check(lib().cgx_qsgd_layered_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
-                                           meta.data_ptr(), _stream(stream)), "cgx_qsgd_layered_quantize")
+    _quantize("cgx_qsgd_layered_quantize", True, grad, plan, seed, packed, meta, stream)
 
 
 def cgx_qsgd_layered_dequant_reduce(packed: Sequence, meta: Sequence, plan: LayeredPlan, total, stream=None) -> None:
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_qsgd_layered_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
-           "cgx_qsgd_layered_dequant_reduce")
+    _reduce("cgx_qsgd_layered_dequant_reduce", True, packed, meta, plan, total, stream)
 
 
 def cgx_qsgd_layered_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: LayeredPlan, seed: int,
                                                packed_out, meta_out, stream=None) -> None:
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_qsgd_layered_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
-                                                            packed_out.data_ptr(), meta_out.data_ptr(),
-                                                            _stream(stream)),
-           "cgx_qsgd_layered_dequant_reduce_requantize")
+    _fused("cgx_qsgd_layered_dequant_reduce_requantize", True, packed, meta, plan, seed, packed_out, meta_out, stream)
 
 
 def cgx_qsgd_sizes(plan: Plan) -> Tuple[int, int]:
     """(packed_bytes, meta_bytes) of a plan under the norm-and-sign quantizer (one float of meta per bucket)."""
-    pb, mb = ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().cgx_qsgd_sizes(*plan.args, plan.dt, ctypes.byref(pb), ctypes.byref(mb)), "cgx_qsgd_sizes")
-    return int(pb.value), int(mb.value)
+    return _sizes_of(plan, qsgd=True)
 
 
 def cgx_qsgd_quantize(grad, plan: Plan, seed: int, packed, meta, stream=None) -> None:
     """As cgx_quantize, norm-and-sign codes; buffers sized by cgx_qsgd_sizes."""
-    _check(lib().cgx_qsgd_quantize(grad.data_ptr(), *plan.args, seed & (2**64 - 1), plan.dt, packed.data_ptr(),
-                                   meta.data_ptr(), _stream(stream)), "cgx_qsgd_quantize")
+    _quantize("cgx_qsgd_quantize", True, grad, plan, seed, packed, meta, stream)
 
 
 def cgx_qsgd_dequant_reduce(packed: Sequence, meta: Sequence, plan: Plan, total, stream=None) -> None:
     """As cgx_dequant_reduce, for chunks written by cgx_qsgd_quantize."""
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_qsgd_dequant_reduce(pp, mp, W, *plan.args, plan.dt, total.data_ptr(), _stream(stream)),
-           "cgx_qsgd_dequant_reduce")
+    _reduce("cgx_qsgd_dequant_reduce", True, packed, meta, plan, total, stream)
 
 
 def cgx_qsgd_dequant_reduce_requantize(packed: Sequence, meta: Sequence, plan: Plan, seed: int, packed_out,
                                        meta_out, stream=None) -> None:
     """As cgx_dequant_reduce_requantize, norm-and-sign codes on both sides."""
-    W, pp, mp = _peer_arrays(packed, meta)
-    _check(lib().cgx_qsgd_dequant_reduce_requantize(pp, mp, W, *plan.args, plan.dt, seed & (2**64 - 1),
-                                                    packed_out.data_ptr(), meta_out.data_ptr(), _stream(stream)),
-           "cgx_qsgd_dequant_reduce_requantize")
+    _fused("cgx_qsgd_dequant_reduce_requantize", True, packed, meta, plan, seed, packed_out, meta_out, stream)
 
 
 def cgx_layer_stats_workspace(plan: Plan, for_sqnorms: bool = False) -> int:
@@ -379,9 +444,11 @@ def cgx_layer_stats_workspace(plan: Plan, for_sqnorms: bool = False) -> int:
 
 def cgx_layer_sqnorms(buf, plan: Plan, sqnorm, workspace, stream=None) -> None:
     """sqnorm (device float64[L]) = per-layer sums of squares of buf; workspace: device uint8 tensor."""
-    _check(lib().cgx_layer_sqnorms(buf.data_ptr(), plan.n, plan.L, plan.offsets.ctypes.data, plan.dt,
-                                   sqnorm.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                   _stream(stream)), "cgx_layer_sqnorms")
+    b = _elements(buf, "cgx_layer_sqnorms: buf", plan.n, plan.dt)
+    out = _device_buffer(sqnorm, "cgx_layer_sqnorms: sqnorm", 8 * plan.L, "float64")
+    ws = _device_buffer(workspace, "cgx_layer_sqnorms: workspace", 0)   # sized check: in the library
+    _check(lib().cgx_layer_sqnorms(b, plan.n, plan.L, plan.offsets.ctypes.data, plan.dt, out, ws,
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "cgx_layer_sqnorms")
 
 
 NOALLOC_MAX_LAYERS, NOALLOC_MAX_TILES = 4096, 262144
@@ -389,16 +456,16 @@ NOALLOC_MAX_LAYERS, NOALLOC_MAX_TILES = 4096, 262144
 
 def cgx_layer_sqnorms_noalloc(buf, plan: Plan, sqnorm, stream=None) -> None:
     """cgx_layer_sqnorms without workspace and without device allocations (fixed tables inside the library)."""
-    _check(lib().cgx_layer_sqnorms_noalloc(buf.data_ptr(), plan.n, plan.L, plan.offsets.ctypes.data, plan.dt,
-                                           sqnorm.data_ptr(), _stream(stream)), "cgx_layer_sqnorms_noalloc")
+    b = _elements(buf, "cgx_layer_sqnorms_noalloc: buf", plan.n, plan.dt)
+    out = _device_buffer(sqnorm, "cgx_layer_sqnorms_noalloc: sqnorm", 8 * plan.L, "float64")
+    _check(lib().cgx_layer_sqnorms_noalloc(b, plan.n, plan.L, plan.offsets.ctypes.data, plan.dt, out, _stream(stream)),
+           "cgx_layer_sqnorms_noalloc")
 
 
 def cgx_layer_sqerrors(grad, packed, meta, plan: Plan, sqerr, workspace, stream=None, qsgd: bool = False) -> None:
     """sqerr (device float64[L]) = per-layer squared l2 norm of grad - dequantize(packed, meta)."""
-    fn = lib().cgx_qsgd_layer_sqerrors if qsgd else lib().cgx_layer_sqerrors
-    _check(fn(grad.data_ptr(), packed.data_ptr(), meta.data_ptr(), *plan.args, plan.dt, sqerr.data_ptr(),
-              workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)),
-           "cgx_qsgd_layer_sqerrors" if qsgd else "cgx_layer_sqerrors")
+    _sqerrors("cgx_qsgd_layer_sqerrors" if qsgd else "cgx_layer_sqerrors", qsgd, grad, packed, meta, plan, sqerr,
+              workspace, stream)
 
 
 def _assign_inputs(layer_offsets, layer_norms, bits_in, candidates):
@@ -442,8 +509,9 @@ def cgx_assign_buckets_from_bits(bits_per_layer, width_candidates, bucket_candid
 
 def cgx_stream_probe(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:
     """Measurement aid: one launch reading read_bytes from src and writing write_bytes to dst."""
-    _check(lib().cgx_stream_probe(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes, _stream(stream)),
-           "cgx_stream_probe")
+    _check(lib().cgx_stream_probe(_device_buffer(src, "cgx_stream_probe: src", read_bytes), read_bytes,
+                                  _device_buffer(dst, "cgx_stream_probe: dst", write_bytes), write_bytes,
+                                  _stream(stream)), "cgx_stream_probe")
 
 
 LOAD_POLICIES = ("plain", "nt", "sc1", "sc0 sc1")
@@ -458,8 +526,9 @@ def cgx_stream_probe_shaped(src, read_bytes: int, dst, write_bytes: int, slice_b
     shape = (ctypes.c_int32 * 9)(slice_bytes, block_threads, LOAD_POLICIES.index(loads), STORE_POLICIES.index(stores),
                                  int(xcd_contiguous), max_blocks, int(paired_loads), alu_ops_per_pass,
                                  lds_bytes_per_block)
-    _check(lib().cgx_stream_probe_shaped(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes, shape,
-                                         _stream(stream)), "cgx_stream_probe_shaped")
+    _check(lib().cgx_stream_probe_shaped(_device_buffer(src, "cgx_stream_probe_shaped: src", read_bytes), read_bytes,
+                                         _device_buffer(dst, "cgx_stream_probe_shaped: dst", write_bytes),
+                                         write_bytes, shape, _stream(stream)), "cgx_stream_probe_shaped")
 
 
 def cgx_shutdown() -> None:

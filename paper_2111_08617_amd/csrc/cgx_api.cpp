@@ -39,6 +39,7 @@ struct CachedPlan {
     uint32_t *d_slots = nullptr;
     int64_t *d_layer_first = nullptr;
     uint64_t last_use = 0;      // cache clock at the latest look-up
+    bool pinned = false;        // a stream capture has recorded launches that read these tables: never dropped
 };
 
 void free_plan(CachedPlan &p)
@@ -155,13 +156,20 @@ std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off,
     return out;
 }
 
-// Finds or builds the device-resident tile table of a (valid) plan.
-int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunk,
+// Finds or builds the device-resident tile table of a (valid) plan for a call on `stream`.
+// A graph that is being captured keeps the raw table pointers of the launches recorded into it, so a table
+// found during a capture is pinned for the life of the library (never the one dropped for a new plan),
+// and a table that does not exist yet is not built during a capture (that would allocate and copy
+// synchronously in the middle of it): the call fails with CGX_ERR_CAPTURE and records nothing.
+int get_plan(hipStream_t stream, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunk,
              int chunks_per_tile, PlanRef *out, const int32_t *layer_buckets = nullptr, bool with_copies = true)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return CGX_ERR_HIP;
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(stream, &capture) == hipSuccess && capture == hipStreamCaptureStatusActive;
+    if (!capturing) (void)hipGetLastError();       // a refused query (legacy stream beside a capture) is not this call's error
     for (const auto &p : g_plans) {
         if (p->device == device && p->bucket == bucket && p->dt == dt &&
             p->chunk == chunk && p->chunks_per_tile == chunks_per_tile && p->bits.size() == size_t(L) &&
@@ -171,10 +179,12 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
             std::memcmp(p->bits.data(), bits, size_t(L)) == 0 &&
             std::memcmp(p->off.data(), off, sizeof(int64_t) * (size_t(L) + 1)) == 0) {
             p->last_use = ++g_clock;
+            if (capturing) p->pinned = true;
             *out = p;
             return CGX_OK;
         }
     }
+    if (capturing) return CGX_ERR_CAPTURE;
     std::shared_ptr<CachedPlan> plan(new CachedPlan, [](CachedPlan *p) {
         free_plan(*p);
         delete p;
@@ -237,13 +247,30 @@ int get_plan(int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket,
     }
     plan->last_use = ++g_clock;
     if (g_plans.size() >= kMaxPlans) {
-        size_t oldest = 0;
-        for (size_t i = 1; i < g_plans.size(); i++)
-            if (g_plans[i]->last_use < g_plans[oldest]->last_use) oldest = i;
-        g_plans.erase(g_plans.begin() + long(oldest));
+        // drop the least recently used table that no captured graph reads (if all are pinned the cache grows)
+        size_t oldest = g_plans.size();
+        for (size_t i = 0; i < g_plans.size(); i++)
+            if (!g_plans[i]->pinned && (oldest == g_plans.size() || g_plans[i]->last_use < g_plans[oldest]->last_use))
+                oldest = i;
+        if (oldest != g_plans.size()) g_plans.erase(g_plans.begin() + long(oldest));
     }
     *out = plan;
     g_plans.push_back(std::move(plan));
+    return CGX_OK;
+}
+
+// The tables of all launches of a call, looked up before its first launch: a call that fails for a
+// missing table (CGX_ERR_CAPTURE) has then queued nothing.
+int get_plans(hipStream_t stream, const std::vector<Launch> &launches, int32_t L, const int64_t *off,
+              const uint8_t *bits, int dt, int chunk, int chunks_per_tile, const int32_t *layer_buckets,
+              std::vector<PlanRef> *out)
+{
+    out->resize(launches.size());
+    for (size_t i = 0; i < launches.size(); i++) {
+        const int rc = get_plan(stream, L, off, bits, launches[i].bucket, dt, chunk, chunks_per_tile, &(*out)[i],
+                                layer_buckets, launches[i].with_copies);
+        if (rc != CGX_OK) return rc;
+    }
     return CGX_OK;
 }
 
@@ -275,11 +302,14 @@ int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int6
     if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
     const int chunk = chunk_length(kQuantizeCall, dt);
     const auto launch_quantize = chunk == cgx::chunk_of(2) ? cgx::launch_quantize_g2 : cgx::launch_quantize_g4;
-    for (const Launch &launch : launches_of(buckets, L, off, bits, chunk)) {
-        PlanRef plan;
-        rc = get_plan(L, off, bits, launch.bucket, dt, chunk, tile_length(kQuantizeCall, dt, n), &plan,
-                      buckets.per_layer, launch.with_copies);
-        if (rc != CGX_OK) return rc;
+    const std::vector<Launch> launches = launches_of(buckets, L, off, bits, chunk);
+    std::vector<PlanRef> plans;
+    rc = get_plans(static_cast<hipStream_t>(stream), launches, L, off, bits, dt, chunk, tile_length(kQuantizeCall, dt, n),
+                   buckets.per_layer, &plans);
+    if (rc != CGX_OK) return rc;
+    for (size_t i = 0; i < launches.size(); i++) {
+        const Launch &launch = launches[i];
+        const PlanRef &plan = plans[i];
         const hipError_t e = launch_quantize(scheme, grad, dt, plan->d_tiles, plan->n_tiles, plan->odd_tiles,
                                                   plan->aligned_tiles, launch.bucket, seed, packed, meta, launch_config(),
                                                   static_cast<hipStream_t>(stream));
@@ -304,11 +334,14 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
-    for (const Launch &launch : launches_of(buckets, L, off, bits, cgx::kDefaultChunk)) {
-        PlanRef plan;
-        rc = get_plan(L, off, bits, launch.bucket, dt, cgx::kDefaultChunk, tile_length(kOtherCall, dt, n), &plan,
-                      buckets.per_layer, launch.with_copies);
-        if (rc != CGX_OK) return rc;
+    const std::vector<Launch> launches = launches_of(buckets, L, off, bits, cgx::kDefaultChunk);
+    std::vector<PlanRef> plans;
+    rc = get_plans(static_cast<hipStream_t>(stream), launches, L, off, bits, dt, cgx::kDefaultChunk,
+                   tile_length(kOtherCall, dt, n), buckets.per_layer, &plans);
+    if (rc != CGX_OK) return rc;
+    for (size_t li = 0; li < launches.size(); li++) {
+        const Launch &launch = launches[li];
+        const PlanRef &plan = plans[li];
         // peers are folded in order, kPeersPerLaunch at a time, so the sum order is local, 0, 1, ..., W-1;
         // a later launch starts from the binary32 result of the one before (W <= kPeersPerLaunch
         // whenever the output is not binary32: only cgx_dequantize asks for that, with W = 1)
@@ -359,11 +392,11 @@ int fused_impl(int scheme, const void *const *packed, const void *const *meta, i
     }
     for (const Launch &launch : launches_of(buckets, L, layer_offsets, bits_per_layer, cgx::kDefaultChunk)) {
         PlanRef in, out;
-        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, dt, cgx::kDefaultChunk,
-                      tile_length(kFusedCall, dt, n), &in, buckets.per_layer, launch.with_copies);
+        rc = get_plan(static_cast<hipStream_t>(stream), L, layer_offsets, bits_per_layer, launch.bucket, dt,
+                      cgx::kDefaultChunk, tile_length(kFusedCall, dt, n), &in, buckets.per_layer, launch.with_copies);
         if (rc != CGX_OK) return rc;
-        rc = get_plan(L, layer_offsets, bits_per_layer, launch.bucket, CGX_F32, cgx::kDefaultChunk,
-                      tile_length(kFusedCall, dt, n), &out, buckets.per_layer, launch.with_copies);
+        rc = get_plan(static_cast<hipStream_t>(stream), L, layer_offsets, bits_per_layer, launch.bucket, CGX_F32,
+                      cgx::kDefaultChunk, tile_length(kFusedCall, dt, n), &out, buckets.per_layer, launch.with_copies);
         if (rc != CGX_OK) return rc;
         if (in->n_tiles != out->n_tiles) return CGX_ERR_SIZE;     // cannot happen: same tiling for both layouts
         const hipError_t e = cgx::launch_dequant_reduce_requantize(
@@ -407,12 +440,14 @@ int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *
         return CGX_ERR_ALIGN;
     // every launch leaves its tiles' partial sums in the workspace; the last one adds them up layer by layer
     const std::vector<Launch> launches = launches_of(buckets, L, off, bits, cgx::kDefaultChunk);
-    for (size_t i = 0; i < launches.size(); i++) {
-        PlanRef plan;
-        rc = get_plan(L, off, bits, launches[i].bucket, dt, cgx::kDefaultChunk, tile_length(kOtherCall, dt, n), &plan,
-                      buckets.per_layer, launches[i].with_copies);
-        if (rc != CGX_OK) return rc;
+    std::vector<PlanRef> plans;
+    rc = get_plans(static_cast<hipStream_t>(stream), launches, L, off, bits, dt, cgx::kDefaultChunk,
+                   tile_length(kOtherCall, dt, n), buckets.per_layer, &plans);
+    if (rc != CGX_OK) return rc;
+    for (const PlanRef &plan : plans)
         if (workspace_bytes < size_t(plan->plan_tiles) * sizeof(double)) return CGX_ERR_SIZE;
+    for (size_t i = 0; i < launches.size(); i++) {
+        const PlanRef &plan = plans[i];
         const hipError_t e = cgx::launch_layer_sqerrors(
             scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots, plan->n_tiles, plan->d_layer_first, L,
             static_cast<double *>(workspace), sqerr, launch_config(), static_cast<hipStream_t>(stream),
@@ -688,8 +723,8 @@ int cgx_layer_sqnorms(const void *buf, int64_t n, int32_t L, const int64_t *laye
     if (!sqnorm || (n > 0 && (!buf || !workspace))) return CGX_ERR_NULL;
     if (misaligned(buf) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(sqnorm) & 7u)) return CGX_ERR_ALIGN;
     PlanRef plan;
-    rc = get_plan(L, layer_offsets, zeros.data(), 32, int(dt), cgx::kDefaultChunk, tile_length(kOtherCall, int(dt), n),
-                  &plan);
+    rc = get_plan(static_cast<hipStream_t>(stream), L, layer_offsets, zeros.data(), 32, int(dt), cgx::kDefaultChunk,
+                  tile_length(kOtherCall, int(dt), n), &plan);
     if (rc != CGX_OK) return rc;
     if (workspace_bytes < size_t(plan->n_tiles) * sizeof(double)) return CGX_ERR_SIZE;
     const hipError_t e = cgx::launch_layer_sqnorms(buf, int(dt), plan->d_tiles, plan->d_slots, plan->n_tiles,
@@ -810,6 +845,8 @@ const char *cgx_status_string(int status)
     case CGX_ERR_DTYPE: return "unknown storage type";
     case CGX_ERR_HIP: return "the HIP runtime reported an error";
     case CGX_ERR_ALIGN: return "device pointers must be 16-byte aligned";
+    case CGX_ERR_CAPTURE: return "the stream is capturing a graph and this plan's tables do not exist yet: run the call "
+                                 "once outside the capture first";
     case CGX_ERR_CAPACITY: return "the plan exceeds the fixed tables of a no-allocation entry point "
                                   "(CGX_NOALLOC_MAX_LAYERS layers, CGX_NOALLOC_MAX_TILES work items)";
     default: return "unknown status";

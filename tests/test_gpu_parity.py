@@ -541,6 +541,49 @@ def test_step_can_be_captured_in_a_graph_and_replayed(torch, oracle):
             assert got.cpu().numpy().tobytes() == ref.tobytes(), f"replay {replay}"
 
 
+def test_captured_graph_survives_any_number_of_later_plans(torch, oracle):
+    """A table read by a captured graph is pinned: 70 further plans (more than the cache holds) do not free
+    it, and the graph still replays to the eager result.  A call whose plan has no table yet is refused
+    during a capture (CGX_ERR_CAPTURE) and records nothing; the capture goes on."""
+    rng = np.random.default_rng(33)
+    x = rng.standard_normal(2048 * 5 + 77).astype(np.float32)
+    off, bits = np.array([0, 4096, x.size], np.int64), np.array([4, 3], np.uint8)
+    plan = cgx.Plan(off, bits, 256)
+    never_seen = cgx.Plan(np.array([0, 4104, x.size], np.int64), bits, 256)
+    pb, mb = cgx.cgx_sizes(plan)
+    g = dev(torch, x)
+    out = (torch.zeros(pb, dtype=torch.uint8, device="cuda"), torch.zeros(mb // 4, device="cuda"))
+    spare = (torch.zeros(pb + 64, dtype=torch.uint8, device="cuda"), torch.zeros(mb // 4 + 16, device="cuda"))
+    cgx.cgx_quantize(g, plan, 5, out[0], out[1])              # builds the table
+    torch.cuda.synchronize()
+    op, om = oracle.quantize(x, off, bits, 256, 5, wl.F32)
+    assert_same_chunk(out[0].cpu().numpy(), out[1].cpu().numpy(), op, om, "eager")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        with pytest.raises(cgx.CgxError) as refused:
+            cgx.cgx_quantize(g, never_seen, 5, spare[0], spare[1])
+        cgx.cgx_quantize(g, plan, 5, out[0], out[1])
+    assert refused.value.status == -11 and "capture" in str(refused.value)
+    torch.cuda.synchronize()
+    for k in range(70):                                       # evicts every table that is not pinned
+        cut = 2048 + 8 * k
+        gpu_quantize(torch, x, np.array([0, cut, x.size], np.int64), np.array([2, 4], np.uint8), 128, k, wl.F32)
+    for replay in range(2):
+        out[0].fill_(9)
+        out[1].fill_(9.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same_chunk(out[0].cpu().numpy(), out[1].cpu().numpy(), op, om, f"replay {replay}")
+    assert (spare[0] == 0).all() and (spare[1] == 0).all()    # the refused call wrote nothing, then or on replay
+    cgx.cgx_quantize(g, never_seen, 5, spare[0], spare[1])    # and works outside a capture
+    torch.cuda.synchronize()
+    sp, sm = oracle.quantize(x, never_seen.offsets, bits, 256, 5, wl.F32)
+    assert np.array_equal(spare[0].cpu().numpy()[:sp.size], sp)
+
+
 def test_calls_from_several_host_threads_and_streams(torch, oracle):
     """The plan cache is shared by host threads; concurrent calls on separate streams with
     separate outputs give the same bytes as a single call."""

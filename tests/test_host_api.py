@@ -381,3 +381,77 @@ def test_norm_and_sign_layered_sizes_and_checks(lib, oracle):
     bad = np.array([64, 48], np.int32)
     assert lib.cgx_qsgd_layered_quantize(16, 300, 2, off.ctypes.data, bits.ctypes.data, bad.ctypes.data, 1, 0, 16, 16,
                                          None) == -5
+
+
+def test_binding_refuses_buffers_the_kernels_would_overrun(lib, monkeypatch):
+    """The C ABI sees no sizes, so the binding checks them: device, contiguity, element type and length of
+    every tensor against the plan, before the call.  Stand-ins with a tensor's attributes and no memory take
+    the place of device tensors here; the compute entry points are replaced by a stub that reports that a
+    call got past the checks."""
+    import torch
+
+    class Stub:
+        def __getattr__(self, name):
+            if name.endswith("sizes") or "workspace" in name or name == "cgx_status_string":
+                return getattr(lib, name)
+
+            def reached(*args):
+                raise AssertionError("the call went through to the library")
+            return reached
+
+    monkeypatch.setattr(cgx, "lib", lambda: Stub())
+
+    class Fake:
+        """A stand-in with the attributes the checks read (no memory behind it: never passed to the library)."""
+        def __init__(self, n, dtype=torch.float32, cuda=True, contiguous=True):
+            self.n, self.dtype, self.is_cuda, self._c, self.device = n, dtype, cuda, contiguous, "cuda:0" if cuda else "cpu"
+        def numel(self): return self.n
+        def element_size(self): return torch.empty(0, dtype=self.dtype).element_size()
+        def is_contiguous(self): return self._c
+        def data_ptr(self): return 0x1000
+
+    off = np.array([0, 4096, 5000], np.int64)
+    plan = cgx.Plan(off, np.array([4, 0], np.uint8), 128)
+    pb, mb = cgx.cgx_sizes(plan)
+    good = dict(grad=Fake(5000), packed=Fake(pb, torch.uint8), meta=Fake(mb // 4))
+
+    def quantize(**kw):
+        a = {**good, **kw}
+        cgx.cgx_quantize(a["grad"], plan, 1, a["packed"], a["meta"], stream=0)
+
+    for bad in (dict(grad=Fake(4999)), dict(grad=Fake(5000, torch.float16)), dict(grad=Fake(5000, cuda=False)),
+                dict(grad=Fake(5000, contiguous=False)), dict(packed=Fake(pb - 1, torch.uint8)),
+                dict(meta=Fake(mb // 4 - 1)), dict(meta=Fake(mb // 4, torch.float64)), dict(grad=np.zeros(5000, np.float32)),
+                dict(grad=torch.zeros(5000))):
+        with pytest.raises(ValueError):
+            quantize(**bad)
+    with pytest.raises(AssertionError, match="went through"):
+        quantize()                                                   # the good set passes every check
+    half = cgx.Plan(off, np.array([4, 0], np.uint8), 128, wl.F16)
+    with pytest.raises(ValueError, match="float16"):
+        cgx.cgx_quantize(Fake(5000), half, 1, good["packed"], good["meta"], stream=0)
+    chunks, metas = [Fake(pb, torch.uint8)] * 3, [Fake(mb // 4)] * 3
+    with pytest.raises(ValueError, match="sum"):
+        cgx.cgx_dequant_reduce(chunks, metas, plan, Fake(4999), stream=0)
+    with pytest.raises(ValueError, match="chunk 2"):
+        cgx.cgx_dequant_reduce(chunks[:2] + [Fake(pb - 16, torch.uint8)], metas, plan, Fake(5000), stream=0)
+    with pytest.raises(ValueError, match="as many"):
+        cgx.cgx_dequant_reduce(chunks, metas[:2], plan, Fake(5000), stream=0)
+    with pytest.raises(ValueError, match="local"):
+        cgx.cgx_dequant_reduce_add(Fake(5000, torch.float16), wl.F32, chunks, metas, plan, Fake(5000), stream=0)
+    with pytest.raises(ValueError, match="output"):
+        cgx.cgx_dequantize(chunks[0], metas[0], plan, wl.F16, Fake(5000), stream=0)      # float32 where binary16 is due
+    with pytest.raises(ValueError, match="output"):
+        cgx.cgx_dequant_reduce_requantize(chunks, metas, plan, 3, Fake(pb - 1, torch.uint8), metas[0], stream=0)
+    with pytest.raises(ValueError):
+        cgx.cgx_requantize(Fake(5000, torch.float16), plan, 1, good["packed"], good["meta"], stream=0)
+    with pytest.raises(ValueError, match="workspace"):
+        cgx.cgx_layer_sqnorms(Fake(5000), plan, Fake(2, torch.float64), Fake(1 << 20, torch.uint8, cuda=False), stream=0)
+    with pytest.raises(ValueError, match="sqnorm"):
+        cgx.cgx_layer_sqnorms_noalloc(Fake(5000), plan, Fake(1, torch.float64), stream=0)
+    qp, qm = cgx.cgx_qsgd_sizes(plan)
+    assert qm == mb // 2
+    with pytest.raises(AssertionError, match="went through"):
+        cgx.cgx_qsgd_quantize(Fake(5000), plan, 1, Fake(qp, torch.uint8), Fake(qm // 4), stream=0)
+    with pytest.raises(ValueError, match="meta"):
+        cgx.cgx_qsgd_quantize(Fake(5000), plan, 1, Fake(qp, torch.uint8), Fake(qm // 4 - 1), stream=0)

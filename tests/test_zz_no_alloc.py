@@ -94,6 +94,7 @@ def test_empty_plans(torch):
     ref, got = both(torch, np.zeros(0, np.float32), np.zeros(4, np.int64), wl.F32)
     assert got.tolist() == [0.0, 0.0, 0.0] and ref.tolist() == got.tolist()
     out = torch.full((2,), 7.0, dtype=torch.float64, device="cuda")
-    cgx.cgx_layer_sqnorms_noalloc(out, cgx.Plan(np.zeros(1, np.int64), np.zeros(0, np.uint8), 32), out)   # L = 0: nothing
+    nothing = torch.zeros(8, device="cuda")
+    cgx.cgx_layer_sqnorms_noalloc(nothing, cgx.Plan(np.zeros(1, np.int64), np.zeros(0, np.uint8), 32), out)   # L = 0
     torch.cuda.synchronize()
     assert out.tolist() == [7.0, 7.0]
