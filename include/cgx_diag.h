@@ -26,7 +26,7 @@ extern "C" {
  * Every element of every non-empty layer lies in exactly one tile and tiles never
  * cross layers (paper Sec. 4.1).  This is the table of one chunk per vectorised
  * tile that most calls walk: cgx_quantize on a binary16 gradient of 2^24 elements
- * or more, and the fused reduce + requantize on 2^27 elements or more, join 2 or 4
+ * or more, and the fused reduce + requantize on 2^27 elements or more, join 2
  * consecutive chunks of a layer into one tile (same bytes out; a wave's set-up is
  * spread over more input).  At most `capacity` records
  * are written; *n_tiles receives the full count.  Pure host computation.
@@ -91,6 +91,20 @@ typedef struct {
 } cgx_probe_shape;
 int cgx_stream_probe_shaped(const void *src, size_t read_bytes, void *dst, size_t write_bytes,
                             const cgx_probe_shape *shape /* host */, void *stream);
+
+/*
+ * Launch-shape overrides, for the tests and for measurements.  The library reads these
+ * environment variables once, at its first call; none of them changes a byte of any result (the
+ * parity tests run the same inputs under several settings and compare digests):
+ *   CGX_CHUNKS_PER_TILE=k   every vectorised tile holds up to k chunks (default: chosen per call)
+ *   CGX_MAX_BLOCKS=k        persistent grids of at most k blocks (default: one wave per tile)
+ *   CGX_QUANTIZE_GROUPS=2|4 chunk size of every quantize call: 1024 or 2048 elements (default:
+ *                           1024 for binary32 input, 2048 for binary16)
+ *   CGX_VIA_LDS=0           the quantizer reads its chunks straight into registers instead of
+ *                           through LDS
+ *   CGX_KEEP_SUMS_MB=k      the reduce writes results of up to k MB through at device scope so that
+ *                           they stay in the memory-side cache (default 128; 0: always streamed)
+ */
 
 #ifdef __cplusplus
 }

@@ -79,8 +79,7 @@ int env_int(const char *name, int fallback)
     return (v && *v) ? std::atoi(v) : fallback;
 }
 
-// Launch-shape tunables, for experiments: CGX_CHUNKS_PER_TILE (0 or unset: chosen per call,
-// see tile_length), CGX_MAX_BLOCKS.
+// Launch-shape overrides for the tests and for measurements (listed in include/cgx_diag.h): read once.
 const cgx::LaunchConfig &launch_config()
 {
     static const cgx::LaunchConfig cfg = [] {
@@ -96,10 +95,10 @@ const cgx::LaunchConfig &launch_config()
 }
 
 // Chunks per vectorised tile.  One keeps the most loads in flight and wins wherever a wave's
-// chunk is 8 KB of input.  Two cases differ on buffers that fill the chip many times over
+// chunk is 4 KB of input or more.  Two cases differ on buffers that fill the chip many times over
 // (measured; shorter buffers lose to the coarser tail of the launch):
-//  - cgx_quantize on binary16: a chunk is only 4 KB of input and the per-wave set-up shows, so
-//    a wave takes 2 chunks, 4 on large buffers (12 % faster at 354 M elements);
+//  - cgx_quantize on binary16, which is the heaviest in arithmetic per byte: a wave takes 2 chunks
+//    (354 M elements: 155 -> 149 us; 4 chunks: 156 us);
 //  - the fused reduce + requantize, which is bound by arithmetic: 2 chunks (3-6 % faster at
 //    164-268 M elements for every width).
 enum CallKind { kQuantizeCall, kFusedCall, kOtherCall };
@@ -120,7 +119,7 @@ int tile_length(CallKind call, int dt, int64_t n)
 {
     const int forced = launch_config().chunks_per_tile;
     if (forced > 0) return forced;
-    if (call == kQuantizeCall && dt == CGX_F16 && n >= (int64_t(1) << 24)) return n < (int64_t(1) << 27) ? 2 : 4;
+    if (call == kQuantizeCall && dt == CGX_F16 && n >= (int64_t(1) << 24)) return 2;
     if (call == kFusedCall && n >= (int64_t(1) << 27)) return 2;
     return 1;
 }

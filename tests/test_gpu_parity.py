@@ -437,7 +437,8 @@ def test_result_does_not_depend_on_launch_geometry(torch, oracle):
         "print(hashlib.sha256(b''.join(t.cpu().numpy().tobytes() for t in (p, m, s, fp, fm))).hexdigest())\n"
     ) % root
     digests = set()
-    for env in ({}, {"CGX_CHUNKS_PER_TILE": "3"}, {"CGX_CHUNKS_PER_TILE": "8", "CGX_MAX_BLOCKS": "5"}):
+    for env in ({}, {"CGX_CHUNKS_PER_TILE": "3"}, {"CGX_CHUNKS_PER_TILE": "8", "CGX_MAX_BLOCKS": "5"},
+                {"CGX_QUANTIZE_GROUPS": "4", "CGX_KEEP_SUMS_MB": "0"}, {"CGX_QUANTIZE_GROUPS": "2", "CGX_VIA_LDS": "0"}):
         out = subprocess.run([sys.executable, "-c", code], env={**os.environ, **env}, capture_output=True, text=True,
                              timeout=300)
         assert out.returncode == 0, out.stderr[-2000:]

@@ -176,29 +176,33 @@ def test_resnet50_config_full_size(torch, oracle):
     full_cycle(torch, oracle, no_one_bit(wl.resnet50()), W=8, what="qsgd resnet50")
 
 
-def test_gpt2_medium_config_full_size(torch, oracle):
-    """355M elements in binary16 storage, 4 bit, bucket 128: quantize the full buffer; reduce over
-    W = 8, requantize and the fused form on one rank's 1/8 share."""
-    w = no_one_bit(wl.gpt2_medium())
+@pytest.mark.parametrize("name", ["gpt2_medium", "bert_base", "decoder_1p3b"])
+def test_large_configs_full_size(torch, oracle, name):
+    """gpt2_medium (355M elements, binary16 storage, 4 bit, bucket 128), bert_base (109M, widths from
+    {2,3,4,8}, bucket 512: the odd width) and decoder_1p3b (1.3G, widths from {2,4,8}, bucket 1024):
+    quantize the full buffer; reduce over W = 8, requantize and the fused form on one rank's 1/8 share."""
+    w = no_one_bit(wl.WORKLOADS[name]())
     g = w.gradient(0, threads=16)
     gp, gm = gpu_quantize(torch, g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
     op, om = oracle.qsgd_quantize(g, w.offsets, w.bits, w.bucket, w.quant_seed(0), w.dt)
-    assert_same_chunk(gp, gm, op, om, "qsgd gpt2_medium quantize")
+    assert_same_chunk(gp, gm, op, om, f"qsgd {name} quantize")
     del g, gp, op
     first, sub_off, sub_bits = wl.share_subplan(w.offsets, w.bits, w.bucket, w.W, 5)
     m = int(sub_off[-1])
     chunks, metas = [], []
     for peer in range(w.W):
-        x = w.gradient(peer, first, first + m)
+        x = w.gradient(peer, first, first + m, threads=16)
         op, om = oracle.qsgd_quantize(x, sub_off, sub_bits, w.bucket, w.quant_seed(peer), w.dt)
         chunks.append(op)
         metas.append(om)
     ref = oracle.qsgd_dequant_reduce(chunks, metas, sub_off, sub_bits, w.bucket, w.dt)
     got, total = gpu_reduce(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt)
-    assert_sum_parity(got, ref, "qsgd gpt2_medium share reduce")
+    assert_sum_parity(got, ref, f"qsgd {name} share reduce")
     fp, fm = gpu_fused(torch, chunks, metas, sub_off, sub_bits, w.bucket, w.dt, 7)
     op, om = oracle.qsgd_quantize(ref["sum32"], sub_off, sub_bits, w.bucket, 7, wl.F32)
-    assert_same_chunk(fp, fm, op, om, "qsgd gpt2_medium share fused reduce+requantize")
+    assert_same_chunk(fp, fm, op, om, f"qsgd {name} share fused reduce+requantize")
+    rp, rm = gpu_quantize(torch, got, sub_off, sub_bits, w.bucket, 7, wl.F32)
+    assert_same_chunk(rp, rm, op, om, f"qsgd {name} share requantize")
 
 
 @pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
