@@ -501,6 +501,8 @@ CEILING_CASES = [
     ("read only, 6 GB", 6_000_000_000, 0),
     ("write only, 115 MB", 0, 115_343_360),
     ("write only, 1.5 GB", 0, 1_500_000_256),
+    ("write only, 6 GB", 0, 6_000_000_000),
+    ("copy 1:1, 115 MB", 57_671_680, 57_671_680),
     ("copy 1:1, 1.5 GB", 750_000_128, 750_000_128),
     ("copy 1:1, 6 GB", 3_000_000_000, 3_000_000_000),
 ]
