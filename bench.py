@@ -553,8 +553,10 @@ def ceilings(args):
         for loads in cgx.LOAD_POLICIES if rb else ("nt",):
             for stores in cgx.STORE_POLICIES if wb else ("nt",):
                 run(loads=loads, stores=stores)
-        best_pol = sorted({(k[2], k[3]): v for k, v in tried.items()}.items(), key=lambda kv: kv[1])[:3]
-        for (loads, stores), _ in best_pol:
+        best_pol = [kv[0] for kv in sorted({(k[2], k[3]): v for k, v in tried.items()}.items(), key=lambda kv: kv[1])[:3]]
+        if ("nt", "nt") not in best_pol:
+            best_pol.append(("nt", "nt"))                    # the kernels' own policies: always swept over the shapes
+        for loads, stores in best_pol:
             for slice_bytes in (2048, 4096, 8192, 16384, 32768, 65536):
                 for block in (64, 256, 1024):
                     for xcd in (False, True):
