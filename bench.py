@@ -261,10 +261,17 @@ def measure(name, args, extras=True):
         fused_wall = (time.perf_counter() - t0) * 1e3 / args.steps
         fused_kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in fe]))
         fused_alg = alg["dequant_reduce"] - 4 * m + (alg["requantize"] - 4 * m)
+        # the fused kernel is bound by the vector ALUs, not by HBM: 46 vector instructions per element at 4 bit
+        # and W = 8 (stored: profiles/alu_counters_rocprofv3.md, SQ_INSTS_VALU per wave / elements per wave)
+        # against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instructions/s
+        alu_peak = 256 * 4 * 16 * 2.4e9
         fused = {"step": "cgx_quantize(full buffer) + cgx_dequant_reduce_requantize(W chunks)",
                  "ms_per_step": round(fused_wall, 5),
                  "dequant_reduce_requantize": dict(rate(fused_alg, fused_kernel_ms),
-                                                   raw_gradient_GBps=round(4 * m / fused_kernel_ms / 1e6, 1))}
+                                                   raw_gradient_GBps=round(4 * m / fused_kernel_ms / 1e6, 1),
+                                                   bound="alu",
+                                                   alu_frac_at_46_instructions_per_element=round(
+                                                       46.0 * m / (fused_kernel_ms * 1e-3) / alu_peak, 4))}
 
     # the remaining calls of a rank's scatter-reduce / all-gather: decompression of a gathered chunk into the
     # storage type, and the reduce with the rank's own contribution still uncompressed
@@ -356,18 +363,19 @@ def measure(name, args, extras=True):
         del ws
 
     # what the memory system gives a plain streaming kernel with each call's read:write mix at its size
-    def probe_ms(read_bytes, write_bytes):
+    # (in the kernel's own shape: bytes of the larger side per wave, non-temporal loads and stores, 256 threads)
+    def probe_ms(read_bytes, write_bytes, slice_bytes):
         rb, wb = read_bytes // 16 * 16, write_bytes // 16 * 16
         srcs = [torch.empty(rb, dtype=torch.uint8, device=dev) for _ in range(R)]
         dsts = [torch.empty(max(wb, 16), dtype=torch.uint8, device=dev) for _ in range(R)]
-        return timed(lambda i: cgx.cgx_stream_probe(srcs[i % R], rb, dsts[i % R], wb))
+        return timed(lambda i: cgx.cgx_stream_probe_shaped(srcs[i % R], rb, dsts[i % R], wb, slice_bytes))
 
     probe = None
     if extras:
         probe = {
-            "quantize": probe_ms(w.n * S, alg["quantize"] - w.n * S),
-            "dequant_reduce": probe_ms(alg["dequant_reduce"] - 4 * m, 4 * m),
-            "requantize": probe_ms(4 * m, alg["requantize"] - 4 * m),
+            "quantize": probe_ms(w.n * S, alg["quantize"] - w.n * S, 4096),       # a chunk is 4 KB of input
+            "dequant_reduce": probe_ms(alg["dequant_reduce"] - 4 * m, 4 * m, 8192),  # a chunk is 8 KB of sums
+            "requantize": probe_ms(4 * m, alg["requantize"] - 4 * m, 4096),
         }
 
     kern_ms = {k: mean_ms(all_events, j) for j, k in enumerate(NAMES)}
