@@ -18,8 +18,12 @@ SOURCES = [("cgx_plan.cpp", "cgx_plan", []), ("cgx_api.cpp", "cgx_api", []), ("c
 
 # -ffp-contract=off: the code decision is binary32 without fused operations.
 # packed-fp32 instructions stay disabled for this target.
+# kernarg preload: the dispatcher puts the first 16 dwords of a kernel's arguments into scalar registers, so a
+# wave's first scalar load is its tile descriptor (0.5 us per launch of 20 us); firmware without the feature
+# runs the loads of the compiler's compatibility prologue instead.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unused-function"]
 
 

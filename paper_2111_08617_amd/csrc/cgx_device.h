@@ -49,6 +49,16 @@ __device__ __forceinline__ KernargPeers &first_kernel_argument()
     return *(KernargPeers *)__builtin_amdgcn_kernarg_segment_ptr();
 }
 
+// The table when the parameter starts byte_offset bytes into the kernarg segment.  (The kernels are built
+// with their first 16 dwords of arguments preloaded into scalar registers by the dispatcher, which
+// spares every wave one dependent scalar load ahead of its tile descriptor; the arguments a wave needs
+// first therefore come first and the 256-byte table last.)
+__device__ __forceinline__ KernargPeers &kernel_argument_peers(size_t byte_offset)
+{
+    return *(KernargPeers *)((const __attribute__((address_space(4))) char *)__builtin_amdgcn_kernarg_segment_ptr() +
+                             byte_offset);
+}
+
 #ifndef CGX_GROUPS
 #define CGX_GROUPS 4
 #endif

@@ -95,16 +95,25 @@ __device__ __forceinline__ void fused_tail(Peers &peers, int W, const Tile &tile
 // tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
 // output (binary32 pass-through layers); the two tables list the same tiles in the same order.
 // WIDE: the call's bucket is longer than a chunk (see quantize_kernel's MAP).
+struct FusedArguments {       // the kernarg segment's layout: offset of the peers' table behind the scalars
+    const Tile *tiles_in, *tiles_out;
+    int64_t n_tiles;
+    int W, dt;
+    uint32_t seed_lo, seed_hi;
+    uint8_t *packed_out;
+    float *meta_out;
+    PeerPtrs peers;
+};
+
 template <int SCHEME, bool WIDE, bool ODD>
-__global__ __launch_bounds__(kBlock) void fused_kernel(const PeerPtrs peers_argument, int W, int dt,
-                                                        const Tile *__restrict__ tiles_in,
-                                                        const Tile *__restrict__ tiles_out, int64_t n_tiles,
-                                                        uint32_t seed_lo, uint32_t seed_hi,
+__global__ __launch_bounds__(kBlock) void fused_kernel(const Tile *__restrict__ tiles_in,
+                                                        const Tile *__restrict__ tiles_out, int64_t n_tiles, int W,
+                                                        int dt, uint32_t seed_lo, uint32_t seed_hi,
                                                         uint8_t *__restrict__ packed_out,
-                                                        float *__restrict__ meta_out)
+                                                        float *__restrict__ meta_out, const PeerPtrs peers_argument)
 {
     (void)peers_argument;
-    KernargPeers &peers = first_kernel_argument();
+    KernargPeers &peers = kernel_argument_peers(offsetof(FusedArguments, peers));
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     int lane_of_wave = int(threadIdx.x) & 63;
@@ -159,17 +168,16 @@ hipError_t launch_dequant_reduce_requantize(int scheme, const PeerPtrs &peers, i
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
     const bool wide = mapping_of(bucket, kChunk) == kMapWide;
-    using Kernel = void (*)(const PeerPtrs, int, int, const Tile *, const Tile *, int64_t, uint32_t, uint32_t,
-                            uint8_t *, float *);
+    using Kernel = void (*)(const Tile *, const Tile *, int64_t, int, int, uint32_t, uint32_t, uint8_t *, float *,
+                            const PeerPtrs);
     static const Kernel table[2][2][2] = {
         {{fused_kernel<kMinMax, false, false>, fused_kernel<kMinMax, true, false>},
          {fused_kernel<kNormSign, false, false>, fused_kernel<kNormSign, true, false>}},
         {{fused_kernel<kMinMax, false, true>, fused_kernel<kMinMax, true, true>},
          {fused_kernel<kNormSign, false, true>, fused_kernel<kNormSign, true, true>}}};
     const Kernel kernel = table[odd_tiles][scheme == kSchemeNormSign][wide];
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, tiles_in, tiles_out, n_tiles,
-                       uint32_t(seed), uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out),
-                       static_cast<float *>(meta_out));
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, tiles_in, tiles_out, n_tiles, W, dt, uint32_t(seed),
+                       uint32_t(seed >> 32), static_cast<uint8_t *>(packed_out), static_cast<float *>(meta_out), peers);
     return hipGetLastError();
 }
 

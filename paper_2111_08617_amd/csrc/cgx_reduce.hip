@@ -11,14 +11,28 @@ namespace {
 // it outlasts a short one (6 % of a 25 us launch with a single short end).  The host asks for
 // it when there is a short end and the plan has fewer than 16384 tiles, or when short ends are
 // at least 1/512 of the tiles.
+// The arguments as the kernarg segment lays them out (each at its natural alignment, in order): gives the
+// offset of the peers' table behind the scalars.
+struct ReduceArguments {
+    const Tile *tiles;
+    int64_t n_tiles;
+    int W, dt;
+    const void *init;
+    void *out;
+    int init_dt, out_dt, keep;
+    PeerPtrs peers;
+};
+
 template <int SCHEME, bool TAILS>
-__global__ __launch_bounds__(kBlock) void reduce_kernel(const PeerPtrs peers_argument, int W, int dt, const SumIo io,
-                                                         const Tile *__restrict__ tiles, int64_t n_tiles)
+__global__ __launch_bounds__(kBlock) void reduce_kernel(const Tile *__restrict__ tiles, int64_t n_tiles, int W, int dt,
+                                                         const void *init, void *out, int init_dt, int out_dt,
+                                                         int keep, const PeerPtrs peers_argument)
 {
     // the vectorised tiles index the table with constants (it then sits in scalar registers);
     // the other kinds index it at run time and read it from the kernarg segment
     const PeerPtrs &peers = peers_argument;
-    KernargPeers &peers_in_memory = first_kernel_argument();
+    KernargPeers &peers_in_memory = kernel_argument_peers(offsetof(ReduceArguments, peers));
+    const SumIo io{init, init_dt, out, out_dt, keep};
     // per-wave staging area: a chunk of binary32 results, or the packed bytes of a block of peers
     __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
@@ -65,7 +79,8 @@ hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int d
                             ? (many_tails ? reduce_kernel<kNormSign, true> : reduce_kernel<kNormSign, false>)
                             : (many_tails ? reduce_kernel<kMinMax, true> : reduce_kernel<kMinMax, false>);
     (void)bucket;
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, peers, W, dt, io, tiles, n_tiles);
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, tiles, n_tiles, W, dt, io.init, io.out, io.init_dt, io.out_dt, io.keep,
+                       peers);
     return hipGetLastError();
 }
 
