@@ -22,7 +22,9 @@ extern "C" {
  * two fields are 0 where they do not apply) and kind 0 = generic
  * quantize, 1 = vectorised quantize, 2 = element-wise copy, 3 = vectorised copy,
  * 4 = vectorised quantize of one whole bucket of 4096 or 8192 elements, 5 = the short end
- * of a layer (less than a chunk of 2048 elements) with power-of-two buckets.
+ * of a layer (less than a chunk of 2048 elements) with power-of-two buckets, 6 = whole buckets
+ * of a size that is no power of two, at most a chunk in all (streamed row by row; only the ragged
+ * end of such a layer and sizes above the chunk take the generic kind 0).
  * Every element of every non-empty layer lies in exactly one tile and tiles never
  * cross layers (paper Sec. 4.1).  This is the table of one chunk per vectorised
  * tile that most calls walk: cgx_quantize on a binary16 gradient of 2^24 elements

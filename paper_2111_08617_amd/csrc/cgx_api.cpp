@@ -21,6 +21,7 @@ struct CachedPlan {
     int device = 0;
     int32_t bucket = 0;
     int dt = 0;
+    uint64_t digest = 0;        // hash of (off, bits, layer_buckets): compared before the arrays themselves
     int chunk = 0;              // elements per chunk of the kernels that walk this table
     int chunks_per_tile = 0;
     std::vector<int64_t> off;
@@ -101,6 +102,12 @@ const cgx::LaunchConfig &launch_config()
 //    (354 M elements: 155 -> 149 us; 4 chunks: 156 us);
 //  - the fused reduce + requantize, which is bound by arithmetic: 2 chunks (3-6 % faster at
 //    164-268 M elements for every width).
+// Bucket sizes of a call: one for all layers, or one per layer (per_layer != nullptr).
+struct Buckets {
+    int32_t uniform;
+    const int32_t *per_layer;
+};
+
 enum CallKind { kQuantizeCall, kFusedCall, kOtherCall };
 
 // Elements per chunk of the kernel a call runs.  The quantizer of binary32 input takes chunks of 1024
@@ -108,11 +115,15 @@ enum CallKind { kQuantizeCall, kFusedCall, kOtherCall };
 // per wave than with 8 KB, and the quantizer follows it: 0.74 -> 0.78 of the HBM peak on 1.3 G
 // elements); on binary16 a chunk of 2048 elements is 4 KB already.  The reduce, fused and statistics
 // kernels take 2048 (a peer's codes of a chunk then fill a whole load instruction at 4 bits).
-int chunk_length(CallKind call, int dt)
+// Bucket sizes between 1024 and 2048 take the quantizer of 2048-element chunks also on binary32 (one bucket per
+// chunk, vectorised or streamed; with chunks of 1024 such a bucket is a two-pass tile or a generic one).
+int chunk_length(CallKind call, int dt, const Buckets &buckets)
 {
     const int forced = launch_config().quantize_groups;
-    if (call == kQuantizeCall) return cgx::chunk_of(forced > 0 ? forced : dt == CGX_F32 ? 2 : 4);
-    return cgx::kDefaultChunk;
+    if (call != kQuantizeCall) return cgx::kDefaultChunk;
+    if (forced > 0) return cgx::chunk_of(forced);
+    const bool long_buckets = !buckets.per_layer && buckets.uniform > 1024 && buckets.uniform <= 2048;
+    return cgx::chunk_of(dt == CGX_F32 && !long_buckets ? 2 : 4);
 }
 
 int tile_length(CallKind call, int dt, int64_t n)
@@ -125,12 +136,6 @@ int tile_length(CallKind call, int dt, int64_t n)
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
-
-// Bucket sizes of a call: one for all layers, or one per layer (per_layer != nullptr).
-struct Buckets {
-    int32_t uniform;
-    const int32_t *per_layer;
-};
 
 // One launch per lane mapping in use (a launch runs one kernel instantiation; the bucket size
 // itself travels in the tile descriptors), named by the smallest bucket size of that mapping;
@@ -155,6 +160,26 @@ std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off,
     return out;
 }
 
+// A 64-bit digest of the plan's arrays, eight bytes at a time (multiply and xor-shift per word): a look-up
+// compares this one word per cached plan and the arrays themselves only on a match.
+uint64_t plan_digest(int32_t L, const int64_t *off, const uint8_t *bits, const int32_t *layer_buckets)
+{
+    uint64_t h = 0x9e3779b97f4a7c15ull ^ uint64_t(L);
+    const auto mix = [&h](const void *p, size_t bytes) {
+        const unsigned char *c = static_cast<const unsigned char *>(p);
+        for (size_t i = 0; i < bytes; i += 8) {
+            uint64_t w = 0;
+            std::memcpy(&w, c + i, bytes - i < 8 ? bytes - i : 8);
+            h = (h ^ w) * 0xff51afd7ed558ccdull;
+            h ^= h >> 32;
+        }
+    };
+    mix(off, sizeof(int64_t) * (size_t(L) + 1));
+    mix(bits, size_t(L));
+    if (layer_buckets) mix(layer_buckets, sizeof(int32_t) * size_t(L));
+    return h;
+}
+
 // Finds or builds the device-resident tile table of a (valid) plan for a call on `stream`.
 // A graph that is being captured keeps the raw table pointers of the launches recorded into it, so a table
 // found during a capture is pinned for the life of the library (never the one dropped for a new plan),
@@ -163,6 +188,7 @@ std::vector<Launch> launches_of(const Buckets &b, int32_t L, const int64_t *off,
 int get_plan(hipStream_t stream, int32_t L, const int64_t *off, const uint8_t *bits, int32_t bucket, int dt, int chunk,
              int chunks_per_tile, PlanRef *out, const int32_t *layer_buckets = nullptr, bool with_copies = true)
 {
+    const uint64_t digest = plan_digest(L, off, bits, layer_buckets);       // before the lock is taken
     std::lock_guard<std::mutex> lock(g_mutex);
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return CGX_ERR_HIP;
@@ -170,7 +196,7 @@ int get_plan(hipStream_t stream, int32_t L, const int64_t *off, const uint8_t *b
     const bool capturing = hipStreamIsCapturing(stream, &capture) == hipSuccess && capture == hipStreamCaptureStatusActive;
     if (!capturing) (void)hipGetLastError();       // a refused query (legacy stream beside a capture) is not this call's error
     for (const auto &p : g_plans) {
-        if (p->device == device && p->bucket == bucket && p->dt == dt &&
+        if (p->digest == digest && p->device == device && p->bucket == bucket && p->dt == dt &&
             p->chunk == chunk && p->chunks_per_tile == chunks_per_tile && p->bits.size() == size_t(L) &&
             p->with_copies == with_copies && p->layer_buckets.size() == (layer_buckets ? size_t(L) : 0) &&
             (!layer_buckets || L == 0 ||
@@ -188,6 +214,7 @@ int get_plan(hipStream_t stream, int32_t L, const int64_t *off, const uint8_t *b
         free_plan(*p);
         delete p;
     });
+    plan->digest = digest;
     plan->device = device;
     plan->bucket = bucket;
     plan->dt = dt;
@@ -229,7 +256,7 @@ int get_plan(hipStream_t stream, int32_t L, const int64_t *off, const uint8_t *b
         plan->plan_tiles = common[size_t(L)];
     }
     for (const Tile &t : tiles)
-        if ((cgx::is_vector_kind(cgx::tile_kind(t)) || cgx::tile_kind(t) == cgx::kQuantTail) && (t.elem0 & 1))
+        if ((cgx::is_streamed_kind(cgx::tile_kind(t)) || cgx::tile_kind(t) == cgx::kQuantTail) && (t.elem0 & 1))
             plan->odd_tiles = true;
     for (const Tile &t : tiles)
         if (cgx::is_vector_kind(cgx::tile_kind(t)) && (t.elem0 * (dt == CGX_F16 ? 2 : 4)) % 16 != 0)
@@ -299,7 +326,7 @@ int quantize_impl(int scheme, const void *grad, int64_t n, int32_t L, const int6
     const cgx::PlanShape shape = cgx::plan_shape(L, off, bits, buckets.uniform, dt, buckets.per_layer);
     if (!grad || !packed || (shape.meta_bytes && !meta)) return CGX_ERR_NULL;
     if (misaligned(grad) || misaligned(packed) || misaligned(meta)) return CGX_ERR_ALIGN;
-    const int chunk = chunk_length(kQuantizeCall, dt);
+    const int chunk = chunk_length(kQuantizeCall, dt, buckets);
     const auto launch_quantize = chunk == cgx::chunk_of(2) ? cgx::launch_quantize_g2 : cgx::launch_quantize_g4;
     const std::vector<Launch> launches = launches_of(buckets, L, off, bits, chunk);
     std::vector<PlanRef> plans;

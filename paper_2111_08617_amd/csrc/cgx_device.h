@@ -477,6 +477,31 @@ struct TailShape {
     __device__ __forceinline__ int valid(int e) const { return count - e >= 8 ? 8 : count - e > 0 ? count - e : 0; }
 };
 
+// A tile of whole buckets of a size that is no power of two (kQuantAny): held row by row, group Gi = 64 r +
+// lane of the tile's count / 8 groups of 8 elements is group r of lane `lane`; a bucket is bucket / 8
+// consecutive groups.
+struct AnyShape {
+    int groups;      // groups of 8 elements in the tile
+    int gb;          // groups per bucket
+    int m;           // buckets in the tile (at most 21: the smallest such bucket is 96)
+    uint32_t inv;    // ceil(2^16 / gb): (Gi * inv) >> 16 == Gi / gb for Gi < 256 and gb <= 256 (checked exhaustively)
+    __device__ __forceinline__ AnyShape(const Tile &tile, int bucket)
+    {
+        groups = int(tile.count >> 3);
+        gb = bucket >> 3;
+        m = int(tile.count) / bucket;
+        inv = (65536u + uint32_t(gb) - 1u) / uint32_t(gb);
+    }
+    __device__ __forceinline__ int bucket_of(int Gi) const { return int((uint32_t(Gi) * inv) >> 16); }
+};
+
+// One dword per lane from global memory straight into LDS: lane l's dword lands at lds_base + 4 * l.
+__device__ __forceinline__ void load_to_lds4(const uint32_t *gptr, uint32_t *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
+                                     (__attribute__((address_space(3))) void *)lds_base, 4, 0, 2 /* nt */);
+}
+
 // Runs CALL with BITS = bits as a constant (kNormSign has no 1-bit codes: the entry points
 // reject such plans, and nothing is instantiated for them).
 #define CGX_FOR_BITS(bits, CALL)                      \

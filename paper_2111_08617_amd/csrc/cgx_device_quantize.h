@@ -326,6 +326,100 @@ __device__ __forceinline__ void quantize_tail(const void *__restrict__ grad, uin
                                           meta + kMetaFloats<SCHEME> * tile.bucket0, packed + tile.packed_off, stage);
 }
 
+// LDS a wave needs for a tile of kind kQuantAny: its codes, a minimum and a maximum per group, a scale per bucket.
+constexpr int kAnyStageBytes = kChunk + 2 * (kChunk / 8) * 4 + kWave * 8;
+
+// x holds the tile row by row (zeros where there is no group) -> meta of its buckets and its packed codes.
+// The scale of a bucket comes from a per-group minimum / maximum parked in LDS: the lanes are split into
+// groups of P (a power of two, 64 / P >= buckets), each of which folds the entries of one bucket.
+template <int SCHEME, int BITS, bool ODD>
+__device__ __forceinline__ void quantize_any_regs(const float (&x)[G][8], const AnyShape &shape, const Tile &tile,
+                                                  uint32_t key, float *__restrict__ meta, uint8_t *__restrict__ out,
+                                                  uint4v *stage, int lane)
+{
+    constexpr uint32_t kLevels = top_level<SCHEME>(BITS);
+    uint8_t *codes = reinterpret_cast<uint8_t *>(stage);
+    float *gmn = reinterpret_cast<float *>(codes + kChunk), *gmx = gmn + kChunk / 8;
+    float2 *scales = reinterpret_cast<float2 *>(gmx + kChunk / 8);
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int Gi = r * kWave + lane;
+        float mn = SCHEME == kNormSign ? 0.0f : x[r][0], mx = SCHEME == kNormSign ? 0.0f : x[r][0];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            if (SCHEME == kNormSign) {
+                mx = __builtin_fmaxf(mx, __builtin_fabsf(x[r][j]));
+            } else {
+                mn = __builtin_fminf(mn, x[r][j]);
+                mx = __builtin_fmaxf(mx, x[r][j]);
+            }
+        }
+        if (Gi < shape.groups) {
+            gmn[Gi] = mn;
+            gmx[Gi] = mx;
+        }
+    }
+    wave_lds_fence();
+    const int lgP = 31 - __builtin_clz(uint32_t(kWave / shape.m));      // floor(log2(64 / buckets))
+    const int bucket_of_lane = lane >> lgP, part = lane & ((1 << lgP) - 1);
+    float mn = SCHEME == kNormSign ? 0.0f : __builtin_inff(), mx = SCHEME == kNormSign ? 0.0f : -__builtin_inff();
+    if (bucket_of_lane < shape.m) {
+        for (int g = part; g < shape.gb; g += 1 << lgP) {
+            if (SCHEME != kNormSign) mn = __builtin_fminf(mn, gmn[bucket_of_lane * shape.gb + g]);
+            mx = __builtin_fmaxf(mx, gmx[bucket_of_lane * shape.gb + g]);
+        }
+    }
+    if (SCHEME == kNormSign)
+        group_max(mx, lgP, lane);
+    else
+        group_minmax(mn, mx, lgP, lane);
+    if (bucket_of_lane < shape.m && part == 0) {
+        const Scale s = bucket_scale(mn, mx, int(kLevels));
+        store_meta<SCHEME>(meta, uint32_t(bucket_of_lane), s);
+        scales[bucket_of_lane] = make_float2(s.mn, s.inv16);
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int Gi = r * kWave + lane;
+        if (Gi < shape.groups) {
+            const float2 sc = scales[shape.bucket_of(Gi)];
+            const Scale s{0.0f, sc.x, sc.y};
+            const uint32_t pair0 = uint32_t(uint64_t(tile.elem0 + int64_t(Gi) * 8) >> 1);
+            stage_codes<BITS>(codes + Gi * BITS, encode_group<SCHEME, BITS, ODD>(x[r], s, pair0, key, uint32_t(tile.elem0) & 1u));
+        }
+    }
+    wave_lds_fence();
+    // the tile's codes are groups * BITS bytes, a multiple of 4, at a multiple of 4 in the stream
+    const int dwords = shape.groups * BITS / 4;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(out);
+    for (int v = lane; v < dwords; v += kWave) stream_store(dst + v, reinterpret_cast<const uint32_t *>(codes)[v]);
+    if (uint32_t(lane) < tile.pad) out[shape.groups * BITS + lane] = 0;        // the layer's zero padding
+    wave_lds_fence();
+}
+
+template <int SCHEME, int DT, int BITS, bool ODD>
+__device__ __forceinline__ void quantize_any(const void *__restrict__ grad, uint8_t *__restrict__ packed,
+                                             float *__restrict__ meta, const Tile &tile, int bucket,
+                                             uint32_t seed_lo, uint32_t seed_hi, int lane, uint4v *stage)
+{
+    const AnyShape shape(tile, bucket);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    float x[G][8];
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int Gi = r * kWave + lane;
+        if (Gi < shape.groups) {
+            load8<DT>(grad, tile.elem0 + int64_t(Gi) * 8, x[r]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++) x[r][j] = 0.0f;
+        }
+    }
+    quantize_any_regs<SCHEME, BITS, ODD>(x, shape, tile, key, meta + kMetaFloats<SCHEME> * tile.bucket0,
+                                         packed + tile.packed_off, stage, lane);
+}
+
 // Any bucket size, any alignment, ragged last bucket: one bucket at a time, two passes.
 // value(j) gives element j of the tile (called twice per element).  With BATCH the values
 // of a pass are fetched 8 at a time so that plain loads overlap; without it (value() is

@@ -295,6 +295,105 @@ __device__ __forceinline__ void reduce_tail(Peers &peers, int W, const SumIo &io
     wave_lds_fence();
 }
 
+// Sums of a tile of whole buckets of a size that is no power of two (kQuantAny), row by row: acc[r] belongs to
+// group Gi = 64 r + lane (valid for Gi < shape.groups).  Two peers at a time: their codes (a multiple of 4
+// bytes at a multiple of 4 in the stream) and the meta of the tile's buckets go straight into LDS, one dword
+// per lane and instruction.
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_any_regs(Peers &peers, int W, const Tile &tile, const AnyShape &shape,
+                                                float (&acc)[G][8], uint4v *stage, int lane)
+{
+    constexpr int kPeerBytes = kChunk * BITS / 8 + 16 + kWave * 8;      // codes (+ over-read), unit[64], offset[64]
+    static_assert(2 * kPeerBytes <= kChunk * 4, "staging area too small");
+    constexpr int kMetaAt = kChunk * BITS / 8 + 16;
+    const int dwords = shape.groups * BITS / 4;
+    uint8_t *area = reinterpret_cast<uint8_t *>(stage);
+    for_peer_blocks<2>(W, [&](int w0, auto wb) {
+        constexpr int WB = decltype(wb)::value;
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            const uint32_t *in = reinterpret_cast<const uint32_t *>(peers.packed[w0 + i] + tile.packed_off);
+            uint32_t *codes = reinterpret_cast<uint32_t *>(area + i * kPeerBytes);
+            for (int v0 = 0; v0 < dwords; v0 += kWave)
+                if (v0 + lane < dwords) load_to_lds4(in + v0 + lane, codes + v0);
+            // meta of bucket j of the tile: lane j fetches it (kMinMax: unit and minimum, two dwords)
+            const uint32_t *m = reinterpret_cast<const uint32_t *>(peers.meta[w0 + i]) + size_t(kMetaFloats<SCHEME>) * tile.bucket0;
+            uint32_t *unit = reinterpret_cast<uint32_t *>(area + i * kPeerBytes + kMetaAt);
+            if (lane < shape.m) {
+                load_to_lds4(m + kMetaFloats<SCHEME> * lane, unit);
+                if (SCHEME != kNormSign) load_to_lds4(m + kMetaFloats<SCHEME> * lane + 1, unit + kWave);
+            }
+        }
+        wait_vector_memory();
+        wave_lds_fence();
+#pragma unroll
+        for (int i = 0; i < WB; i++) {
+            const uint8_t *codes = area + i * kPeerBytes;
+            const float *unit = reinterpret_cast<const float *>(area + i * kPeerBytes + kMetaAt);
+#pragma unroll
+            for (int r = 0; r < G; r++) {
+                const int Gi = r * kWave + lane;
+                if (Gi < shape.groups) {
+                    const int j = shape.bucket_of(Gi);
+                    const float2 m = make_float2(unit[j], SCHEME == kNormSign ? 0.0f : unit[kWave + j]);
+                    float f[8];
+                    codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes, Gi * BITS), f);
+#pragma unroll
+                    for (int k = 0; k < 8; k++) acc[r][k] = __fadd_rn(acc[r][k], decode<SCHEME>(f[k], m));
+                }
+            }
+        }
+        wave_lds_fence();
+    });
+}
+
+template <int SCHEME, int BITS, typename Peers>
+__device__ __forceinline__ void reduce_any(Peers &peers, int W, const SumIo &io, const Tile &tile, int bucket,
+                                           int lane, uint4v *stage)
+{
+    const AnyShape shape(tile, bucket);
+    float acc[G][8];
+#pragma unroll
+    for (int r = 0; r < G; r++) {
+        const int Gi = r * kWave + lane;
+        if (Gi < shape.groups) {
+            init8(io, tile.elem0 + int64_t(Gi) * 8, acc[r]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc[r][k] = -0.0f;
+        }
+    }
+    reduce_any_regs<SCHEME, BITS>(peers, W, tile, shape, acc, stage, lane);
+    // the sums leave through LDS as whole vectors: count is a multiple of 32 elements
+    if (io.out_dt == CGX_F16) {
+#pragma unroll
+        for (int r = 0; r < G; r++) {
+            const int Gi = r * kWave + lane;
+            half8v h;
+#pragma unroll
+            for (int k = 0; k < 8; k++) h[k] = _Float16(acc[r][k]);
+            if (Gi < shape.groups) reinterpret_cast<half8v *>(stage)[Gi] = h;
+        }
+        wave_lds_fence();
+        flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<_Float16 *>(io.out) + tile.elem0),
+                                shape.groups, lane, io.keep != 0);
+    } else {
+#pragma unroll
+        for (int r = 0; r < G; r++) {
+            const int Gi = r * kWave + lane;
+            if (Gi < shape.groups) {
+                float4v *p = reinterpret_cast<float4v *>(stage) + 2 * Gi;
+                p[0] = float4v{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+                p[1] = float4v{acc[r][4], acc[r][5], acc[r][6], acc[r][7]};
+            }
+        }
+        wave_lds_fence();
+        flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<float *>(io.out) + tile.elem0),
+                                2 * shape.groups, lane, io.keep != 0);
+    }
+    wave_lds_fence();
+}
+
 // Ordered sum over the peers of element j of a generic quantized tile (start = the value
 // the sum starts from).
 template <int SCHEME, typename Peers>

@@ -92,6 +92,24 @@ __device__ __forceinline__ void fused_tail(Peers &peers, int W, const Tile &tile
                                           meta_out + kMetaFloats<SCHEME> * tile.bucket0, packed_out + out_off, stage);
 }
 
+// Whole buckets of a size that is no power of two: the row-by-row sums feed the row-by-row quantizer.
+template <int SCHEME, int BITS, bool ODD, typename Peers>
+__device__ __forceinline__ void fused_any(Peers &peers, int W, const Tile &tile, int64_t out_off, uint32_t out_pad,
+                                          int bucket, uint32_t seed_lo, uint32_t seed_hi,
+                                          uint8_t *__restrict__ packed_out, float *__restrict__ meta_out, int lane,
+                                          uint4v *stage)
+{
+    const AnyShape shape(tile, bucket);
+    const uint32_t key = rng_key(seed_lo, seed_hi, uint32_t((uint64_t(tile.elem0) >> 1) >> 32));
+    float acc[G][8];
+    clear_sums(acc);
+    reduce_any_regs<SCHEME, BITS>(peers, W, tile, shape, acc, stage, lane);
+    Tile out = tile;                                 // the same elements and buckets at their place in the output stream
+    out.pad = out_pad;
+    quantize_any_regs<SCHEME, BITS, ODD>(acc, shape, out, key, meta_out + kMetaFloats<SCHEME> * tile.bucket0,
+                                         packed_out + out_off, stage, lane);
+}
+
 // tiles_in follows the layout of the chunks (storage type dt), tiles_out that of the
 // output (binary32 pass-through layers); the two tables list the same tiles in the same order.
 // WIDE: the call's bucket is longer than a chunk (see quantize_kernel's MAP).
@@ -141,7 +159,12 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(const Tile *__restrict__ 
         } else if (kind == kQuantTail) {
             CGX_FOR_BITS(tile_bits(tile), (fused_tail<SCHEME, BITS, ODD>(peers, W, tile, out_off, bucket, seed_lo,
                                                                          seed_hi, packed_out, meta_out, lane, stage)))
-        } else if (kind == kQuantSlow) {
+        } else if (!WIDE && kind == kQuantAny) {
+            if constexpr (!WIDE) {
+                CGX_FOR_BITS(tile_bits(tile), (fused_any<SCHEME, BITS, ODD>(peers, W, tile, out_off, out_pad, bucket, seed_lo,
+                                                                            seed_hi, packed_out, meta_out, lane, stage)))
+            }
+        } else if (kind == kQuantSlow || kind == kQuantAny) {
             quantize_generic<SCHEME, false>(
                 [&](uint32_t j) { return generic_sum<SCHEME>(peers, W, tile, bucket, j, -0.0f); },
                 packed_out + out_off, meta_out, tile, out_pad, bucket, seed_lo, seed_hi, lane);

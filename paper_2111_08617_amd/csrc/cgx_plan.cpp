@@ -159,7 +159,12 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
                 // the short end of a layer with power-of-two buckets runs through the chunk code, masked
                 const bool tail = fast_bucket && j % kChunk == 0 && t.count < uint32_t(kChunk) &&
                                   same_key_block(t.elem0, t.count);
-                t.info = uint32_t(b) | uint32_t(tail ? kQuantTail : kQuantSlow) << 4 | (tail ? lpb_log2 << 8 : 0u) | size_bits;
+                // whole buckets of a size that is no power of two, a chunk or less in all: the streamed path
+                // for any bucket size (the ragged end of a layer stays on the generic one)
+                const bool any = !tail && !is_pow2(own_bucket) && own_bucket <= kChunk && t.count % uint32_t(own_bucket) == 0 &&
+                                 t.count <= uint32_t(kChunk) && same_key_block(t.elem0, t.count);
+                t.info = uint32_t(b) | uint32_t(tail ? kQuantTail : any ? kQuantAny : kQuantSlow) << 4 |
+                         (tail ? lpb_log2 << 8 : 0u) | size_bits;
                 tiles.push_back(t);
             }
         }
@@ -174,7 +179,7 @@ void build_tiles(int32_t L, const int64_t *off, const uint8_t *bits, int32_t buc
     std::vector<uint32_t> order(tiles.size());
     for (size_t i = 0; i < order.size(); i++) order[i] = uint32_t(i);
     std::stable_partition(order.begin(), order.end(),
-                          [&](uint32_t i) { return !is_vector_kind(tile_kind(tiles[i])); });
+                          [&](uint32_t i) { return !is_streamed_kind(tile_kind(tiles[i])); });
     std::vector<Tile> sorted(tiles.size());
     for (size_t i = 0; i < order.size(); i++) sorted[i] = tiles[order[i]];
     tiles.swap(sorted);

@@ -34,11 +34,14 @@ enum TileKind : uint32_t {
     kQuantFast = 1,  // power-of-two bucket <= chunk, whole chunks
     kCopyFast = 3,   // pass-through, 16-byte vectors
     kQuantWide = 4,  // one whole power-of-two bucket longer than a chunk (4096, 8192)
-    kQuantTail = 5   // power-of-two bucket <= chunk, the last tile of a layer, shorter than a chunk
+    kQuantTail = 5,  // power-of-two bucket <= chunk, the last tile of a layer, shorter than a chunk
+    kQuantAny = 6    // whole buckets of a size that is no power of two (a multiple of 32, at most a chunk in all)
 };
 
-// Vectorised quantized tiles (everything else costs several dependent memory round trips).
+// Chunk-shaped quantized tiles (whole chunks of the bucket-major or row-by-row mapping).
 CGX_HOST_DEVICE inline bool is_vector_kind(uint32_t kind) { return kind == kQuantFast || kind == kQuantWide; }
+// Tiles that stream (everything else costs several dependent memory round trips and goes first in the table).
+CGX_HOST_DEVICE inline bool is_streamed_kind(uint32_t kind) { return is_vector_kind(kind) || kind == kQuantAny; }
 
 struct Tile {               // 32 bytes, read by the kernels with scalar loads
     int64_t elem0;          // first element, index in the fused buffer

@@ -16,7 +16,8 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
 {
     // per-wave staging area for a chunk's packed codes (at most kChunk bytes, at 8 bits), and with
     // VIA_LDS for the chunk as stored
-    constexpr int kStageBytes = VIA_LDS ? kChunk * (DT == CGX_F16 ? 2 : 4) : kChunk;
+    constexpr int kInputBytes = VIA_LDS ? kChunk * (DT == CGX_F16 ? 2 : 4) : kChunk;
+    constexpr int kStageBytes = (MAP == kMapBuckets && kAnyStageBytes > kInputBytes) ? kAnyStageBytes : kInputBytes;
     __shared__ uint4v stage_all[kWavesPerBlock][kStageBytes / 16];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     int lane_of_wave = int(threadIdx.x) & 63;
@@ -45,7 +46,12 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
         } else if (kind == kQuantTail) {
             CGX_FOR_BITS(tile_bits(tile), (quantize_tail<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
                                                                                   seed_lo, seed_hi, lane, stage)))
-        } else if (kind == kQuantSlow) {
+        } else if (MAP == kMapBuckets && kind == kQuantAny) {
+            if constexpr (MAP == kMapBuckets) {
+                CGX_FOR_BITS(tile_bits(tile), (quantize_any<SCHEME, DT, BITS, ODD>(grad, packed, meta, tile, bucket,
+                                                                                     seed_lo, seed_hi, lane, stage)))
+            }
+        } else if (kind == kQuantSlow || kind == kQuantAny) {
             quantize_generic<SCHEME, true>([&](uint32_t j) { return load_elem<DT>(grad, tile.elem0 + j); },
                                            packed + tile.packed_off, meta, tile, tile.pad, bucket, seed_lo,
                                            seed_hi, lane);

@@ -55,6 +55,8 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const Tile *__restrict__
                 CGX_FOR_BITS(tile_bits(tile),
                              (reduce_tail<SCHEME, BITS>(peers_in_memory, W, io, tile, bucket, lane, stage)))
             }
+        } else if (kind == kQuantAny) {
+            CGX_FOR_BITS(tile_bits(tile), (reduce_any<SCHEME, BITS>(peers_in_memory, W, io, tile, bucket, lane, stage)))
         } else if (kind == kQuantSlow || kind == kQuantTail) {
             reduce_slow<SCHEME>(peers_in_memory, W, io, tile, bucket, lane);
         } else if (dt == CGX_F16) {

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_ar
         double s = 0.0;                              // pass-through tiles: no error
         if (is_vector_kind(kind)) {
             CGX_FOR_BITS(tile_bits(tile), (s = sqerror_fast<SCHEME, DT, BITS>(grad, chunk, tile, bucket, lane, stage)))
-        } else if (kind == kQuantSlow || kind == kQuantTail) {
+        } else if (kind == kQuantSlow || kind == kQuantTail || kind == kQuantAny) {
             for (uint32_t j = lane; j < tile.count; j += kWave) {
                 const double d = double(load_elem<DT>(grad, tile.elem0 + j)) -
                                  double(generic_sum<SCHEME>(chunk, 1, tile, bucket, j, -0.0f));

@@ -132,6 +132,42 @@ def test_vectorised_path_all_bit_widths(torch, oracle, bucket, dt):
     full_cycle(torch, oracle, w, W=4, what=f"chunks B={bucket}")
 
 
+@pytest.mark.parametrize("dt", [wl.F32, wl.F16], ids=["f32", "f16"])
+@pytest.mark.parametrize("bucket", [96, 160, 224, 672, 992, 1056, 2016, 2080])
+def test_bucket_sizes_that_are_no_power_of_two(torch, oracle, bucket, dt):
+    """Multiples of 32 that are no power of two: whole buckets stream row by row (tile kind 6), only the ragged
+    end of a layer and sizes above the chunk stay on the generic path; every bit width, layers of whole
+    buckets, ragged layers, layers that start on odd elements, pass-through layers in between; then the same
+    chunks through cgx_dequantize (binary16 out) and the reduce with a local addend."""
+    sizes = [bucket * 21, bucket * 3 + 40, 8, bucket, bucket * 40 + 1000, bucket * 7 + 1, 500, bucket * 2 + bucket // 2,
+             bucket * 64, bucket * 5]
+    bits = [1, 2, 0, 3, 4, 5, 0, 6, 7, 8]
+    w = wl.Workload("anysize", [(s,) for s in sizes], np.array(bits, np.uint8), bucket, dt, 5, 3000 + bucket,
+                    wl._normal, np.linspace(0.01, 2.0, len(sizes)))
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    for chunk in (1024, 2048):
+        kinds = (cgx.cgx_plan_tiles(plan, chunk)["info"] >> 4) & 15
+        if bucket <= chunk:
+            assert (kinds == 6).sum() >= 8 and (kinds == 0).sum() <= 5       # generic: the ragged ends only
+        else:
+            assert not (kinds == 6).any()
+    full_cycle(torch, oracle, w, W=5, what=f"any-size B={bucket}")
+    chunks = [oracle.quantize(w.gradient(p), w.offsets, w.bits, bucket, w.quant_seed(p), dt) for p in range(3)]
+    dp = [dev(torch, c[0]) for c in chunks]
+    dm = [dev(torch, c[1].reshape(-1)) for c in chunks]
+    out16 = torch.zeros(w.n, dtype=torch.float16, device="cuda")
+    cgx.cgx_dequantize(dp[0], dm[0], plan, wl.F16, out16)
+    local = dev(torch, w.gradient(7))
+    total = torch.zeros(w.n, device="cuda")
+    cgx.cgx_dequant_reduce_add(local, dt, dp, dm, plan, total)
+    torch.cuda.synchronize()
+    one = oracle.dequant_reduce([chunks[0][0]], [chunks[0][1]], w.offsets, w.bits, bucket, dt)["sum32"]
+    assert np.array_equal(out16.cpu().numpy().view(np.uint16), oracle.float_to_half(one))
+    ref = oracle.dequant_reduce([c[0] for c in chunks], [c[1] for c in chunks], w.offsets, w.bits, bucket, dt,
+                                local=w.gradient(7))
+    assert np.array_equal(total.cpu().numpy().view(np.uint32), ref["sum32"].view(np.uint32))
+
+
 def test_single_tensor_config(torch, oracle):
     """2^20 elements ~ N(0, 0.01^2), 4 bit, bucket 128, seed 0, reduce over W = 2."""
     w = wl.single_tensor(seed=0)

@@ -235,7 +235,7 @@ def test_tiles_cover_every_layer_exactly_once(lib, make, CHUNK):
     segs = layer_segments(w)
     es = 2 if w.dt else 4
     # generic and pass-through tiles first, then the vectorised ones; buffer order within each class
-    vectorised = np.isin((tiles["info"] >> 4) & 15, (1, 4))
+    vectorised = np.isin((tiles["info"] >> 4) & 15, (1, 4, 6))
     assert not vectorised[:int((~vectorised).sum())].any()
     for cls in (tiles[~vectorised], tiles[vectorised]):
         assert (np.diff(cls["elem0"]) > 0).all()
@@ -260,7 +260,7 @@ def test_tiles_cover_every_layer_exactly_once(lib, make, CHUNK):
             assert kind == 3                                          # every copy tile is vectorised
             assert t["packed_off"] == seg + j * es
         else:
-            assert kind in (0, 1, 4, 5)
+            assert kind in (0, 1, 4, 5, 6)
             assert j % w.bucket == 0                                  # tiles start on a bucket
             assert last or t["count"] % w.bucket == 0                 # and hold whole buckets
             assert t["packed_off"] == seg + j * b // 8
@@ -275,6 +275,11 @@ def test_tiles_cover_every_layer_exactly_once(lib, make, CHUNK):
                 assert (int(t["info"]) >> 8) & 15 == int(np.log2(w.bucket * 64 // CHUNK))
             if kind == 0:                                             # generic: only where nothing else fits
                 assert w.bucket & (w.bucket - 1) != 0 or w.bucket > CHUNK
+                if w.bucket & (w.bucket - 1) != 0 and w.bucket <= CHUNK:
+                    assert last and t["count"] % w.bucket != 0       # only the ragged end of a layer
+            if kind == 6:                                             # whole buckets of a size that is no power of two
+                assert w.bucket & (w.bucket - 1) != 0 and w.bucket <= CHUNK
+                assert t["count"] % w.bucket == 0 and t["count"] <= CHUNK and t["count"] % 32 == 0
             if kind == 4:                                             # one whole bucket of several chunks
                 assert t["count"] == w.bucket and w.bucket in (4096, 8192) + ((2048,) if CHUNK == 1024 else ())
                 assert (int(t["info"]) >> 8) & 15 == 6
