@@ -516,6 +516,36 @@ CEILING_CASES = [
 ]
 
 
+def issue_rates(args):
+    """Cost of each vector instruction form in cycles of a SIMD at the nominal clock: every SIMD of the chip
+    holds 8 waves that each execute 16 * iterations instructions of the form in independent chains."""
+    import torch
+
+    from paper_2111_08617_amd import binding as cgx
+
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    cus, clock_ghz, iterations, blocks = 256, 2.4, 2000, 256 * 8
+    out = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+    rows = []
+    for form, text in enumerate(cgx.cgx_issue_probe_forms()):
+        cgx.cgx_issue_probe(form, blocks, 10, out)
+        times = []
+        for _ in range(max(3, args.steps // 4)):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            cgx.cgx_issue_probe(form, blocks, iterations, out)
+            b.record(stream)
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b))
+        ms = min(times)
+        per_simd = blocks * 4 * 16 * iterations / (cus * 4)
+        rows.append({"form": text, "ms": round(ms, 4), "cycles_per_instruction": round(ms * 1e-3 * clock_ghz * 1e9 / per_simd, 2),
+                     "T_lane_ops_per_s": round(blocks * 4 * 16 * iterations * 64 / ms / 1e9, 2)})
+    print(json.dumps({"mode": "issue_rates", "compute_units": cus, "clock_GHz": clock_ghz, "waves_per_simd": 8,
+                      "instructions_per_wave": 16 * iterations, "forms": rows}))
+
+
 def ceilings(args):
     """What a kernel that only moves bytes sustains, by launch shape and cache policy: a staged sweep of
     cgx_stream_probe_shaped per (size, read:write mix).  Stage 1: every load x store policy at the kernels' own
@@ -623,6 +653,9 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the step: sweep the arithmetic-free streaming probe over launch shapes and cache "
                          "policies at the sizes and read:write mixes of the calls (what the memory system allows)")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="instead of the benchmark: what each vector instruction form of the kernels' inner loops costs "
+                         "a SIMD (cgx_issue_probe), one JSON line")
     ap.add_argument("--ceilings-case", default="", help="with --ceilings: only the cases whose name contains this")
     ap.add_argument("--ceilings-all", action="store_true", help="with --ceilings: list every configuration tried")
     args = ap.parse_args()
@@ -636,6 +669,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     cgx.lib()
+    if args.issue_rates:
+        issue_rates(args)
+        return
     if args.ceilings:
         ceilings(args)
         return

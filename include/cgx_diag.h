@@ -95,6 +95,21 @@ int cgx_stream_probe_shaped(const void *src, size_t read_bytes, void *dst, size_
                             const cgx_probe_shape *shape /* host */, void *stream);
 
 /*
+ * What one vector instruction form costs: a launch of `blocks` blocks of 256 threads (1 to 65536) in
+ * which every wavefront executes 16 * iterations instructions of form number `form` (1 to 2^20
+ * iterations, 16 independent dependency chains per lane, nothing else in the loop).  With 8 resident
+ * waves per SIMD (blocks = 8 * compute units), launch time * clock / (blocks * 4 * 16 * iterations /
+ * (compute units * 4)) is the form's cost in cycles of a SIMD.  The forms are those of the kernels'
+ * inner loops and the alternatives weighed against them; cgx_issue_probe_form returns the text of a
+ * form, NULL past the last one.  out (device, 16-byte aligned, out_bytes >= blocks * 1024) receives
+ * one word per thread; its content is unspecified.  CGX_ERR_SIZE for a value outside these ranges.
+ * The benchmark's --issue-rates mode prints the table; it is the evidence for pricing the fused
+ * kernel, which is bound by the vector ALUs, and for the choice of its decoding instructions.
+ */
+const char *cgx_issue_probe_form(int32_t form);
+int cgx_issue_probe(int32_t form, int32_t blocks, int32_t iterations, void *out, size_t out_bytes, void *stream);
+
+/*
  * Launch-shape overrides, for the tests and for measurements.  The library reads these
  * environment variables once, at its first call; none of them changes a byte of any result (the
  * parity tests run the same inputs under several settings and compare digests):

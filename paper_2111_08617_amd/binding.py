@@ -30,7 +30,7 @@ EXPORTS = ("cgx_sizes", "cgx_quantize", "cgx_dequant_reduce", "cgx_dequant_reduc
            "cgx_layered_stats_workspace", "cgx_layered_layer_sqerrors", "cgx_qsgd_layered_sizes",
            "cgx_qsgd_layered_quantize", "cgx_qsgd_layered_dequant_reduce", "cgx_qsgd_layered_dequant_reduce_requantize",
            "cgx_plan_tiles", "cgx_plan_tiles_chunk", "cgx_stream_probe", "cgx_stream_probe_shaped",
-           "cgx_status_string", "cgx_shutdown")
+           "cgx_issue_probe", "cgx_issue_probe_form", "cgx_status_string", "cgx_shutdown")
 
 TILE_DTYPE = np.dtype([("elem0", "<i8"), ("packed_off", "<i8"), ("bucket0", "<u4"), ("count", "<u4"),
                        ("info", "<u4"), ("pad", "<u4")])
@@ -105,11 +105,14 @@ def lib() -> ctypes.CDLL:
         L.cgx_stream_probe_shaped.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
         L.cgx_plan_tiles.argtypes = plan + [c.c_int, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
         L.cgx_plan_tiles_chunk.argtypes = plan + [c.c_int, c.c_int32, c.c_void_p, c.c_int64, c.POINTER(c.c_int64)]
+        L.cgx_issue_probe.argtypes = [c.c_int32, c.c_int32, c.c_int32, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.cgx_issue_probe_form.restype = c.c_char_p
+        L.cgx_issue_probe_form.argtypes = [c.c_int32]
         L.cgx_status_string.restype = c.c_char_p
         L.cgx_status_string.argtypes = [c.c_int]
         L.cgx_shutdown.argtypes = []
         for name in EXPORTS:
-            if name != "cgx_status_string":
+            if name not in ("cgx_status_string", "cgx_issue_probe_form"):
                 getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -529,6 +532,23 @@ def cgx_stream_probe_shaped(src, read_bytes: int, dst, write_bytes: int, slice_b
     _check(lib().cgx_stream_probe_shaped(_device_buffer(src, "cgx_stream_probe_shaped: src", read_bytes), read_bytes,
                                          _device_buffer(dst, "cgx_stream_probe_shaped: dst", write_bytes),
                                          write_bytes, shape, _stream(stream)), "cgx_stream_probe_shaped")
+
+
+def cgx_issue_probe_forms() -> list:
+    """The instruction forms cgx_issue_probe knows, in order (see cgx_diag.h)."""
+    forms = []
+    while True:
+        text = lib().cgx_issue_probe_form(len(forms))
+        if text is None:
+            return forms
+        forms.append(text.decode())
+
+
+def cgx_issue_probe(form: int, blocks: int, iterations: int, out, stream=None) -> None:
+    """One launch of the issue-rate probe; out: device buffer of at least blocks * 1024 bytes."""
+    nbytes = out.numel() * out.element_size()
+    _check(lib().cgx_issue_probe(form, blocks, iterations, _device_buffer(out, "cgx_issue_probe: out", blocks * 1024),
+                                 nbytes, _stream(stream)), "cgx_issue_probe")
 
 
 def cgx_shutdown() -> None:

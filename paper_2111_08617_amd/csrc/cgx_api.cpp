@@ -858,6 +858,19 @@ int cgx_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write
     return cgx_stream_probe_shaped(src, read_bytes, dst, write_bytes, &shape, stream);
 }
 
+const char *cgx_issue_probe_form(int32_t form) { return cgx::issue_probe_form(form); }
+
+int cgx_issue_probe(int32_t form, int32_t blocks, int32_t iterations, void *out, size_t out_bytes, void *stream)
+{
+    if (!out) return CGX_ERR_NULL;
+    if (!cgx::issue_probe_form(form) || blocks < 1 || blocks > 65536 || iterations < 1 || iterations > (1 << 20) ||
+        out_bytes < size_t(blocks) * 256 * 4)
+        return CGX_ERR_SIZE;
+    if (misaligned(out)) return CGX_ERR_ALIGN;
+    const hipError_t e = cgx::launch_issue_probe(form, blocks, iterations, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CGX_OK : CGX_ERR_HIP;
+}
+
 const char *cgx_status_string(int status)
 {
     switch (status) {

@@ -99,5 +99,10 @@ struct ProbeShape {
 };
 hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes,
                                const ProbeShape &shape, hipStream_t stream);
+// The issue-rate probe: the text of instruction form number `form` (nullptr past the last), and one launch
+// of `blocks` blocks of 256 threads that each run 16 * iterations instructions of that form per wave and
+// leave one word per thread in out.
+const char *issue_probe_form(int form);
+hipError_t launch_issue_probe(int form, int blocks, int iterations, void *out, hipStream_t stream);
 
 }  // namespace cgx

@@ -2,7 +2,8 @@
 // style of the method's kernels (lane-contiguous 16-byte vectors, 1 KB per instruction and wave)
 // and a launch shape and cache policies chosen by the caller.  A measurement aid: what it
 // sustains at a given size and read:write mix is the ceiling the memory system sets for a
-// streaming kernel of that shape.
+// streaming kernel of that shape.  Behind it, the issue-rate probe: what one vector instruction form
+// costs a SIMD.
 #include "cgx_device.h"
 
 namespace cgx {
@@ -97,7 +98,126 @@ __global__ __launch_bounds__(1024) void stream_probe_kernel(const uint4v *__rest
     }
 }
 
+// ---------------------------------------------------------------- issue-rate probe
+//
+// One vector instruction form, repeated in 16 independent chains per lane with no memory access
+// in the loop: the time of a launch divided by the instructions each SIMD executed is what that
+// form costs a SIMD with eight resident waves.  The forms are the ones the kernels' inner loops
+// are made of, plus the alternatives that were weighed against them.  %0 is a chain's register
+// (read and written), %1 and %2 other vector registers, %3 a scalar register.
+#define CGX_ISSUE_FORMS(X)                                                                                       \
+    X(0, "v_add_f32 %0, %1, %0")                                                                                 \
+    X(1, "v_sub_f32 %0, %1, %0")                                                                                 \
+    X(2, "v_mul_f32 %0, %1, %0")                                                                                 \
+    X(3, "v_fmac_f32 %0, %1, %2")                                                                                \
+    X(4, "v_fma_f32 %0, %0, %1, %2")                                                                             \
+    X(5, "v_fma_f32 %0, %1, %3, %0")                                                                             \
+    X(6, "v_add_f32 %0, %3, %0")                                                                                 \
+    X(7, "v_and_b32 %0, %1, %0")                                                                                 \
+    X(8, "v_and_b32 %0, 60, %0")                                                                                 \
+    X(9, "v_and_b32 %0, 0x0f0f0f0f, %0")                                                                         \
+    X(10, "v_and_b32 %0, %3, %0")                                                                                \
+    X(11, "v_xor_b32 %0, %1, %0")                                                                                \
+    X(12, "v_or_b32 %0, %1, %0")                                                                                 \
+    X(13, "v_lshrrev_b32 %0, 4, %0")                                                                             \
+    X(14, "v_lshlrev_b32 %0, 3, %0")                                                                             \
+    X(15, "v_add_u32 %0, %1, %0")                                                                                \
+    X(16, "v_mov_b32 %0, %1")                                                                                    \
+    X(17, "v_cvt_f32_ubyte0 %0, %0")                                                                             \
+    X(18, "v_cvt_f32_ubyte2 %0, %0")                                                                             \
+    X(19, "v_cvt_u32_f32 %0, %0")                                                                                \
+    X(20, "v_cvt_f16_f32 %0, %0")                                                                                \
+    X(21, "v_cvt_f32_f16 %0, %0")                                                                                \
+    X(22, "v_cvt_f32_fp8_sdwa %0, %0 src0_sel:BYTE_2")                                                           \
+    X(23, "v_mul_lo_u32 %0, %1, %0")                                                                             \
+    X(24, "v_min_f32 %0, %1, %0")                                                                                \
+    X(25, "v_max_f32 %0, %1, %0")                                                                                \
+    X(26, "v_min_u32_sdwa %0, %1, %0 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1")        \
+    X(27, "v_xor_b32_sdwa %0, %1, %0 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1")        \
+    X(28, "v_lshl_or_b32 %0, %0, 4, %1")                                                                         \
+    X(29, "v_or3_b32 %0, %0, %1, %2")                                                                            \
+    X(30, "v_xad_u32 %0, %0, %1, %2")                                                                            \
+    X(31, "v_bfe_u32 %0, %0, 4, 4")                                                                              \
+    X(32, "v_perm_b32 %0, %0, %1, %2")                                                                           \
+    X(33, "v_alignbit_b32 %0, %0, %1, 8")                                                                        \
+    X(34, "v_bitop3_b32 %0, %0, %1, %2 bitop3:0x80")                                                             \
+    X(35, "v_mov_b32_dpp %0, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")                                 \
+    X(36, "v_min_f32_dpp %0, %1, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")                             \
+    X(37, "v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]")                                       \
+    X(38, "v_rcp_f32 %0, %0")
+// one more form is written out below: its result is a register pair
+#define CGX_ISSUE_FORM_PAIR "v_cvt_pk_f32_fp8 %0:[2], %0 ; v_xor_b32 %0, %0[0], %0[1] (two results, folded by a v_xor_b32)"
+
+constexpr int kIssueForms = 40;
+constexpr int kIssueChains = 16;
+
+template <int FORM>
+struct IssueForm;
+#define CGX_ISSUE_FORM(N, TEXT)                                                              \
+    template <>                                                                              \
+    struct IssueForm<N> {                                                                    \
+        static __device__ __forceinline__ void step(uint32_t &a, uint32_t b, uint32_t c, uint32_t s) \
+        {                                                                                    \
+            asm volatile(TEXT : "+v"(a) : "v"(b), "v"(c), "s"(s));                           \
+        }                                                                                    \
+    };
+CGX_ISSUE_FORMS(CGX_ISSUE_FORM)
+#undef CGX_ISSUE_FORM
+template <>
+struct IssueForm<kIssueForms - 1> {
+    static __device__ __forceinline__ void step(uint32_t &a, uint32_t, uint32_t, uint32_t)
+    {
+        uint64_t pair;
+        asm volatile("v_cvt_pk_f32_fp8 %0, %1" : "=v"(pair) : "v"(a));
+        asm volatile("v_xor_b32 %0, %1, %2" : "=v"(a) : "v"(uint32_t(pair)), "v"(uint32_t(pair >> 32)));
+    }
+};
+
+template <int FORM>
+__global__ __launch_bounds__(256) void issue_probe_kernel(uint32_t *__restrict__ out, int iterations, uint32_t scalar)
+{
+    const uint32_t b = 0x3f800000u + 0x01010101u * (threadIdx.x & 63u), c = (b * 7u) | 1u;
+    uint32_t a[kIssueChains];
+#pragma unroll
+    for (int j = 0; j < kIssueChains; j++) a[j] = b * uint32_t(j + 3);
+    for (int i = 0; i < iterations; i++) {
+#pragma unroll
+        for (int j = 0; j < kIssueChains; j++) IssueForm<FORM>::step(a[j], b, c, scalar);
+    }
+    uint32_t x = 0;
+#pragma unroll
+    for (int j = 0; j < kIssueChains; j++) x ^= a[j];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = x;
+}
+
+template <int FORM>
+void launch_issue_form(int form, unsigned blocks, uint32_t *out, int iterations, hipStream_t stream)
+{
+    if constexpr (FORM < kIssueForms) {
+        if (form == FORM)
+            hipLaunchKernelGGL(issue_probe_kernel<FORM>, dim3(blocks), dim3(256), 0, stream, out, iterations, 0x3f800000u);
+        else
+            launch_issue_form<FORM + 1>(form, blocks, out, iterations, stream);
+    }
+}
+
 }  // namespace
+
+const char *issue_probe_form(int form)
+{
+    static const char *const names[kIssueForms] = {
+#define CGX_ISSUE_NAME(N, TEXT) TEXT,
+        CGX_ISSUE_FORMS(CGX_ISSUE_NAME)
+#undef CGX_ISSUE_NAME
+        CGX_ISSUE_FORM_PAIR};
+    return form >= 0 && form < kIssueForms ? names[form] : nullptr;
+}
+
+hipError_t launch_issue_probe(int form, int blocks, int iterations, void *out, hipStream_t stream)
+{
+    launch_issue_form<0>(form, unsigned(blocks), static_cast<uint32_t *>(out), iterations, stream);
+    return hipGetLastError();
+}
 
 hipError_t launch_stream_probe(const void *src, size_t read_bytes, void *dst, size_t write_bytes,
                                const ProbeShape &shape, hipStream_t stream)

@@ -264,6 +264,40 @@ def test_degenerate_values(torch, oracle):
     assert_same_chunk(gp, gm, op, om, "binary16 subnormals")
 
 
+@pytest.mark.parametrize("b", [2, 4, 8])
+def test_units_at_both_ends_of_the_exponent_range(torch, oracle, b):
+    """Chunks whose buckets' units are huge (2^100 and beyond, where a scaled unit would overflow), tiny
+    (subnormal units) or ordinary, in different peers: the reduce and the fused call, two tiles of two chunks
+    and a short end."""
+    B, n, W = 256, 2048 * 4 + 1200, 5
+    off, bits = np.array([0, n], np.int64), np.array([b], np.uint8)
+    rng = np.random.default_rng(100 + b)
+    top = float(2 ** b - 1)
+    chunks, metas = [], []
+    for peer in range(W):
+        x = rng.standard_normal(n).astype(np.float32)
+        scale = np.ones(n // B + 1, np.float32)
+        kinds = rng.integers(0, 6, scale.size)
+        scale[kinds == 0] = np.float32(2.0 ** 99 * top)         # unit just below 2^100 ...
+        scale[kinds == 1] = np.float32(2.0 ** 101 * top)        # ... and above it
+        scale[kinds == 2] = np.float32(2.0 ** 120)
+        scale[kinds == 3] = np.float32(2.0 ** -140)             # subnormal unit
+        x *= np.repeat(scale, B)[:n]
+        if peer == 3:
+            x = rng.standard_normal(n).astype(np.float32)      # one peer with ordinary values everywhere
+        op, om = oracle.quantize(x, off, bits, B, 7 + peer, wl.F32)
+        chunks.append(op)
+        metas.append(om)
+    units = np.concatenate([m[:, 0] for m in metas])
+    assert (units >= 2.0 ** 100).any() and (units < 2.0 ** -126).any() and ((units > 1e-3) & (units < 10)).any()
+    ref = oracle.dequant_reduce(chunks, metas, off, bits, B, wl.F32)
+    got, _ = gpu_reduce(torch, chunks, metas, off, bits, B, wl.F32)
+    assert np.array_equal(got.view(np.uint32), ref["sum32"].view(np.uint32)), "reduce"
+    fp, fm = gpu_fused(torch, chunks, metas, off, bits, B, wl.F32, 31)
+    op, om = oracle.quantize(ref["sum32"], off, bits, B, 31, wl.F32)
+    assert_same_chunk(fp, fm, op, om, "fused")
+
+
 def test_repeatable_and_seed_sensitive(torch, oracle):
     w = wl.tiny_mixed(seed=5, bucket=256)
     g = w.gradient()

@@ -127,6 +127,14 @@ def test_argument_errors_are_found_on_the_host(lib):
                 (8192, 256, 1, 1, 2, 0), (8192, 256, 1, 1, 0, -1), (8192, 256, 1, 1, 0, 0, 2),
                 (8192, 256, 1, 1, 0, 0, 0, -1), (8192, 256, 1, 1, 0, 0, 0, 0, 65537)):
         assert shaped(*bad) == -2
+    forms = cgx.cgx_issue_probe_forms()
+    assert len(forms) >= 30 and forms[0].startswith("v_add_f32") and len(set(forms)) == len(forms)
+    assert lib.cgx_issue_probe_form(-1) is None and lib.cgx_issue_probe_form(len(forms)) is None
+    assert lib.cgx_issue_probe(0, 8, 10, None, 8 * 1024, None) == -1
+    for bad in ((-1, 8, 10, 8192), (len(forms), 8, 10, 8192), (0, 0, 10, 8192), (0, 65537, 10, 1 << 27),
+                (0, 8, 0, 8192), (0, 8, (1 << 20) + 1, 8192), (0, 8, 10, 8191)):
+        assert lib.cgx_issue_probe(bad[0], bad[1], bad[2], buf, bad[3], None) == -2
+    assert lib.cgx_issue_probe(0, 8, 10, buf + 4, 8192, None) == -9
     fused = lib.cgx_dequant_reduce_requantize
     assert fused(ptrs, ptrs, 0, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
     assert fused(ptrs, ptrs, 17, 300, 2, o, b, 128, 0, 1, buf, buf, None) == -6
