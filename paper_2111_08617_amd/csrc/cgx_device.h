@@ -83,6 +83,7 @@ typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float4v float4u __attribute__((aligned(4)));
 typedef half8v half8u __attribute__((aligned(2)));
 typedef uint4v uint4u2 __attribute__((aligned(2)));
+typedef uint4v uint4u4 __attribute__((aligned(4)));
 
 // ---------------------------------------------------------------- generator
 

@@ -55,47 +55,94 @@ __device__ __forceinline__ double square(float x)
     return d * d;
 }
 
-// Sum of squares of a run of elements of the buffer (tile of a pass-through plan).
+// Sum of squares of a run of elements of the buffer (a tile of a pass-through plan: at most kCopyTile
+// elements), formed by the kNormWaves waves of a block: each wave takes kCopyTile / kNormWaves
+// elements (4 KB of binary32: the slice size at which a wave that only reads runs closest to the
+// memory's peak; eight times that per wave reached 0.78 of it).
+// Elements that no 16-byte load may fetch (a tile off the vector grid, or its last few) go to
+// wave 0, one per lane and pass.
+constexpr int kNormWaves = 8;
+constexpr int kNormBlock = kNormWaves * kWave;
+
+// 16 bytes as stored, widened.
 template <int DT>
-__device__ __forceinline__ double sqnorm_tile(const void *__restrict__ buf, const Tile &tile, bool fast, int lane)
+__device__ __forceinline__ double square_sum16(const uint4v &v)
 {
     double s = 0.0;
-    const uint32_t groups = fast ? tile.count / 8 : 0;
-    for (uint32_t g0 = 0; g0 < groups; g0 += 4 * kWave) {
-        Raw8<DT> raw[4];
+    if (DT == CGX_F16) {
+        const half8v h = __builtin_bit_cast(half8v, v);
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const uint32_t g = g0 + u * kWave + lane;
-            raw[u].load(buf, tile.elem0 + int64_t(g < groups ? g : g0) * 8);    // clamped; masked below
-        }
+        for (int j = 0; j < 8; j++) s += square(float(h[j]));
+    } else {
+        const float4v f = __builtin_bit_cast(float4v, v);
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            float x[8];
-            raw[u].widen(x);
-            if (g0 + u * kWave + lane < groups) {
-#pragma unroll
-                for (int j = 0; j < 8; j++) s += square(x[j]);
-            }
-        }
+        for (int j = 0; j < 4; j++) s += square(f[j]);
     }
-    for (uint32_t j = groups * 8 + lane; j < tile.count; j += kWave) s += square(load_elem<DT>(buf, tile.elem0 + j));
     return s;
 }
 
 template <int DT>
-__global__ __launch_bounds__(kBlock) void sqnorm_kernel(const void *__restrict__ buf,
-                                                         const Tile *__restrict__ tiles,
-                                                         const uint32_t *__restrict__ slots, int64_t n_tiles,
-                                                         double *__restrict__ partial)
+__device__ __forceinline__ double sqnorm_share(const void *__restrict__ buf, const Tile &tile, bool fast, int wave, int lane)
 {
+    // which lane squares which element does not matter to the sum: every load instruction takes 1 KB of
+    // consecutive addresses, 16 bytes per lane
+    constexpr uint32_t kPerVec = DT == CGX_F16 ? 8 : 4;
+    constexpr int kLoads = kCopyTile / kNormWaves / kPerVec / kWave;       // per lane: 4 (binary32) or 2
+    double s = 0.0;
+    const uint32_t vecs = fast ? tile.count / kPerVec : 0;
+    const uint32_t v0 = uint32_t(wave) * (kLoads * kWave);
+    if (v0 < vecs) {
+        // aligned like an element, not like a vector: a layer may start anywhere
+        using Vec = std::conditional_t<DT == CGX_F16, uint4u2, uint4u4>;
+        const Vec *base = reinterpret_cast<const Vec *>(static_cast<const uint8_t *>(buf) +
+                                                        tile.elem0 * int64_t(DT == CGX_F16 ? 2 : 4));
+        uint4v raw[kLoads];
+#pragma unroll
+        for (int u = 0; u < kLoads; u++) {
+            const uint32_t v = v0 + u * kWave + lane;
+            raw[u] = __builtin_nontemporal_load(base + (v < vecs ? v : v0));      // clamped; masked below
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; u++)
+            if (v0 + u * kWave + lane < vecs) s += square_sum16<DT>(raw[u]);
+    }
+    if (wave == 0)
+        for (uint32_t j = vecs * kPerVec + lane; j < tile.count; j += kWave) s += square(load_elem<DT>(buf, tile.elem0 + j));
+    return s;
+}
+
+// One block per tile; the waves' sums meet in LDS and are added in wave order.
+template <int DT>
+__global__ __launch_bounds__(kNormBlock) void sqnorm_kernel(const void *__restrict__ buf,
+                                                             const Tile *__restrict__ tiles,
+                                                             const uint32_t *__restrict__ slots, int64_t n_tiles,
+                                                             double *__restrict__ partial)
+{
+    __shared__ double sums[kNormWaves];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     const int lane = int(threadIdx.x) & 63;
-    const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
-    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const Tile tile = tiles[t];
-        const double s = wave_sum(sqnorm_tile<DT>(buf, tile, tile_kind(tile) == kCopyFast, lane));
-        if (lane == 0) partial[slots[t]] = s;
+        const double s = wave_sum(sqnorm_share<DT>(buf, tile, tile_kind(tile) == kCopyFast, wave, lane));
+        if (lane == 0) sums[wave] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double total = sums[0];
+#pragma unroll
+            for (int w = 1; w < kNormWaves; w++) total += sums[w];
+            partial[slots[t]] = total;
+        }
+        __syncthreads();                     // sums is free again before the next tile's results arrive
     }
+}
+
+// Blocks of the norm kernel: one per tile unless the configuration caps the grid.
+inline unsigned norm_grid(int64_t n_tiles, const LaunchConfig &cfg)
+{
+    int64_t blocks = n_tiles;
+    if (cfg.max_blocks > 0 && blocks > cfg.max_blocks) blocks = cfg.max_blocks;
+    if (blocks > 0x7fffffff) blocks = 0x7fffffff;
+    return unsigned(blocks);
 }
 
 // Squared error of a vectorised tile: the codes are decoded as in the reduce (one peer) and
@@ -273,11 +320,10 @@ hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, cons
                                 const LaunchConfig &cfg, hipStream_t stream)
 {
     if (L == 0) return hipSuccess;
-    const dim3 block(kBlock);
     if (n_tiles > 0) {
-        const dim3 grid(grid_for(n_tiles, cfg));
         const auto kernel = dt == CGX_F16 ? sqnorm_kernel<CGX_F16> : sqnorm_kernel<CGX_F32>;
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, buf, tiles, slots, n_tiles, partial);
+        hipLaunchKernelGGL(kernel, dim3(norm_grid(n_tiles, cfg)), dim3(kNormBlock), 0, stream, buf, tiles, slots, n_tiles,
+                           partial);
     }
     hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,
                        static_cast<const double *>(partial), layer_first, out);
@@ -310,7 +356,7 @@ hipError_t launch_layer_sqnorms_noalloc(const void *buf, int dt, const int64_t *
         hipLaunchKernelGGL(expand_tiles_kernel, dim3(unsigned(L)), dim3(kBlock), 0, stream,
                            static_cast<const int64_t *>(d_off), static_cast<const int64_t *>(d_first), d_tiles, d_slots);
         const auto kernel = dt == CGX_F16 ? sqnorm_kernel<CGX_F16> : sqnorm_kernel<CGX_F32>;
-        hipLaunchKernelGGL(kernel, dim3(grid_for(n_tiles, LaunchConfig{})), dim3(kBlock), 0, stream, buf,
+        hipLaunchKernelGGL(kernel, dim3(norm_grid(n_tiles, LaunchConfig{})), dim3(kNormBlock), 0, stream, buf,
                            static_cast<const Tile *>(d_tiles), static_cast<const uint32_t *>(d_slots), n_tiles, d_partial);
     }
     hipLaunchKernelGGL(layer_sum_kernel, dim3(unsigned(L)), dim3(kSumBlock), 0, stream,

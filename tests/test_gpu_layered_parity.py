@@ -263,3 +263,20 @@ def test_norm_and_sign_random_plans_with_a_bucket_size_per_layer(torch, oracle, 
     w.bits = np.where(w.bits == 1, 2, w.bits).astype(np.uint8)
     buckets = np.random.default_rng(50 + seed).choice(BUCKETS, w.L).astype(np.int32)
     qsgd_cycle(torch, oracle, w, buckets, f"norm-sign random plan {seed} (buckets {buckets.tolist()}, bits {w.bits.tolist()})")
+
+
+ANY_BUCKETS = [96, 160, 224, 672, 992, 1056, 2016, 2080, 128, 1024, 2048]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_layered_plans_that_mix_sizes_that_are_no_power_of_two(torch, oracle, seed):
+    """One launch whose tiles are of every kind: buckets of 96 ... 2080 elements next to powers of two."""
+    w = wl.random_plan(100 + seed)
+    if w.n == 0:
+        pytest.skip("empty plan")
+    buckets = np.random.default_rng(200 + seed).choice(ANY_BUCKETS, w.L).astype(np.int32)
+    what = f"mixed sizes, plan {100 + seed} (buckets {buckets.tolist()}, bits {w.bits.tolist()})"
+    cycle(torch, oracle, w, buckets, what)
+    if seed < 5:
+        w.bits = np.where(w.bits == 1, 2, w.bits).astype(np.uint8)
+        qsgd_cycle(torch, oracle, w, buckets, "norm-sign " + what)
