@@ -475,7 +475,8 @@ int sqerrors_impl(int scheme, const void *grad, const void *packed, const void *
     for (size_t i = 0; i < launches.size(); i++) {
         const PlanRef &plan = plans[i];
         const hipError_t e = cgx::launch_layer_sqerrors(
-            scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots, plan->n_tiles, plan->d_layer_first, L,
+            scheme, grad, dt, packed, meta, plan->d_tiles, plan->d_slots, plan->n_tiles, plan->aligned_tiles,
+            plan->d_layer_first, L,
             static_cast<double *>(workspace), sqerr, launch_config(), static_cast<hipStream_t>(stream),
             i + 1 == launches.size());
         if (e != hipSuccess) return CGX_ERR_HIP;

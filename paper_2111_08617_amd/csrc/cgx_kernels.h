@@ -24,7 +24,7 @@ struct PeerPtrs {
 struct LaunchConfig {
     int chunks_per_tile = 0;   // fast-tile length in chunks of kChunk elements; 0: chosen per call
     int max_blocks = 0;        // 0: one wave per tile; >0: persistent grid of at most this many blocks
-    int via_lds = 1;           // quantize: fetch aligned chunks through LDS
+    int via_lds = 1;           // quantize and squared errors: fetch aligned chunks of the buffer through LDS
     int quantize_groups = 0;   // 2 or 4: chunk size of every quantize call; 0: chosen per call
     long keep_sums_max_bytes = 128l << 20;   // reduce: results up to this size are kept in the memory-side cache
 };
@@ -71,7 +71,7 @@ hipError_t launch_layer_sqnorms(const void *buf, int dt, const Tile *tiles, cons
                                 const int64_t *layer_first, int32_t L, double *partial, double *out,
                                 const LaunchConfig &cfg, hipStream_t stream);
 hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const void *packed, const void *meta,
-                                 const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
+                                 const Tile *tiles, const uint32_t *slots, int64_t n_tiles, bool aligned_tiles,
                                  const int64_t *layer_first, int32_t L, double *partial,
                                  double *out, const LaunchConfig &cfg, hipStream_t stream, bool sum_layers = true);
 // (sum_layers = false: only the tiles' partial sums are written; a plan served by several tile

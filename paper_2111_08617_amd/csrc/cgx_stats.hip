@@ -147,10 +147,16 @@ inline unsigned norm_grid(int64_t n_tiles, const LaunchConfig &cfg)
 
 // Squared error of a vectorised tile: the codes are decoded as in the reduce (one peer) and
 // compared with the gradient they were cut from.
-template <int SCHEME, int DT, int BITS, typename Peers>
+// VIA_LDS: every vectorised tile starts on a 16-byte boundary of the buffer (a property of the tile
+// table; the host picks the instantiation).  The chunk of the gradient then comes in through LDS, 1 KB of
+// consecutive bytes per load instruction, into an area of its own (x_stage) while the codes go to
+// theirs, both in flight together; otherwise each lane loads its groups straight into registers.
+template <int SCHEME, int DT, int BITS, bool VIA_LDS, typename Peers>
 __device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, Peers &chunk,
-                                               const Tile &tile, int bucket, int lane, uint4v *stage)
+                                               const Tile &tile, int bucket, int lane, uint4v *stage, uint4v *x_stage)
 {
+    constexpr int S = DT == CGX_F16 ? 2 : 4;
+    constexpr int kVecs = kChunk * S / 16;
     const LaneMap map(tile, bucket, lane);
     const int chunks = int(tile.count / kChunk);
     const int buckets_per_chunk = kChunk / bucket;
@@ -158,11 +164,37 @@ __device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, Pe
     for (int c = 0; c < chunks; c++) {
         const int64_t first = tile.elem0 + int64_t(c) * kChunk;
         float x[G][8], v[G][8];
+        if constexpr (VIA_LDS) {
+            const uint4v *src = reinterpret_cast<const uint4v *>(reinterpret_cast<const uint8_t *>(grad) + first * S);
 #pragma unroll
-        for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
+            for (int k = 0; k < kVecs / kWave; k++) load_to_lds16(src + k * kWave + lane, x_stage + k * kWave);
+        } else {
+#pragma unroll
+            for (int r = 0; r < G; r++) load8<DT>(grad, first + map.group(r), x[r]);
+        }
         clear_sums(v);
+        // (waits for every load of this wave, the gradient's included)
         reduce_chunk<SCHEME, BITS>(chunk, 1, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
                                    tile.bucket0 + c * buckets_per_chunk + map.bi, map, v, stage, lane);
+        if constexpr (VIA_LDS) {
+#pragma unroll
+            for (int r = 0; r < G; r++) {
+                if (DT == CGX_F16) {
+                    const half8v h = *reinterpret_cast<const half8v *>(reinterpret_cast<const _Float16 *>(x_stage) + map.group(r));
+#pragma unroll
+                    for (int j = 0; j < 8; j++) x[r][j] = float(h[j]);
+                } else {
+                    const float4v *p = reinterpret_cast<const float4v *>(reinterpret_cast<const float *>(x_stage) + map.group(r));
+                    const float4v a = p[0], b = p[1];
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        x[r][j] = a[j];
+                        x[r][4 + j] = b[j];
+                    }
+                }
+            }
+            wave_lds_fence();                // before the next chunk overwrites the area
+        }
 #pragma unroll
         for (int r = 0; r < G; r++)
 #pragma unroll
@@ -174,7 +206,12 @@ __device__ __forceinline__ double sqerror_fast(const void *__restrict__ grad, Pe
     return s;
 }
 
-template <int SCHEME, int DT>
+// LDS per wave: the staging area of one peer's codes (at most kChunk bytes, plus what the odd widths
+// read past their last group), and with VIA_LDS a chunk of the gradient before it.
+constexpr int kErrorCodeVecs = kChunk / 16;
+constexpr int kErrorChunkVecs = kChunk / 4;
+
+template <int SCHEME, int DT, bool VIA_LDS>
 __global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_argument, const void *__restrict__ grad,
                                                           const Tile *__restrict__ tiles,
                                                           const uint32_t *__restrict__ slots, int64_t n_tiles,
@@ -182,10 +219,12 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_ar
 {
     (void)chunk_argument;
     KernargPeers &chunk = first_kernel_argument();
-    __shared__ uint4v stage_all[kWavesPerBlock][kChunk / 4];
+    constexpr int kPerWave = VIA_LDS ? kErrorChunkVecs + kErrorCodeVecs : kErrorChunkVecs;
+    __shared__ uint4v stage_all[kWavesPerBlock][kPerWave];
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
     const int lane = int(threadIdx.x) & 63;
-    uint4v *stage = stage_all[wave];
+    uint4v *x_stage = stage_all[wave];
+    uint4v *stage = VIA_LDS ? x_stage + kErrorChunkVecs : x_stage;
     const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
     for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
         const Tile tile = tiles[t];
@@ -193,7 +232,8 @@ __global__ __launch_bounds__(kBlock) void sqerror_kernel(const PeerPtrs chunk_ar
         const uint32_t kind = tile_kind(tile);
         double s = 0.0;                              // pass-through tiles: no error
         if (is_vector_kind(kind)) {
-            CGX_FOR_BITS(tile_bits(tile), (s = sqerror_fast<SCHEME, DT, BITS>(grad, chunk, tile, bucket, lane, stage)))
+            CGX_FOR_BITS(tile_bits(tile),
+                         (s = sqerror_fast<SCHEME, DT, BITS, VIA_LDS>(grad, chunk, tile, bucket, lane, stage, x_stage)))
         } else if (kind == kQuantSlow || kind == kQuantTail || kind == kQuantAny) {
             for (uint32_t j = lane; j < tile.count; j += kWave) {
                 const double d = double(load_elem<DT>(grad, tile.elem0 + j)) -
@@ -365,7 +405,7 @@ hipError_t launch_layer_sqnorms_noalloc(const void *buf, int dt, const int64_t *
 }
 
 hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const void *packed, const void *meta,
-                                 const Tile *tiles, const uint32_t *slots, int64_t n_tiles,
+                                 const Tile *tiles, const uint32_t *slots, int64_t n_tiles, bool aligned_tiles,
                                  const int64_t *layer_first, int32_t L, double *partial,
                                  double *out, const LaunchConfig &cfg, hipStream_t stream, bool sum_layers)
 {
@@ -376,10 +416,13 @@ hipError_t launch_layer_sqerrors(int scheme, const void *grad, int dt, const voi
         PeerPtrs chunk{};
         chunk.packed[0] = static_cast<const uint8_t *>(packed);
         chunk.meta[0] = static_cast<const float *>(meta);
-        const auto kernel =
-            scheme == kSchemeNormSign
-                ? (dt == CGX_F16 ? sqerror_kernel<kNormSign, CGX_F16> : sqerror_kernel<kNormSign, CGX_F32>)
-                : (dt == CGX_F16 ? sqerror_kernel<kMinMax, CGX_F16> : sqerror_kernel<kMinMax, CGX_F32>);
+        using Kernel = void (*)(const PeerPtrs, const void *, const Tile *, const uint32_t *, int64_t, double *);
+        static const Kernel table[2][2][2] = {
+            {{sqerror_kernel<kMinMax, CGX_F32, false>, sqerror_kernel<kMinMax, CGX_F32, true>},
+             {sqerror_kernel<kMinMax, CGX_F16, false>, sqerror_kernel<kMinMax, CGX_F16, true>}},
+            {{sqerror_kernel<kNormSign, CGX_F32, false>, sqerror_kernel<kNormSign, CGX_F32, true>},
+             {sqerror_kernel<kNormSign, CGX_F16, false>, sqerror_kernel<kNormSign, CGX_F16, true>}}};
+        const Kernel kernel = table[scheme == kSchemeNormSign][dt == CGX_F16][aligned_tiles && cfg.via_lds];
         hipLaunchKernelGGL(kernel, grid, block, 0, stream, chunk, grad, tiles, slots, n_tiles, partial);
     }
     if (sum_layers)
