@@ -236,6 +236,30 @@ def measure(name, args, extras=True):
                       "ms_per_step": round(ov_ms, 5),
                       "value": round((w.n * S + 8 * m) / (ov_ms * 1e6), 1)}
 
+    # the same step as one captured graph of R steps (one per buffer set), replayed: what the launches of the
+    # three calls cost when the host is out of the way (the plans' tables exist by now, so capture is legal)
+    graph_leg = None
+    if extras:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for r in range(R):
+                step(r)
+        torch.cuda.synchronize()
+        replays = max(1, -(-args.steps // R))
+        for _ in range(max(1, args.warmup // R)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / (replays * R)
+        graph_leg = {"step": "the three calls of %d steps captured in one graph, replayed %d times" % (R, replays),
+                     "ms_per_step": round(g_ms, 5), "value": round((w.n * S + 8 * m) / (g_ms * 1e6), 1)}
+        del graph
+
     # the same rank's work with the fused entry point: quantize + dequant_reduce_requantize
     fused = None
     if W <= cgx.MAX_FUSED_PEERS and (extras or args.with_fused):
@@ -432,6 +456,7 @@ def measure(name, args, extras=True):
                       % (len(events[::stride]), args.steps, stride),
         },
         "two_streams": overlapped,
+        "graph": graph_leg,
         "fused": fused,
         "next_rows": next_rows,
         "norm_sign": norm_sign,

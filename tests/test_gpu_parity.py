@@ -397,6 +397,18 @@ def test_random_plans(torch, oracle, seed):
     full_cycle(torch, oracle, w, W=w.W, what=f"random plan {seed} (bucket {w.bucket}, bits {w.bits.tolist()})")
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_random_plans_with_any_legal_bucket_size(torch, oracle, seed):
+    """The same random plans with the bucket size drawn from all multiples of 32 up to 2176 (whole-bucket
+    tiles that are no power of two, sizes just above a chunk) and now and then from the rest up to 8192."""
+    w = wl.random_plan(500 + seed)
+    if w.n == 0:
+        pytest.skip("empty plan (covered by the edge cases)")
+    rng = np.random.default_rng(900 + seed)
+    w.bucket = int(32 * rng.integers(1, 69)) if seed % 6 else int(32 * rng.integers(69, 257))
+    full_cycle(torch, oracle, w, W=min(w.W, 5), what=f"random plan {500 + seed} (bucket {w.bucket}, bits {w.bits.tolist()})")
+
+
 def test_decoder_1p3b_config_full_size(torch, oracle):
     """292 tensors, 1.316G elements, Laplace values with outliers, bits in {2,4,8}, bucket 1024:
     quantize the full buffer (the launch bench.py times); reduce over W = 8 and requantize on
