@@ -79,14 +79,51 @@ __device__ __forceinline__ void codes_to_float(uint64_t v, float (&f)[8])
     }
 }
 
+// ---- two conversions per instruction (min/max codes of 2 and 4 bits)
+//
+// A code q <= 15 alone in a byte is also the 8-bit float (E4M3) q / 512: the subnormals and the
+// first binade of that format form one linear grid.  v_cvt_pk_f32_fp8 converts two bytes per
+// instruction, exactly, and fma(q / 512, unit * 512, mn) is bit for bit fma(float(q), unit, mn):
+// scaling by a power of two is exact unless unit * 512 overflows, which the caller rules out per
+// peer.  A pair of conversions costs a SIMD little more than one v_cvt_f32_ubyte.
+template <int SCHEME, int BITS>
+constexpr bool kPairedConversion = SCHEME == kMinMax && BITS == 4;
+constexpr float kPairedScale = 512.0f;
+
+// false: unit * 512 would not be finite (or unit is not) and the codes take the plain conversion
+__device__ __forceinline__ bool paired_usable(float2 m) { return __builtin_fabsf(m.x) < 0x1p118f; }
+
+// Levels / 512 of one group of 8 codes.
+template <int BITS>
+__device__ __forceinline__ void codes_to_scaled_float(uint64_t v, float (&f)[8])
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const uint32_t w = uint32_t(v);
+    if (BITS == 4) {
+        const uint32_t even = w & 0x0f0f0f0fu, odd = (w >> 4) & 0x0f0f0f0fu;
+        const float2v e0 = __builtin_amdgcn_cvt_pk_f32_fp8(even, false), e1 = __builtin_amdgcn_cvt_pk_f32_fp8(even, true);
+        const float2v o0 = __builtin_amdgcn_cvt_pk_f32_fp8(odd, false), o1 = __builtin_amdgcn_cvt_pk_f32_fp8(odd, true);
+        f[0] = e0.x, f[2] = e0.y, f[4] = e1.x, f[6] = e1.y;
+        f[1] = o0.x, f[3] = o0.y, f[5] = o1.x, f[7] = o1.y;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const float2v p = __builtin_amdgcn_cvt_pk_f32_fp8((w >> (2 * j)) & 0x0303u, false);     // codes j and j + 4
+            f[j] = p.x, f[4 + j] = p.y;
+        }
+    }
+}
+
 // Folds peers w0 .. w0+WB-1 into acc.  Each peer's share of the chunk (kChunk*BITS/8 bytes)
 // is fetched as whole 16-byte vectors, consecutive across lanes, directly into the wave's
 // LDS staging area, and read back by the lanes that own the codes.
 // TAIL: the chunk is the short end of a layer; only its first nvecs 16-byte vectors exist in the
 // packed streams (what lies behind them in LDS is stale, and so are the sums of elements past
 // the end: the caller drops them).
-template <int SCHEME, int BITS, int WB, bool TAIL, typename Peers>
-__device__ __forceinline__ void reduce_peers(Peers &peers, int w0, int64_t in_off, uint32_t g,
+// PAIRED: the two-per-instruction conversion above; the result says whether every peer's unit allowed it:
+// if not, acc holds garbage and the caller forms the sums again without PAIRED.
+template <int SCHEME, int BITS, int WB, bool TAIL, bool PAIRED, typename Peers>
+__device__ __forceinline__ bool reduce_peers(Peers &peers, int w0, int64_t in_off, uint32_t g,
                                              const int (&code_off)[G], float (&acc)[G][8], uint4v *stage,
                                              int lane, int nvecs)
 {
@@ -107,12 +144,20 @@ __device__ __forceinline__ void reduce_peers(Peers &peers, int w0, int64_t in_of
     wait_vector_memory();
     wave_lds_fence();
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage);
+    bool usable = true;
 #pragma unroll
     for (int i = 0; i < WB; i++) {
+        if constexpr (PAIRED && kPairedConversion<SCHEME, BITS>) {
+            usable = usable && paired_usable(m[i]);
+            m[i].x *= kPairedScale;
+        }
 #pragma unroll
         for (int r = 0; r < G; r++) {
             float f[8];
-            codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes + i * kBytes, code_off[r]), f);
+            if constexpr (PAIRED && kPairedConversion<SCHEME, BITS>)
+                codes_to_scaled_float<BITS>(staged_codes<BITS>(codes + i * kBytes, code_off[r]), f);
+            else
+                codes_to_float<SCHEME, BITS>(staged_codes<BITS>(codes + i * kBytes, code_off[r]), f);
 #pragma unroll
             for (int j = 0; j < 8; j++) acc[r][j] = __fadd_rn(acc[r][j], decode<SCHEME>(f[j], m[i]));
         }
@@ -120,11 +165,13 @@ __device__ __forceinline__ void reduce_peers(Peers &peers, int w0, int64_t in_of
         if (i % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
     wave_lds_fence();
+    return __builtin_amdgcn_ballot_w64(!usable) == 0;
 }
 
 // Sum over the W peers of one chunk's dequantized values, added to acc in peer order.
-template <int SCHEME, int BITS, bool TAIL = false, typename Peers>
-__device__ __forceinline__ void reduce_chunk(Peers &peers, int W, int64_t in_off, uint32_t g,
+// PAIRED: as in reduce_peers; false is returned when the sums have to be formed again without it.
+template <int SCHEME, int BITS, bool TAIL = false, bool PAIRED = false, typename Peers>
+__device__ __forceinline__ bool reduce_chunk(Peers &peers, int W, int64_t in_off, uint32_t g,
                                              const LaneMap &map, float (&acc)[G][8], uint4v *stage, int lane,
                                              int nvecs = 0)
 {
@@ -139,9 +186,12 @@ __device__ __forceinline__ void reduce_chunk(Peers &peers, int W, int64_t in_off
     int code_off[G];
 #pragma unroll
     for (int r = 0; r < G; r++) code_off[r] = (map.group(r) >> 3) * BITS;
+    bool good = true;
     for_peer_blocks<kWide>(W, [&](int w0, auto wb) {
-        reduce_peers<SCHEME, BITS, decltype(wb)::value, TAIL>(peers, w0, in_off, g, code_off, acc, stage, lane, nvecs);
+        good &= reduce_peers<SCHEME, BITS, decltype(wb)::value, TAIL, PAIRED>(peers, w0, in_off, g, code_off, acc, stage,
+                                                                             lane, nvecs);
     });
+    return good;
 }
 
 // -0 is the identity of binary32 addition for every addend, signed zeros included, so
@@ -218,6 +268,7 @@ __device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io
         float acc[G][8];
 #pragma unroll
         for (int r = 0; r < G; r++) init8(io, first + map.group(r), acc[r]);
+        // (the plain conversion: this kernel is bound by memory, and the paired one costs it registers)
         reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
                                    tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
         // the results leave through LDS as well, so that every store instruction writes 1 KB of

@@ -21,8 +21,13 @@ __device__ __forceinline__ void fused_fast(Peers &peers, int W, const Tile &tile
     for (int c = 0; c < chunks; c++) {
         float acc[G][8];
         clear_sums(acc);
-        reduce_chunk<SCHEME, BITS>(peers, W, tile.packed_off + int64_t(c) * (kChunk * BITS / 8),
-                                   tile.bucket0 + c * buckets_per_chunk + map.bi, map, acc, stage, lane);
+        const int64_t in_off = tile.packed_off + int64_t(c) * (kChunk * BITS / 8);
+        const uint32_t g = tile.bucket0 + c * buckets_per_chunk + map.bi;
+        if (!reduce_chunk<SCHEME, BITS, false, true>(peers, W, in_off, g, map, acc, stage, lane)) {
+            // a unit of 2^118 or more (or none at all): once more with the plain conversion
+            clear_sums(acc);
+            reduce_chunk<SCHEME, BITS>(peers, W, in_off, g, map, acc, stage, lane);
+        }
         quantize_chunk<SCHEME, BITS, ODD>(acc, map, lane, tile.elem0 + int64_t(c) * kChunk, key,
                                      meta_out + kMetaFloats<SCHEME> * (tile.bucket0 + c * buckets_per_chunk),
                                      packed_out + out_off + int64_t(c) * (kChunk * BITS / 8), stage);

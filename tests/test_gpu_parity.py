@@ -266,9 +266,9 @@ def test_degenerate_values(torch, oracle):
 
 @pytest.mark.parametrize("b", [2, 4, 8])
 def test_units_at_both_ends_of_the_exponent_range(torch, oracle, b):
-    """Chunks whose buckets' units are huge (2^100 and beyond, where a scaled unit would overflow), tiny
-    (subnormal units) or ordinary, in different peers: the reduce and the fused call, two tiles of two chunks
-    and a short end."""
+    """Chunks whose buckets' units are huge (on both sides of 2^118, where the fused kernel's scaled unit
+    starts to overflow and it falls back to the plain conversion), tiny (subnormal units) or ordinary, in
+    different peers: the reduce and the fused call, whole chunks and a short end."""
     B, n, W = 256, 2048 * 4 + 1200, 5
     off, bits = np.array([0, n], np.int64), np.array([b], np.uint8)
     rng = np.random.default_rng(100 + b)
@@ -278,9 +278,9 @@ def test_units_at_both_ends_of_the_exponent_range(torch, oracle, b):
         x = rng.standard_normal(n).astype(np.float32)
         scale = np.ones(n // B + 1, np.float32)
         kinds = rng.integers(0, 6, scale.size)
-        scale[kinds == 0] = np.float32(2.0 ** 99 * top)         # unit just below 2^100 ...
-        scale[kinds == 1] = np.float32(2.0 ** 101 * top)        # ... and above it
-        scale[kinds == 2] = np.float32(2.0 ** 120)
+        scale[kinds == 0] = np.float32(2.0 ** 114 * top)        # units around 2^117 ...
+        scale[kinds == 1] = np.float32(2.0 ** 116 * top)        # ... and around 2^119
+        scale[kinds == 2] = np.float32(2.0 ** 100)
         scale[kinds == 3] = np.float32(2.0 ** -140)             # subnormal unit
         x *= np.repeat(scale, B)[:n]
         if peer == 3:
@@ -289,7 +289,8 @@ def test_units_at_both_ends_of_the_exponent_range(torch, oracle, b):
         chunks.append(op)
         metas.append(om)
     units = np.concatenate([m[:, 0] for m in metas])
-    assert (units >= 2.0 ** 100).any() and (units < 2.0 ** -126).any() and ((units > 1e-3) & (units < 10)).any()
+    assert (units >= 2.0 ** 118).any() and ((units > 2.0 ** 110) & (units < 2.0 ** 118)).any()
+    assert (units < 2.0 ** -126).any() and ((units > 1e-3) & (units < 10)).any()
     ref = oracle.dequant_reduce(chunks, metas, off, bits, B, wl.F32)
     got, _ = gpu_reduce(torch, chunks, metas, off, bits, B, wl.F32)
     assert np.array_equal(got.view(np.uint32), ref["sum32"].view(np.uint32)), "reduce"
