@@ -571,6 +571,64 @@ def issue_rates(args):
                       "instructions_per_wave": 16 * iterations, "forms": rows}))
 
 
+def size_sweep(args):
+    """Launch time against size: cgx_quantize, cgx_dequant_reduce (W = 8) and the streaming probe in the kernels'
+    shape on single-layer plans of 8 to 200 M elements (4 bit, buckets of 1024).  A straight-line fit of time
+    against algorithmic bytes separates what a launch costs once (the intercept) from what it sustains while it
+    streams (the slope).  Event-timed here; under `rocprofv3 --kernel-trace` the dispatches give the pure
+    kernel times (12 launches of each kernel per size, in this order)."""
+    import numpy as np
+    import torch
+
+    from paper_2111_08617_amd import binding as cgx
+
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    reps, W = 12, 8
+    rows = []
+    for mega in (8, 16, 25, 50, 100, 200):
+        n = mega * 1024 * 1024
+        plan = cgx.Plan(np.array([0, n], np.int64), np.array([4], np.uint8), 1024)
+        pb, mb = cgx.cgx_sizes(plan)
+        R = max(2, min(8, int(2.5e9 / (n * 4.5))))
+        g = [torch.randn(n, device=dev) for _ in range(R)]
+        outs = [(torch.empty(pb, dtype=torch.uint8, device=dev), torch.empty(mb // 4, device=dev)) for _ in range(W)]
+        for p in range(W):
+            cgx.cgx_quantize(g[p % R], plan, p, outs[p][0], outs[p][1])
+        calls = {
+            "quantize": (n * 4 + pb + mb,
+                         lambda i: cgx.cgx_quantize(g[i % R], plan, i, outs[i % W][0], outs[i % W][1])),
+            "probe_quantize_shape": (n * 4 + pb // 16 * 16,
+                                     lambda i: cgx.cgx_stream_probe_shaped(g[i % R], n * 4, outs[i % W][0], pb // 16 * 16,
+                                                                           4096, 256, "nt", "nt")),
+            "dequant_reduce": (W * (pb + mb) + 4 * n,
+                               lambda i: cgx.cgx_dequant_reduce([o[0] for o in outs], [o[1] for o in outs], plan, g[i % R])),
+        }
+        for name, (nbytes, fn) in calls.items():
+            for i in range(2):
+                fn(i)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+            torch.cuda.synchronize()
+            for i in range(reps):
+                evs[i][0].record(stream)
+                fn(i)
+                evs[i][1].record(stream)
+            torch.cuda.synchronize()
+            ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
+            rows.append({"call": name, "elements": n, "bytes": nbytes, "ms": round(ms, 5),
+                         "hbm_frac": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4)})
+        del g, outs
+        torch.cuda.empty_cache()
+    fits = {}
+    for name in ("quantize", "probe_quantize_shape", "dequant_reduce"):
+        x = np.array([r["bytes"] / 1e6 for r in rows if r["call"] == name])
+        y = np.array([r["ms"] * 1e3 for r in rows if r["call"] == name])
+        slope, intercept = np.polyfit(x, y, 1)
+        fits[name] = {"us_per_MB": round(float(slope), 4), "us_per_launch": round(float(intercept), 2),
+                      "streaming_frac_of_peak": round(1.0 / float(slope) / (HBM_PEAK_GBPS / 1e3), 4)}
+    print(json.dumps({"mode": "size_sweep", "launches_per_size": reps + 2, "rows": rows, "fits_by_events": fits}))
+
+
 def ceilings(args):
     """What a kernel that only moves bytes sustains, by launch shape and cache policy: a staged sweep of
     cgx_stream_probe_shaped per (size, read:write mix).  Stage 1: every load x store policy at the kernels' own
@@ -681,6 +739,9 @@ def main():
     ap.add_argument("--issue-rates", action="store_true",
                     help="instead of the benchmark: what each vector instruction form of the kernels' inner loops costs "
                          "a SIMD (cgx_issue_probe), one JSON line")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="instead of the benchmark: quantize, dequant_reduce and the probe on single-layer plans of "
+                         "8 to 200 M elements, with a straight-line fit of time against bytes")
     ap.add_argument("--ceilings-case", default="", help="with --ceilings: only the cases whose name contains this")
     ap.add_argument("--ceilings-all", action="store_true", help="with --ceilings: list every configuration tried")
     args = ap.parse_args()
@@ -696,6 +757,9 @@ def main():
     cgx.lib()
     if args.issue_rates:
         issue_rates(args)
+        return
+    if args.size_sweep:
+        size_sweep(args)
         return
     if args.ceilings:
         ceilings(args)

@@ -115,13 +115,6 @@ __device__ __forceinline__ uint32_t draw16(uint32_t seed_lo, uint32_t seed_hi, u
 
 // ---------------------------------------------------------------- cross-lane
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v)
-{
-    const int s = __builtin_bit_cast(int, v);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(s, s, CTRL, 0xf, 0xf, false));
-}
-
 __device__ __forceinline__ float swizzle_xor16(float v)
 {
     // bit-mask mode: and 0x1f, or 0, xor 0x10 -> lane ^ 16 within each half
@@ -134,44 +127,85 @@ __device__ __forceinline__ float permute_xor32(float v, int lane)
                               __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, v)));
 }
 
-// Minimum and maximum over groups of 2^lg neighbouring lanes, result in every lane.
+// The smaller / larger of two numbers as the instruction gives it.  fminf / fmaxf compile to the same
+// instruction behind one more per operand that quiets a signalling NaN (a value that has crossed lanes
+// as an integer is not known to be quiet): four of the eight instructions of a butterfly step.  The
+// operands here are minima and maxima of the gradient; with a NaN among them the bucket's result is
+// unspecified anyway.
+__device__ __forceinline__ float min_plain(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+__device__ __forceinline__ float max_plain(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// min / max of a lane's value and the value of its partner lane under one of the four lane patterns
+// that stay within a row of 16, in one instruction (the partner's value is the first operand, fetched
+// through the data-parallel-primitive path).  Such an operand must not have been written by the two
+// vector instructions before it; the compiler does not look into this text, hence the s_nop.
+#define CGX_DPP_EXCHANGE(NAME, OP, PATTERN)                                                            \
+    __device__ __forceinline__ float NAME(float v)                                                     \
+    {                                                                                                  \
+        float r;                                                                                       \
+        asm("s_nop 1\n\t" OP " %0, %1, %1 " PATTERN " row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v)); \
+        return r;                                                                                      \
+    }
+CGX_DPP_EXCHANGE(min_xor1, "v_min_f32_dpp", "quad_perm:[1,0,3,2]")
+CGX_DPP_EXCHANGE(max_xor1, "v_max_f32_dpp", "quad_perm:[1,0,3,2]")
+CGX_DPP_EXCHANGE(min_xor2, "v_min_f32_dpp", "quad_perm:[2,3,0,1]")
+CGX_DPP_EXCHANGE(max_xor2, "v_max_f32_dpp", "quad_perm:[2,3,0,1]")
+CGX_DPP_EXCHANGE(min_half_mirror, "v_min_f32_dpp", "row_half_mirror")
+CGX_DPP_EXCHANGE(max_half_mirror, "v_max_f32_dpp", "row_half_mirror")
+CGX_DPP_EXCHANGE(min_mirror, "v_min_f32_dpp", "row_mirror")
+CGX_DPP_EXCHANGE(max_mirror, "v_max_f32_dpp", "row_mirror")
+#undef CGX_DPP_EXCHANGE
+
+// Minimum and maximum over groups of 2^lg neighbouring lanes, result in every lane.  Every lane of the
+// wave takes part (the callers are in wave-uniform control flow).
 __device__ __forceinline__ void group_minmax(float &mn, float &mx, int lg, int lane)
 {
-    if (lg >= 1) {   // lane ^ 1: quad_perm [1,0,3,2]
-        mn = __builtin_fminf(mn, dpp_move<0xB1>(mn));
-        mx = __builtin_fmaxf(mx, dpp_move<0xB1>(mx));
+    if (lg >= 1) {   // lane ^ 1
+        mn = min_xor1(mn);
+        mx = max_xor1(mx);
     }
-    if (lg >= 2) {   // lane ^ 2: quad_perm [2,3,0,1]
-        mn = __builtin_fminf(mn, dpp_move<0x4E>(mn));
-        mx = __builtin_fmaxf(mx, dpp_move<0x4E>(mx));
+    if (lg >= 2) {   // lane ^ 2
+        mn = min_xor2(mn);
+        mx = max_xor2(mx);
     }
     if (lg >= 3) {   // quads are uniform now: row_half_mirror pairs each quad with its neighbour
-        mn = __builtin_fminf(mn, dpp_move<0x141>(mn));
-        mx = __builtin_fmaxf(mx, dpp_move<0x141>(mx));
+        mn = min_half_mirror(mn);
+        mx = max_half_mirror(mx);
     }
     if (lg >= 4) {   // row_mirror pairs the two halves of a row of 16
-        mn = __builtin_fminf(mn, dpp_move<0x140>(mn));
-        mx = __builtin_fmaxf(mx, dpp_move<0x140>(mx));
+        mn = min_mirror(mn);
+        mx = max_mirror(mx);
     }
     if (lg >= 5) {
-        mn = __builtin_fminf(mn, swizzle_xor16(mn));
-        mx = __builtin_fmaxf(mx, swizzle_xor16(mx));
+        mn = min_plain(mn, swizzle_xor16(mn));
+        mx = max_plain(mx, swizzle_xor16(mx));
     }
     if (lg >= 6) {
-        mn = __builtin_fminf(mn, permute_xor32(mn, lane));
-        mx = __builtin_fmaxf(mx, permute_xor32(mx, lane));
+        mn = min_plain(mn, permute_xor32(mn, lane));
+        mx = max_plain(mx, permute_xor32(mx, lane));
     }
 }
 
 // Maximum alone, same exchange pattern.
 __device__ __forceinline__ void group_max(float &mx, int lg, int lane)
 {
-    if (lg >= 1) mx = __builtin_fmaxf(mx, dpp_move<0xB1>(mx));
-    if (lg >= 2) mx = __builtin_fmaxf(mx, dpp_move<0x4E>(mx));
-    if (lg >= 3) mx = __builtin_fmaxf(mx, dpp_move<0x141>(mx));
-    if (lg >= 4) mx = __builtin_fmaxf(mx, dpp_move<0x140>(mx));
-    if (lg >= 5) mx = __builtin_fmaxf(mx, swizzle_xor16(mx));
-    if (lg >= 6) mx = __builtin_fmaxf(mx, permute_xor32(mx, lane));
+    if (lg >= 1) mx = max_xor1(mx);
+    if (lg >= 2) mx = max_xor2(mx);
+    if (lg >= 3) mx = max_half_mirror(mx);
+    if (lg >= 4) mx = max_mirror(mx);
+    if (lg >= 5) mx = max_plain(mx, swizzle_xor16(mx));
+    if (lg >= 6) mx = max_plain(mx, permute_xor32(mx, lane));
 }
 
 // ---------------------------------------------------------------- the two quantizers
