@@ -636,6 +636,55 @@ def size_sweep(args):
     print(json.dumps({"mode": "size_sweep", "timed_launches_per_size": reps, "rows": rows, "fits_by_events": fits}))
 
 
+def bucket_sizes(args):
+    """cgx_quantize, cgx_dequant_reduce (W = 8) and cgx_dequant_reduce_requantize on one layer of 64 M elements
+    (4 bit) for bucket sizes that are powers of two and sizes that are not.  Event-timed; under
+    `rocprofv3 --kernel-trace` every call is a run of 13 launches of one kernel (3 warm-up + 10 timed) after the
+    8 quantize launches that make the chunks."""
+    import numpy as np
+    import torch
+
+    from paper_2111_08617_amd import binding as cgx
+
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    rows = []
+    for bucket in (128, 1024, 2048, 96, 160, 672, 992, 1056, 2016):
+        n = 64 * 1024 * 1024 // (bucket * 32) * (bucket * 32)
+        plan = cgx.Plan(np.array([0, n], np.int64), np.array([4], np.uint8), bucket)
+        pb, mb = cgx.cgx_sizes(plan)
+        g = [torch.randn(n, device=dev) for _ in range(3)]
+        outs = [(torch.empty(pb, dtype=torch.uint8, device=dev), torch.empty(mb // 4, device=dev)) for _ in range(8)]
+        for p in range(8):
+            cgx.cgx_quantize(g[p % 3], plan, p, outs[p][0], outs[p][1])
+        total = torch.empty(n, device=dev)
+        fused_out = (torch.empty(pb, dtype=torch.uint8, device=dev), torch.empty(mb // 4, device=dev))
+        packed, metas = [o[0] for o in outs], [o[1] for o in outs]
+
+        def timed(fn, reps=10):
+            for i in range(3):
+                fn(i)
+            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+            torch.cuda.synchronize()
+            for i in range(reps):
+                ev[i][0].record(stream)
+                fn(i)
+                ev[i][1].record(stream)
+            torch.cuda.synchronize()
+            return float(np.median([a.elapsed_time(b) for a, b in ev]))
+
+        q = timed(lambda i: cgx.cgx_quantize(g[i % 3], plan, i, outs[i % 8][0], outs[i % 8][1]))
+        r = timed(lambda i: cgx.cgx_dequant_reduce(packed, metas, plan, total))
+        f = timed(lambda i: cgx.cgx_dequant_reduce_requantize(packed, metas, plan, i, fused_out[0], fused_out[1]))
+        q_bytes, r_bytes, f_bytes = n * 4 + pb + mb, 8 * (pb + mb) + 4 * n, 9 * (pb + mb)
+        rows.append({"bucket": bucket, "elements": n,
+                     "quantize": rate(q_bytes, q), "dequant_reduce": rate(r_bytes, r),
+                     "dequant_reduce_requantize": rate(f_bytes, f)})
+        del g, outs, total, fused_out, packed, metas
+        torch.cuda.empty_cache()
+    print(json.dumps({"mode": "bucket_sizes", "bits": 4, "W": 8, "rows": rows}))
+
+
 def ceilings(args):
     """What a kernel that only moves bytes sustains, by launch shape and cache policy: a staged sweep of
     cgx_stream_probe_shaped per (size, read:write mix).  Stage 1: every load x store policy at the kernels' own
@@ -749,6 +798,9 @@ def main():
     ap.add_argument("--size-sweep", action="store_true",
                     help="instead of the benchmark: quantize, dequant_reduce and the probe on single-layer plans of "
                          "8 to 200 M elements, with a straight-line fit of time against bytes")
+    ap.add_argument("--bucket-sizes", action="store_true",
+                    help="instead of the benchmark: quantize, dequant_reduce and the fused call on one 64 M-element layer "
+                         "for bucket sizes that are powers of two and sizes that are not")
     ap.add_argument("--ceilings-case", default="", help="with --ceilings: only the cases whose name contains this")
     ap.add_argument("--ceilings-all", action="store_true", help="with --ceilings: list every configuration tried")
     args = ap.parse_args()
@@ -767,6 +819,9 @@ def main():
         return
     if args.size_sweep:
         size_sweep(args)
+        return
+    if args.bucket_sizes:
+        bucket_sizes(args)
         return
     if args.ceilings:
         ceilings(args)
