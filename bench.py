@@ -529,6 +529,8 @@ CEILING_CASES = [
     ("quantize decoder_1p3b (6:1, 6.1 GB)", 5_262_893_056, 844_533_008),
     ("dequant_reduce decoder_1p3b share (5:4, 1.5 GB)", 811_545_472, 657_858_560),
     ("requantize decoder_1p3b share (6:1, 0.76 GB)", 657_858_560, 101_443_184),
+    ("dequantize decoder_1p3b share (1:8, 0.74 GB)", 83_500_000, 657_858_560),
+    ("dequantize resnet50 (1:8, 115 MB)", 13_167_184, 102_228_128),
     ("read only, 115 MB", 115_343_360, 0),
     ("read only, 1.5 GB", 1_500_000_256, 0),
     ("read only, 6 GB", 6_000_000_000, 0),

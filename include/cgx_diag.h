@@ -39,8 +39,8 @@ int cgx_plan_tiles(int64_t n, int32_t L, const int64_t *layer_offsets, const uin
 /*
  * The same table for kernels whose chunk is chunk_elements (1024 or 2048; CGX_ERR_SIZE otherwise).
  * cgx_plan_tiles gives the table of 2048-element chunks, which the reduce, fused and statistics
- * kernels and the binary16 quantizer walk; cgx_quantize on binary32 input and cgx_requantize
- * walk the table of 1024-element chunks (buckets of 2048 elements are then one-bucket tiles of
+ * kernels and the binary16 quantizer walk; cgx_quantize on binary32 input, cgx_requantize and
+ * cgx_dequantize to binary32 walk the table of 1024-element chunks (buckets of 2048 elements are then one-bucket tiles of
  * kind 4, like those of 4096 and 8192).
  */
 int cgx_plan_tiles_chunk(int64_t n, int32_t L, const int64_t *layer_offsets, const uint8_t *bits_per_layer,
@@ -121,6 +121,9 @@ int cgx_issue_probe(int32_t form, int32_t blocks, int32_t iterations, void *out,
  *                           through LDS
  *   CGX_KEEP_SUMS_MB=k      the reduce writes results of up to k MB through at device scope so that
  *                           they stay in the memory-side cache (default 128; 0: always streamed)
+ *   CGX_DEQUANTIZE_THROUGH=0  cgx_dequantize runs like a reduce of one chunk (2048-element chunks, the
+ *                           reduce's store policy) instead of with 1024-element chunks and stores written
+ *                           through at system scope
  */
 
 #ifdef __cplusplus

@@ -13,7 +13,8 @@ OBJ = os.path.join(HERE, "_build")
 SOURCES = [("cgx_plan.cpp", "cgx_plan", []), ("cgx_api.cpp", "cgx_api", []), ("cgx_adaptive.cpp", "cgx_adaptive", []),
            ("cgx_quantize.hip", "cgx_quantize_g2", ["-DCGX_GROUPS=2"]),
            ("cgx_quantize.hip", "cgx_quantize_g4", ["-DCGX_GROUPS=4"]),
-           ("cgx_reduce.hip", "cgx_reduce", []), ("cgx_fused.hip", "cgx_fused", []), ("cgx_stats.hip", "cgx_stats", []),
+           ("cgx_reduce.hip", "cgx_reduce_g2", ["-DCGX_GROUPS=2"]),
+           ("cgx_reduce.hip", "cgx_reduce_g4", ["-DCGX_GROUPS=4"]), ("cgx_fused.hip", "cgx_fused", []), ("cgx_stats.hip", "cgx_stats", []),
            ("cgx_probe.hip", "cgx_probe", [])]
 
 # -ffp-contract=off: the code decision is binary32 without fused operations.

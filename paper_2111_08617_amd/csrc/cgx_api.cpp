@@ -89,6 +89,7 @@ const cgx::LaunchConfig &launch_config()
         c.max_blocks = env_int("CGX_MAX_BLOCKS", c.max_blocks);
         c.via_lds = env_int("CGX_VIA_LDS", c.via_lds);
         c.keep_sums_max_bytes = long(env_int("CGX_KEEP_SUMS_MB", int(c.keep_sums_max_bytes >> 20))) << 20;
+        c.dequantize_through = env_int("CGX_DEQUANTIZE_THROUGH", c.dequantize_through);
         c.quantize_groups = env_int("CGX_QUANTIZE_GROUPS", 0) == 2 ? 2 : env_int("CGX_QUANTIZE_GROUPS", 0) == 4 ? 4 : 0;
         return c;
     }();
@@ -360,11 +361,18 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
         if (misaligned(packed[w]) || misaligned(meta[w])) return CGX_ERR_ALIGN;
     }
     if (misaligned(out) || misaligned(local)) return CGX_ERR_ALIGN;
-    const std::vector<Launch> launches = launches_of(buckets, L, off, bits, cgx::kDefaultChunk);
+    // A decompression (one chunk, nothing to add to) writes eight bytes per byte it reads; a kernel that only
+    // moves bytes in that mix sustains 0.75 of the HBM peak with 8 KB written per wave and 0.91 with 4 KB, so it
+    // takes the kernel of 1024-element chunks (buckets up to 1024 elements; longer ones keep 2048).
+    const bool decompression = W == 1 && !local && launch_config().dequantize_through;
+    const bool short_buckets = !buckets.per_layer && buckets.uniform <= 1024;
+    const int chunk = decompression && short_buckets && out_dt == CGX_F32 ? cgx::chunk_of(2) : cgx::kDefaultChunk;
+    const std::vector<Launch> launches = launches_of(buckets, L, off, bits, chunk);
     std::vector<PlanRef> plans;
-    rc = get_plans(static_cast<hipStream_t>(stream), launches, L, off, bits, dt, cgx::kDefaultChunk,
+    rc = get_plans(static_cast<hipStream_t>(stream), launches, L, off, bits, dt, chunk,
                    tile_length(kOtherCall, dt, n), buckets.per_layer, &plans);
     if (rc != CGX_OK) return rc;
+    const auto launch_reduce = chunk == cgx::kDefaultChunk ? cgx::launch_dequant_reduce_g4 : cgx::launch_dequant_reduce_g2;
     for (size_t li = 0; li < launches.size(); li++) {
         const Launch &launch = launches[li];
         const PlanRef &plan = plans[li];
@@ -384,8 +392,11 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
             // call that consumes it (requantize, the optimizer): measured on 102 MB of sums, the reduce
             // runs 7 % and the requantize after it 10 % faster; on 658 MB the reader loses what the
             // writer gains
-            const bool keep = int64_t(n) * (out_dt == CGX_F16 ? 2 : 4) <= launch_config().keep_sums_max_bytes;
-            const hipError_t e = cgx::launch_dequant_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
+            // A decompression (one chunk, nothing to add to) writes eight bytes per byte it reads: its stores
+            // go through at system scope whatever the size (see StorePolicy in cgx_device.h).
+            const bool small = int64_t(n) * (out_dt == CGX_F16 ? 2 : 4) <= launch_config().keep_sums_max_bytes;
+            const int keep = decompression ? 2 : small ? 1 : 0;
+            const hipError_t e = launch_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
                                                             plan->many_tails, launch.bucket, init, init_dt, out,
                                                             out_dt, keep, launch_config(),
                                                             static_cast<hipStream_t>(stream));

@@ -63,6 +63,9 @@ __device__ __forceinline__ KernargPeers &kernel_argument_peers(size_t byte_offse
 #define CGX_GROUPS 4
 #endif
 constexpr int kGroups = CGX_GROUPS;            // groups of 8 elements per lane and chunk
+// (names of the launchers of files that are compiled once per chunk size)
+#define CGX_CONCAT2(a, b) a##b
+#define CGX_CONCAT(a, b) CGX_CONCAT2(a, b)
 constexpr int kChunk = chunk_of(kGroups);      // elements a wave takes per pass of the vectorised path
 
 constexpr int kWave = 64;
@@ -388,16 +391,26 @@ __device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, in
     for (int v = lane; v < vecs; v += kWave) stream_store(dst + v, stage[v]);
 }
 
-// The same to an element-aligned destination (sums).  keep: the stores are written through at
-// device scope (sc1) instead of as a non-temporal stream.  Measured: a result of about 100 MB then
-// stays in the 256 MB memory-side cache, the launch that writes it gets 7 % shorter and the one
-// that reads it next 10 %; results of several hundred MB gain 3 % in the writer and lose 7 % in the
-// reader, so the host asks for it only below a size (see reduce_impl).
-__device__ __forceinline__ void flush_stage_to_elements(const uint4v *stage, uint4u2 *dst, int vecs, int lane, bool keep)
+// The same to an element-aligned destination (sums), with the cache policy the host chose for the call:
+//   kStoreStream   non-temporal: results larger than the memory-side cache
+//   kStoreKeep     written through at device scope (sc1).  Measured: a result of about 100 MB then
+//                  stays in the 256 MB memory-side cache, the launch that writes it gets 7 % shorter and the
+//                  one that reads it next 10 %; results of several hundred MB gain 3 % in the writer and
+//                  lose 7 % in the reader, so the host asks for it only below a size (see reduce_impl)
+//   kStoreThrough  written through at system scope, non-temporal (sc0 sc1 nt): for calls that write
+//                  eight bytes per byte they read (cgx_dequantize).  An arithmetic-free kernel in that mix
+//                  sustains 0.61 of the HBM peak with non-temporal loads and stores, 0.75 with ordinary
+//                  loads and these stores (8 KB per wave), and 0.91 with 4 KB per wave
+enum StorePolicy { kStoreStream = 0, kStoreKeep = 1, kStoreThrough = 2 };
+
+__device__ __forceinline__ void flush_stage_to_elements(const uint4v *stage, uint4u2 *dst, int vecs, int lane, int policy)
 {
-    if (keep) {
+    if (policy == kStoreKeep) {
         for (int v = lane; v < vecs; v += kWave)
             asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst + v), "v"(stage[v]) : "memory");
+    } else if (policy == kStoreThrough) {
+        for (int v = lane; v < vecs; v += kWave)
+            asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(dst + v), "v"(stage[v]) : "memory");
     } else {
         for (int v = lane; v < vecs; v += kWave) __builtin_nontemporal_store(stage[v], dst + v);
     }
@@ -409,6 +422,14 @@ __device__ __forceinline__ void load_to_lds16(const uint4v *gptr, uint4v *lds_ba
 {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
                                      (__attribute__((address_space(3))) void *)lds_base, 16, 0, 2 /* nt */);
+}
+
+// The same as an ordinary (cached) load: in a call that mostly writes, the few bytes it reads come
+// in faster this way (see kStoreThrough).
+__device__ __forceinline__ void load_to_lds16_cached(const uint4v *gptr, uint4v *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
 }
 
 // Waits until every outstanding vector-memory operation of this wave has completed

@@ -137,7 +137,13 @@ __device__ __forceinline__ bool reduce_peers(Peers &peers, int w0, int64_t in_of
 #pragma unroll
         for (int k = 0; k < kPerLane; k++) {
             const int v = lane + k * kWave;
-            if (TAIL ? v < nvecs : (kVecs % kWave == 0 || v < kVecs)) load_to_lds16(in + v, stage + i * kVecs + k * kWave);
+            if (TAIL ? v < nvecs : (kVecs % kWave == 0 || v < kVecs)) {
+                // a block of one peer is what a decompression (W = 1) consists of: ordinary loads there
+                if (WB == 1)
+                    load_to_lds16_cached(in + v, stage + i * kVecs + k * kWave);
+                else
+                    load_to_lds16(in + v, stage + i * kVecs + k * kWave);
+            }
         }
         m[i] = load_meta<SCHEME>(peers.meta[w0 + i], g);
     }
@@ -212,7 +218,7 @@ struct SumIo {
     int init_dt;
     void *out;
     int out_dt;
-    int keep;          // the result is small enough to stay in the memory-side cache: see flush_stage_to_elements
+    int keep;          // StorePolicy of the result: see flush_stage_to_elements
 };
 
 __device__ __forceinline__ void init8(const SumIo &io, int64_t e, float (&acc)[8])
@@ -283,7 +289,7 @@ __device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io
             }
             wave_lds_fence();
             flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<_Float16 *>(io.out) + first),
-                                    kChunk / 8, lane, io.keep != 0);
+                                    kChunk / 8, lane, io.keep);
         } else {
 #pragma unroll
             for (int r = 0; r < G; r++) {
@@ -293,7 +299,7 @@ __device__ __forceinline__ void reduce_fast(Peers &peers, int W, const SumIo &io
             }
             wave_lds_fence();
             flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<float *>(io.out) + first),
-                                    kChunk / 4, lane, io.keep != 0);
+                                    kChunk / 4, lane, io.keep);
         }
         wave_lds_fence();
     }
@@ -427,7 +433,7 @@ __device__ __forceinline__ void reduce_any(Peers &peers, int W, const SumIo &io,
         }
         wave_lds_fence();
         flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<_Float16 *>(io.out) + tile.elem0),
-                                shape.groups, lane, io.keep != 0);
+                                shape.groups, lane, io.keep);
     } else {
 #pragma unroll
         for (int r = 0; r < G; r++) {
@@ -440,7 +446,7 @@ __device__ __forceinline__ void reduce_any(Peers &peers, int W, const SumIo &io,
         }
         wave_lds_fence();
         flush_stage_to_elements(stage, reinterpret_cast<uint4u2 *>(reinterpret_cast<float *>(io.out) + tile.elem0),
-                                2 * shape.groups, lane, io.keep != 0);
+                                2 * shape.groups, lane, io.keep);
     }
     wave_lds_fence();
 }

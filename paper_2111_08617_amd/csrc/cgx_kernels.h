@@ -27,6 +27,7 @@ struct LaunchConfig {
     int via_lds = 1;           // quantize and squared errors: fetch aligned chunks of the buffer through LDS
     int quantize_groups = 0;   // 2 or 4: chunk size of every quantize call; 0: chosen per call
     long keep_sums_max_bytes = 128l << 20;   // reduce: results up to this size are kept in the memory-side cache
+    int dequantize_through = 1;              // cgx_dequantize: stores written through at system scope
 };
 
 // odd_tiles: some vectorised tile starts on an odd element index (the kernels then take the
@@ -46,14 +47,20 @@ constexpr int kDefaultChunk = chunk_of(4);
 
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
 // term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
-// keep_output: the result is written through at device scope rather than streamed (it then stays in the
-// memory-side cache if it is small enough; the caller decides by size).
+// store_policy: 0 the result is streamed (non-temporal), 1 written through at device scope (it then stays in
+// the memory-side cache if it is small enough; the caller decides by size), 2 written through at system scope,
+// non-temporal (calls that mostly write: a decompression).
 // many_tails: the short ends of layers are a real share of the plan's tiles (the kernel then
 // takes them through the masked chunk path instead of the generic one).
-hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+// (two builds: chunks of 1024 elements, which a decompression takes, and of 2048)
+hipError_t launch_dequant_reduce_g2(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
                                  bool many_tails,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
-                                 bool keep_output, const LaunchConfig &cfg, hipStream_t stream);
+                                 int store_policy, const LaunchConfig &cfg, hipStream_t stream);
+hipError_t launch_dequant_reduce_g4(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+                                 bool many_tails,
+                                 int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
+                                 int store_policy, const LaunchConfig &cfg, hipStream_t stream);
 
 // packed_out / meta_out = quantize(deq_0 + ... + deq_{W-1}) without the binary32 sum ever
 // reaching memory; tiles_in describes the chunks (storage type dt), tiles_out the output

@@ -64,8 +64,6 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
 }  // namespace
 
 // This file is compiled once per chunk size (CGX_GROUPS = 2 and 4): launch_quantize_g2, launch_quantize_g4.
-#define CGX_CONCAT2(a, b) a##b
-#define CGX_CONCAT(a, b) CGX_CONCAT2(a, b)
 hipError_t CGX_CONCAT(launch_quantize_g, CGX_GROUPS)(int scheme, const void *grad, int dt, const Tile *tiles, int64_t n_tiles, bool odd_tiles,
                            bool aligned_tiles, int32_t bucket, uint64_t seed, void *packed, void *meta,
                            const LaunchConfig &cfg, hipStream_t stream)

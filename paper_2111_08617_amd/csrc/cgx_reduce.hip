@@ -69,14 +69,15 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const Tile *__restrict__
 
 }  // namespace
 
-hipError_t launch_dequant_reduce(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
+// This file is compiled once per chunk size (CGX_GROUPS = 2 and 4): launch_dequant_reduce_g2, launch_dequant_reduce_g4.
+hipError_t CGX_CONCAT(launch_dequant_reduce_g, CGX_GROUPS)(int scheme, const PeerPtrs &peers, int W, int dt, const Tile *tiles, int64_t n_tiles,
                                  bool many_tails,
                                  int32_t bucket, const void *init, int init_dt, void *out, int out_dt,
-                                 bool keep_output, const LaunchConfig &cfg, hipStream_t stream)
+                                 int store_policy, const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
-    const SumIo io{init, init_dt, out, out_dt, keep_output ? 1 : 0};
+    const SumIo io{init, init_dt, out, out_dt, store_policy};
     const auto kernel = scheme == kSchemeNormSign
                             ? (many_tails ? reduce_kernel<kNormSign, true> : reduce_kernel<kNormSign, false>)
                             : (many_tails ? reduce_kernel<kMinMax, true> : reduce_kernel<kMinMax, false>);
