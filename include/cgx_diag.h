@@ -121,6 +121,8 @@ int cgx_issue_probe(int32_t form, int32_t blocks, int32_t iterations, void *out,
  *                           through LDS
  *   CGX_KEEP_SUMS_MB=k      the reduce writes results of up to k MB through at device scope so that
  *                           they stay in the memory-side cache (default 128; 0: always streamed)
+ *   CGX_REDUCE_GROUPS=2|4   chunk size of every reduce call with buckets of up to 1024 elements: 1024 or 2048
+ *                           elements (default: 2048, and 1024 for cgx_dequantize to binary32)
  *   CGX_DEQUANTIZE_THROUGH=0  cgx_dequantize runs like a reduce of one chunk (2048-element chunks, the
  *                           reduce's store policy) instead of with 1024-element chunks and stores written
  *                           through at system scope

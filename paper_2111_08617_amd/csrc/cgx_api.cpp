@@ -90,6 +90,7 @@ const cgx::LaunchConfig &launch_config()
         c.via_lds = env_int("CGX_VIA_LDS", c.via_lds);
         c.keep_sums_max_bytes = long(env_int("CGX_KEEP_SUMS_MB", int(c.keep_sums_max_bytes >> 20))) << 20;
         c.dequantize_through = env_int("CGX_DEQUANTIZE_THROUGH", c.dequantize_through);
+        c.reduce_groups = env_int("CGX_REDUCE_GROUPS", 0) == 2 ? 2 : env_int("CGX_REDUCE_GROUPS", 0) == 4 ? 4 : 0;
         c.quantize_groups = env_int("CGX_QUANTIZE_GROUPS", 0) == 2 ? 2 : env_int("CGX_QUANTIZE_GROUPS", 0) == 4 ? 4 : 0;
         return c;
     }();
@@ -366,7 +367,9 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
     // takes the kernel of 1024-element chunks (buckets up to 1024 elements; longer ones keep 2048).
     const bool decompression = W == 1 && !local && launch_config().dequantize_through;
     const bool short_buckets = !buckets.per_layer && buckets.uniform <= 1024;
-    const int chunk = decompression && short_buckets && out_dt == CGX_F32 ? cgx::chunk_of(2) : cgx::kDefaultChunk;
+    const int forced = launch_config().reduce_groups;
+    const int chunk = forced > 0 ? (short_buckets ? cgx::chunk_of(forced) : cgx::kDefaultChunk)
+                      : decompression && short_buckets && out_dt == CGX_F32 ? cgx::chunk_of(2) : cgx::kDefaultChunk;
     const std::vector<Launch> launches = launches_of(buckets, L, off, bits, chunk);
     std::vector<PlanRef> plans;
     rc = get_plans(static_cast<hipStream_t>(stream), launches, L, off, bits, dt, chunk,

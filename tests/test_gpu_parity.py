@@ -499,8 +499,8 @@ def test_non_finite_inputs_do_not_disturb_other_buckets(torch, oracle):
 
 
 def test_result_does_not_depend_on_launch_geometry(torch, oracle):
-    """Counter-based draws: tiles of several chunks and a small persistent grid give the same bytes
-    (quantize, reduce and the fused reduce + requantize)."""
+    """Counter-based draws: tiles of several chunks, a small persistent grid, either chunk size and either
+    store policy give the same bytes (quantize, reduce, the fused reduce + requantize, decompression)."""
     import hashlib
     import os
     import subprocess
@@ -517,11 +517,15 @@ def test_result_does_not_depend_on_launch_geometry(torch, oracle):
         "s = torch.zeros(w.n, device='cuda'); cgx.cgx_dequant_reduce([p, p], [m, m], plan, s); torch.cuda.synchronize()\n"
         "fp = torch.zeros(pb, dtype=torch.uint8, device='cuda'); fm = torch.zeros(mb // 4, device='cuda')\n"
         "cgx.cgx_dequant_reduce_requantize([p, p], [m, m], plan, 78, fp, fm); torch.cuda.synchronize()\n"
-        "print(hashlib.sha256(b''.join(t.cpu().numpy().tobytes() for t in (p, m, s, fp, fm))).hexdigest())\n"
+        "d32 = torch.zeros(w.n, device='cuda'); cgx.cgx_dequantize(p, m, plan, wl.F32, d32)\n"
+        "d16 = torch.zeros(w.n, dtype=torch.float16, device='cuda'); cgx.cgx_dequantize(p, m, plan, wl.F16, d16)\n"
+        "torch.cuda.synchronize()\n"
+        "print(hashlib.sha256(b''.join(t.cpu().numpy().tobytes() for t in (p, m, s, fp, fm, d32, d16))).hexdigest())\n"
     ) % root
     digests = set()
     for env in ({}, {"CGX_CHUNKS_PER_TILE": "3"}, {"CGX_CHUNKS_PER_TILE": "8", "CGX_MAX_BLOCKS": "5"},
-                {"CGX_QUANTIZE_GROUPS": "4", "CGX_KEEP_SUMS_MB": "0"}, {"CGX_QUANTIZE_GROUPS": "2", "CGX_VIA_LDS": "0"}):
+                {"CGX_QUANTIZE_GROUPS": "4", "CGX_KEEP_SUMS_MB": "0"}, {"CGX_QUANTIZE_GROUPS": "2", "CGX_VIA_LDS": "0"},
+                {"CGX_REDUCE_GROUPS": "2"}, {"CGX_REDUCE_GROUPS": "4", "CGX_DEQUANTIZE_THROUGH": "0"}):
         out = subprocess.run([sys.executable, "-c", code], env={**os.environ, **env}, capture_output=True, text=True,
                              timeout=300)
         assert out.returncode == 0, out.stderr[-2000:]
