@@ -156,9 +156,9 @@ __device__ __forceinline__ float max_plain(float a, float b)
 #define CGX_DPP_EXCHANGE(NAME, OP, PATTERN)                                                            \
     __device__ __forceinline__ float NAME(float v)                                                     \
     {                                                                                                  \
-        float r;                                                                                       \
-        asm("s_nop 1\n\t" OP " %0, %1, %1 " PATTERN " row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v)); \
-        return r;                                                                                      \
+        /* in place: a lane whose partner is switched off keeps its own value */                       \
+        asm("s_nop 1\n\t" OP " %0, %0, %0 " PATTERN " row_mask:0xf bank_mask:0xf" : "+v"(v));         \
+        return v;                                                                                      \
     }
 CGX_DPP_EXCHANGE(min_xor1, "v_min_f32_dpp", "quad_perm:[1,0,3,2]")
 CGX_DPP_EXCHANGE(max_xor1, "v_max_f32_dpp", "quad_perm:[1,0,3,2]")
