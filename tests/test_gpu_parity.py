@@ -99,6 +99,17 @@ def full_cycle(torch, oracle, w, W, seed_shift=0, what=""):
     ref = oracle.dequant_reduce(chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
     got, total = gpu_reduce(torch, chunks, metas, w.offsets, w.bits, w.bucket, w.dt)
     assert_sum_parity(got, ref, f"{what} reduce")
+    # decompression of one chunk into either storage type (canaries behind the output)
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    dp0, dm0 = dev(torch, chunks[0]), (dev(torch, metas[0].reshape(-1)) if metas[0].size else torch.zeros(4, device="cuda"))
+    for out_dt, tdt in ((wl.F32, torch.float32), (wl.F16, torch.float16)):
+        out = torch.full((w.n + 16,), 9.0, dtype=tdt, device="cuda")
+        cgx.cgx_dequantize(dp0, dm0, plan, out_dt, out)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        assert (o[w.n:] == 9.0).all(), f"{what}: dequantize wrote past the end"
+        want = oracle.dequantize(chunks[0], metas[0], w.offsets, w.bits, w.bucket, w.dt, out_dt)
+        assert o[:w.n].tobytes() == want.tobytes(), f"{what}: dequantize to {'f16' if out_dt else 'f32'}"
     # requantize: the definition is quantize(sum) on binary32 input, so compare on the GPU's own sum
     rp, rm = gpu_quantize(torch, total[:w.n], w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32, requant=True)
     op, om = oracle.quantize(got, w.offsets, w.bits, w.bucket, 99 + seed_shift, wl.F32)
