@@ -394,15 +394,12 @@ int reduce_impl(int scheme, const void *const *packed, const void *const *meta, 
             // a result that fits the 256 MB memory-side cache with room to spare is left there for the
             // call that consumes it (requantize, the optimizer): measured on 102 MB of sums, the reduce
             // runs 7 % and the requantize after it 10 % faster; on 658 MB the reader loses what the
-            // writer gains
-            // A decompression (one chunk, nothing to add to) writes eight bytes per byte it reads: its stores
-            // go through at system scope whatever the size (see StorePolicy in cgx_device.h).
+            // writer gains.  A decompression's stores go through at system scope whatever the size.
             const bool small = int64_t(n) * (out_dt == CGX_F16 ? 2 : 4) <= launch_config().keep_sums_max_bytes;
-            const int keep = decompression ? 2 : small ? 1 : 0;
-            const hipError_t e = launch_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles,
-                                                            plan->many_tails, launch.bucket, init, init_dt, out,
-                                                            out_dt, keep, launch_config(),
-                                                            static_cast<hipStream_t>(stream));
+            const int policy = decompression ? cgx::kStoreThrough : small ? cgx::kStoreKeep : cgx::kStoreStream;
+            const hipError_t e = launch_reduce(scheme, peers, k, dt, plan->d_tiles, plan->n_tiles, plan->many_tails,
+                                               launch.bucket, init, init_dt, out, out_dt, policy, launch_config(),
+                                               static_cast<hipStream_t>(stream));
             if (e != hipSuccess) return CGX_ERR_HIP;
         }
     }

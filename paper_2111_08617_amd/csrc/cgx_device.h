@@ -391,7 +391,8 @@ __device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, in
     for (int v = lane; v < vecs; v += kWave) stream_store(dst + v, stage[v]);
 }
 
-// The same to an element-aligned destination (sums), with the cache policy the host chose for the call:
+// The same to an element-aligned destination (sums), with the cache policy (StorePolicy, cgx_kernels.h) the host
+// chose for the call:
 //   kStoreStream   non-temporal: results larger than the memory-side cache
 //   kStoreKeep     written through at device scope (sc1).  Measured: a result of about 100 MB then
 //                  stays in the 256 MB memory-side cache, the launch that writes it gets 7 % shorter and the
@@ -401,8 +402,6 @@ __device__ __forceinline__ void flush_stage(const uint4v *stage, uint4v *dst, in
 //                  eight bytes per byte they read (cgx_dequantize).  An arithmetic-free kernel in that mix
 //                  sustains 0.61 of the HBM peak with non-temporal loads and stores, 0.75 with ordinary
 //                  loads and these stores (8 KB per wave), and 0.91 with 4 KB per wave
-enum StorePolicy { kStoreStream = 0, kStoreKeep = 1, kStoreThrough = 2 };
-
 __device__ __forceinline__ void flush_stage_to_elements(const uint4v *stage, uint4u2 *dst, int vecs, int lane, int policy)
 {
     if (policy == kStoreKeep) {

@@ -46,10 +46,13 @@ hipError_t launch_quantize_g4(int scheme, const void *grad, int dt, const Tile *
 // Chunk size of every other kernel (reduce, fused, statistics).
 constexpr int kDefaultChunk = chunk_of(4);
 
+// How a reduce writes its result (see flush_stage_to_elements in cgx_device.h).
+enum StorePolicy { kStoreStream = 0, kStoreKeep = 1, kStoreThrough = 2 };
+
 // out[e] = init[e] + deq_0[e] + ... + deq_{W-1}[e] in that order (init == nullptr: no such
 // term), W <= kPeersPerLaunch; init is binary32 or binary16, out binary32 or binary16.
-// store_policy: 0 the result is streamed (non-temporal), 1 written through at device scope (it then stays in
-// the memory-side cache if it is small enough; the caller decides by size), 2 written through at system scope,
+// store_policy (StorePolicy): the result is streamed (non-temporal), written through at device scope (it then stays
+// in the memory-side cache if it is small enough; the caller decides by size), or written through at system scope,
 // non-temporal (calls that mostly write: a decompression).
 // many_tails: the short ends of layers are a real share of the plan's tiles (the kernel then
 // takes them through the masked chunk path instead of the generic one).
