@@ -468,3 +468,13 @@ def test_binding_refuses_buffers_the_kernels_would_overrun(lib, monkeypatch):
         cgx.cgx_qsgd_quantize(Fake(5000), plan, 1, Fake(qp, torch.uint8), Fake(qm // 4), stream=0)
     with pytest.raises(ValueError, match="meta"):
         cgx.cgx_qsgd_quantize(Fake(5000), plan, 1, Fake(qp, torch.uint8), Fake(qm // 4 - 1), stream=0)
+
+
+def test_group_to_bucket_lookup_by_multiply_and_shift_is_exact():
+    """The kernels that stream buckets of a size that is no power of two find the bucket of group G of a tile
+    as (G * ceil(2^16 / gb)) >> 16, gb = groups of 8 elements per bucket: equal to G // gb for every group of a
+    chunk (G < 256) and every bucket size up to the chunk (gb <= 256)."""
+    G = np.arange(256, dtype=np.uint64)
+    for gb in range(1, 257):
+        inv = (65536 + gb - 1) // gb
+        assert np.array_equal((G * np.uint64(inv)) >> np.uint64(16), G // np.uint64(gb)), gb
