@@ -187,3 +187,25 @@ def test_statistics_of_layers_that_start_anywhere(torch, oracle, dt):
     p, m = oracle.quantize(g, w.offsets, w.bits, w.bucket, 2, dt)
     assert_close(gpu_sqerrors(torch, g, p, m, w.offsets, w.bits, w.bucket, dt),
                  oracle.layer_sqerrors(g, p, m, w.offsets, w.bits, w.bucket, dt), "shifted sqerrors")
+
+
+def test_measurement_aids_run_and_stay_in_bounds(torch):
+    """The streaming probe (every load and store policy, both block numberings, a persistent grid, odd sizes)
+    and the issue-rate probe (every instruction form) run, and write nothing past the bytes they were given."""
+    src = torch.arange(0, 3 * 8192 + 48, dtype=torch.int32, device="cuda").view(torch.uint8)
+    rb = src.numel() // 16 * 16
+    for wb in (0, 1600, rb // 2 // 16 * 16, rb):
+        for loads in cgx.LOAD_POLICIES:
+            for stores in cgx.STORE_POLICIES:
+                dst = torch.full((wb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+                for slice_bytes, block, xcd, max_blocks in ((8192, 256, False, 0), (2048, 1024, True, 0), (4096, 64, True, 3)):
+                    cgx.cgx_stream_probe_shaped(src, rb, dst, wb, slice_bytes, block, loads, stores, xcd, max_blocks)
+                torch.cuda.synchronize()
+                assert (dst[wb:] == 0xA5).all(), (wb, loads, stores)
+    cgx.cgx_stream_probe(src, rb, torch.empty(rb, dtype=torch.uint8, device="cuda"), rb)
+    forms = cgx.cgx_issue_probe_forms()
+    out = torch.full((8 * 256 + 16,), -1, dtype=torch.int32, device="cuda")
+    for form in range(len(forms)):
+        cgx.cgx_issue_probe(form, 8, 3, out)
+    torch.cuda.synchronize()
+    assert (out[8 * 256:] == -1).all()
