@@ -421,6 +421,20 @@ def test_random_plans_with_any_legal_bucket_size(torch, oracle, seed):
     full_cycle(torch, oracle, w, W=min(w.W, 5), what=f"random plan {500 + seed} (bucket {w.bucket}, bits {w.bits.tolist()})")
 
 
+@pytest.mark.parametrize("bucket,dt", [(96, wl.F32), (992, wl.F16), (2016, wl.F32)], ids=["96-f32", "992-f16", "2016-f32"])
+def test_long_buffers_with_bucket_sizes_that_are_no_power_of_two(torch, oracle, bucket, dt):
+    """Tens of thousands of streamed tiles per launch: layers of millions of elements, every width."""
+    rng = np.random.default_rng(bucket)
+    sizes = [int(rng.integers(1 << 20, 1 << 22)) for _ in range(5)] + [(1 << 23) + 12345]
+    bits = np.array([4, 2, 8, 3, 0, 5], np.uint8)
+    w = wl.Workload("long", [(s,) for s in sizes], bits, bucket, dt, 3, 40 + bucket, wl._normal,
+                    10.0 ** rng.uniform(-3, 0, len(sizes)))
+    plan = cgx.Plan(w.offsets, w.bits, w.bucket, w.dt)
+    kinds = (cgx.cgx_plan_tiles(plan)["info"] >> 4) & 15
+    assert (kinds == 6).sum() > 5000
+    full_cycle(torch, oracle, w, W=w.W, what=f"long B={bucket}")
+
+
 def test_decoder_1p3b_config_full_size(torch, oracle):
     """292 tensors, 1.316G elements, Laplace values with outliers, bits in {2,4,8}, bucket 1024:
     quantize the full buffer (the launch bench.py times); reduce over W = 8 and requantize on
