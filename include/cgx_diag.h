@@ -121,6 +121,9 @@ int cgx_issue_probe(int32_t form, int32_t blocks, int32_t iterations, void *out,
  *                           through LDS
  *   CGX_KEEP_SUMS_MB=k      the reduce writes results of up to k MB through at device scope so that
  *                           they stay in the memory-side cache (default 128; 0: always streamed)
+ *   CGX_QUANTIZE_TILES_PER_WAVE_X4=k  grid of the binary32 quantizer on plans of up to 2^19 tiles: k/4 tiles per
+ *                           wave (default 5: four fifths of the waves that one tile each would take; 4: one
+ *                           wave per tile)
  *   CGX_REDUCE_GROUPS=2|4   chunk size of every reduce call with buckets of up to 1024 elements: 1024 or 2048
  *                           elements (default: 2048, and 1024 for cgx_dequantize to binary32)
  *   CGX_DEQUANTIZE_THROUGH=0  cgx_dequantize runs like a reduce of one chunk (2048-element chunks, the

@@ -91,6 +91,7 @@ const cgx::LaunchConfig &launch_config()
         c.keep_sums_max_bytes = long(env_int("CGX_KEEP_SUMS_MB", int(c.keep_sums_max_bytes >> 20))) << 20;
         c.dequantize_through = env_int("CGX_DEQUANTIZE_THROUGH", c.dequantize_through);
         c.reduce_groups = env_int("CGX_REDUCE_GROUPS", 0) == 2 ? 2 : env_int("CGX_REDUCE_GROUPS", 0) == 4 ? 4 : 0;
+        c.quantize_tiles_per_wave_x4 = env_int("CGX_QUANTIZE_TILES_PER_WAVE_X4", c.quantize_tiles_per_wave_x4);
         c.quantize_groups = env_int("CGX_QUANTIZE_GROUPS", 0) == 2 ? 2 : env_int("CGX_QUANTIZE_GROUPS", 0) == 4 ? 4 : 0;
         return c;
     }();

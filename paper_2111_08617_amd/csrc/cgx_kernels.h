@@ -29,6 +29,7 @@ struct LaunchConfig {
     long keep_sums_max_bytes = 128l << 20;   // reduce: results up to this size are kept in the memory-side cache
     int dequantize_through = 1;              // cgx_dequantize: stores written through at system scope
     int reduce_groups = 0;                   // 2 or 4: chunk size of every reduce call (0: chosen per call)
+    int quantize_tiles_per_wave_x4 = 5;      // quantize: tiles per wave of the grid, in quarters (4: one wave per tile)
 };
 
 // odd_tiles: some vectorised tile starts on an odd element index (the kernels then take the

@@ -23,13 +23,18 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const void *__restrict
     int lane_of_wave = int(threadIdx.x) & 63;
     uint4v *stage = stage_all[wave];
     const int64_t stride = int64_t(gridDim.x) * kWavesPerBlock;
-    for (int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave; t < n_tiles; t += stride) {
+    int64_t t = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+    if (t >= n_tiles) return;
+    Tile upcoming = tiles[t];
+    for (; t < n_tiles; t += stride) {
         // the lane index is made opaque once per tile: otherwise everything that depends on the
         // lane alone (offsets, masks, of every bit width's path) is hoisted out of this loop and
         // stays in registers across all of it
         asm volatile("" : "+v"(lane_of_wave));
         const int lane = lane_of_wave;
-        const Tile tile = tiles[t];
+        const Tile tile = upcoming;
+        // a wave that takes more than one tile has the next descriptor on its way meanwhile
+        if (t + stride < n_tiles) upcoming = tiles[t + stride];
         const int bucket = tile_bucket(tile);       // per tile: a launch may mix sizes of one lane mapping
         const uint32_t kind = tile_kind(tile);
         if (is_vector_kind(kind)) {
@@ -69,7 +74,19 @@ hipError_t CGX_CONCAT(launch_quantize_g, CGX_GROUPS)(int scheme, const void *gra
                            const LaunchConfig &cfg, hipStream_t stream)
 {
     if (n_tiles == 0) return hipSuccess;
-    const dim3 grid(grid_for(n_tiles, cfg)), block(kBlock);
+    // Four fifths of the waves that one tile each would take: every fourth wave takes a second tile, whose
+    // descriptor it fetches while it works on the first.  For the kernel of 1024-element chunks on plans of up to
+    // 2^19 tiles.  Measured by kernel trace, the two grids alternating on one box: ResNet-50 plan (25 k tiles)
+    // 20.9 -> 20.0 us, the requantize of a 13.7 M-element share 12.6 -> 11.9 us, full BERT-base buffer 77.6 ->
+    // 76.3 us, a 44 M-element share 34.6 -> 34.2 us; the 1.3 G-element buffer (1.28 M tiles) 978 -> 988 us and
+    // binary16 input (2048-element chunks, two per tile) 25.5 -> 26.7 us on a small buffer, hence the limits.
+    // With one and a half tiles per wave the gain is gone from 100 M elements on, with two it is a loss.
+    LaunchConfig shaped = cfg;
+    if (kGroups == 2 && cfg.max_blocks == 0 && cfg.quantize_tiles_per_wave_x4 > 4 && n_tiles <= (int64_t(1) << 19)) {
+        const int64_t blocks = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+        shaped.max_blocks = int((blocks * 4 + cfg.quantize_tiles_per_wave_x4 - 1) / cfg.quantize_tiles_per_wave_x4);
+    }
+    const dim3 grid(grid_for(n_tiles, shaped)), block(kBlock);
     const uint32_t seed_lo = uint32_t(seed), seed_hi = uint32_t(seed >> 32);
     using Kernel = void (*)(const void *, const Tile *, int64_t, uint32_t, uint32_t, uint8_t *, float *);
 #define CGX_QUANTIZE_MAPS(S, D, O) \

@@ -550,7 +550,8 @@ def test_result_does_not_depend_on_launch_geometry(torch, oracle):
     digests = set()
     for env in ({}, {"CGX_CHUNKS_PER_TILE": "3"}, {"CGX_CHUNKS_PER_TILE": "8", "CGX_MAX_BLOCKS": "5"},
                 {"CGX_QUANTIZE_GROUPS": "4", "CGX_KEEP_SUMS_MB": "0"}, {"CGX_QUANTIZE_GROUPS": "2", "CGX_VIA_LDS": "0"},
-                {"CGX_REDUCE_GROUPS": "2"}, {"CGX_REDUCE_GROUPS": "4", "CGX_DEQUANTIZE_THROUGH": "0"}):
+                {"CGX_REDUCE_GROUPS": "2"}, {"CGX_REDUCE_GROUPS": "4", "CGX_DEQUANTIZE_THROUGH": "0"},
+                {"CGX_QUANTIZE_TILES_PER_WAVE_X4": "4"}, {"CGX_QUANTIZE_TILES_PER_WAVE_X4": "11"}):
         out = subprocess.run([sys.executable, "-c", code], env={**os.environ, **env}, capture_output=True, text=True,
                              timeout=300)
         assert out.returncode == 0, out.stderr[-2000:]
