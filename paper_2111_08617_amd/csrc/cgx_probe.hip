@@ -145,10 +145,16 @@ __global__ __launch_bounds__(1024) void stream_probe_kernel(const uint4v *__rest
     X(36, "v_min_f32_dpp %0, %1, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")                             \
     X(37, "v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]")                                       \
     X(38, "v_rcp_f32 %0, %0")
-// one more form is written out below: its result is a register pair
+// two more forms are written out below: one whose result is a register pair, and one that reads LDS
 #define CGX_ISSUE_FORM_PAIR "v_cvt_pk_f32_fp8 %0:[2], %0 ; v_xor_b32 %0, %0[0], %0[1] (two results, folded by a v_xor_b32)"
+#define CGX_ISSUE_FORM_TABLE \
+    "v_lshrrev_b32 t, 7, %0 ; v_and_b32 t, 60, t ; v_add_u32 t, %1, t ; ds_read_b32 t, t ; v_add_f32 %0, t, %0 (the decode of a code by lookup: 16 entries in LDS, %1 the wave's table)"
+#define CGX_ISSUE_FORM_LANES \
+    "v_lshrrev_b32 t, 8, %0 ; ds_bpermute_b32 t, t, %1 ; v_add_f32 %0, t, %0 (the decode of a code by lookup in another lane's register, any of 64 lanes)"
+#define CGX_ISSUE_FORM_LANES16 \
+    "v_lshrrev_b32 t, 8, %0 ; v_and_b32 t, 60, t ; ds_bpermute_b32 t, t, %1 ; v_add_f32 %0, t, %0 (the same, 16 lanes)"
 
-constexpr int kIssueForms = 40;
+constexpr int kIssueForms = 43;
 constexpr int kIssueChains = 16;
 
 template <int FORM>
@@ -156,7 +162,7 @@ struct IssueForm;
 #define CGX_ISSUE_FORM(N, TEXT)                                                              \
     template <>                                                                              \
     struct IssueForm<N> {                                                                    \
-        static __device__ __forceinline__ void step(uint32_t &a, uint32_t b, uint32_t c, uint32_t s) \
+        static __device__ __forceinline__ void step(uint32_t &a, uint32_t b, uint32_t c, uint32_t s, const uint32_t *) \
         {                                                                                    \
             asm volatile(TEXT : "+v"(a) : "v"(b), "v"(c), "s"(s));                           \
         }                                                                                    \
@@ -164,25 +170,61 @@ struct IssueForm;
 CGX_ISSUE_FORMS(CGX_ISSUE_FORM)
 #undef CGX_ISSUE_FORM
 template <>
-struct IssueForm<kIssueForms - 1> {
-    static __device__ __forceinline__ void step(uint32_t &a, uint32_t, uint32_t, uint32_t)
+struct IssueForm<kIssueForms - 4> {
+    static __device__ __forceinline__ void step(uint32_t &a, uint32_t, uint32_t, uint32_t, const uint32_t *)
     {
         uint64_t pair;
         asm volatile("v_cvt_pk_f32_fp8 %0, %1" : "=v"(pair) : "v"(a));
         asm volatile("v_xor_b32 %0, %1, %2" : "=v"(a) : "v"(uint32_t(pair)), "v"(uint32_t(pair >> 32)));
     }
 };
+// The lookup is left to the compiler (it places the waits on LDS); every wave has a table of its own, whose 16
+// dwords lie in 16 banks, so lanes that read different entries do not collide.
+template <>
+struct IssueForm<kIssueForms - 3> {
+    static __device__ __forceinline__ void step(uint32_t &a, uint32_t, uint32_t, uint32_t, const uint32_t *table)
+    {
+        const float entry = __uint_as_float(*reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(table) + ((a >> 7) & 60u)));
+        a = __float_as_uint(__uint_as_float(a) + entry);
+    }
+};
+
+// The table in the lanes of one register: the permute takes bits 7:2 of its address for the lane it reads and
+// touches no memory.
+template <>
+struct IssueForm<kIssueForms - 2> {
+    static __device__ __forceinline__ void step(uint32_t &a, uint32_t, uint32_t c, uint32_t, const uint32_t *)
+    {
+        const float entry = __int_as_float(__builtin_amdgcn_ds_bpermute(int(a >> 8), int(c)));
+        a = __float_as_uint(__uint_as_float(a) + entry);
+    }
+};
+template <>
+struct IssueForm<kIssueForms - 1> {
+    static __device__ __forceinline__ void step(uint32_t &a, uint32_t, uint32_t c, uint32_t, const uint32_t *)
+    {
+        const float entry = __int_as_float(__builtin_amdgcn_ds_bpermute(int((a >> 8) & 60u), int(c)));
+        a = __float_as_uint(__uint_as_float(a) + entry);
+    }
+};
 
 template <int FORM>
 __global__ __launch_bounds__(256) void issue_probe_kernel(uint32_t *__restrict__ out, int iterations, uint32_t scalar)
 {
+    __shared__ uint32_t tables[4][16];
     const uint32_t b = 0x3f800000u + 0x01010101u * (threadIdx.x & 63u), c = (b * 7u) | 1u;
+    uint32_t *table = tables[(threadIdx.x >> 6) & 3u];
+    if constexpr (FORM == kIssueForms - 3) {
+        // entries of about 2^-20 .. 2^-19: the chains keep moving and stay finite
+        if ((threadIdx.x & 63u) < 16u) table[threadIdx.x & 63u] = 0x35800000u + 0x00011111u * (threadIdx.x & 63u);
+        __syncthreads();
+    }
     uint32_t a[kIssueChains];
 #pragma unroll
     for (int j = 0; j < kIssueChains; j++) a[j] = b * uint32_t(j + 3);
     for (int i = 0; i < iterations; i++) {
 #pragma unroll
-        for (int j = 0; j < kIssueChains; j++) IssueForm<FORM>::step(a[j], b, c, scalar);
+        for (int j = 0; j < kIssueChains; j++) IssueForm<FORM>::step(a[j], b, c, scalar, table);
     }
     uint32_t x = 0;
 #pragma unroll
@@ -209,7 +251,7 @@ const char *issue_probe_form(int form)
 #define CGX_ISSUE_NAME(N, TEXT) TEXT,
         CGX_ISSUE_FORMS(CGX_ISSUE_NAME)
 #undef CGX_ISSUE_NAME
-        CGX_ISSUE_FORM_PAIR};
+        CGX_ISSUE_FORM_PAIR, CGX_ISSUE_FORM_TABLE, CGX_ISSUE_FORM_LANES, CGX_ISSUE_FORM_LANES16};
     return form >= 0 && form < kIssueForms ? names[form] : nullptr;
 }
 
