@@ -100,8 +100,9 @@ int cgx_stream_probe_shaped(const void *src, size_t read_bytes, void *dst, size_
  * iterations, 16 independent dependency chains per lane, nothing else in the loop).  With 8 resident
  * waves per SIMD (blocks = 8 * compute units), launch time * clock / (blocks * 4 * 16 * iterations /
  * (compute units * 4)) is the form's cost in cycles of a SIMD.  The forms are those of the kernels'
- * inner loops and the alternatives weighed against them; cgx_issue_probe_form returns the text of a
- * form, NULL past the last one.  out (device, 16-byte aligned, out_bytes >= blocks * 1024) receives
+ * inner loops and the alternatives weighed against them (the last few are short sequences, a lookup in
+ * LDS or in another lane's register followed by an addition, counted as one); cgx_issue_probe_form
+ * returns the text of a form, NULL past the last one.  out (device, 16-byte aligned, out_bytes >= blocks * 1024) receives
  * one word per thread; its content is unspecified.  CGX_ERR_SIZE for a value outside these ranges.
  * The benchmark's --issue-rates mode prints the table; it is the evidence for pricing the fused
  * kernel, which is bound by the vector ALUs, and for the choice of its decoding instructions.

@@ -145,7 +145,8 @@ __global__ __launch_bounds__(1024) void stream_probe_kernel(const uint4v *__rest
     X(36, "v_min_f32_dpp %0, %1, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")                             \
     X(37, "v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]")                                       \
     X(38, "v_rcp_f32 %0, %0")
-// two more forms are written out below: one whose result is a register pair, and one that reads LDS
+// four more forms are written out below: one whose result is a register pair, and three short sequences
+// that decode a code by lookup (a table in LDS; a table in the lanes of a register, twice)
 #define CGX_ISSUE_FORM_PAIR "v_cvt_pk_f32_fp8 %0:[2], %0 ; v_xor_b32 %0, %0[0], %0[1] (two results, folded by a v_xor_b32)"
 #define CGX_ISSUE_FORM_TABLE \
     "v_lshrrev_b32 t, 7, %0 ; v_and_b32 t, 60, t ; v_add_u32 t, %1, t ; ds_read_b32 t, t ; v_add_f32 %0, t, %0 (the decode of a code by lookup: 16 entries in LDS, %1 the wave's table)"
